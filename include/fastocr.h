@@ -1,0 +1,198 @@
+/*
+ * fastocr.h -- C ABI of the FastOCR per-decode-step hot path for AMD MI355X (gfx950).
+ *
+ * The path has three steps, repeated at every decode step (Sec. 3, Alg. 1 of the
+ * FastOCR paper):
+ *   1. fastocr_focal_score        head-averaged attention of the current query over the
+ *                                 whole cache, read at the image tokens (Eq. 1, Eq. 2);
+ *   2. fastocr_topk_fixation      TopK_{ceil(tau N)} of those scores (Sec. 3.1.2), warm
+ *                                 started from the previous step's focal token set
+ *                                 (Cross-Step Fixation Reuse, Sec. 3.2);
+ *   3. fastocr_sparse_decode_attn attention restricted to the kept set K = T u F
+ *                                 (Eq. 2, non-focal branch);
+ * plus fastocr_dense_decode_attn, attention over the full cache (Eq. 2, focal branch;
+ * also the warm-up steps and the "vanilla" comparator of Table 2).
+ *
+ * General conventions
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller unless marked HOST.
+ *     The library never allocates, frees, writes or compacts the KV cache: the full cache
+ *     stays in place (no eviction).
+ *   - Calls validate their arguments on the host, enqueue kernels on `hip_stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream) and return without
+ *     synchronising.  The return value is a fastocr_status; device-side faults are not
+ *     reported here.
+ *   - `ws` is caller-provided device scratch of at least fastocr_workspace_bytes(...)
+ *     bytes, 256-byte aligned, private to the call until the stream reaches its end.
+ *   - Sequences are independent.  Sequence b holds seq_len[b] tokens; its image tokens
+ *     are the contiguous span [vis_start[b], vis_start[b] + vis_len[b]); every other
+ *     position (text before, text after, generated tokens, the current token) is text.
+ *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *   - Image-token indices (sel_idx, prev_idx) are relative to the start of the span.
+ */
+#ifndef FASTOCR_H
+#define FASTOCR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FASTOCR_OK = 0,
+    FASTOCR_EINVAL = -1,        /* null pointer, negative size, tau outside [0,1], ...   */
+    FASTOCR_EUNSUPPORTED = -2,  /* dtype / head_dim / group size the kernels do not cover */
+    FASTOCR_EWORKSPACE = -3,    /* ws NULL, misaligned or smaller than required           */
+    FASTOCR_EHIP = -4           /* a HIP runtime call (launch, event) failed              */
+} fastocr_status;
+
+typedef enum { FASTOCR_F32 = 0, FASTOCR_BF16 = 1 } fastocr_dtype;
+
+typedef enum {
+    FASTOCR_OP_FOCAL_SCORE = 0,
+    FASTOCR_OP_TOPK_FIXATION = 1,
+    FASTOCR_OP_SPARSE_DECODE_ATTN = 2,
+    FASTOCR_OP_DENSE_DECODE_ATTN = 3
+} fastocr_op;
+
+/*
+ * One layer's KV cache (device memory, read-only for the library).
+ * Element (sequence b, token j, kv head g, component c) of K lives at element offset
+ *   contiguous (page_tokens == 0):  b*stride_seq + j*stride_token + g*stride_head + c
+ *   paged      (page_tokens  > 0):  block_table[b*max_pages_per_seq + j/page_tokens]*stride_page
+ *                                   + (j % page_tokens)*stride_token + g*stride_head + c
+ * from `k` (same for `v`).  head_dim is contiguous.  Strides are in elements, must be
+ * multiples of 8 elements (16-byte rows for bf16) and k, v 16-byte aligned.
+ */
+typedef struct {
+    const void *k;
+    const void *v;
+    int32_t dtype;              /* fastocr_dtype; Q and the attention output use it too  */
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    int64_t stride_token;
+    int64_t stride_head;
+    int64_t stride_seq;
+    int32_t page_tokens;
+    int64_t stride_page;
+    const int32_t *block_table; /* DEVICE int32 [batch, max_pages_per_seq]; NULL if contiguous */
+    int32_t max_pages_per_seq;
+} fastocr_kv_view;
+
+/*
+ * Per-sequence geometry: DEVICE int32[batch] arrays plus HOST upper bounds that size the
+ * launch grids.  Required: 0 <= vis_start[b], 0 <= vis_len[b], vis_start[b]+vis_len[b] <=
+ * seq_len[b] <= max_seq_len, vis_len[b] <= max_vis_len.  The arrays are read on the
+ * device only; a sequence that violates the bounds is clamped to them, never read out of
+ * range.
+ */
+typedef struct {
+    int32_t batch;
+    const int32_t *seq_len;
+    const int32_t *vis_start;
+    const int32_t *vis_len;
+    int32_t max_seq_len;
+    int32_t max_vis_len;
+} fastocr_batch_view;
+
+/* ceil(tau * n_visual), the size of the focal token set (Sec. 3.1.2), clamped to
+ * [0, n_visual].  tau * n is formed in double and a product that exceeds an integer by
+ * less than 1e-9 does not round up.  Host function, no GPU involved. */
+int64_t fastocr_keep_count(int64_t n_visual, double tau);
+
+/* Bytes of device scratch `op` needs for these shapes (host function; only the host
+ * fields of the views are read).  kmax is ignored except for the top-k.  Returns 0 on
+ * invalid arguments. */
+size_t fastocr_workspace_bytes(int op, const fastocr_kv_view *kv, const fastocr_batch_view *bv,
+                               int n_q_heads, int64_t kmax);
+
+/*
+ * Step 1 (Eq. 1; text under Eq. 2; softmax of App. B).  For every sequence b and image
+ * token i:
+ *     scores[b*max_vis_len + i] = (1/n_q_heads) * sum_h softmax_j(scale * <q[b,h], K[b,j,kv(h)]>)[vis_start[b]+i]
+ * with the softmax over ALL seq_len[b] cached tokens.  Entries i >= vis_len[b] are not
+ * written.
+ *   q        [batch, n_q_heads, head_dim], kv->dtype, contiguous, 16-byte aligned
+ *   scores   fp32 [batch, max_vis_len]
+ *   lse      fp32 [batch, n_q_heads] natural-log sum-exp of each head's logits, or NULL
+ *   img_mass fp32 [batch] sum_i scores[b,i] = the image-attention ratio of Eq. 1, or NULL
+ */
+int fastocr_focal_score(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
+                        int n_q_heads, float scale, float *scores, float *lse, float *img_mass,
+                        void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Step 2 (Sec. 3.1.2 TopK; Sec. 3.2 / Alg. 1 reuse of the previous focal token set).
+ * For every sequence b: the k_b = fastocr_keep_count(vis_len[b], tau) image tokens with
+ * the largest score, ties broken towards the lower index, written to
+ * sel_idx[b*kmax + 0..k_b) in ASCENDING index order; sel_cnt[b] = k_b.  Entries beyond
+ * k_b are left as they were.
+ *   scores   fp32 [batch, max_vis_len] (row pitch max_vis_len)
+ *   prev_idx int32 [batch, kmax] / prev_cnt int32 [batch]: last step's set, or both NULL.
+ *            Used only to bound the search (the k_b-th best of the old set's current
+ *            scores is a lower bound of the new threshold); the result never depends on
+ *            it.  A set of the wrong size, out of range or not strictly ascending is
+ *            ignored.  prev_idx may alias sel_idx and prev_cnt may alias sel_cnt.
+ *   kmax     row pitch of sel_idx / prev_idx; must be >= keep_count(max_vis_len, tau)
+ * NaN scores order above every number.
+ */
+int fastocr_topk_fixation(const float *scores, const fastocr_batch_view *bv, double tau,
+                          const int32_t *prev_idx, const int32_t *prev_cnt, int32_t *sel_idx,
+                          int32_t *sel_cnt, int64_t kmax, void *ws, size_t ws_bytes,
+                          void *hip_stream);
+
+/*
+ * Step 3 (Eq. 2, non-focal branch).  For every sequence b and query head h:
+ *     out[b,h,:] = sum_{j in J_b} softmax_{J_b}(scale * <q[b,h], K[b,j,kv(h)]>)[j] * V[b,j,kv(h),:]
+ *     J_b = {text positions of b} u {vis_start[b] + sel_idx[b*kmax + r] : 0 <= r < sel_cnt[b]}
+ * sel_idx entries must be distinct and inside [0, vis_len[b]); their order is free.
+ * An entry outside the span is clamped into it.  An empty J_b gives a zero row.
+ *   out  [batch, n_q_heads, head_dim], kv->dtype (bf16 rounded to nearest even), 16-byte aligned;
+ *        q as in fastocr_focal_score
+ */
+int fastocr_sparse_decode_attn(const fastocr_kv_view *kv, const fastocr_batch_view *bv,
+                               const void *q, int n_q_heads, float scale, const int32_t *sel_idx,
+                               const int32_t *sel_cnt, int64_t kmax, void *out, void *ws,
+                               size_t ws_bytes, void *hip_stream);
+
+/*
+ * Eq. 2, focal branch: the same with J_b = [0, seq_len[b]).
+ *   lse  fp32 [batch, n_q_heads] natural-log sum-exp of the logits, or NULL
+ */
+int fastocr_dense_decode_attn(const fastocr_kv_view *kv, const fastocr_batch_view *bv,
+                              const void *q, int n_q_heads, float scale, void *out, float *lse,
+                              void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Per-kernel timing with HIP events recorded on the stream the kernel is launched on.
+ * fastocr_kernel_timer_enable(kernel, capacity) makes every later launch of that kernel
+ * record a start/stop event pair (up to `capacity` launches; capacity 0 disables and
+ * frees the events).  fastocr_kernel_timer_read synchronises the recorded events and
+ * writes up to `max_out` durations in milliseconds to the HOST array `ms_out`; returns
+ * the number of launches recorded so far (or a negative status) and resets the count.
+ */
+typedef enum {
+    FASTOCR_KERNEL_SCORE_LOGITS = 0,   /* streams K: logits + per-split softmax statistics */
+    FASTOCR_KERNEL_SCORE_FINALIZE = 1,
+    FASTOCR_KERNEL_TOPK = 2,
+    FASTOCR_KERNEL_SPARSE_ATTN = 3,
+    FASTOCR_KERNEL_DENSE_ATTN = 4,
+    FASTOCR_KERNEL_ATTN_COMBINE = 5,
+    FASTOCR_KERNEL_COUNT = 6
+} fastocr_kernel;
+
+int fastocr_kernel_timer_enable(int kernel, int capacity);
+int fastocr_kernel_timer_read(int kernel, float *ms_out, int max_out);
+
+/* Launch-shape overrides for measurement sweeps: key "splits_score" | "splits_dense" |
+ * "splits_sparse" (0 = automatic).  Returns FASTOCR_EINVAL for an unknown key. */
+int fastocr_set_tuning(const char *key, int value);
+
+const char *fastocr_strerror(int status);
+const char *fastocr_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASTOCR_H */

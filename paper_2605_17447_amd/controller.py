@@ -1,0 +1,86 @@
+"""Host-side step controller: which call each layer of a decode step enqueues.
+
+Implements the per-step control flow of Algorithm 1 (App. A) for a frozen focal layer set C:
+warm-up steps run full attention everywhere; afterwards a focal layer attends the full cache
+and refreshes the kept image tokens (Cross-Layer Propagation, Sec. 3.1.2), every other layer
+attends text + the kept tokens, and the set left by the deepest focal layer serves layer 0 of
+the next step (Cross-Step Fixation Reuse, Sec. 3.2).  No arithmetic happens here: the
+controller only owns device buffers and orders the four C-ABI calls on one stream.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence, Tuple
+
+import torch
+
+from . import binding as _b
+
+
+class FixationController:
+    def __init__(self, caches: Sequence[_b.KvCache], n_q_heads: int, scale: float,
+                 focal_layers: Sequence[int], tau: float, warmup: int, max_seq_len: int,
+                 max_vis_len: int, batch_size: int, device, focal_gap: int = 1, ops=None):
+        self.caches = list(caches)
+        self.n_layers = len(self.caches)
+        self.focal = sorted(set(int(c) for c in focal_layers))
+        if not self.focal:
+            raise ValueError("the focal layer set must not be empty")
+        if self.focal[0] < 0 or self.focal[-1] >= self.n_layers:
+            raise ValueError("focal layer outside the stack")
+        # the focal gap is a spacing in layers between focal layers (Sec. 3.1.1)
+        for a, c in zip(self.focal, self.focal[1:]):
+            if c - a <= focal_gap:
+                raise ValueError(f"focal layers {a} and {c} are closer than the focal gap {focal_gap}")
+        if not (0.0 <= tau <= 1.0):
+            raise ValueError("tau must lie in [0, 1]")
+        self.tau, self.warmup, self.scale, self.n_q_heads = float(tau), int(warmup), float(scale), n_q_heads
+        self.ops = ops if ops is not None else _b
+        self.device = device
+        self.kmax = max(1, self.ops.keep_count(max_vis_len, tau))
+        self.scores = torch.zeros((batch_size, max(max_vis_len, 1)), dtype=torch.float32, device=device)
+        self.kept_idx = torch.zeros((batch_size, self.kmax), dtype=torch.int32, device=device)
+        self.kept_cnt = torch.zeros((batch_size,), dtype=torch.int32, device=device)
+        self.kept_from: Optional[object] = None     # None: no set yet; "F_last"; or a layer index
+        self._ws = None
+        self._ws_bytes = 0
+
+    def _workspace(self, cache, batch):
+        need = 0
+        for op in (_b.OP_FOCAL_SCORE, _b.OP_TOPK_FIXATION, _b.OP_SPARSE_DECODE_ATTN, _b.OP_DENSE_DECODE_ATTN):
+            need = max(need, self.ops.workspace_bytes(op, cache, batch, self.n_q_heads, self.kmax))
+        if self._ws is None or self._ws_bytes < need:
+            self._ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
+            self._ws_bytes = need
+        return self._ws
+
+    def step(self, t: int, batch: "_b.SeqBatch", queries: Sequence[torch.Tensor],
+             outs: Sequence[torch.Tensor], stream=None) -> List[Tuple[int, str, Optional[object]]]:
+        """Enqueue decode step t (1-based).  queries[l], outs[l]: [B, Hq, d] per layer.
+        Returns the schedule it ran as (layer, mode, kept-set source) triples."""
+        ops, trace = self.ops, []
+        post_warmup = t > self.warmup
+        if post_warmup and self.kept_from is not None:
+            self.kept_from = "F_last"             # what the previous step left behind
+        for l, cache in enumerate(self.caches):
+            ws = self._workspace(cache, batch)
+            q, out = queries[l], outs[l]
+            if not post_warmup:
+                ops.dense_decode_attn(cache, batch, q, self.scale, out, ws, stream=stream)
+                trace.append((l, "full", None))
+                continue
+            selects = (l in self.focal) or (l == 0 and self.kept_from is None)
+            if selects:
+                ops.dense_decode_attn(cache, batch, q, self.scale, out, ws, stream=stream)
+                ops.focal_score(cache, batch, q, self.scale, self.scores, ws, stream=stream)
+                warm = self.kept_from is not None
+                ops.topk_fixation(self.scores, batch, self.tau, self.kept_idx, self.kept_cnt, ws,
+                                  prev_idx=self.kept_idx if warm else None,
+                                  prev_cnt=self.kept_cnt if warm else None, stream=stream)
+                self.kept_from = l
+                trace.append((l, "full+select", None))
+            else:
+                ops.sparse_decode_attn(cache, batch, q, self.scale, self.kept_idx, self.kept_cnt, out, ws,
+                                       stream=stream)
+                trace.append((l, "pruned", self.kept_from))
+        # after the last layer the kept set is the deepest focal layer's: it is next step's F_last
+        return trace

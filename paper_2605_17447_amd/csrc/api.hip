@@ -1,0 +1,311 @@
+// C ABI of the FastOCR decode hot path: host-side validation, workspace sizing, launch-shape
+// choice and per-kernel event timers.  Every check happens before the first HIP call, so the
+// error paths can be exercised without a GPU.
+#include <math.h>
+#include <string.h>
+
+#include "fastocr.h"
+#include "kernels.hpp"
+
+namespace fastocr {
+
+int g_tune_k_via_lds = 1;
+static int g_tune_splits[4] = {0, 0, 0, 0};     // indexed by fastocr_op
+
+// ---- per-kernel timers ------------------------------------------------------------------
+struct KernelTimer {
+    int capacity = 0;
+    int count = 0;
+    hipEvent_t *start = nullptr;
+    hipEvent_t *stop = nullptr;
+};
+static KernelTimer g_timers[K_COUNT];
+
+void timer_begin(int kernel, hipStream_t s)
+{
+    KernelTimer &t = g_timers[kernel];
+    if (t.count < t.capacity) (void)hipEventRecord(t.start[t.count], s);
+}
+
+void timer_end(int kernel, hipStream_t s)
+{
+    KernelTimer &t = g_timers[kernel];
+    if (t.count < t.capacity) {
+        (void)hipEventRecord(t.stop[t.count], s);
+        ++t.count;
+    }
+}
+
+// ---- shapes -----------------------------------------------------------------------------
+constexpr int kNumCU = 256;       // MI355X
+
+static int check_views(const fastocr_kv_view *kv, const fastocr_batch_view *bv, int n_q_heads)
+{
+    if (!kv || !bv) return FASTOCR_EINVAL;
+    if (!kv->k || !kv->v) return FASTOCR_EINVAL;
+    if (kv->dtype != FASTOCR_F32 && kv->dtype != FASTOCR_BF16) return FASTOCR_EUNSUPPORTED;
+    if (kv->n_kv_heads < 1 || kv->head_dim < 1) return FASTOCR_EINVAL;
+    if (n_q_heads < 1 || n_q_heads % kv->n_kv_heads != 0) return FASTOCR_EINVAL;
+    if (kv->head_dim > 256 || n_q_heads > 256) return FASTOCR_EUNSUPPORTED;
+    if (kv->stride_token < kv->head_dim || kv->stride_head < 0 || kv->stride_seq < 0) return FASTOCR_EINVAL;
+    if (bv->batch < 0 || bv->max_seq_len < 0 || bv->max_vis_len < 0) return FASTOCR_EINVAL;
+    if (bv->max_vis_len > bv->max_seq_len) return FASTOCR_EINVAL;
+    if (bv->batch > 65535) return FASTOCR_EUNSUPPORTED;
+    if (bv->batch > 0 && (!bv->seq_len || !bv->vis_start || !bv->vis_len)) return FASTOCR_EINVAL;
+    if (kv->page_tokens < 0) return FASTOCR_EINVAL;
+    if (kv->page_tokens > 0) {
+        if (!kv->block_table || kv->stride_page < 1) return FASTOCR_EINVAL;
+        const int64_t need = ((int64_t)bv->max_seq_len + kv->page_tokens - 1) / kv->page_tokens;
+        if (kv->max_pages_per_seq < need || kv->max_pages_per_seq < 1) return FASTOCR_EINVAL;
+    }
+    return FASTOCR_OK;
+}
+
+static Shape make_shape(const fastocr_kv_view *kv, const fastocr_batch_view *bv, int n_q_heads)
+{
+    Shape s;
+    s.kv.k = kv->k;
+    s.kv.v = kv->v;
+    s.kv.stride_token = kv->stride_token;
+    s.kv.stride_head = kv->stride_head;
+    s.kv.stride_seq = kv->stride_seq;
+    s.kv.stride_page = kv->stride_page;
+    s.kv.block_table = kv->block_table;
+    s.kv.max_pages = kv->max_pages_per_seq;
+    s.kv.page_tokens = kv->page_tokens;
+    s.kv.n_kv_heads = kv->n_kv_heads;
+    s.kv.head_dim = kv->head_dim;
+    s.bv.seq_len = bv->seq_len;
+    s.bv.vis_start = bv->vis_start;
+    s.bv.vis_len = bv->vis_len;
+    s.bv.max_seq_len = bv->max_seq_len;
+    s.bv.max_vis_len = bv->max_vis_len;
+    s.batch = bv->batch;
+    s.n_q_heads = n_q_heads;
+    s.dtype = kv->dtype;
+    s.paged = kv->page_tokens > 0;
+    // The MFMA kernels read 16-byte vectors: every cache row must start 16-byte aligned.
+    auto a16 = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
+    const bool aligned = a16(kv->k) && a16(kv->v) && kv->stride_token % 8 == 0 &&
+                         kv->stride_head % 8 == 0 && kv->stride_seq % 8 == 0 && kv->stride_page % 8 == 0;
+    s.fast = kv->dtype == FASTOCR_BF16 && kv->head_dim == 128 && n_q_heads / kv->n_kv_heads <= 16 && aligned;
+    return s;
+}
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Number of position ranges per (sequence, kv head): enough workgroups to fill the chip a few
+// times over, never less than one tile per wave.  A pure function of the host-side shape so
+// that the workspace query and the launch agree.
+static int choose_splits(int op, const Shape &s, int max_positions)
+{
+    const bool fast = s.fast;
+    int forced = g_tune_splits[op];
+    const int tile = fast ? 32 : 64;
+    const int waves_per_wg = fast ? 4 : 1;
+    const int ntile = (max_positions + tile - 1) / tile;
+    const int by_work = (ntile + waves_per_wg - 1) / waves_per_wg;
+    int nsplit;
+    if (forced > 0) {
+        nsplit = forced;
+    } else {
+        const int streams = s.batch * (fast ? s.kv.n_kv_heads : s.n_q_heads);
+        const int target_wg = fast ? (op == FASTOCR_OP_FOCAL_SCORE ? 4 : 2) * kNumCU : 8 * kNumCU;
+        nsplit = (target_wg + streams - 1) / (streams > 0 ? streams : 1);
+    }
+    if (nsplit > by_work) nsplit = by_work;
+    if (nsplit > 256) nsplit = 256;
+    if (nsplit < 1) nsplit = 1;
+    return nsplit;
+}
+
+static size_t round256(size_t x) { return (x + 255) / 256 * 256; }
+
+}  // namespace fastocr
+
+using namespace fastocr;
+
+extern "C" {
+
+int64_t fastocr_keep_count(int64_t n_visual, double tau)
+{
+    if (n_visual <= 0 || !(tau > 0.0)) return 0;
+    double x = ceil(tau * (double)n_visual - 1e-9);
+    if (x < 0.0) x = 0.0;
+    if (x > (double)n_visual) x = (double)n_visual;
+    return (int64_t)x;
+}
+
+size_t fastocr_workspace_bytes(int op, const fastocr_kv_view *kv, const fastocr_batch_view *bv,
+                               int n_q_heads, int64_t kmax)
+{
+    (void)kmax;
+    if (op == FASTOCR_OP_TOPK_FIXATION) {
+        if (!bv || bv->batch < 0 || bv->max_vis_len < 0) return 0;
+        return round256(topk_workspace_bytes(bv->batch, bv->max_vis_len));
+    }
+    if (op < 0 || op > FASTOCR_OP_DENSE_DECODE_ATTN) return 0;
+    if (check_views(kv, bv, n_q_heads) != FASTOCR_OK) return 0;
+    Shape s = make_shape(kv, bv, n_q_heads);
+    // the sparse path may be asked to attend everything (tau = 1): size for the whole sequence
+    const int nsplit = choose_splits(op, s, bv->max_seq_len);
+    if (op == FASTOCR_OP_FOCAL_SCORE) return round256(score_workspace_bytes(s, nsplit) + 256);
+    return round256(attn_workspace_bytes(s, nsplit) + 256);
+}
+
+static int check_ws(const void *ws, size_t ws_bytes, size_t need)
+{
+    if (need == 0) return FASTOCR_OK;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) != 0 || ws_bytes < need) return FASTOCR_EWORKSPACE;
+    return FASTOCR_OK;
+}
+
+static int check_qo(const fastocr_kv_view *kv, const void *q, const void *out, float scale)
+{
+    if (!q || !isfinite(scale)) return FASTOCR_EINVAL;
+    if (!aligned16(q) || (out && !aligned16(out))) return FASTOCR_EINVAL;
+    (void)kv;
+    return FASTOCR_OK;
+}
+
+int fastocr_focal_score(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
+                        int n_q_heads, float scale, float *scores, float *lse, float *img_mass,
+                        void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_views(kv, bv, n_q_heads);
+    if (rc != FASTOCR_OK) return rc;
+    rc = check_qo(kv, q, nullptr, scale);
+    if (rc != FASTOCR_OK) return rc;
+    if (!scores && bv->max_vis_len > 0 && bv->batch > 0) return FASTOCR_EINVAL;
+    const size_t need = fastocr_workspace_bytes(FASTOCR_OP_FOCAL_SCORE, kv, bv, n_q_heads, 0);
+    rc = check_ws(ws, ws_bytes, need);
+    if (rc != FASTOCR_OK) return rc;
+    if (bv->batch == 0) return FASTOCR_OK;
+    Shape s = make_shape(kv, bv, n_q_heads);
+    const int nsplit = choose_splits(FASTOCR_OP_FOCAL_SCORE, s, bv->max_seq_len);
+    hipError_t e = launch_score(s, q, scale, scores, lse, img_mass, ws, nsplit, (hipStream_t)hip_stream);
+    return e == hipSuccess ? FASTOCR_OK : FASTOCR_EHIP;
+}
+
+int fastocr_topk_fixation(const float *scores, const fastocr_batch_view *bv, double tau,
+                          const int32_t *prev_idx, const int32_t *prev_cnt, int32_t *sel_idx,
+                          int32_t *sel_cnt, int64_t kmax, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (!bv || bv->batch < 0 || bv->max_vis_len < 0 || bv->max_seq_len < 0) return FASTOCR_EINVAL;
+    if (bv->max_vis_len > bv->max_seq_len) return FASTOCR_EINVAL;
+    if (bv->batch > 65535) return FASTOCR_EUNSUPPORTED;
+    if (!(tau >= 0.0 && tau <= 1.0)) return FASTOCR_EINVAL;
+    if (bv->batch > 0 && (!bv->seq_len || !bv->vis_start || !bv->vis_len)) return FASTOCR_EINVAL;
+    if (!sel_idx || !sel_cnt) return FASTOCR_EINVAL;
+    if (!scores && bv->max_vis_len > 0 && bv->batch > 0) return FASTOCR_EINVAL;
+    if ((prev_idx == nullptr) != (prev_cnt == nullptr)) return FASTOCR_EINVAL;
+    if (kmax < 1 || kmax < fastocr_keep_count(bv->max_vis_len, tau)) return FASTOCR_EINVAL;
+    const size_t need = fastocr_workspace_bytes(FASTOCR_OP_TOPK_FIXATION, nullptr, bv, 0, kmax);
+    int rc = check_ws(ws, ws_bytes, need);
+    if (rc != FASTOCR_OK) return rc;
+    if (bv->batch == 0) return FASTOCR_OK;
+    BatchDev bd{bv->seq_len, bv->vis_start, bv->vis_len, bv->max_seq_len, bv->max_vis_len};
+    hipError_t e = launch_topk(scores, bd, bv->batch, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax,
+                               ws, (hipStream_t)hip_stream);
+    return e == hipSuccess ? FASTOCR_OK : FASTOCR_EHIP;
+}
+
+static int attn_common(int op, const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
+                       int n_q_heads, float scale, const int32_t *sel_idx, const int32_t *sel_cnt,
+                       int64_t kmax, void *out, float *lse, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_views(kv, bv, n_q_heads);
+    if (rc != FASTOCR_OK) return rc;
+    if (!out) return FASTOCR_EINVAL;
+    rc = check_qo(kv, q, out, scale);
+    if (rc != FASTOCR_OK) return rc;
+    if (op == FASTOCR_OP_SPARSE_DECODE_ATTN && (!sel_idx || !sel_cnt || kmax < 1)) return FASTOCR_EINVAL;
+    const size_t need = fastocr_workspace_bytes(op, kv, bv, n_q_heads, kmax);
+    rc = check_ws(ws, ws_bytes, need);
+    if (rc != FASTOCR_OK) return rc;
+    if (bv->batch == 0) return FASTOCR_OK;
+    Shape s = make_shape(kv, bv, n_q_heads);
+    const int nsplit = choose_splits(op, s, bv->max_seq_len);
+    hipError_t e = launch_attn(s, q, scale, sel_idx, sel_cnt, kmax, out, lse, ws, nsplit, (hipStream_t)hip_stream);
+    return e == hipSuccess ? FASTOCR_OK : FASTOCR_EHIP;
+}
+
+int fastocr_sparse_decode_attn(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
+                               int n_q_heads, float scale, const int32_t *sel_idx, const int32_t *sel_cnt,
+                               int64_t kmax, void *out, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    return attn_common(FASTOCR_OP_SPARSE_DECODE_ATTN, kv, bv, q, n_q_heads, scale, sel_idx, sel_cnt, kmax,
+                       out, nullptr, ws, ws_bytes, hip_stream);
+}
+
+int fastocr_dense_decode_attn(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
+                              int n_q_heads, float scale, void *out, float *lse, void *ws, size_t ws_bytes,
+                              void *hip_stream)
+{
+    return attn_common(FASTOCR_OP_DENSE_DECODE_ATTN, kv, bv, q, n_q_heads, scale, nullptr, nullptr, 0,
+                       out, lse, ws, ws_bytes, hip_stream);
+}
+
+int fastocr_kernel_timer_enable(int kernel, int capacity)
+{
+    if (kernel < 0 || kernel >= K_COUNT || capacity < 0) return FASTOCR_EINVAL;
+    KernelTimer &t = g_timers[kernel];
+    for (int i = 0; i < t.capacity; ++i) {
+        (void)hipEventDestroy(t.start[i]);
+        (void)hipEventDestroy(t.stop[i]);
+    }
+    delete[] t.start;
+    delete[] t.stop;
+    t = KernelTimer();
+    if (capacity == 0) return FASTOCR_OK;
+    t.start = new hipEvent_t[capacity];
+    t.stop = new hipEvent_t[capacity];
+    for (int i = 0; i < capacity; ++i) {
+        if (hipEventCreate(&t.start[i]) != hipSuccess || hipEventCreate(&t.stop[i]) != hipSuccess) {
+            t.capacity = 0;
+            return FASTOCR_EHIP;
+        }
+    }
+    t.capacity = capacity;
+    return FASTOCR_OK;
+}
+
+int fastocr_kernel_timer_read(int kernel, float *ms_out, int max_out)
+{
+    if (kernel < 0 || kernel >= K_COUNT || (max_out > 0 && !ms_out)) return FASTOCR_EINVAL;
+    KernelTimer &t = g_timers[kernel];
+    const int n = t.count;
+    for (int i = 0; i < n && i < max_out; ++i) {
+        if (hipEventSynchronize(t.stop[i]) != hipSuccess) return FASTOCR_EHIP;
+        if (hipEventElapsedTime(&ms_out[i], t.start[i], t.stop[i]) != hipSuccess) return FASTOCR_EHIP;
+    }
+    t.count = 0;
+    return n;
+}
+
+int fastocr_set_tuning(const char *key, int value)
+{
+    if (!key || value < 0) return FASTOCR_EINVAL;
+    if (!strcmp(key, "splits_score")) g_tune_splits[FASTOCR_OP_FOCAL_SCORE] = value;
+    else if (!strcmp(key, "splits_sparse")) g_tune_splits[FASTOCR_OP_SPARSE_DECODE_ATTN] = value;
+    else if (!strcmp(key, "splits_dense")) g_tune_splits[FASTOCR_OP_DENSE_DECODE_ATTN] = value;
+    else if (!strcmp(key, "k_via_lds")) g_tune_k_via_lds = value ? 1 : 0;
+    else return FASTOCR_EINVAL;
+    return FASTOCR_OK;
+}
+
+const char *fastocr_strerror(int status)
+{
+    switch (status) {
+    case FASTOCR_OK: return "ok";
+    case FASTOCR_EINVAL: return "invalid argument";
+    case FASTOCR_EUNSUPPORTED: return "unsupported dtype, head_dim or head count";
+    case FASTOCR_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case FASTOCR_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+const char *fastocr_version(void) { return "fastocr-mi355x 0.1 (gfx950)"; }
+
+}  // extern "C"

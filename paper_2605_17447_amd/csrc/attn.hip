@@ -1,0 +1,420 @@
+// Decode attention over an explicit token list: split-K flash-decode for gfx950.
+//
+// One launch covers both branches of Eq. 2: the focal branch attends all cached tokens
+// (dense), the non-focal branch attends the kept set T u F (gather: text before the image
+// span, the selected image tokens, text after the span).  The attended list is cut into
+// `nsplit` position ranges; a workgroup owns one (sequence, kv head, range), its four waves
+// walk interleaved 32-token tiles with a private online softmax each, merge through LDS and
+// write one fp32 partial (m, Z, acc[d]); a second small kernel merges the partials.
+//
+// bf16, head_dim 128 path: the G = Hq/Hkv query heads that share a kv head form the 16-wide
+// side of v_mfma_f32_16x16x32_bf16 (rows beyond G are zero), tokens the other side.
+//   QK^T : A = K tile (16 tokens x 32 dims), B = Q^T  -> C[token][head]
+//   PV   : A = V^T (16 dims x 32 tokens),   B = P^T  -> C[dim][head]
+// The C layout of the first product (lane = head, 4 tokens per lane group) is exactly the
+// B layout the second one needs, so probabilities never cross lanes.  V rows are loaded
+// coalesced (16 lanes x 16 B = one 256 B row) and transposed in registers with v_perm_b32.
+// K is loaded the same coalesced way and re-laid to the A layout through a wave-private,
+// XOR-swizzled LDS tile (or loaded straight in A layout, 64 B per row per instruction).
+#include "kernels.hpp"
+
+namespace fastocr {
+
+extern int g_tune_k_via_lds;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kTile = 32;          // tokens per wave tile (two 16-token MFMA tiles)
+constexpr int kWaves = 4;
+
+__device__ __forceinline__ void wave_lds_fence()
+{
+    // LDS traffic of one wave executes in order; this only stops the compiler from moving
+    // the reads of other lanes' data above the writes that produce it.
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Row of the 32-token tile that lane group `lg` holds as element e of its 8-token k-block:
+// elements 0..3 come from the first 16-token half, 4..7 from the second.
+__device__ __forceinline__ int tile_row(int lg, int e) { return (e < 4) ? (4 * lg + e) : (16 + 4 * lg + (e - 4)); }
+
+// -----------------------------------------------------------------------------------------
+// MFMA kernel: bf16, head_dim = 128, G <= 16.
+// -----------------------------------------------------------------------------------------
+template <bool GATHER, bool PAGED, bool KLDS>
+__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
+    KvDev kv, BatchDev bv, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2,
+    const int32_t *__restrict__ sel_idx, const int32_t *__restrict__ sel_cnt, int64_t kmax,
+    float *__restrict__ part_o, float *__restrict__ part_ml, int nsplit)
+{
+    __shared__ __align__(16) unsigned char smem[kWaves][8192];
+    __shared__ float sm_m[kWaves][16], sm_z[kWaves][16];
+
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int li = lane & 15, lg = lane >> 4;
+    const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+
+    const SeqGeom geo = seq_geom(bv, b);
+    int cnt = 0;
+    const int32_t *sel = nullptr;
+    if (GATHER) {
+        cnt = min(max(sel_cnt[b], 0), (int)min((int64_t)geo.N, kmax));
+        sel = sel_idx + (int64_t)b * kmax;
+    }
+    const int L = GATHER ? (geo.S - geo.N + cnt) : geo.S;
+    const int ntile = (L + kTile - 1) / kTile;
+    const int tps = (ntile + nsplit - 1) / nsplit;
+    const int t0 = split * tps, t1 = min(ntile, t0 + tps);
+
+    // Q as the B operand: lane (head li, k-block lg) holds dims 8*(4kk+lg) .. +7 for step kk.
+    u32x4 qreg[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        qreg[kk] = u32x4{0u, 0u, 0u, 0u};
+        if (li < G) {
+            const uint16_t *qp = q + ((int64_t)b * Hq + (int64_t)kvh * G + li) * 128 + 8 * (4 * kk + lg);
+            qreg[kk] = *reinterpret_cast<const u32x4 *>(qp);
+        }
+    }
+
+    const uint16_t *kbase = reinterpret_cast<const uint16_t *>(kv.k);
+    const uint16_t *vbase = reinterpret_cast<const uint16_t *>(kv.v);
+
+    // element offset of the row this lane looks up for tile `tile` (position tile*32 + lane%32)
+    auto rowoff_of = [&](int tile) -> int64_t {
+        int p = min(tile * kTile + (lane & 31), L - 1);
+        int tok = pos_to_token<GATHER>(p, geo, cnt, sel);
+        return row_offset<PAGED>(kv, b, tok, kvh);
+    };
+    const int64_t seq_base = row_offset<false>(kv, b, 0, kvh);
+
+    auto load_tile = [&](int tile, int64_t off, u32x4(&K)[8], u32x4(&V)[8]) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int r = tile_row(lg, e);
+            int64_t ro;
+            if (GATHER || PAGED) ro = __shfl(off, r);
+            else ro = seq_base + (int64_t)min(tile * kTile + r, L - 1) * kv.stride_token;
+            V[e] = *reinterpret_cast<const u32x4 *>(vbase + ro + 8 * li);
+            if (KLDS) K[e] = *reinterpret_cast<const u32x4 *>(kbase + ro + 8 * li);
+        }
+        if (!KLDS) {
+#pragma unroll
+            for (int T = 0; T < 2; ++T) {
+                const int r = 16 * T + li;
+                int64_t ro;
+                if (GATHER || PAGED) ro = __shfl(off, r);
+                else ro = seq_base + (int64_t)min(tile * kTile + r, L - 1) * kv.stride_token;
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+                    K[4 * T + kk] = *reinterpret_cast<const u32x4 *>(kbase + ro + 8 * (4 * kk + lg));
+            }
+        }
+    };
+
+    float m = -INFINITY, zl = 0.f;
+    f32x4 acc[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    auto compute = [&](int tile, u32x4(&K)[8], u32x4(&V)[8]) {
+        u32x4 ka[8];
+        if (KLDS) {
+            unsigned char *sw = smem[wave];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int r = tile_row(lg, e);
+                *reinterpret_cast<u32x4 *>(sw + r * 256 + ((li ^ (r & 15)) << 4)) = K[e];
+            }
+            wave_lds_fence();
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    const int c = 4 * kk + lg;
+                    ka[4 * T + kk] = *reinterpret_cast<const u32x4 *>(sw + (16 * T + li) * 256 + (((c ^ li) & 15) << 4));
+                }
+            wave_lds_fence();
+        } else {
+#pragma unroll
+            for (int x = 0; x < 8; ++x) ka[x] = K[x];
+        }
+        f32x4 s0 = f32x4{0.f, 0.f, 0.f, 0.f}, s1 = s0;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[kk]),
+                                                         __builtin_bit_cast(bf16x8, qreg[kk]), s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[4 + kk]),
+                                                         __builtin_bit_cast(bf16x8, qreg[kk]), s1, 0, 0, 0);
+        }
+        // lane (head li, group lg): s0[r] is token 4lg+r of the tile, s1[r] token 16+4lg+r
+        float s[8];
+        const int pbase = tile * kTile + 4 * lg;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            s[r] = (pbase + r < L) ? s0[r] * scale_log2 : -INFINITY;
+            s[4 + r] = (pbase + 16 + r < L) ? s1[r] * scale_log2 : -INFINITY;
+        }
+        float mx = s[0];
+#pragma unroll
+        for (int e = 1; e < 8; ++e) mx = fmaxf(mx, s[e]);
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m, mx);          // finite: every tile holds a valid position
+        const float alpha = fast_exp2(m - m_new);
+        float p[8], ps = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { p[e] = fast_exp2(s[e] - m_new); ps += p[e]; }
+        zl = zl * alpha + ps;
+        m = m_new;
+        bf16x8 pb;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pb[e] = (__bf16)p[e];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            acc[t] *= alpha;
+            const int w = t >> 1;
+            const uint32_t selb = (t & 1) ? 0x07060302u : 0x05040100u;
+            u32x4 a;
+#pragma unroll
+            for (int pp = 0; pp < 4; ++pp) a[pp] = __builtin_amdgcn_perm(V[2 * pp + 1][w], V[2 * pp][w], selb);
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), pb, acc[t], 0, 0, 0);
+        }
+    };
+
+    if (t0 + wave < t1) {
+        u32x4 KA[8], VA[8], KB[8], VB[8];
+        int tile = t0 + wave;
+        int64_t off_a = 0, off_b = 0;
+        if (GATHER || PAGED) off_a = rowoff_of(tile);
+        load_tile(tile, off_a, KA, VA);
+        if (GATHER || PAGED) off_b = rowoff_of(tile + kWaves);
+        while (true) {
+            int nxt = tile + kWaves;
+            if (nxt < t1) {
+                load_tile(nxt, off_b, KB, VB);
+                if (GATHER || PAGED) off_a = rowoff_of(nxt + kWaves);
+            }
+            compute(tile, KA, VA);
+            if (nxt >= t1) break;
+            tile = nxt;
+            nxt = tile + kWaves;
+            if (nxt < t1) {
+                load_tile(nxt, off_a, KA, VA);
+                if (GATHER || PAGED) off_b = rowoff_of(nxt + kWaves);
+            }
+            compute(tile, KB, VB);
+            if (nxt >= t1) break;
+            tile = nxt;
+        }
+    }
+
+    // ---- cross-wave merge through LDS -----------------------------------------------------
+    zl += __shfl_xor(zl, 16);
+    zl += __shfl_xor(zl, 32);
+    float *buf = reinterpret_cast<float *>(smem[wave]);        // [16 heads][128 dims]
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) buf[li * 128 + 32 * lg + 8 * r + t] = acc[t][r];
+    if (lg == 0) { sm_m[wave][li] = m; sm_z[wave][li] = zl; }
+    __syncthreads();
+
+    for (int idx = threadIdx.x; idx < G * 128; idx += 256) {
+        const int hh = idx >> 7, c = idx & 127;
+        float M = sm_m[0][hh];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) M = fmaxf(M, sm_m[w][hh]);
+        float o = 0.f, Z = 0.f;
+        if (M > -INFINITY) {
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                const float f = fast_exp2(sm_m[w][hh] - M);
+                o += f * reinterpret_cast<const float *>(smem[w])[hh * 128 + c];
+                Z += f * sm_z[w][hh];
+            }
+        }
+        const int64_t ph = ((int64_t)b * Hq + (int64_t)kvh * G + hh) * nsplit + split;
+        part_o[ph * 128 + c] = o;
+        if (c == 0) { part_ml[ph * 2] = M; part_ml[ph * 2 + 1] = Z; }
+    }
+}
+
+// -----------------------------------------------------------------------------------------
+// Generic kernel: any dtype / head_dim <= 256 / group size.  One wave per (range, query
+// head, sequence); lanes over tokens for q.k, lanes over dims for p.V.  Plain fp32 FMAs.
+// -----------------------------------------------------------------------------------------
+template <typename T, bool GATHER, bool PAGED>
+__global__ __launch_bounds__(64) void attn_generic_kernel(
+    KvDev kv, BatchDev bv, const T *__restrict__ q, int Hq, float scale_log2,
+    const int32_t *__restrict__ sel_idx, const int32_t *__restrict__ sel_cnt, int64_t kmax,
+    float *__restrict__ part_o, float *__restrict__ part_ml, int nsplit)
+{
+    __shared__ float qs[256];
+    const int lane = threadIdx.x;
+    const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int d = kv.head_dim;
+    const int G = Hq / kv.n_kv_heads;
+    const int g = h / G;
+
+    const SeqGeom geo = seq_geom(bv, b);
+    int cnt = 0;
+    const int32_t *sel = nullptr;
+    if (GATHER) {
+        cnt = min(max(sel_cnt[b], 0), (int)min((int64_t)geo.N, kmax));
+        sel = sel_idx + (int64_t)b * kmax;
+    }
+    const int L = GATHER ? (geo.S - geo.N + cnt) : geo.S;
+    const int ntile = (L + 63) / 64;
+    const int tps = (ntile + nsplit - 1) / nsplit;
+    const int t0 = split * tps, t1 = min(ntile, t0 + tps);
+
+    for (int c = lane; c < d; c += 64) qs[c] = load_elem<T>(q + ((int64_t)b * Hq + h) * d + c);
+    __syncthreads();
+
+    const T *kbase = reinterpret_cast<const T *>(kv.k);
+    const T *vbase = reinterpret_cast<const T *>(kv.v);
+    float m = -INFINITY, z = 0.f;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+
+    for (int tile = t0; tile < t1; ++tile) {
+        const int p = tile * 64 + lane;
+        const bool valid = p < L;
+        const int tok = pos_to_token<GATHER>(min(p, L - 1), geo, cnt, sel);
+        const int64_t off = row_offset<PAGED>(kv, b, tok, g);
+        float s = 0.f;
+        for (int c = 0; c < d; ++c) s = fmaf(qs[c], load_elem<T>(kbase + off + c), s);
+        s = valid ? s * scale_log2 : -INFINITY;
+        const float m_new = fmaxf(m, wave_max(s));
+        const float alpha = fast_exp2(m - m_new);
+        const float pj = fast_exp2(s - m_new);
+        z = z * alpha + wave_sum(pj);
+        m = m_new;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) acc[x] *= alpha;
+        const int nv = min(64, L - tile * 64);
+        for (int jj = 0; jj < nv; ++jj) {
+            const float pb = __shfl(pj, jj);
+            const int64_t oj = __shfl(off, jj);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const int c = lane + 64 * x;
+                if (c < d) acc[x] = fmaf(pb, load_elem<T>(vbase + oj + c), acc[x]);
+            }
+        }
+    }
+    const int64_t ph = ((int64_t)b * Hq + h) * nsplit + split;
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        const int c = lane + 64 * x;
+        if (c < d) part_o[ph * d + c] = acc[x];
+    }
+    if (lane == 0) { part_ml[ph * 2] = m; part_ml[ph * 2 + 1] = z; }
+}
+
+// -----------------------------------------------------------------------------------------
+// Merge of the per-range partials: out = sum_s 2^(m_s - M) acc_s / sum_s 2^(m_s - M) Z_s.
+// -----------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void attn_combine_kernel(
+    const float *__restrict__ part_o, const float *__restrict__ part_ml, int nsplit, int d,
+    T *__restrict__ out, float *__restrict__ lse)
+{
+    const int64_t bh = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;    // b*Hq + h
+    const int c = threadIdx.x;
+    const float *ml = part_ml + bh * nsplit * 2;
+    float M = -INFINITY;
+    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, ml[2 * s]);
+    float Z = 0.f, o = 0.f;
+    if (M > -INFINITY) {
+        for (int s = 0; s < nsplit; ++s) {
+            const float f = fast_exp2(ml[2 * s] - M);
+            Z += f * ml[2 * s + 1];
+            if (c < d) o += f * part_o[(bh * nsplit + s) * d + c];
+        }
+    }
+    if (c < d) store_elem<T>(out + bh * d + c, Z > 0.f ? o / Z : 0.f);
+    if (lse && c == 0) lse[bh] = Z > 0.f ? (M + log2f(Z)) * kLn2 : -INFINITY;
+}
+
+// -----------------------------------------------------------------------------------------
+// Host side
+// -----------------------------------------------------------------------------------------
+int attn_tile_tokens(const Shape &s) { return mfma_path(s) ? kTile * kWaves : 64; }
+
+size_t attn_workspace_bytes(const Shape &s, int nsplit)
+{
+    const size_t rows = (size_t)s.batch * s.n_q_heads * nsplit;
+    return rows * (size_t)(s.kv.head_dim + 2) * sizeof(float);
+}
+
+template <bool GATHER, bool PAGED>
+static void launch_mfma(const Shape &s, const void *q, float scale_log2, const int32_t *sel_idx,
+                        const int32_t *sel_cnt, int64_t kmax, float *part_o, float *part_ml,
+                        int nsplit, hipStream_t stream)
+{
+    const int G = s.n_q_heads / s.kv.n_kv_heads;
+    dim3 grid(nsplit, s.kv.n_kv_heads, s.batch), block(256);
+    if (g_tune_k_via_lds)
+        attn_mfma_kernel<GATHER, PAGED, true><<<grid, block, 0, stream>>>(
+            s.kv, s.bv, (const uint16_t *)q, s.n_q_heads, G, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit);
+    else
+        attn_mfma_kernel<GATHER, PAGED, false><<<grid, block, 0, stream>>>(
+            s.kv, s.bv, (const uint16_t *)q, s.n_q_heads, G, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit);
+}
+
+template <typename T, bool GATHER, bool PAGED>
+static void launch_generic(const Shape &s, const void *q, float scale_log2, const int32_t *sel_idx,
+                           const int32_t *sel_cnt, int64_t kmax, float *part_o, float *part_ml,
+                           int nsplit, hipStream_t stream)
+{
+    dim3 grid(nsplit, s.n_q_heads, s.batch), block(64);
+    attn_generic_kernel<T, GATHER, PAGED><<<grid, block, 0, stream>>>(
+        s.kv, s.bv, (const T *)q, s.n_q_heads, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit);
+}
+
+hipError_t launch_attn(const Shape &s, const void *q, float scale, const int32_t *sel_idx,
+                       const int32_t *sel_cnt, int64_t kmax, void *out, float *lse, void *ws,
+                       int nsplit, hipStream_t stream)
+{
+    const bool gather = sel_idx != nullptr;
+    const int d = s.kv.head_dim;
+    float *part_o = reinterpret_cast<float *>(ws);
+    float *part_ml = part_o + (size_t)s.batch * s.n_q_heads * nsplit * d;
+    const float scale_log2 = scale * kLog2e;
+    const int kid = gather ? K_SPARSE_ATTN : K_DENSE_ATTN;
+
+    timer_begin(kid, stream);
+#define FASTOCR_DISPATCH(FN, ...)                                                                      \
+    do {                                                                                               \
+        if (gather) { if (s.paged) FN<__VA_ARGS__ true, true>(s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, stream); \
+                      else         FN<__VA_ARGS__ true, false>(s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, stream); } \
+        else        { if (s.paged) FN<__VA_ARGS__ false, true>(s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, stream); \
+                      else         FN<__VA_ARGS__ false, false>(s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, stream); } \
+    } while (0)
+    if (mfma_path(s)) {
+        FASTOCR_DISPATCH(launch_mfma, );
+    } else if (s.dtype == DT_BF16) {
+        FASTOCR_DISPATCH(launch_generic, uint16_t, );
+    } else {
+        FASTOCR_DISPATCH(launch_generic, float, );
+    }
+#undef FASTOCR_DISPATCH
+    timer_end(kid, stream);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+
+    timer_begin(K_ATTN_COMBINE, stream);
+    dim3 grid(s.n_q_heads, s.batch), block(256);
+    if (s.dtype == DT_BF16)
+        attn_combine_kernel<uint16_t><<<grid, block, 0, stream>>>(part_o, part_ml, nsplit, d, (uint16_t *)out, lse);
+    else
+        attn_combine_kernel<float><<<grid, block, 0, stream>>>(part_o, part_ml, nsplit, d, (float *)out, lse);
+    timer_end(K_ATTN_COMBINE, stream);
+    return hipGetLastError();
+}
+
+}  // namespace fastocr

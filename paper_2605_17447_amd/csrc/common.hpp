@@ -1,0 +1,117 @@
+// Shared device-side plumbing of the FastOCR HIP kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fastocr {
+
+// Kernel-side copies of the C-ABI views (plain data, passed by value).
+struct KvDev {
+    const void *k;
+    const void *v;
+    int64_t stride_token, stride_head, stride_seq, stride_page;   // elements
+    const int32_t *block_table;
+    int32_t max_pages, page_tokens;
+    int32_t n_kv_heads, head_dim;
+};
+
+struct BatchDev {
+    const int32_t *seq_len, *vis_start, *vis_len;
+    int32_t max_seq_len, max_vis_len;
+};
+
+// Sequence geometry, clamped to the host-side bounds the grids and workspaces were sized
+// with, so that a bad device-side length can never drive a read or write out of range.
+struct SeqGeom {
+    int S;    // tokens in the sequence
+    int v0;   // first image token
+    int N;    // image tokens
+};
+
+__device__ __forceinline__ SeqGeom seq_geom(const BatchDev &bv, int b)
+{
+    SeqGeom g;
+    g.S = min(max(bv.seq_len[b], 0), bv.max_seq_len);
+    g.v0 = min(max(bv.vis_start[b], 0), g.S);
+    g.N = min(min(max(bv.vis_len[b], 0), g.S - g.v0), bv.max_vis_len);
+    return g;
+}
+
+// Element offset of (sequence b, token j, kv head g, component 0).
+template <bool PAGED>
+__device__ __forceinline__ int64_t row_offset(const KvDev &kv, int b, int j, int g)
+{
+    if (PAGED) {
+        int pg = j / kv.page_tokens;
+        int in = j - pg * kv.page_tokens;
+        pg = min(pg, kv.max_pages - 1);
+        int64_t page = kv.block_table[(int64_t)b * kv.max_pages + pg];
+        return page * kv.stride_page + (int64_t)in * kv.stride_token + (int64_t)g * kv.stride_head;
+    }
+    return (int64_t)b * kv.stride_seq + (int64_t)j * kv.stride_token + (int64_t)g * kv.stride_head;
+}
+
+// Position p of the attended list -> token index of the sequence.
+//   dense : identity.
+//   gather: [text before the span][selected image tokens][text after the span]
+template <bool GATHER>
+__device__ __forceinline__ int pos_to_token(int p, const SeqGeom &g, int cnt, const int32_t *sel)
+{
+    if (!GATHER) return p;
+    if (p < g.v0) return p;
+    if (p < g.v0 + cnt) {
+        int i = sel[p - g.v0];
+        i = min(max(i, 0), g.N - 1);
+        return g.v0 + i;
+    }
+    return p - cnt + g.N;
+}
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b)
+{
+    return __uint_as_float(((uint32_t)b) << 16);
+}
+
+// round-to-nearest-even fp32 -> bf16 bits (NaN kept quiet)
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ float load_elem(const T *p);
+template <> __device__ __forceinline__ float load_elem<float>(const float *p) { return *p; }
+template <> __device__ __forceinline__ float load_elem<uint16_t>(const uint16_t *p) { return bf16_bits_to_f32(*p); }
+
+template <typename T> __device__ __forceinline__ void store_elem(T *p, float x);
+template <> __device__ __forceinline__ void store_elem<float>(float *p, float x) { *p = x; }
+template <> __device__ __forceinline__ void store_elem<uint16_t>(uint16_t *p, float x) { *p = f32_to_bf16_bits(x); }
+
+__device__ __forceinline__ float wave_max(float x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+    return x;
+}
+
+__device__ __forceinline__ float wave_sum(float x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+    return x;
+}
+
+// exp2 with exp2(-inf) = 0 and no NaN for (-inf) - (-inf) handled by the callers
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Workspace layout helpers shared by host and device code -------------------------------
+
+// logits are parked with a row pitch that is a multiple of 64 tokens
+__host__ __device__ inline int64_t logit_pitch(int max_seq_len) { return ((int64_t)max_seq_len + 63) / 64 * 64; }
+
+}  // namespace fastocr

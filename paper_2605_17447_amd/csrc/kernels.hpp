@@ -1,0 +1,53 @@
+// Host-side launch interface between the C-ABI layer (api.hip) and the kernel files.
+#pragma once
+#include "common.hpp"
+
+namespace fastocr {
+
+// Kernel ids mirror fastocr_kernel in fastocr.h (used by the per-kernel timers).
+enum KernelId {
+    K_SCORE_LOGITS = 0, K_SCORE_FINALIZE = 1, K_TOPK = 2, K_SPARSE_ATTN = 3, K_DENSE_ATTN = 4,
+    K_ATTN_COMBINE = 5, K_COUNT = 6
+};
+
+// Event hooks implemented in api.hip: no-ops unless a timer is enabled for the kernel.
+void timer_begin(int kernel, hipStream_t s);
+void timer_end(int kernel, hipStream_t s);
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+
+struct Shape {
+    KvDev kv;
+    BatchDev bv;
+    int batch;
+    int n_q_heads;
+    int dtype;
+    bool paged;
+    bool fast;      // the MFMA kernels cover this shape: bf16, head_dim 128, group size <= 16,
+                    // 16-byte aligned rows (decided once from the views by the C-ABI layer)
+};
+
+inline bool mfma_path(const Shape &s) { return s.fast; }
+
+// ---- attention (attn.hip) ---------------------------------------------------------------
+// Workspace: part_o fp32 [B][Hq][nsplit][d] followed by part_ml fp32 [B][Hq][nsplit][2].
+int attn_tile_tokens(const Shape &s);
+size_t attn_workspace_bytes(const Shape &s, int nsplit);
+hipError_t launch_attn(const Shape &s, const void *q, float scale, const int32_t *sel_idx,
+                       const int32_t *sel_cnt, int64_t kmax, void *out, float *lse, void *ws,
+                       int nsplit, hipStream_t stream);
+
+// ---- focal scoring (score.hip) ----------------------------------------------------------
+// Workspace: logits fp32 [B][Hq][pitch], part_ml fp32 [B][Hq][nsplit][2], mass partials.
+int score_tile_tokens(const Shape &s);
+size_t score_workspace_bytes(const Shape &s, int nsplit);
+hipError_t launch_score(const Shape &s, const void *q, float scale, float *scores, float *lse,
+                        float *img_mass, void *ws, int nsplit, hipStream_t stream);
+
+// ---- top-k (topk.hip) -------------------------------------------------------------------
+size_t topk_workspace_bytes(int batch, int max_vis_len);
+hipError_t launch_topk(const float *scores, const BatchDev &bv, int batch, double tau,
+                       const int32_t *prev_idx, const int32_t *prev_cnt, int32_t *sel_idx,
+                       int32_t *sel_cnt, int64_t kmax, void *ws, hipStream_t stream);
+
+}  // namespace fastocr

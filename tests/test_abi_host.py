@@ -1,0 +1,150 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, sizes workspaces, computes ceil(tau N) like the oracle, and rejects bad
+arguments before any HIP call."""
+import ctypes
+import os
+import re
+from fractions import Fraction
+import math
+
+import pytest
+
+import oracle
+from paper_2605_17447_amd import binding as fb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x1000          # non-null, 256-byte aligned "device pointer"; never dereferenced on these paths
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return fb.load_library()
+
+
+def _kv(dtype=fb.BF16, Hkv=4, d=128, S=4160, paged=False, **kw):
+    v = fb.KvView(FAKE, FAKE, dtype, Hkv, d, d, S * d, Hkv * S * d, 0, 0, None, 0)
+    if paged:
+        v.page_tokens, v.stride_page, v.block_table, v.max_pages_per_seq = 64, Hkv * 64 * d, FAKE, 65
+        v.stride_head = 64 * d
+    for k, val in kw.items():
+        setattr(v, k, val)
+    return v
+
+
+def _bv(B=2, S=4160, N=4096, **kw):
+    v = fb.BatchView(B, FAKE, FAKE, FAKE, S, N)
+    for k, val in kw.items():
+        setattr(v, k, val)
+    return v
+
+
+def test_header_symbols_are_all_exported(lib):
+    text = open(os.path.join(ROOT, "include", "fastocr.h")).read()
+    declared = sorted(set(re.findall(r"\b(fastocr_[a-z_]+)\s*\(", text)))
+    assert set(declared) == set(fb.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_version_and_strerror(lib):
+    assert "gfx950" in fb.version()
+    assert fb.strerror(0) == "ok" and "workspace" in fb.strerror(fb.EWORKSPACE)
+    assert fb.strerror(-99) == "unknown status"
+
+
+def test_keep_count_agrees_with_oracle_and_exact_arithmetic():
+    for tau in ("0.004", "0.02", "0.05", "0.07", "0.10", "0.25", "0.55", "1.0"):
+        for n in list(range(0, 600)) + [4096, 9216, 16383, 16384, 20000]:
+            k = fb.keep_count(n, float(tau))
+            assert k == oracle.keep_count(n, float(tau)) == math.ceil(Fraction(tau) * n)
+    assert fb.keep_count(256, 0.05) == 13 and fb.keep_count(16384, 0.05) == 820
+    assert fb.keep_count(100, 0.0) == 0 and fb.keep_count(100, -1.0) == 0
+
+
+def test_workspace_sizes_cover_the_documented_buffers(lib):
+    kv, bv = _kv(), _bv()
+    Hq = 28
+    w_score = lib.fastocr_workspace_bytes(fb.OP_FOCAL_SCORE, ctypes.byref(kv), ctypes.byref(bv), Hq, 0)
+    # at least the parked fp32 logits [B, Hq, S]
+    assert w_score >= 2 * Hq * 4160 * 4 and w_score % 256 == 0
+    w_dense = lib.fastocr_workspace_bytes(fb.OP_DENSE_DECODE_ATTN, ctypes.byref(kv), ctypes.byref(bv), Hq, 0)
+    w_sparse = lib.fastocr_workspace_bytes(fb.OP_SPARSE_DECODE_ATTN, ctypes.byref(kv), ctypes.byref(bv), Hq, 205)
+    assert w_dense >= 2 * Hq * (128 + 2) * 4 and w_sparse >= 2 * Hq * (128 + 2) * 4
+    assert lib.fastocr_workspace_bytes(fb.OP_TOPK_FIXATION, None, ctypes.byref(bv), 0, 205) == 0
+    big = _bv(S=70000, N=65536)
+    assert lib.fastocr_workspace_bytes(fb.OP_TOPK_FIXATION, None, ctypes.byref(big), 0, 1) >= 2 * 65536 * 4
+    # invalid shapes give 0
+    assert lib.fastocr_workspace_bytes(fb.OP_FOCAL_SCORE, ctypes.byref(kv), ctypes.byref(bv), 30, 0) == 0
+    assert lib.fastocr_workspace_bytes(99, ctypes.byref(kv), ctypes.byref(bv), Hq, 0) == 0
+
+
+def _score(lib, kv, bv, Hq=28, q=FAKE, scale=0.088, scores=FAKE, ws=FAKE, ws_bytes=1 << 40):
+    return lib.fastocr_focal_score(ctypes.byref(kv) if kv else None, ctypes.byref(bv) if bv else None, q, Hq,
+                                   scale, scores, None, None, ws, ws_bytes, None)
+
+
+def _dense(lib, kv, bv, Hq=28, q=FAKE, out=FAKE, ws=FAKE, ws_bytes=1 << 40, scale=0.088):
+    return lib.fastocr_dense_decode_attn(ctypes.byref(kv), ctypes.byref(bv), q, Hq, scale, out, None, ws,
+                                         ws_bytes, None)
+
+
+def test_argument_validation_happens_before_any_gpu_work(lib):
+    kv, bv = _kv(), _bv()
+    assert _score(lib, None, bv) == fb.EINVAL
+    assert _score(lib, kv, None) == fb.EINVAL
+    assert _score(lib, kv, bv, q=None) == fb.EINVAL
+    assert _score(lib, kv, bv, q=FAKE + 2) == fb.EINVAL                      # q not 16-byte aligned
+    assert _score(lib, kv, bv, scale=float("nan")) == fb.EINVAL
+    assert _score(lib, kv, bv, Hq=30) == fb.EINVAL                           # Hq % Hkv != 0
+    assert _score(lib, kv, bv, scores=None) == fb.EINVAL
+    assert _score(lib, _kv(dtype=7), bv) == fb.EUNSUPPORTED
+    assert _score(lib, _kv(d=512, stride_token=512), bv) == fb.EUNSUPPORTED
+    assert _score(lib, _kv(k=None), bv) == fb.EINVAL
+    assert _score(lib, kv, _bv(max_vis_len=5000)) == fb.EINVAL               # span longer than the sequence
+    assert _score(lib, kv, _bv(seq_len=None)) == fb.EINVAL
+    assert _score(lib, kv, _bv(B=-1)) == fb.EINVAL
+    assert _score(lib, _kv(stride_token=64), bv) == fb.EINVAL                # rows overlap
+    # paged view whose block table is too short for max_seq_len, or missing
+    assert _score(lib, _kv(paged=True, max_pages_per_seq=10), bv) == fb.EINVAL
+    assert _score(lib, _kv(paged=True, block_table=None), bv) == fb.EINVAL
+    # workspace
+    assert _score(lib, kv, bv, ws=None) == fb.EWORKSPACE
+    assert _score(lib, kv, bv, ws=FAKE + 16) == fb.EWORKSPACE
+    assert _score(lib, kv, bv, ws_bytes=1024) == fb.EWORKSPACE
+    assert _dense(lib, kv, bv, out=None) == fb.EINVAL
+    assert _dense(lib, kv, bv, ws_bytes=16) == fb.EWORKSPACE
+    # an empty batch is a valid no-op and launches nothing
+    assert _score(lib, kv, _bv(B=0)) == fb.OK
+    assert _dense(lib, kv, _bv(B=0)) == fb.OK
+
+
+def test_topk_and_sparse_validation(lib):
+    bv = _bv()
+    call = lambda tau=0.05, prev_idx=None, prev_cnt=None, sel=FAKE, cnt=FAKE, kmax=205, b=bv: \
+        lib.fastocr_topk_fixation(FAKE, ctypes.byref(b), tau, prev_idx, prev_cnt, sel, cnt, kmax, None, 0, None)
+    assert call(tau=1.5) == fb.EINVAL and call(tau=-0.1) == fb.EINVAL and call(tau=float("nan")) == fb.EINVAL
+    assert call(kmax=204) == fb.EINVAL                                        # row pitch below ceil(tau N)
+    assert call(prev_idx=FAKE) == fb.EINVAL                                   # prev_idx without prev_cnt
+    assert call(sel=None) == fb.EINVAL and call(cnt=None) == fb.EINVAL
+    assert call(b=_bv(B=0)) == fb.OK
+    big = _bv(S=70000, N=65536)
+    assert call(b=big, kmax=4000) == fb.EWORKSPACE                            # needs a key buffer past the LDS cap
+    kv = _kv()
+    sp = lambda sel=FAKE, cnt=FAKE, kmax=205, ws_bytes=1 << 40: lib.fastocr_sparse_decode_attn(
+        ctypes.byref(kv), ctypes.byref(bv), FAKE, 28, 0.088, sel, cnt, kmax, FAKE, FAKE, ws_bytes, None)
+    assert sp(sel=None) == fb.EINVAL and sp(cnt=None) == fb.EINVAL and sp(kmax=0) == fb.EINVAL
+    assert sp(ws_bytes=64) == fb.EWORKSPACE
+
+
+def test_tuning_keys(lib):
+    assert lib.fastocr_set_tuning(b"splits_dense", 3) == fb.OK
+    kv, bv = _kv(), _bv()
+    w3 = lib.fastocr_workspace_bytes(fb.OP_DENSE_DECODE_ATTN, ctypes.byref(kv), ctypes.byref(bv), 28, 0)
+    assert lib.fastocr_set_tuning(b"splits_dense", 6) == fb.OK
+    w6 = lib.fastocr_workspace_bytes(fb.OP_DENSE_DECODE_ATTN, ctypes.byref(kv), ctypes.byref(bv), 28, 0)
+    assert w6 > w3
+    assert lib.fastocr_set_tuning(b"splits_dense", 0) == fb.OK
+    assert lib.fastocr_set_tuning(b"no_such_key", 1) == fb.EINVAL
+    assert lib.fastocr_set_tuning(None, 1) == fb.EINVAL
+    assert lib.fastocr_kernel_timer_enable(99, 4) == fb.EINVAL
+    assert lib.fastocr_kernel_timer_read(0, None, 0) == 0

@@ -1,0 +1,196 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element, on
+the same seeded inputs.  Sizes span several tiles and ragged tails; the oracle finishes each in
+seconds."""
+import numpy as np
+import pytest
+import torch
+
+import fastocr_synth as fs
+import oracle
+import paper_2605_17447_amd as fo
+from paper_2605_17447_amd import binding as fb
+from util import TinyCase
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from gpu_util import (DEV, GpuProblem, check_out, check_scores, check_set_valid, from_np,
+                          problem_from_case, to_np)
+
+
+def full_check(p: "GpuProblem", tau: float, what: str, exact_topk=True):
+    """All four calls of one problem against the oracle."""
+    oc = p.oracle_args()
+    ref_sc, ref_lse, ref_mass = oracle.focal_score(*oc)
+    sc, lse, mass = p.scores(want_lse=True, want_mass=True)
+    check_scores(sc, ref_sc, p.vis_len, what + " scores")
+    nz = [b for b in range(p.B) if p.seq_len[b] > 0]
+    assert np.allclose(lse.cpu().numpy()[nz], ref_lse[nz], rtol=2e-5, atol=2e-5), what + " lse"
+    assert np.allclose(mass.cpu().numpy(), ref_mass, atol=2e-5), what + " image mass"
+
+    ref_idx, ref_cnt = oracle.topk_fixation(ref_sc, p.vis_len, tau)
+    idx, cnt = p.topk(sc, tau)
+    idx_h, cnt_h = idx.cpu().numpy(), cnt.cpu().numpy()
+    for b in range(p.B):
+        check_set_valid(idx_h[b], int(cnt_h[b]), ref_sc[b, : p.vis_len[b]], int(ref_cnt[b]), f"{what} set b={b}")
+    if exact_topk:
+        # same fp32 scores on both sides -> the sets must agree bit for bit
+        sc_h = sc.cpu().numpy()
+        for b in range(p.B):
+            want = oracle.topk(sc_h[b, : p.vis_len[b]], int(ref_cnt[b]))
+            assert np.array_equal(idx_h[b, : cnt_h[b]], want), f"{what}: top-k differs on identical scores, b={b}"
+
+    # attention over the oracle's set (so both sides attend the same tokens)
+    kmax = max(1, ref_idx.shape[1])
+    sel = torch.from_numpy(ref_idx).to(DEV).contiguous()
+    selc = torch.from_numpy(ref_cnt).to(DEV)
+    ref_sparse, _ = oracle.decode_attn(*oc, ref_idx, ref_cnt)
+    check_out(p.sparse(sel, selc), ref_sparse, what + " sparse")
+    ref_dense, ref_dlse = oracle.decode_attn(*oc)
+    out, dl = p.dense(want_lse=True)
+    check_out(out, ref_dense, what + " dense")
+    assert np.allclose(dl.cpu().numpy()[nz], ref_dlse[nz], rtol=2e-5, atol=2e-5), what + " dense lse"
+
+
+# ------------------------------------------------------------------ config 1 (fp32, tiny)
+
+@pytest.mark.parametrize("seed", range(6))
+def test_config1_fp32_all_calls(seed):
+    wl = fs.config(1)
+    bt = fs.make_batch(wl, seed=fs.BASE_SEED + 31 * seed, device=DEV)
+    c = fs.centres(bt)
+    q = fs.queries_for_step(bt, 1, [x[0] for x in c])
+    p = GpuProblem(bt.k, bt.v, q, bt.seq_len(1), bt.vis_start, bt.n_vis, wl.head_dim ** -0.5)
+    full_check(p, 0.05, f"config1 seed {seed}")
+    sc, _, _ = p.scores()
+    idx, cnt = p.topk(sc, 0.05)
+    assert int(cnt[0]) == 13
+
+
+@pytest.mark.parametrize("Hq,Hkv,d", [(4, 1, 64), (6, 3, 32), (8, 8, 16), (7, 1, 40), (12, 4, 256), (2, 2, 8)])
+def test_generic_fp32_shapes(Hq, Hkv, d):
+    case = TinyCase(seed=Hq * 7 + d, B=3, Hq=Hq, Hkv=Hkv, d=d, n_vis=[130, 64, 257], pre=[5, 0, 70],
+                    post=[9, 3, 0], dtype="f32")
+    full_check(problem_from_case(case), 0.1, f"fp32 Hq{Hq} Hkv{Hkv} d{d}")
+
+
+@pytest.mark.parametrize("Hq,Hkv,d", [(4, 2, 64), (8, 2, 96)])
+def test_generic_bf16_shapes(Hq, Hkv, d):
+    case = TinyCase(seed=Hq + d, B=2, Hq=Hq, Hkv=Hkv, d=d, n_vis=[200, 90], pre=[4, 1], post=[3, 60], dtype="bf16")
+    full_check(problem_from_case(case), 0.1, f"bf16 generic Hq{Hq} Hkv{Hkv} d{d}")
+
+
+# ------------------------------------------------------------------ bf16 MFMA path
+
+@pytest.mark.parametrize("Hq,Hkv", [(28, 4), (64, 8), (16, 1), (4, 4), (6, 2)])
+def test_mfma_bf16_ragged_batch(Hq, Hkv):
+    case = TinyCase(seed=100 + Hq, B=3, Hq=Hq, Hkv=Hkv, d=128, n_vis=[1000, 777, 1500], pre=[32, 5, 0],
+                    post=[41, 130, 7], dtype="bf16")
+    full_check(problem_from_case(case), 0.05, f"mfma Hq{Hq} Hkv{Hkv}")
+
+
+@pytest.mark.parametrize("k_via_lds", [1, 0])
+def test_mfma_both_key_load_paths(k_via_lds):
+    fb.set_tuning("k_via_lds", k_via_lds)
+    try:
+        case = TinyCase(seed=5, B=2, Hq=28, Hkv=4, d=128, n_vis=[900, 333], pre=[17, 3], post=[11, 64], dtype="bf16")
+        full_check(problem_from_case(case), 0.1, f"k_via_lds={k_via_lds}")
+    finally:
+        fb.set_tuning("k_via_lds", 1)
+
+
+@pytest.mark.parametrize("nsplit", [1, 2, 5, 64])
+def test_split_counts_give_the_same_result(nsplit):
+    for key in ("splits_score", "splits_dense", "splits_sparse"):
+        fb.set_tuning(key, nsplit)
+    try:
+        case = TinyCase(seed=6, B=2, Hq=28, Hkv=4, d=128, n_vis=[1200, 500], pre=[20, 3], post=[30, 9], dtype="bf16")
+        full_check(problem_from_case(case), 0.05, f"nsplit={nsplit}")
+        case = TinyCase(seed=7, B=2, Hq=4, Hkv=1, d=64, n_vis=[300, 200], pre=[2, 3], post=[3, 9], dtype="f32")
+        full_check(problem_from_case(case), 0.05, f"fp32 nsplit={nsplit}")
+    finally:
+        for key in ("splits_score", "splits_dense", "splits_sparse"):
+            fb.set_tuning(key, 0)
+
+
+def test_token_major_layout():
+    case = TinyCase(seed=8, B=2, Hq=28, Hkv=4, d=128, n_vis=[700, 640], pre=[8, 3], post=[5, 70], dtype="bf16")
+    full_check(problem_from_case(case, layout="bshd"), 0.05, "bshd bf16")
+    case = TinyCase(seed=9, B=2, Hq=4, Hkv=2, d=64, n_vis=[150, 99], pre=[8, 3], post=[5, 7], dtype="f32")
+    full_check(problem_from_case(case, layout="bshd"), 0.05, "bshd fp32")
+
+
+def test_paged_ragged_layout_config5_shape():
+    wl = fs.config(5, batch=5, steps=8, n_visual=(300, 1500), grid_w=(16, 40), text_prefix=(3, 200), page_tokens=64)
+    bt = fs.make_batch(wl, device=DEV)
+    c = fs.centres(bt)
+    for t in (1, 8):
+        q = fs.queries_for_step(bt, t, [x[t - 1] for x in c])
+        p = GpuProblem(bt.k, bt.v, q, bt.seq_len(t), bt.vis_start, bt.n_vis, wl.head_dim ** -0.5,
+                       block_table=bt.block_table)
+        full_check(p, 0.05, f"paged step {t}")
+    # fp32 pages through the generic kernels
+    wl32 = fs.config(5, batch=3, steps=2, n_visual=(100, 400), grid_w=(8, 20), text_prefix=(3, 50), page_tokens=16,
+                     dtype="f32", head_dim=64, n_q_heads=4, n_kv_heads=2)
+    bt = fs.make_batch(wl32, device=DEV)
+    q = fs.queries_for_step(bt, 1, [x[0] for x in fs.centres(bt)])
+    p = GpuProblem(bt.k, bt.v, q, bt.seq_len(1), bt.vis_start, bt.n_vis, 0.125, block_table=bt.block_table)
+    full_check(p, 0.1, "paged fp32")
+
+
+# ------------------------------------------------------------------ invariants on the GPU path
+
+def test_tau_one_equals_dense_and_tau_zero_is_text_only():
+    case = TinyCase(seed=10, B=2, Hq=28, Hkv=4, d=128, n_vis=[500, 260], pre=[9, 3], post=[6, 40], dtype="bf16")
+    p = problem_from_case(case)
+    sc, _, _ = p.scores()
+    idx, cnt = p.topk(sc, 1.0)
+    assert cnt.tolist() == [500, 260] and idx[1, :260].tolist() == list(range(260))
+    dense, _ = p.dense()
+    sparse = p.sparse(idx, cnt)
+    assert torch.allclose(dense.float(), sparse.float(), rtol=2e-2, atol=1e-3)
+    oc = p.oracle_args()
+    check_out(sparse, oracle.decode_attn(*oc)[0], "tau=1 vs oracle dense")
+    idx0, cnt0 = p.topk(sc, 0.0)
+    assert cnt0.tolist() == [0, 0]
+    ref0, _ = oracle.decode_attn(*oc, np.zeros((2, 1), np.int32), np.zeros(2, np.int32))
+    check_out(p.sparse(idx0, cnt0), ref0, "tau=0")
+
+
+def test_cache_is_never_modified():
+    case = TinyCase(seed=11, B=2, Hq=28, Hkv=4, d=128, n_vis=[400, 300], pre=[9, 3], post=[6, 40], dtype="bf16")
+    p = problem_from_case(case)
+    k0, v0, q0 = p.k.clone(), p.v.clone(), p.q.clone()
+    sc, _, _ = p.scores()
+    idx, cnt = p.topk(sc, 0.05)
+    p.sparse(idx, cnt)
+    p.dense()
+    torch.cuda.synchronize()
+    assert torch.equal(p.k, k0) and torch.equal(p.v, v0) and torch.equal(p.q, q0)
+
+
+def test_repeat_runs_are_bit_identical():
+    case = TinyCase(seed=12, B=2, Hq=64, Hkv=8, d=128, n_vis=[2000, 1300], pre=[9, 3], post=[6, 40], dtype="bf16")
+    p = problem_from_case(case)
+    first = None
+    for _ in range(5):
+        sc, _, _ = p.scores()
+        idx, cnt = p.topk(sc, 0.05)
+        out = p.sparse(idx, cnt)
+        cur = (sc.clone(), idx.clone(), cnt.clone(), out.clone())
+        if first is None:
+            first = cur
+        else:
+            assert all(torch.equal(a, b) for a, b in zip(first, cur))
+
+
+def test_degenerate_sequences():
+    # no image tokens, image span at the very start / very end, one-token sequence, empty sequence
+    case = TinyCase(seed=13, B=5, Hq=28, Hkv=4, d=128, n_vis=[0, 40, 33, 0, 0], pre=[50, 0, 9, 1, 0],
+                    post=[0, 10, 0, 0, 0], dtype="bf16")
+    p = problem_from_case(case)
+    full_check(p, 0.25, "degenerate bf16")
+    case = TinyCase(seed=14, B=4, Hq=4, Hkv=1, d=64, n_vis=[0, 3, 1, 0], pre=[2, 0, 0, 0], post=[0, 0, 0, 0], dtype="f32")
+    full_check(problem_from_case(case), 0.5, "degenerate fp32")
+    out, _ = p.dense()
+    assert torch.all(out[4] == 0)                      # an empty sequence attends nothing
