@@ -185,6 +185,15 @@ typedef enum {
 int fastocr_kernel_timer_enable(int kernel, int capacity);
 int fastocr_kernel_timer_read(int kernel, float *ms_out, int max_out);
 
+/*
+ * Measurement helper, not part of the method: a plain streaming kernel of known size.
+ * dst != NULL copies `bytes` (rounded down to 16) from src to dst; dst == NULL only reads
+ * src (`sink`, 4 device bytes, is then required and practically never written).  Used for the
+ * measured HBM ceiling and to calibrate the profiler's fetch/write byte counters.
+ * src, dst 16-byte aligned device pointers.
+ */
+int fastocr_stream_probe(const void *src, void *dst, size_t bytes, void *sink, void *hip_stream);
+
 /* Launch-shape overrides for measurement sweeps: key "splits_score" | "splits_dense" |
  * "splits_sparse" (0 = automatic).  Returns FASTOCR_EINVAL for an unknown key. */
 int fastocr_set_tuning(const char *key, int value);

@@ -10,6 +10,7 @@
 namespace fastocr {
 
 int g_tune_k_via_lds = 1;
+int g_tune_dbg = 0;
 static int g_tune_splits[4] = {0, 0, 0, 0};     // indexed by fastocr_op
 
 // ---- per-kernel timers ------------------------------------------------------------------
@@ -283,6 +284,15 @@ int fastocr_kernel_timer_read(int kernel, float *ms_out, int max_out)
     return n;
 }
 
+int fastocr_stream_probe(const void *src, void *dst, size_t bytes, void *sink, void *hip_stream)
+{
+    if (!src || bytes < 16 || (reinterpret_cast<uintptr_t>(src) & 15u) || (reinterpret_cast<uintptr_t>(dst) & 15u))
+        return FASTOCR_EINVAL;
+    if (!dst && !sink) return FASTOCR_EINVAL;
+    hipError_t e = launch_stream_probe(src, dst, bytes, sink, (hipStream_t)hip_stream);
+    return e == hipSuccess ? FASTOCR_OK : FASTOCR_EHIP;
+}
+
 int fastocr_set_tuning(const char *key, int value)
 {
     if (!key || value < 0) return FASTOCR_EINVAL;
@@ -290,6 +300,7 @@ int fastocr_set_tuning(const char *key, int value)
     else if (!strcmp(key, "splits_sparse")) g_tune_splits[FASTOCR_OP_SPARSE_DECODE_ATTN] = value;
     else if (!strcmp(key, "splits_dense")) g_tune_splits[FASTOCR_OP_DENSE_DECODE_ATTN] = value;
     else if (!strcmp(key, "k_via_lds")) g_tune_k_via_lds = value ? 1 : 0;
+    else if (!strcmp(key, "dbg")) g_tune_dbg = value;
     else return FASTOCR_EINVAL;
     return FASTOCR_OK;
 }

@@ -186,29 +186,27 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
     };
 
     if (t0 + wave < t1) {
+        // Two register buffers, software pipelined.  The prefetch is unconditional (past the end
+        // the last tile is loaded again): a branch between a load and the wait that matches it
+        // would make the compiler drain every outstanding load at the join.
         u32x4 KA[8], VA[8], KB[8], VB[8];
         int tile = t0 + wave;
+        const int last = tile + (t1 - 1 - tile) / kWaves * kWaves;
         int64_t off_a = 0, off_b = 0;
         if (GATHER || PAGED) off_a = rowoff_of(tile);
         load_tile(tile, off_a, KA, VA);
-        if (GATHER || PAGED) off_b = rowoff_of(tile + kWaves);
+        if (GATHER || PAGED) off_b = rowoff_of(min(tile + kWaves, last));
         while (true) {
-            int nxt = tile + kWaves;
-            if (nxt < t1) {
-                load_tile(nxt, off_b, KB, VB);
-                if (GATHER || PAGED) off_a = rowoff_of(nxt + kWaves);
-            }
+            load_tile(min(tile + kWaves, last), off_b, KB, VB);
+            if (GATHER || PAGED) off_a = rowoff_of(min(tile + 2 * kWaves, last));
             compute(tile, KA, VA);
-            if (nxt >= t1) break;
-            tile = nxt;
-            nxt = tile + kWaves;
-            if (nxt < t1) {
-                load_tile(nxt, off_a, KA, VA);
-                if (GATHER || PAGED) off_b = rowoff_of(nxt + kWaves);
-            }
+            tile += kWaves;
+            if (tile > last) break;
+            load_tile(min(tile + kWaves, last), off_a, KA, VA);
+            if (GATHER || PAGED) off_b = rowoff_of(min(tile + 2 * kWaves, last));
             compute(tile, KB, VB);
-            if (nxt >= t1) break;
-            tile = nxt;
+            tile += kWaves;
+            if (tile > last) break;
         }
     }
 

@@ -58,13 +58,15 @@ template <bool GATHER>
 __device__ __forceinline__ int pos_to_token(int p, const SeqGeom &g, int cnt, const int32_t *sel)
 {
     if (!GATHER) return p;
-    if (p < g.v0) return p;
-    if (p < g.v0 + cnt) {
-        int i = sel[p - g.v0];
-        i = min(max(i, 0), g.N - 1);
-        return g.v0 + i;
-    }
-    return p - cnt + g.N;
+    // The index is loaded unconditionally (slot clamped into the row, which always holds at
+    // least one entry) and the case is chosen arithmetically: a load inside a branch would make
+    // the compiler drain every outstanding prefetch at the join.
+    const int slot = min(max(p - g.v0, 0), max(cnt - 1, 0));
+    int i = sel[slot];
+    i = min(max(i, 0), max(g.N - 1, 0));
+    const int mid = g.v0 + i;
+    const int tail = p - cnt + g.N;
+    return (p < g.v0) ? p : ((p < g.v0 + cnt) ? mid : tail);
 }
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b)

@@ -50,4 +50,7 @@ hipError_t launch_topk(const float *scores, const BatchDev &bv, int batch, doubl
                        const int32_t *prev_idx, const int32_t *prev_cnt, int32_t *sel_idx,
                        int32_t *sel_cnt, int64_t kmax, void *ws, hipStream_t stream);
 
+// ---- streaming probe (probe.hip) ----------------------------------------------------------
+hipError_t launch_stream_probe(const void *src, void *dst, size_t bytes, void *sink, hipStream_t stream);
+
 }  // namespace fastocr

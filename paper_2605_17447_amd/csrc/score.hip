@@ -15,6 +15,7 @@
 namespace fastocr {
 
 extern int g_tune_k_via_lds;
+extern int g_tune_dbg;
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -34,7 +35,7 @@ __device__ __forceinline__ int tile_row(int lg, int e) { return (e < 4) ? (4 * l
 template <bool PAGED, bool KLDS>
 __global__ __launch_bounds__(256, 3) void score_mfma_kernel(
     KvDev kv, BatchDev bv, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2,
-    float *__restrict__ logits, int64_t pitch, float *__restrict__ part_ml, int nsplit)
+    float *__restrict__ logits, int64_t pitch, float *__restrict__ part_ml, int nsplit, int dbg)
 {
     __shared__ __align__(16) unsigned char smem[kWaves][8192];
     __shared__ float sm_m[kWaves][16], sm_z[kWaves][16];
@@ -91,7 +92,7 @@ __global__ __launch_bounds__(256, 3) void score_mfma_kernel(
     };
 
     float m = -INFINITY, zl = 0.f;
-    float *lrow = logits + ((int64_t)b * Hq + (int64_t)kvh * G + li) * pitch;
+    float *ltile = logits + ((int64_t)b * kv.n_kv_heads + kvh) * pitch * G;    // [token][G]
 
     auto compute = [&](int tile, u32x4(&K)[8]) {
         u32x4 ka[8];
@@ -130,9 +131,25 @@ __global__ __launch_bounds__(256, 3) void score_mfma_kernel(
             a[r] = (pbase + r < L) ? s0[r] * scale_log2 : -INFINITY;
             c2[r] = (pbase + 16 + r < L) ? s1[r] * scale_log2 : -INFINITY;
         }
-        if (li < G) {
-            *reinterpret_cast<f32x4 *>(lrow + pbase) = a;
-            *reinterpret_cast<f32x4 *>(lrow + pbase + 16) = c2;
+        if (!(dbg & 1)) {
+            // Park the tile's logits token-major ([token][G heads]): staged through LDS so that the
+            // wave writes one contiguous run of 32*G floats with 16-byte stores.
+            float *st = reinterpret_cast<float *>(smem[wave]);
+            if (li < G) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    st[(4 * lg + r) * G + li] = a[r];
+                    st[(16 + 4 * lg + r) * G + li] = c2[r];
+                }
+            }
+            wave_lds_fence();
+            float *dst = ltile + (int64_t)((dbg & 8) ? (tile & 3) : tile) * kTile * G;
+#pragma unroll
+            for (int x = 0; x < 2; ++x) {
+                const int o = 4 * (lane + 64 * x);
+                if (o < kTile * G && (!(dbg & 16) || (tile & 4))) *reinterpret_cast<f32x4 *>(dst + o) = *reinterpret_cast<const f32x4 *>(st + o);
+            }
+            wave_lds_fence();
         }
         float mx = fmaxf(fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3])), fmaxf(fmaxf(c2[0], c2[1]), fmaxf(c2[2], c2[3])));
         mx = fmaxf(mx, __shfl_xor(mx, 16));
@@ -146,29 +163,28 @@ __global__ __launch_bounds__(256, 3) void score_mfma_kernel(
     };
 
     if (t0 + wave < t1) {
+        // Two register buffers, software pipelined: the loads of the next tile are issued before the
+        // current one is consumed.  They are issued unconditionally (past the end the last tile is
+        // loaded again) so that no branch separates a load from the wait that matches it -- a
+        // conditional prefetch makes the compiler drain every outstanding load at the join.
         u32x4 KA[8], KB[8];
         int tile = t0 + wave;
+        const int last = tile + (t1 - 1 - tile) / kWaves * kWaves;
         int64_t off_a = 0, off_b = 0;
         if (PAGED) off_a = rowoff_of(tile);
         load_tile(tile, off_a, KA);
-        if (PAGED) off_b = rowoff_of(tile + kWaves);
+        if (PAGED) off_b = rowoff_of(min(tile + kWaves, last));
         while (true) {
-            int nxt = tile + kWaves;
-            if (nxt < t1) {
-                load_tile(nxt, off_b, KB);
-                if (PAGED) off_a = rowoff_of(nxt + kWaves);
-            }
+            load_tile(min(tile + kWaves, last), off_b, KB);
+            if (PAGED) off_a = rowoff_of(min(tile + 2 * kWaves, last));
             compute(tile, KA);
-            if (nxt >= t1) break;
-            tile = nxt;
-            nxt = tile + kWaves;
-            if (nxt < t1) {
-                load_tile(nxt, off_a, KA);
-                if (PAGED) off_b = rowoff_of(nxt + kWaves);
-            }
+            tile += kWaves;
+            if (tile > last) break;
+            load_tile(min(tile + kWaves, last), off_a, KA);
+            if (PAGED) off_b = rowoff_of(min(tile + 2 * kWaves, last));
             compute(tile, KB);
-            if (nxt >= t1) break;
-            tile = nxt;
+            tile += kWaves;
+            if (tile > last) break;
         }
     }
 
@@ -212,7 +228,8 @@ __global__ __launch_bounds__(64) void score_generic_kernel(
     for (int c = lane; c < d; c += 64) qs[c] = load_elem<T>(q + ((int64_t)b * Hq + h) * d + c);
     __syncthreads();
     const T *kbase = reinterpret_cast<const T *>(kv.k);
-    float *lrow = logits + ((int64_t)b * Hq + h) * pitch;
+    const int G = Hq / kv.n_kv_heads;
+    float *lrow = logits + ((int64_t)b * kv.n_kv_heads + g) * pitch * G + (h - g * G);   // [token][G]
     float m = -INFINITY, z = 0.f;
     for (int tile = t0; tile < t1; ++tile) {
         const int p = tile * 64 + lane;
@@ -221,7 +238,7 @@ __global__ __launch_bounds__(64) void score_generic_kernel(
         float s = 0.f;
         for (int c = 0; c < d; ++c) s = fmaf(qs[c], load_elem<T>(kbase + off + c), s);
         s = valid ? s * scale_log2 : -INFINITY;
-        lrow[p] = s;                                     // p < pitch: pitch is a multiple of 64
+        lrow[(int64_t)p * G] = s;                        // p < pitch: pitch is a multiple of 64
         const float m_new = fmaxf(m, wave_max(s));
         z = z * fast_exp2(m - m_new) + wave_sum(fast_exp2(s - m_new));
         m = m_new;
@@ -237,7 +254,7 @@ __global__ __launch_bounds__(64) void score_generic_kernel(
 constexpr int kFinThreads = 256;
 
 __global__ __launch_bounds__(kFinThreads) void score_finalize_kernel(
-    BatchDev bv, int Hq, const float *__restrict__ logits, int64_t pitch,
+    BatchDev bv, int Hq, int n_kv_heads, const float *__restrict__ logits, int64_t pitch,
     const float *__restrict__ part_ml, int nsplit, float *__restrict__ scores,
     float *__restrict__ lse, float *__restrict__ mass_part)
 {
@@ -260,9 +277,14 @@ __global__ __launch_bounds__(kFinThreads) void score_finalize_kernel(
     const int i = blockIdx.x * kFinThreads + threadIdx.x;
     float sc = 0.f;
     if (i < geo.N) {
-        const float *lp = logits + (int64_t)b * Hq * pitch + geo.v0 + i;
+        // logits are parked as [sequence][kv head][token][G]
+        const int G = Hq / n_kv_heads;
+        const float *lp = logits + ((int64_t)b * n_kv_heads * pitch + geo.v0 + i) * G;
         float acc = 0.f;
-        for (int h = 0; h < Hq; ++h) acc += fast_exp2(lp[(int64_t)h * pitch] - lse2[h]);
+        for (int g = 0; g < n_kv_heads; ++g) {
+            const float *lg_ = lp + (int64_t)g * pitch * G;
+            for (int x = 0; x < G; ++x) acc += fast_exp2(lg_[x] - lse2[g * G + x]);
+        }
         sc = acc / (float)Hq;
         scores[(int64_t)b * bv.max_vis_len + i] = sc;
     }
@@ -316,7 +338,7 @@ hipError_t launch_score(const Shape &s, const void *q, float scale, float *score
     if (mfma_path(s)) {
         dim3 grid(nsplit, s.kv.n_kv_heads, s.batch), block(256);
 #define FASTOCR_SCORE(P, KL) score_mfma_kernel<P, KL><<<grid, block, 0, stream>>>( \
-        s.kv, s.bv, (const uint16_t *)q, s.n_q_heads, G, scale_log2, logits, pitch, part_ml, nsplit)
+        s.kv, s.bv, (const uint16_t *)q, s.n_q_heads, G, scale_log2, logits, pitch, part_ml, nsplit, g_tune_dbg)
         if (s.paged) { if (g_tune_k_via_lds) FASTOCR_SCORE(true, true); else FASTOCR_SCORE(true, false); }
         else         { if (g_tune_k_via_lds) FASTOCR_SCORE(false, true); else FASTOCR_SCORE(false, false); }
 #undef FASTOCR_SCORE
@@ -336,7 +358,7 @@ hipError_t launch_score(const Shape &s, const void *q, float scale, float *score
     const int nblk = fin_blocks(s);
     dim3 fgrid(nblk, s.batch), fblock(kFinThreads);
     score_finalize_kernel<<<fgrid, fblock, (size_t)s.n_q_heads * sizeof(float), stream>>>(
-        s.bv, s.n_q_heads, logits, pitch, part_ml, nsplit, scores, lse, img_mass ? mass_part : nullptr);
+        s.bv, s.n_q_heads, s.kv.n_kv_heads, logits, pitch, part_ml, nsplit, scores, lse, img_mass ? mass_part : nullptr);
     if (img_mass) mass_reduce_kernel<<<s.batch, 64, 0, stream>>>(mass_part, nblk, img_mass);
     timer_end(K_SCORE_FINALIZE, stream);
     return hipGetLastError();
