@@ -38,6 +38,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the comparator / breakdown passes")
     ap.add_argument("--cpu-budget-s", type=float, default=20.0)
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
+                    help="launch-shape override passed to fastocr_set_tuning (measurement sweeps)")
     return ap.parse_args()
 
 
@@ -59,6 +61,9 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     fo.load_library()
+    for kv_ in args.tune:
+        key, val = kv_.split("=")
+        fb.set_tuning(key, int(val))
 
     n_steps, n_warm = args.steps, args.warmup
     total = n_steps + n_warm

@@ -10,7 +10,6 @@
 namespace fastocr {
 
 int g_tune_k_via_lds = 1;
-int g_tune_dbg = 0;
 static int g_tune_splits[4] = {0, 0, 0, 0};     // indexed by fastocr_op
 
 // ---- per-kernel timers ------------------------------------------------------------------
@@ -111,7 +110,9 @@ static int choose_splits(int op, const Shape &s, int max_positions)
         nsplit = forced;
     } else {
         const int streams = s.batch * (fast ? s.kv.n_kv_heads : s.n_q_heads);
-        const int target_wg = fast ? (op == FASTOCR_OP_FOCAL_SCORE ? 4 : 2) * kNumCU : 8 * kNumCU;
+        // Measured on MI355X: the streaming kernels run best with about one workgroup per compute
+        // unit (few, long, equally sized streams), the plain-FMA kernels with many small ones.
+        const int target_wg = fast ? kNumCU : 8 * kNumCU;
         nsplit = (target_wg + streams - 1) / (streams > 0 ? streams : 1);
     }
     if (nsplit > by_work) nsplit = by_work;
@@ -300,7 +301,6 @@ int fastocr_set_tuning(const char *key, int value)
     else if (!strcmp(key, "splits_sparse")) g_tune_splits[FASTOCR_OP_SPARSE_DECODE_ATTN] = value;
     else if (!strcmp(key, "splits_dense")) g_tune_splits[FASTOCR_OP_DENSE_DECODE_ATTN] = value;
     else if (!strcmp(key, "k_via_lds")) g_tune_k_via_lds = value ? 1 : 0;
-    else if (!strcmp(key, "dbg")) g_tune_dbg = value;
     else return FASTOCR_EINVAL;
     return FASTOCR_OK;
 }

@@ -37,6 +37,13 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_wave_barrier();
 }
 
+__device__ __forceinline__ u32x4 stream_load(const uint16_t *p)
+{
+    // K and V are read once per call: non-temporal loads stream measurably faster on this chip
+    // and keep the cache lines that are reused (queries, indices, partials) in place.
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+}
+
 // Row of the 32-token tile that lane group `lg` holds as element e of its 8-token k-block:
 // elements 0..3 come from the first 16-token half, 4..7 from the second.
 __device__ __forceinline__ int tile_row(int lg, int e) { return (e < 4) ? (4 * lg + e) : (16 + 4 * lg + (e - 4)); }
@@ -98,8 +105,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
             int64_t ro;
             if (GATHER || PAGED) ro = __shfl(off, r);
             else ro = seq_base + (int64_t)min(tile * kTile + r, L - 1) * kv.stride_token;
-            V[e] = *reinterpret_cast<const u32x4 *>(vbase + ro + 8 * li);
-            if (KLDS) K[e] = *reinterpret_cast<const u32x4 *>(kbase + ro + 8 * li);
+            V[e] = stream_load(vbase + ro + 8 * li);
+            if (KLDS) K[e] = stream_load(kbase + ro + 8 * li);
         }
         if (!KLDS) {
 #pragma unroll
@@ -110,7 +117,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
                 else ro = seq_base + (int64_t)min(tile * kTile + r, L - 1) * kv.stride_token;
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk)
-                    K[4 * T + kk] = *reinterpret_cast<const u32x4 *>(kbase + ro + 8 * (4 * kk + lg));
+                    K[4 * T + kk] = stream_load(kbase + ro + 8 * (4 * kk + lg));
             }
         }
     };

@@ -14,15 +14,12 @@
 
 namespace fastocr {
 
-extern int g_tune_k_via_lds;
-extern int g_tune_dbg;
-
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kTile = 32;
-constexpr int kWaves = 4;
+constexpr int kTile = 32;          // tokens per wave tile
+constexpr float kMinusHuge = -1.0e30f;   // finite stand-in for "no logit yet": keeps 2^(m - m') free of inf - inf
 
 __device__ __forceinline__ void wave_lds_fence()
 {
@@ -30,12 +27,39 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_wave_barrier();
 }
 
-__device__ __forceinline__ int tile_row(int lg, int e) { return (e < 4) ? (4 * lg + e) : (16 + 4 * lg + (e - 4)); }
+__device__ __forceinline__ u32x4 stream_load(const uint16_t *p)
+{
+    // The cache is read once per call: a non-temporal load keeps it from displacing the data
+    // that is reused (queries, parked logits) and streams measurably faster on this chip.
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+}
 
-template <bool PAGED, bool KLDS>
-__global__ __launch_bounds__(256, 3) void score_mfma_kernel(
+// parked logits: fp32 [sequence][kv head][token (pitch)][Gp], Gp = G rounded up to 4 heads
+__host__ __device__ inline int park_heads(int G) { return (G + 3) / 4 * 4; }
+
+__device__ __forceinline__ void softmax_merge(float &m, float &z, float mo, float zo)
+{
+    const float M = fmaxf(m, mo);
+    z = z * fast_exp2(m - M) + zo * fast_exp2(mo - M);
+    m = M;
+}
+
+// One workgroup per (token range, kv head, sequence); its four waves walk interleaved 32-token
+// tiles.  A tile is loaded with 1 KB-contiguous 16-byte loads (4 rows of 256 B per instruction),
+// re-laid through a wave-private XOR-swizzled LDS tile into the MFMA B layout, and multiplied
+//     C[head][token] = Q (16 heads x 32 dims) * K^T (32 dims x 16 tokens)   (v_mfma_f32_16x16x32_bf16)
+// so that a lane ends up with 4 consecutive heads of one token: the parked row [token][Gp] is
+// written with one 16-byte store per lane and no transposition.
+//   GR = 8 : the group's heads fill rows 0..7 for the tile's first 16 tokens and rows 8..15 for
+//            its second 16 tokens (the same accumulator, Q placed in the upper rows for the
+//            second product): all 64 lanes hold live logits, one 1 KB store per tile.
+//   GR = 16: heads fill all 16 rows; two accumulators per tile.
+// Each lane keeps a running (max, sum-exp) for its 4 heads; lanes, waves and ranges are merged
+// at the end.
+template <bool PAGED, int GR, int kWaves, int NBUF>
+__global__ __launch_bounds__(64 * kWaves) void score_mfma_kernel(
     KvDev kv, BatchDev bv, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2,
-    float *__restrict__ logits, int64_t pitch, float *__restrict__ part_ml, int nsplit, int dbg)
+    float *__restrict__ logits, int64_t pitch, float *__restrict__ part_ml, int nsplit)
 {
     __shared__ __align__(16) unsigned char smem[kWaves][8192];
     __shared__ float sm_m[kWaves][16], sm_z[kWaves][16];
@@ -43,6 +67,7 @@ __global__ __launch_bounds__(256, 3) void score_mfma_kernel(
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int li = lane & 15, lg = lane >> 4;
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+    const int Gp = park_heads(G);
 
     const SeqGeom geo = seq_geom(bv, b);
     const int L = geo.S;
@@ -50,13 +75,20 @@ __global__ __launch_bounds__(256, 3) void score_mfma_kernel(
     const int tps = (ntile + nsplit - 1) / nsplit;
     const int t0 = split * tps, t1 = min(ntile, t0 + tps);
 
-    u32x4 qreg[4];
+    // Q as the A operand: lane (row li, k-block lg) holds dims 32*kk + 8*lg .. +7 of step kk.
+    u32x4 qlo[4], qhi[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-        qreg[kk] = u32x4{0u, 0u, 0u, 0u};
-        if (li < G) {
-            const uint16_t *qp = q + ((int64_t)b * Hq + (int64_t)kvh * G + li) * 128 + 8 * (4 * kk + lg);
-            qreg[kk] = *reinterpret_cast<const u32x4 *>(qp);
+        qlo[kk] = u32x4{0u, 0u, 0u, 0u};
+        qhi[kk] = u32x4{0u, 0u, 0u, 0u};
+        const int hl = li, hh = li - 8;
+        if (hl < G && (GR == 16 || hl < 8)) {
+            const uint16_t *qp = q + ((int64_t)b * Hq + (int64_t)kvh * G + hl) * 128 + 8 * (4 * kk + lg);
+            qlo[kk] = *reinterpret_cast<const u32x4 *>(qp);
+        }
+        if (GR == 8 && hh >= 0 && hh < G) {
+            const uint16_t *qp = q + ((int64_t)b * Hq + (int64_t)kvh * G + hh) * 128 + 8 * (4 * kk + lg);
+            qhi[kk] = *reinterpret_cast<const u32x4 *>(qp);
         }
     }
     const uint16_t *kbase = reinterpret_cast<const uint16_t *>(kv.k);
@@ -67,130 +99,136 @@ __global__ __launch_bounds__(256, 3) void score_mfma_kernel(
         return row_offset<PAGED>(kv, b, p, kvh);
     };
 
+    // load e covers rows 4e .. 4e+3 of the tile: lane group lg takes row 4e+lg, lane li its 16-byte chunk
     auto load_tile = [&](int tile, int64_t off, u32x4(&K)[8]) {
-        if (KLDS) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int r = tile_row(lg, e);
-                int64_t ro;
-                if (PAGED) ro = __shfl(off, r);
-                else ro = seq_base + (int64_t)min(tile * kTile + r, L - 1) * kv.stride_token;
-                K[e] = *reinterpret_cast<const u32x4 *>(kbase + ro + 8 * li);
-            }
-        } else {
-#pragma unroll
-            for (int T = 0; T < 2; ++T) {
-                const int r = 16 * T + li;
-                int64_t ro;
-                if (PAGED) ro = __shfl(off, r);
-                else ro = seq_base + (int64_t)min(tile * kTile + r, L - 1) * kv.stride_token;
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk)
-                    K[4 * T + kk] = *reinterpret_cast<const u32x4 *>(kbase + ro + 8 * (4 * kk + lg));
-            }
+        for (int e = 0; e < 8; ++e) {
+            const int r = 4 * e + lg;
+            int64_t ro;
+            if (PAGED) ro = __shfl(off, r);
+            else ro = seq_base + (int64_t)min(tile * kTile + r, L - 1) * kv.stride_token;
+            K[e] = stream_load(kbase + ro + 8 * li);
         }
     };
 
-    float m = -INFINITY, zl = 0.f;
-    float *ltile = logits + ((int64_t)b * kv.n_kv_heads + kvh) * pitch * G;    // [token][G]
+    // heads of this lane: hbase .. hbase+3 ; token of the tile: li (+16 in the upper lane groups for GR = 8)
+    const int hbase = (GR == 8) ? 4 * (lg & 1) : 4 * lg;
+    const int tok_in_tile = (GR == 8) ? li + 16 * (lg >> 1) : li;
+    const bool park = hbase < Gp;
+    float m[4], z[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) { m[r] = kMinusHuge; z[r] = 0.f; }
+    float *lpark = logits + ((int64_t)b * kv.n_kv_heads + kvh) * pitch * Gp + hbase;
 
     auto compute = [&](int tile, u32x4(&K)[8]) {
-        u32x4 ka[8];
-        if (KLDS) {
-            unsigned char *sw = smem[wave];
+        unsigned char *sw = smem[wave];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int r = tile_row(lg, e);
-                *reinterpret_cast<u32x4 *>(sw + r * 256 + ((li ^ (r & 15)) << 4)) = K[e];
+        for (int e = 0; e < 8; ++e) {
+            const int r = 4 * e + lg;
+            *reinterpret_cast<u32x4 *>(sw + r * 256 + ((li ^ (r & 15)) << 4)) = K[e];
+        }
+        wave_lds_fence();
+        u32x4 kb[8];
+#pragma unroll
+        for (int T = 0; T < 2; ++T)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const int c = 4 * kk + lg;
+                kb[4 * T + kk] = *reinterpret_cast<const u32x4 *>(sw + (16 * T + li) * 256 + (((c ^ li) & 15) << 4));
             }
-            wave_lds_fence();
+        wave_lds_fence();
+        const int p0 = tile * kTile;
+        if (GR == 8) {
+            f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int T = 0; T < 2; ++T)
+            for (int kk = 0; kk < 4; ++kk)
+                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qlo[kk]),
+                                                            __builtin_bit_cast(bf16x8, kb[kk]), s, 0, 0, 0);
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    const int c = 4 * kk + lg;
-                    ka[4 * T + kk] = *reinterpret_cast<const u32x4 *>(sw + (16 * T + li) * 256 + (((c ^ li) & 15) << 4));
-                }
-            wave_lds_fence();
+            for (int kk = 0; kk < 4; ++kk)
+                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qhi[kk]),
+                                                            __builtin_bit_cast(bf16x8, kb[4 + kk]), s, 0, 0, 0);
+            const int p = p0 + tok_in_tile;
+            const bool valid = p < L;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) s[r] = valid ? s[r] * scale_log2 : -INFINITY;
+            if (park) *reinterpret_cast<f32x4 *>(lpark + (int64_t)p * Gp) = s;     // p < pitch
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float mn = fmaxf(m[r], s[r]);
+                z[r] = z[r] * fast_exp2(m[r] - mn) + fast_exp2(s[r] - mn);
+                m[r] = mn;
+            }
         } else {
+            f32x4 s0 = f32x4{0.f, 0.f, 0.f, 0.f}, s1 = s0;
 #pragma unroll
-            for (int x = 0; x < 8; ++x) ka[x] = K[x];
-        }
-        f32x4 s0 = f32x4{0.f, 0.f, 0.f, 0.f}, s1 = s0;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[kk]),
-                                                         __builtin_bit_cast(bf16x8, qreg[kk]), s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[4 + kk]),
-                                                         __builtin_bit_cast(bf16x8, qreg[kk]), s1, 0, 0, 0);
-        }
-        const int pbase = tile * kTile + 4 * lg;
-        f32x4 a, c2;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            a[r] = (pbase + r < L) ? s0[r] * scale_log2 : -INFINITY;
-            c2[r] = (pbase + 16 + r < L) ? s1[r] * scale_log2 : -INFINITY;
-        }
-        if (!(dbg & 1)) {
-            // Park the tile's logits token-major ([token][G heads]): staged through LDS so that the
-            // wave writes one contiguous run of 32*G floats with 16-byte stores.
-            float *st = reinterpret_cast<float *>(smem[wave]);
-            if (li < G) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    st[(4 * lg + r) * G + li] = a[r];
-                    st[(16 + 4 * lg + r) * G + li] = c2[r];
-                }
+            for (int kk = 0; kk < 4; ++kk) {
+                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qlo[kk]),
+                                                             __builtin_bit_cast(bf16x8, kb[kk]), s0, 0, 0, 0);
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qlo[kk]),
+                                                             __builtin_bit_cast(bf16x8, kb[4 + kk]), s1, 0, 0, 0);
             }
-            wave_lds_fence();
-            float *dst = ltile + (int64_t)((dbg & 8) ? (tile & 3) : tile) * kTile * G;
+            const int p = p0 + li;
+            const bool v0 = p < L, v1 = p + 16 < L;
 #pragma unroll
-            for (int x = 0; x < 2; ++x) {
-                const int o = 4 * (lane + 64 * x);
-                if (o < kTile * G && (!(dbg & 16) || (tile & 4))) *reinterpret_cast<f32x4 *>(dst + o) = *reinterpret_cast<const f32x4 *>(st + o);
+            for (int r = 0; r < 4; ++r) {
+                s0[r] = v0 ? s0[r] * scale_log2 : -INFINITY;
+                s1[r] = v1 ? s1[r] * scale_log2 : -INFINITY;
             }
-            wave_lds_fence();
-        }
-        float mx = fmaxf(fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3])), fmaxf(fmaxf(c2[0], c2[1]), fmaxf(c2[2], c2[3])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m, mx);
-        float ps = 0.f;
+            if (park) {
+                *reinterpret_cast<f32x4 *>(lpark + (int64_t)p * Gp) = s0;
+                *reinterpret_cast<f32x4 *>(lpark + (int64_t)(p + 16) * Gp) = s1;
+            }
 #pragma unroll
-        for (int r = 0; r < 4; ++r) ps += fast_exp2(a[r] - m_new) + fast_exp2(c2[r] - m_new);
-        zl = zl * fast_exp2(m - m_new) + ps;
-        m = m_new;
+            for (int r = 0; r < 4; ++r) {
+                const float mn = fmaxf(m[r], fmaxf(s0[r], s1[r]));
+                z[r] = z[r] * fast_exp2(m[r] - mn) + fast_exp2(s0[r] - mn) + fast_exp2(s1[r] - mn);
+                m[r] = mn;
+            }
+        }
     };
 
     if (t0 + wave < t1) {
-        // Two register buffers, software pipelined: the loads of the next tile are issued before the
-        // current one is consumed.  They are issued unconditionally (past the end the last tile is
-        // loaded again) so that no branch separates a load from the wait that matches it -- a
-        // conditional prefetch makes the compiler drain every outstanding load at the join.
-        u32x4 KA[8], KB[8];
+        // NBUF register buffers, software pipelined: a buffer is refilled (with the tile NBUF rounds
+        // ahead) right after it has been consumed, so NBUF-1 tiles are in flight during a compute.
+        // The refills are unconditional (past the end the last tile is loaded again) so that no
+        // branch separates a load from the wait that matches it -- a conditional prefetch makes the
+        // compiler drain every outstanding load at the join.
+        u32x4 KB[NBUF][8];
+        int64_t off[NBUF];
         int tile = t0 + wave;
         const int last = tile + (t1 - 1 - tile) / kWaves * kWaves;
-        int64_t off_a = 0, off_b = 0;
-        if (PAGED) off_a = rowoff_of(tile);
-        load_tile(tile, off_a, KA);
-        if (PAGED) off_b = rowoff_of(min(tile + kWaves, last));
-        while (true) {
-            load_tile(min(tile + kWaves, last), off_b, KB);
-            if (PAGED) off_a = rowoff_of(min(tile + 2 * kWaves, last));
-            compute(tile, KA);
-            tile += kWaves;
-            if (tile > last) break;
-            load_tile(min(tile + kWaves, last), off_a, KA);
-            if (PAGED) off_b = rowoff_of(min(tile + 2 * kWaves, last));
-            compute(tile, KB);
-            tile += kWaves;
-            if (tile > last) break;
+#pragma unroll
+        for (int i = 0; i < NBUF; ++i) {
+            const int tl = min(tile + i * kWaves, last);
+            off[i] = PAGED ? rowoff_of(tl) : 0;
+            load_tile(tl, off[i], KB[i]);
+        }
+        for (;;) {
+#pragma unroll
+            for (int i = 0; i < NBUF; ++i) {
+                compute(tile, KB[i]);
+                const int tl = min(tile + NBUF * kWaves, last);
+                off[i] = PAGED ? rowoff_of(tl) : 0;
+                load_tile(tl, off[i], KB[i]);
+                tile += kWaves;
+                if (tile > last) goto stream_done;
+            }
         }
     }
+stream_done:
 
-    zl += __shfl_xor(zl, 16);
-    zl += __shfl_xor(zl, 32);
-    if (lg == 0) { sm_m[wave][li] = m; sm_z[wave][li] = zl; }
+    // ---- merge lanes that hold the same heads, then waves, then write the range's statistics ----
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) softmax_merge(m[r], z[r], __shfl_xor(m[r], o), __shfl_xor(z[r], o));
+        if (GR == 8) softmax_merge(m[r], z[r], __shfl_xor(m[r], 32), __shfl_xor(z[r], 32));
+    }
+    if (li == 0 && (GR == 16 || lg < 2)) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) { sm_m[wave][hbase + r] = m[r]; sm_z[wave][hbase + r] = z[r]; }
+    }
     __syncthreads();
     if (threadIdx.x < G) {
         const int hh = threadIdx.x;
@@ -198,17 +236,15 @@ __global__ __launch_bounds__(256, 3) void score_mfma_kernel(
 #pragma unroll
         for (int w = 1; w < kWaves; ++w) M = fmaxf(M, sm_m[w][hh]);
         float Z = 0.f;
-        if (M > -INFINITY) {
 #pragma unroll
-            for (int w = 0; w < kWaves; ++w) Z += fast_exp2(sm_m[w][hh] - M) * sm_z[w][hh];
-        }
+        for (int w = 0; w < kWaves; ++w) Z += fast_exp2(sm_m[w][hh] - M) * sm_z[w][hh];
         const int64_t ph = ((int64_t)b * Hq + (int64_t)kvh * G + hh) * nsplit + split;
         part_ml[ph * 2] = M;
         part_ml[ph * 2 + 1] = Z;
     }
 }
 
-// Generic: one wave per (range, query head, sequence), lanes over tokens.
+// Generic: one wave per (range, query head, sequence), lanes over tokens.  Plain fp32 FMAs.
 template <typename T, bool PAGED>
 __global__ __launch_bounds__(64) void score_generic_kernel(
     KvDev kv, BatchDev bv, const T *__restrict__ q, int Hq, float scale_log2,
@@ -218,7 +254,8 @@ __global__ __launch_bounds__(64) void score_generic_kernel(
     const int lane = threadIdx.x;
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int d = kv.head_dim;
-    const int g = h / (Hq / kv.n_kv_heads);
+    const int G = Hq / kv.n_kv_heads, Gp = park_heads(G);
+    const int g = h / G;
     const SeqGeom geo = seq_geom(bv, b);
     const int L = geo.S;
     const int ntile = (L + 63) / 64;
@@ -228,9 +265,8 @@ __global__ __launch_bounds__(64) void score_generic_kernel(
     for (int c = lane; c < d; c += 64) qs[c] = load_elem<T>(q + ((int64_t)b * Hq + h) * d + c);
     __syncthreads();
     const T *kbase = reinterpret_cast<const T *>(kv.k);
-    const int G = Hq / kv.n_kv_heads;
-    float *lrow = logits + ((int64_t)b * kv.n_kv_heads + g) * pitch * G + (h - g * G);   // [token][G]
-    float m = -INFINITY, z = 0.f;
+    float *lrow = logits + ((int64_t)b * kv.n_kv_heads + g) * pitch * Gp + (h - g * G);   // [token][Gp]
+    float m = kMinusHuge, z = 0.f;
     for (int tile = t0; tile < t1; ++tile) {
         const int p = tile * 64 + lane;
         const bool valid = p < L;
@@ -238,7 +274,7 @@ __global__ __launch_bounds__(64) void score_generic_kernel(
         float s = 0.f;
         for (int c = 0; c < d; ++c) s = fmaf(qs[c], load_elem<T>(kbase + off + c), s);
         s = valid ? s * scale_log2 : -INFINITY;
-        lrow[(int64_t)p * G] = s;                        // p < pitch: pitch is a multiple of 64
+        lrow[(int64_t)p * Gp] = s;                       // p < pitch: pitch is a multiple of 64
         const float m_new = fmaxf(m, wave_max(s));
         z = z * fast_exp2(m - m_new) + wave_sum(fast_exp2(s - m_new));
         m = m_new;
@@ -250,8 +286,13 @@ __global__ __launch_bounds__(64) void score_generic_kernel(
     }
 }
 
-// Finalize: per-head log-sum-exp from the range statistics, then the head average.
+// Finalize: per-head log-sum-exp from the range statistics, then the head average
+//     score_i = (1/Hq) sum_h 2^(logit_h,i - lse_h)
+// read back from the parked [token][Gp] rows.  LP lanes share a token (one 16-byte quad of heads
+// per kv head each), so that a wave's loads cover contiguous memory.
 constexpr int kFinThreads = 256;
+
+__host__ __device__ inline int fin_lanes_per_token(int Gp) { return Gp == 8 ? 2 : (Gp == 16 ? 4 : 1); }
 
 __global__ __launch_bounds__(kFinThreads) void score_finalize_kernel(
     BatchDev bv, int Hq, int n_kv_heads, const float *__restrict__ logits, int64_t pitch,
@@ -264,27 +305,37 @@ __global__ __launch_bounds__(kFinThreads) void score_finalize_kernel(
     const SeqGeom geo = seq_geom(bv, b);
     for (int h = threadIdx.x; h < Hq; h += kFinThreads) {
         const float *ml = part_ml + ((int64_t)b * Hq + h) * nsplit * 2;
-        float M = -INFINITY;
+        float M = kMinusHuge;
         for (int s = 0; s < nsplit; ++s) M = fmaxf(M, ml[2 * s]);
         float Z = 0.f;
-        if (M > -INFINITY)
-            for (int s = 0; s < nsplit; ++s) Z += fast_exp2(ml[2 * s] - M) * ml[2 * s + 1];
+        for (int s = 0; s < nsplit; ++s) Z += fast_exp2(ml[2 * s] - M) * ml[2 * s + 1];
         const float l2 = Z > 0.f ? M + log2f(Z) : -INFINITY;
         lse2[h] = l2;
         if (lse && blockIdx.x == 0) lse[(int64_t)b * Hq + h] = l2 * kLn2;
     }
     __syncthreads();
-    const int i = blockIdx.x * kFinThreads + threadIdx.x;
-    float sc = 0.f;
+    const int G = Hq / n_kv_heads, Gp = park_heads(G);
+    const int LP = fin_lanes_per_token(Gp);
+    const int nq = Gp / 4 / LP;                        // 16-byte quads per lane per kv head
+    const int i = (blockIdx.x * kFinThreads + threadIdx.x) / LP;
+    const int sub = threadIdx.x % LP;
+    float acc = 0.f;
     if (i < geo.N) {
-        // logits are parked as [sequence][kv head][token][G]
-        const int G = Hq / n_kv_heads;
-        const float *lp = logits + ((int64_t)b * n_kv_heads * pitch + geo.v0 + i) * G;
-        float acc = 0.f;
+        const float *lp = logits + ((int64_t)b * n_kv_heads * pitch + geo.v0 + i) * Gp;
         for (int g = 0; g < n_kv_heads; ++g) {
-            const float *lg_ = lp + (int64_t)g * pitch * G;
-            for (int x = 0; x < G; ++x) acc += fast_exp2(lg_[x] - lse2[g * G + x]);
+            const float *row = lp + (int64_t)g * pitch * Gp;
+            for (int qd = 0; qd < nq; ++qd) {
+                const int x0 = 4 * (sub * nq + qd);
+                const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(row + x0));
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (x0 + r < G) acc += fast_exp2(v[r] - lse2[g * G + x0 + r]);
+            }
         }
+    }
+    for (int o = 1; o < LP; o <<= 1) acc += __shfl_xor(acc, o);
+    float sc = 0.f;
+    if (i < geo.N && sub == 0) {
         sc = acc / (float)Hq;
         scores[(int64_t)b * bv.max_vis_len + i] = sc;
     }
@@ -312,13 +363,23 @@ __global__ void mass_reduce_kernel(const float *__restrict__ mass_part, int nblk
 // -----------------------------------------------------------------------------------------
 int score_tile_tokens(const Shape &s) { return mfma_path(s) ? kTile : 64; }
 
-static int fin_blocks(const Shape &s) { return max(1, (s.bv.max_vis_len + kFinThreads - 1) / kFinThreads); }
+static int fin_blocks(const Shape &s)
+{
+    const int LP = fin_lanes_per_token(park_heads(s.n_q_heads / s.kv.n_kv_heads));
+    const int per = kFinThreads / LP;
+    return max(1, (s.bv.max_vis_len + per - 1) / per);
+}
+
+static size_t parked_floats(const Shape &s)
+{
+    const int Gp = park_heads(s.n_q_heads / s.kv.n_kv_heads);
+    return (size_t)s.batch * s.kv.n_kv_heads * (size_t)logit_pitch(s.bv.max_seq_len) * Gp;
+}
 
 size_t score_workspace_bytes(const Shape &s, int nsplit)
 {
-    const size_t rows = (size_t)s.batch * s.n_q_heads;
-    size_t bytes = rows * (size_t)logit_pitch(s.bv.max_seq_len) * sizeof(float);
-    bytes += rows * (size_t)nsplit * 2 * sizeof(float);
+    size_t bytes = parked_floats(s) * sizeof(float);
+    bytes += (size_t)s.batch * s.n_q_heads * (size_t)nsplit * 2 * sizeof(float);
     bytes += (size_t)s.batch * fin_blocks(s) * sizeof(float);
     return bytes;
 }
@@ -329,18 +390,18 @@ hipError_t launch_score(const Shape &s, const void *q, float scale, float *score
     const int64_t pitch = logit_pitch(s.bv.max_seq_len);
     const size_t rows = (size_t)s.batch * s.n_q_heads;
     float *logits = reinterpret_cast<float *>(ws);
-    float *part_ml = logits + rows * pitch;
+    float *part_ml = logits + parked_floats(s);
     float *mass_part = part_ml + rows * nsplit * 2;
     const float scale_log2 = scale * kLog2e;
     const int G = s.n_q_heads / s.kv.n_kv_heads;
 
     timer_begin(K_SCORE_LOGITS, stream);
     if (mfma_path(s)) {
-        dim3 grid(nsplit, s.kv.n_kv_heads, s.batch), block(256);
-#define FASTOCR_SCORE(P, KL) score_mfma_kernel<P, KL><<<grid, block, 0, stream>>>( \
-        s.kv, s.bv, (const uint16_t *)q, s.n_q_heads, G, scale_log2, logits, pitch, part_ml, nsplit, g_tune_dbg)
-        if (s.paged) { if (g_tune_k_via_lds) FASTOCR_SCORE(true, true); else FASTOCR_SCORE(true, false); }
-        else         { if (g_tune_k_via_lds) FASTOCR_SCORE(false, true); else FASTOCR_SCORE(false, false); }
+        dim3 grid(nsplit, s.kv.n_kv_heads, s.batch);
+#define FASTOCR_SCORE(P, GR) score_mfma_kernel<P, GR, 4, 2><<<grid, dim3(256), 0, stream>>>( \
+        s.kv, s.bv, (const uint16_t *)q, s.n_q_heads, G, scale_log2, logits, pitch, part_ml, nsplit)
+        if (s.paged) { if (G <= 8) FASTOCR_SCORE(true, 8); else FASTOCR_SCORE(true, 16); }
+        else         { if (G <= 8) FASTOCR_SCORE(false, 8); else FASTOCR_SCORE(false, 16); }
 #undef FASTOCR_SCORE
     } else {
         dim3 grid(nsplit, s.n_q_heads, s.batch), block(64);
