@@ -5,8 +5,10 @@ scoring of the current queries against all cached keys, top-k of ceil(tau N) ima
 warm-started from the previous step's set, and sparse decode attention over text + selected
 image tokens.  Workload: the large dense-document configuration (bf16, batch 16, Hq 64, Hkv 8,
 head_dim 128, N = 16384 image tokens, 256-token text prefix, mid-run text length), tau = 0.05,
-synthetic drifting-fixation queries; the sequence grows by one token per step.  Inputs are
-resident in HBM before the timed region starts.
+synthetic drifting-fixation queries; the sequence grows by one token per step.  Consecutive steps
+alternate between `--layers` (default 2) distinct caches of that shape, as consecutive layer-steps
+of a model do, so that no step finds its K/V in the 256 MB memory-side cache from the step before.
+Inputs are resident in HBM before the timed region starts.
 
 Prints ONE JSON line.  The dense decode-attention comparator and the per-kernel breakdown are
 measured in separate passes after the timed region and reported as extra keys.
@@ -37,7 +39,11 @@ def parse_args():
     ap.add_argument("--start-step", type=int, default=0, help="decode step the run starts at (0 = mid-run)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the comparator / breakdown passes")
-    ap.add_argument("--cpu-budget-s", type=float, default=20.0)
+    ap.add_argument("--cpu-budget-s", type=float, default=12.0)
+    ap.add_argument("--layers", type=int, default=2, help="distinct caches the steps rotate over")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also launch the plain copy / read probe kernels of known size (1 GiB) three times "
+                         "each, so that a profiler's byte counters can be scaled against them")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
                     help="launch-shape override passed to fastocr_set_tuning (measurement sweeps)")
     return ap.parse_args()
@@ -74,16 +80,21 @@ def main():
     tau = args.tau
 
     # ---- inputs (resident before timing) ---------------------------------------------------
-    bt = fs.make_batch(wl, device=dev)
+    L = max(1, args.layers)
+    bts = [fs.make_batch(wl, device=dev, layer=l) for l in range(L)]
+    bt = bts[0]
     cs = fs.centres(bt, t_first + total)
     B, Hq, Hkv, d = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim
-    qs = torch.stack([fs.queries_for_step(bt, t_first + i, [c[t_first + i - 1] for c in cs]) for i in range(total)])
+    qs = torch.stack([fs.queries_for_step(bts[i % L], t_first + i, [c[t_first + i - 1] for c in cs])
+                      for i in range(total)])
     seq_lens = torch.tensor([bt.seq_len(t_first + i) for i in range(total)], dtype=torch.int32, device=dev)
     vis_start = torch.tensor(bt.vis_start, dtype=torch.int32, device=dev)
     vis_len = torch.tensor(bt.n_vis, dtype=torch.int32, device=dev)
     max_vis = max(bt.n_vis)
     batches = [fo.SeqBatch(seq_lens[i], vis_start, vis_len, max(bt.seq_len(t_first + i)), max_vis) for i in range(total)]
-    cache = fo.KvCache(bt.k, bt.v)
+    layer_caches = [fo.KvCache(x.k, x.v) for x in bts]
+    caches = [layer_caches[i % L] for i in range(total)]
+    cache = layer_caches[0]
     scale = float(np.float32(d ** -0.5))
     kmax = max(1, fo.keep_count(max_vis, tau))
     need = max(fo.workspace_bytes(op, cache, batches[-1], Hq, kmax) for op in range(4))
@@ -96,6 +107,7 @@ def main():
     state = {"have_prev": False}
 
     def three_step(i):
+        cache = caches[i]
         fo.focal_score(cache, batches[i], qs[i], scale, scores, ws)
         if state["have_prev"]:
             fo.topk_fixation(scores, batches[i], tau, idx, cnt, ws, prev_idx=idx, prev_cnt=cnt)
@@ -118,6 +130,17 @@ def main():
     logits_ms = fb.kernel_timer_read(fb.KERNEL_SCORE_LOGITS)
     fb.kernel_timer_enable(fb.KERNEL_SCORE_LOGITS, 0)
 
+    if args.calibrate:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        sink = torch.zeros(4, dtype=torch.int32, device=dev)
+        for _ in range(3):
+            fb.stream_probe(src, dst, sink)          # reads 1 GiB, writes 1 GiB
+        for _ in range(3):
+            fb.stream_probe(src, None, sink)         # reads 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+
     ms_per_step = elapsed * 1e3 / n_steps
     value = n_steps / elapsed
 
@@ -128,9 +151,16 @@ def main():
     score_bytes = B * (mean_S * R + Hq * d * e)                 # K rows of every cached token + the queries
     k_ms = float(np.mean(logits_ms)) if logits_ms else float("nan")
     achieved = score_bytes / (k_ms * 1e-3) / 1e9
+    traffic = None
+    prof = os.path.join(ROOT, "profiles", "three_step_config4_tau0.05.md")
+    if wl.config_id == 4 and abs(tau - 0.05) < 1e-12 and not args.batch and os.path.exists(prof):
+        # HBM bytes per launch of this kernel from the committed rocprofv3 --pmc summary of this command
+        for line in open(prof):
+            if line.startswith("machine-readable:"):
+                traffic = json.loads(line.split(":", 1)[1])["traffic_bytes_per_launch"]
     roofline = {"bound": "hbm", "kernel": "score_mfma_kernel (focal scoring, K stream)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "algorithmic_bytes": int(score_bytes), "avg_launch_us": round(k_ms * 1e3, 2),
                 "launches": len(logits_ms)}
 
@@ -141,9 +171,10 @@ def main():
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": "config%d %s: batch %d, Hq %d, Hkv %d, head_dim %d, N %d visual + %d-token text "
-                               "prefix, decode steps %d..%d, tau %g, warm-started top-k"
+                               "prefix, decode steps %d..%d, tau %g, warm-started top-k, steps rotate "
+                               "over %d distinct caches"
                                % (wl.config_id, wl.name, B, Hq, Hkv, d, max_vis, bt.prefix[0], t_first + n_warm,
-                                  t_first + total - 1, tau)},
+                                  t_first + total - 1, tau, L)},
         "roofline": roofline,
     }
 
@@ -155,19 +186,19 @@ def main():
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(n_warm, total):
-            fo.dense_decode_attn(cache, batches[i], qs[i], scale, out_dense, ws)
+            fo.dense_decode_attn(caches[i], batches[i], qs[i], scale, out_dense, ws)
         torch.cuda.synchronize()
         dense_ms = (time.perf_counter() - t0) * 1e3 / n_steps
         t0 = time.perf_counter()
         for i in range(n_warm, total):
-            fo.sparse_decode_attn(cache, batches[i], qs[i], scale, idx, cnt, out, ws)
+            fo.sparse_decode_attn(caches[i], batches[i], qs[i], scale, idx, cnt, out, ws)
         torch.cuda.synchronize()
         sparse_ms = (time.perf_counter() - t0) * 1e3 / n_steps
         for kid in names:
             fb.kernel_timer_enable(kid, 4 * n_steps)
         for i in range(n_warm, total):
             three_step(i)
-            fo.dense_decode_attn(cache, batches[i], qs[i], scale, out_dense, ws)
+            fo.dense_decode_attn(caches[i], batches[i], qs[i], scale, out_dense, ws)
         torch.cuda.synchronize()
         kernels_us = {}
         for kid, nm in names.items():
@@ -198,27 +229,30 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         threads = oracle.max_threads()
+        n_seq, cpu_s, n_steps_cpu = 0, 0.0, 0
         i = total - 1
-        t_dec = t_first + i
-        ok = oracle.Cache.from_bhsd(fs.to_oracle_array(bt.k[:1]), fs.to_oracle_array(bt.v[:1]))
-        q1 = fs.to_oracle_array(qs[i][:1])
-        n_seq, cpu_s = 0, 0.0
-        while cpu_s < args.cpu_budget_s and n_seq < B:
-            b = n_seq
-            if b > 0:
-                ok = oracle.Cache.from_bhsd(fs.to_oracle_array(bt.k[b:b + 1]), fs.to_oracle_array(bt.v[b:b + 1]))
+        while cpu_s < args.cpu_budget_s and i >= 0:
+            t_dec = t_first + i
+            src = bts[i % L]
+            for b in range(B):
+                ok = oracle.Cache.from_bhsd(fs.to_oracle_array(src.k[b:b + 1]), fs.to_oracle_array(src.v[b:b + 1]))
                 q1 = fs.to_oracle_array(qs[i][b:b + 1])
-            geo = ([bt.seq_len(t_dec)[b]], [bt.vis_start[b]], [bt.n_vis[b]])
-            t0 = time.perf_counter()
-            sc, _, _ = oracle.focal_score(ok, *geo, q1, scale, n_threads=threads)
-            sel, c = oracle.topk_fixation(sc, geo[2], tau)
-            oracle.decode_attn(ok, *geo, q1, scale, sel, c, n_threads=threads)
-            cpu_s += time.perf_counter() - t0
-            n_seq += 1
+                geo = ([bt.seq_len(t_dec)[b]], [bt.vis_start[b]], [bt.n_vis[b]])
+                t0 = time.perf_counter()
+                sc, _, _ = oracle.focal_score(ok, *geo, q1, scale, n_threads=threads)
+                sel, c = oracle.topk_fixation(sc, geo[2], tau)
+                oracle.decode_attn(ok, *geo, q1, scale, sel, c, n_threads=threads)
+                cpu_s += time.perf_counter() - t0
+                n_seq += 1
+                if cpu_s >= args.cpu_budget_s:
+                    break
+            n_steps_cpu += 1
+            i -= 1
         result["cpu_baseline"] = {
             "value": round(n_seq / (B * cpu_s), 5), "unit": "layer-steps/s", "cores": threads, "kind": "oracle",
-            "sample": "%d of %d sequences of decode step %d, whole three-step path, %.1f s of CPU time; "
-                      "rate scaled to the full batch" % (n_seq, B, t_dec, cpu_s)}
+            "sample": "%d sequence-steps (batch %d, decode steps %d..%d backwards) of the whole three-step path, "
+                      "%.1f s of CPU time; rate scaled to the full batch"
+                      % (n_seq, B, t_first + total - 1, t_first + total - n_steps_cpu, cpu_s)}
 
     print(json.dumps(result))
 

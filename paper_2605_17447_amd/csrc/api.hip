@@ -21,19 +21,12 @@ struct KernelTimer {
 };
 static KernelTimer g_timers[K_COUNT];
 
-void timer_begin(int kernel, hipStream_t s)
+TimerEvents timer_events(int kernel)
 {
     KernelTimer &t = g_timers[kernel];
-    if (t.count < t.capacity) (void)hipEventRecord(t.start[t.count], s);
-}
-
-void timer_end(int kernel, hipStream_t s)
-{
-    KernelTimer &t = g_timers[kernel];
-    if (t.count < t.capacity) {
-        (void)hipEventRecord(t.stop[t.count], s);
-        ++t.count;
-    }
+    if (t.count >= t.capacity) return TimerEvents{nullptr, nullptr};
+    const int i = t.count++;
+    return TimerEvents{t.start[i], t.stop[i]};
 }
 
 // ---- shapes -----------------------------------------------------------------------------

@@ -357,27 +357,27 @@ size_t attn_workspace_bytes(const Shape &s, int nsplit)
 }
 
 template <bool GATHER, bool PAGED>
-static void launch_mfma(const Shape &s, const void *q, float scale_log2, const int32_t *sel_idx,
+static void launch_mfma(int kid, const Shape &s, const void *q, float scale_log2, const int32_t *sel_idx,
                         const int32_t *sel_cnt, int64_t kmax, float *part_o, float *part_ml,
                         int nsplit, hipStream_t stream)
 {
     const int G = s.n_q_heads / s.kv.n_kv_heads;
     dim3 grid(nsplit, s.kv.n_kv_heads, s.batch), block(256);
     if (g_tune_k_via_lds)
-        attn_mfma_kernel<GATHER, PAGED, true><<<grid, block, 0, stream>>>(
+        FASTOCR_LAUNCH(kid, (attn_mfma_kernel<GATHER, PAGED, true>), grid, block, 0, stream,
             s.kv, s.bv, (const uint16_t *)q, s.n_q_heads, G, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit);
     else
-        attn_mfma_kernel<GATHER, PAGED, false><<<grid, block, 0, stream>>>(
+        FASTOCR_LAUNCH(kid, (attn_mfma_kernel<GATHER, PAGED, false>), grid, block, 0, stream,
             s.kv, s.bv, (const uint16_t *)q, s.n_q_heads, G, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit);
 }
 
 template <typename T, bool GATHER, bool PAGED>
-static void launch_generic(const Shape &s, const void *q, float scale_log2, const int32_t *sel_idx,
+static void launch_generic(int kid, const Shape &s, const void *q, float scale_log2, const int32_t *sel_idx,
                            const int32_t *sel_cnt, int64_t kmax, float *part_o, float *part_ml,
                            int nsplit, hipStream_t stream)
 {
     dim3 grid(nsplit, s.n_q_heads, s.batch), block(64);
-    attn_generic_kernel<T, GATHER, PAGED><<<grid, block, 0, stream>>>(
+    FASTOCR_LAUNCH(kid, (attn_generic_kernel<T, GATHER, PAGED>), grid, block, 0, stream,
         s.kv, s.bv, (const T *)q, s.n_q_heads, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit);
 }
 
@@ -392,13 +392,12 @@ hipError_t launch_attn(const Shape &s, const void *q, float scale, const int32_t
     const float scale_log2 = scale * kLog2e;
     const int kid = gather ? K_SPARSE_ATTN : K_DENSE_ATTN;
 
-    timer_begin(kid, stream);
 #define FASTOCR_DISPATCH(FN, ...)                                                                      \
     do {                                                                                               \
-        if (gather) { if (s.paged) FN<__VA_ARGS__ true, true>(s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, stream); \
-                      else         FN<__VA_ARGS__ true, false>(s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, stream); } \
-        else        { if (s.paged) FN<__VA_ARGS__ false, true>(s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, stream); \
-                      else         FN<__VA_ARGS__ false, false>(s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, stream); } \
+        if (gather) { if (s.paged) FN<__VA_ARGS__ true, true>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, stream); \
+                      else         FN<__VA_ARGS__ true, false>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, stream); } \
+        else        { if (s.paged) FN<__VA_ARGS__ false, true>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, stream); \
+                      else         FN<__VA_ARGS__ false, false>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, stream); } \
     } while (0)
     if (mfma_path(s)) {
         FASTOCR_DISPATCH(launch_mfma, );
@@ -408,17 +407,14 @@ hipError_t launch_attn(const Shape &s, const void *q, float scale, const int32_t
         FASTOCR_DISPATCH(launch_generic, float, );
     }
 #undef FASTOCR_DISPATCH
-    timer_end(kid, stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
-    timer_begin(K_ATTN_COMBINE, stream);
     dim3 grid(s.n_q_heads, s.batch), block(256);
     if (s.dtype == DT_BF16)
-        attn_combine_kernel<uint16_t><<<grid, block, 0, stream>>>(part_o, part_ml, nsplit, d, (uint16_t *)out, lse);
+        FASTOCR_LAUNCH(K_ATTN_COMBINE, attn_combine_kernel<uint16_t>, grid, block, 0, stream, part_o, part_ml, nsplit, d, (uint16_t *)out, lse);
     else
-        attn_combine_kernel<float><<<grid, block, 0, stream>>>(part_o, part_ml, nsplit, d, (float *)out, lse);
-    timer_end(K_ATTN_COMBINE, stream);
+        FASTOCR_LAUNCH(K_ATTN_COMBINE, attn_combine_kernel<float>, grid, block, 0, stream, part_o, part_ml, nsplit, d, (float *)out, lse);
     return hipGetLastError();
 }
 

@@ -1,5 +1,7 @@
 // Host-side launch interface between the C-ABI layer (api.hip) and the kernel files.
 #pragma once
+#include <hip/hip_ext.h>
+
 #include "common.hpp"
 
 namespace fastocr {
@@ -10,9 +12,18 @@ enum KernelId {
     K_ATTN_COMBINE = 5, K_COUNT = 6
 };
 
-// Event hooks implemented in api.hip: no-ops unless a timer is enabled for the kernel.
-void timer_begin(int kernel, hipStream_t s);
-void timer_end(int kernel, hipStream_t s);
+// Per-kernel timing (api.hip): when a timer is enabled for `kernel`, the next launch gets a pair of
+// events that the runtime stamps at the kernel's own start and end (hipExtLaunchKernelGGL);
+// otherwise both are null and the launch is an ordinary one.
+struct TimerEvents { hipEvent_t start, stop; };
+TimerEvents timer_events(int kernel);
+
+#define FASTOCR_LAUNCH(KID, KERNEL, GRID, BLOCK, SHMEM, STREAM, ...)                                   \
+    do {                                                                                               \
+        const ::fastocr::TimerEvents te_ = ::fastocr::timer_events(KID);                               \
+        hipExtLaunchKernelGGL((KERNEL), (GRID), (BLOCK), (SHMEM), (STREAM), te_.start, te_.stop, 0,    \
+                              __VA_ARGS__);                                                            \
+    } while (0)
 
 enum { DT_F32 = 0, DT_BF16 = 1 };
 

@@ -395,33 +395,29 @@ hipError_t launch_score(const Shape &s, const void *q, float scale, float *score
     const float scale_log2 = scale * kLog2e;
     const int G = s.n_q_heads / s.kv.n_kv_heads;
 
-    timer_begin(K_SCORE_LOGITS, stream);
     if (mfma_path(s)) {
         dim3 grid(nsplit, s.kv.n_kv_heads, s.batch);
-#define FASTOCR_SCORE(P, GR) score_mfma_kernel<P, GR, 4, 2><<<grid, dim3(256), 0, stream>>>( \
+#define FASTOCR_SCORE(P, GR) FASTOCR_LAUNCH(K_SCORE_LOGITS, (score_mfma_kernel<P, GR, 4, 2>), grid, dim3(256), 0, stream, \
         s.kv, s.bv, (const uint16_t *)q, s.n_q_heads, G, scale_log2, logits, pitch, part_ml, nsplit)
         if (s.paged) { if (G <= 8) FASTOCR_SCORE(true, 8); else FASTOCR_SCORE(true, 16); }
         else         { if (G <= 8) FASTOCR_SCORE(false, 8); else FASTOCR_SCORE(false, 16); }
 #undef FASTOCR_SCORE
     } else {
         dim3 grid(nsplit, s.n_q_heads, s.batch), block(64);
-#define FASTOCR_SCORE(T, P) score_generic_kernel<T, P><<<grid, block, 0, stream>>>( \
+#define FASTOCR_SCORE(T, P) FASTOCR_LAUNCH(K_SCORE_LOGITS, (score_generic_kernel<T, P>), grid, block, 0, stream, \
         s.kv, s.bv, (const T *)q, s.n_q_heads, scale_log2, logits, pitch, part_ml, nsplit)
         if (s.dtype == DT_BF16) { if (s.paged) FASTOCR_SCORE(uint16_t, true); else FASTOCR_SCORE(uint16_t, false); }
         else                    { if (s.paged) FASTOCR_SCORE(float, true); else FASTOCR_SCORE(float, false); }
 #undef FASTOCR_SCORE
     }
-    timer_end(K_SCORE_LOGITS, stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
-    timer_begin(K_SCORE_FINALIZE, stream);
     const int nblk = fin_blocks(s);
     dim3 fgrid(nblk, s.batch), fblock(kFinThreads);
-    score_finalize_kernel<<<fgrid, fblock, (size_t)s.n_q_heads * sizeof(float), stream>>>(
+    FASTOCR_LAUNCH(K_SCORE_FINALIZE, score_finalize_kernel, fgrid, fblock, (size_t)s.n_q_heads * sizeof(float), stream,
         s.bv, s.n_q_heads, s.kv.n_kv_heads, logits, pitch, part_ml, nsplit, scores, lse, img_mass ? mass_part : nullptr);
     if (img_mass) mass_reduce_kernel<<<s.batch, 64, 0, stream>>>(mass_part, nblk, img_mass);
-    timer_end(K_SCORE_FINALIZE, stream);
     return hipGetLastError();
 }
 

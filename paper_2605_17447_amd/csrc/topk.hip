@@ -238,10 +238,8 @@ hipError_t launch_topk(const float *scores, const BatchDev &bv, int batch, doubl
             (void)hipGetLastError();
         attr_set = true;
     }
-    timer_begin(K_TOPK, stream);
-    topk_kernel<<<batch, kTopkThreads, dyn, stream>>>(scores, bv, tau, prev_idx, prev_cnt, sel_idx,
-                                                      sel_cnt, kmax, reinterpret_cast<uint32_t *>(ws), lds_keys);
-    timer_end(K_TOPK, stream);
+    FASTOCR_LAUNCH(K_TOPK, topk_kernel, dim3(batch), dim3(kTopkThreads), dyn, stream, scores, bv, tau, prev_idx,
+                   prev_cnt, sel_idx, sel_cnt, kmax, reinterpret_cast<uint32_t *>(ws), lds_keys);
     return hipGetLastError();
 }
 
