@@ -158,7 +158,7 @@ def main():
         for line in open(prof):
             if line.startswith("machine-readable:"):
                 traffic = json.loads(line.split(":", 1)[1])["traffic_bytes_per_launch"]
-    roofline = {"bound": "hbm", "kernel": "score_mfma_kernel (focal scoring, K stream)",
+    roofline = {"bound": "hbm", "kernel": "score_resident_kernel (focal scoring: K stream, logits kept in registers)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "algorithmic_bytes": int(score_bytes), "avg_launch_us": round(k_ms * 1e3, 2),

@@ -10,6 +10,7 @@
 namespace fastocr {
 
 int g_tune_k_via_lds = 1;
+static int g_tune_score_resident = 1;
 static int g_tune_splits[4] = {0, 0, 0, 0};     // indexed by fastocr_op
 
 // ---- per-kernel timers ------------------------------------------------------------------
@@ -114,6 +115,20 @@ static int choose_splits(int op, const Shape &s, int max_positions)
     return nsplit;
 }
 
+// Compute units of the current device (queried once per device).
+static int device_cu_count()
+{
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 0;
+        cached[dev] = n > 0 ? n : -1;
+    }
+    return cached[dev] > 0 ? cached[dev] : 0;
+}
+
 static size_t round256(size_t x) { return (x + 255) / 256 * 256; }
 
 }  // namespace fastocr
@@ -144,7 +159,13 @@ size_t fastocr_workspace_bytes(int op, const fastocr_kv_view *kv, const fastocr_
     Shape s = make_shape(kv, bv, n_q_heads);
     // the sparse path may be asked to attend everything (tau = 1): size for the whole sequence
     const int nsplit = choose_splits(op, s, bv->max_seq_len);
-    if (op == FASTOCR_OP_FOCAL_SCORE) return round256(score_workspace_bytes(s, nsplit) + 256);
+    if (op == FASTOCR_OP_FOCAL_SCORE) {
+        // sized for either scoring path, so that the choice can be made at launch
+        size_t need = score_workspace_bytes(s, nsplit);
+        ResidentPlan rp;
+        if (resident_plan(s, kNumCU, &rp)) need = need > resident_workspace_bytes(s, rp) ? need : resident_workspace_bytes(s, rp);
+        return round256(need + 256);
+    }
     return round256(attn_workspace_bytes(s, nsplit) + 256);
 }
 
@@ -178,7 +199,12 @@ int fastocr_focal_score(const fastocr_kv_view *kv, const fastocr_batch_view *bv,
     if (bv->batch == 0) return FASTOCR_OK;
     Shape s = make_shape(kv, bv, n_q_heads);
     const int nsplit = choose_splits(FASTOCR_OP_FOCAL_SCORE, s, bv->max_seq_len);
-    hipError_t e = launch_score(s, q, scale, scores, lse, img_mass, ws, nsplit, (hipStream_t)hip_stream);
+    ResidentPlan rp;
+    hipError_t e;
+    if (g_tune_score_resident && resident_plan(s, kNumCU, &rp) && rp.nranges * s.batch <= device_cu_count())
+        e = launch_score_resident(s, rp, q, scale, scores, lse, img_mass, ws, (hipStream_t)hip_stream);
+    else
+        e = launch_score(s, q, scale, scores, lse, img_mass, ws, nsplit, (hipStream_t)hip_stream);
     return e == hipSuccess ? FASTOCR_OK : FASTOCR_EHIP;
 }
 
@@ -294,6 +320,7 @@ int fastocr_set_tuning(const char *key, int value)
     else if (!strcmp(key, "splits_sparse")) g_tune_splits[FASTOCR_OP_SPARSE_DECODE_ATTN] = value;
     else if (!strcmp(key, "splits_dense")) g_tune_splits[FASTOCR_OP_DENSE_DECODE_ATTN] = value;
     else if (!strcmp(key, "k_via_lds")) g_tune_k_via_lds = value ? 1 : 0;
+    else if (!strcmp(key, "score_resident")) g_tune_score_resident = value ? 1 : 0;
     else return FASTOCR_EINVAL;
     return FASTOCR_OK;
 }

@@ -22,27 +22,8 @@ namespace fastocr {
 
 extern int g_tune_k_via_lds;
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
 constexpr int kTile = 32;          // tokens per wave tile (two 16-token MFMA tiles)
 constexpr int kWaves = 4;
-
-__device__ __forceinline__ void wave_lds_fence()
-{
-    // LDS traffic of one wave executes in order; this only stops the compiler from moving
-    // the reads of other lanes' data above the writes that produce it.
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-}
-
-__device__ __forceinline__ u32x4 stream_load(const uint16_t *p)
-{
-    // K and V are read once per call: non-temporal loads stream measurably faster on this chip
-    // and keep the cache lines that are reused (queries, indices, partials) in place.
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
-}
 
 // Row of the 32-token tile that lane group `lg` holds as element e of its 8-token k-block:
 // elements 0..3 come from the first 16-token half, 4..7 from the second.

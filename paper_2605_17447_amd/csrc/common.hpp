@@ -108,6 +108,36 @@ __device__ __forceinline__ float wave_sum(float x)
 // exp2 with exp2(-inf) = 0 and no NaN for (-inf) - (-inf) handled by the callers
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// LDS traffic of one wave executes in order; this only stops the compiler from moving the reads
+// of other lanes' data above the writes that produce it.
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// K and V are read once per call: non-temporal loads stream measurably faster on this chip and
+// keep the cache lines that are reused (queries, indices, partials, parked logits) in place.
+__device__ __forceinline__ u32x4 stream_load(const uint16_t *p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+}
+
+// Finite stand-in for "no logit yet": keeps 2^(m - m') free of inf - inf.
+constexpr float kMinusHuge = -1.0e30f;
+
+// (max, sum-exp) of two disjoint sets of base-2 logits -> of their union
+__device__ __forceinline__ void softmax_merge(float &m, float &z, float mo, float zo)
+{
+    const float M = fmaxf(m, mo);
+    z = z * fast_exp2(m - M) + zo * fast_exp2(mo - M);
+    m = M;
+}
+
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 

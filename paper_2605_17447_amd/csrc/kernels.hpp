@@ -55,6 +55,15 @@ size_t score_workspace_bytes(const Shape &s, int nsplit);
 hipError_t launch_score(const Shape &s, const void *q, float scale, float *scores, float *lse,
                         float *img_mass, void *ws, int nsplit, hipStream_t stream);
 
+// ---- focal scoring with register-resident logits (score_resident.hip) ---------------------
+// Workspace: range statistics fp32 [B][nranges][Hq][2], image-mass partials fp32 [B][nranges],
+// barrier counters uint32 [B] + one status word.
+struct ResidentPlan { int nranges, range_tokens, wpk; };
+bool resident_plan(const Shape &s, int num_cu, ResidentPlan *plan);
+size_t resident_workspace_bytes(const Shape &s, const ResidentPlan &p);
+hipError_t launch_score_resident(const Shape &s, const ResidentPlan &p, const void *q, float scale, float *scores,
+                                 float *lse, float *img_mass, void *ws, hipStream_t stream);
+
 // ---- top-k (topk.hip) -------------------------------------------------------------------
 size_t topk_workspace_bytes(int batch, int max_vis_len);
 hipError_t launch_topk(const float *scores, const BatchDev &bv, int batch, double tau,

@@ -4,8 +4,6 @@
 
 namespace fastocr {
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
 __global__ __launch_bounds__(256) void stream_probe_kernel(const u32x4 *__restrict__ src,
                                                            u32x4 *__restrict__ dst, size_t n16,
                                                            uint32_t *__restrict__ sink)

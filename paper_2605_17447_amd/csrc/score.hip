@@ -14,35 +14,10 @@
 
 namespace fastocr {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
 constexpr int kTile = 32;          // tokens per wave tile
-constexpr float kMinusHuge = -1.0e30f;   // finite stand-in for "no logit yet": keeps 2^(m - m') free of inf - inf
-
-__device__ __forceinline__ void wave_lds_fence()
-{
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-}
-
-__device__ __forceinline__ u32x4 stream_load(const uint16_t *p)
-{
-    // The cache is read once per call: a non-temporal load keeps it from displacing the data
-    // that is reused (queries, parked logits) and streams measurably faster on this chip.
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
-}
 
 // parked logits: fp32 [sequence][kv head][token (pitch)][Gp], Gp = G rounded up to 4 heads
 __host__ __device__ inline int park_heads(int G) { return (G + 3) / 4 * 4; }
-
-__device__ __forceinline__ void softmax_merge(float &m, float &z, float mo, float zo)
-{
-    const float M = fmaxf(m, mo);
-    z = z * fast_exp2(m - M) + zo * fast_exp2(mo - M);
-    m = M;
-}
 
 // One workgroup per (token range, kv head, sequence); its four waves walk interleaved 32-token
 // tiles.  A tile is loaded with 1 KB-contiguous 16-byte loads (4 rows of 256 B per instruction),

@@ -1,0 +1,444 @@
+// Focal-layer scoring with the logits kept on chip (Eq. 1; text under Eq. 2).
+//
+// The head average is taken after each head's softmax, so a score needs every head's
+// normaliser over the whole cache.  The two-kernel path parks all fp32 logits in HBM; mixing
+// those writes into the K stream costs far more than their bytes on this chip.  This kernel
+// keeps them in registers instead:
+//   - one 512-thread workgroup per (image-token range, sequence), at most one per compute unit,
+//     so the whole grid is resident at once;
+//   - wave w streams KV head w % Hkv (8/Hkv waves share a head and interleave its tiles), a
+//     32-token tile (8 KB) at a time.  Tiles travel HBM -> LDS directly (global_load_lds, 16 bytes
+//     per lane, two 8 KB slots per wave, no staging registers); the XOR swizzle that makes the
+//     MFMA operand reads conflict-free is applied by permuting which 16-byte chunk of a row each
+//     lane fetches;
+//   - C[head][token] = Q * K^T with v_mfma_f32_16x16x32_bf16 leaves 4 heads x 1 token per lane; those
+//     4 logits stay in 4 VGPRs named for the tile -- the image-tile loop is fully unrolled for
+//     that (up to 32 tiles = 128 VGPRs per lane); text tokens only feed the softmax statistics;
+//   - the ranges of one sequence exchange their per-head (max, sum-exp) through the workspace
+//     (agent-scope atomic stores and loads) and meet at a per-sequence barrier (atomic counter,
+//     bounded spin);
+//   - every wave then turns its parked logits into probabilities, the heads of a token are
+//     summed through LDS and the finished scores are written -- the only HBM writes.
+// Shapes that do not fit (group size > 8, Hkv not dividing 8, more sequences than compute
+// units, more than 32 tiles per wave, pages shorter than a tile) take the two-kernel path.
+#include "kernels.hpp"
+
+namespace fastocr {
+
+constexpr int kResWaves = 8;
+constexpr int kResThreads = 64 * kResWaves;
+constexpr int kResTmax = 32;          // image tiles per wave held in registers
+constexpr int kResTile = 32;
+constexpr int kResMaxHq = 64;
+
+#define RES_EACH_TILE(M)                                                                            \
+    M(0) M(1) M(2) M(3) M(4) M(5) M(6) M(7) M(8) M(9) M(10) M(11) M(12) M(13) M(14) M(15)               \
+    M(16) M(17) M(18) M(19) M(20) M(21) M(22) M(23) M(24) M(25) M(26) M(27) M(28) M(29) M(30) M(31)
+static_assert(kResTmax == 32, "RES_EACH_TILE lists kResTmax tiles");
+#define RES_DECLARE(J) f32x4 park_##J;
+// image tile J of the wave: multiply, keep the logits, refill the tile's LDS slot
+#define RES_STREAM_STEP(J)                                                                          \
+    {                                                                                               \
+        wait_and_read(ntext + (J), kb);                                                             \
+        issue_img((J) + 2, ntext + (J));                                                            \
+        park_##J = logits_of(kb, img_first(J) + tok_in_tile < r1);                                  \
+        if ((J) + 1 >= nimg) goto img_done;                                                         \
+    }
+// tile J after the barrier: probabilities of this lane's 4 heads, summed with the partner lane's 4
+#define RES_FINISH_STEP(J)                                                                          \
+    {                                                                                               \
+        float v = 0.f;                                                                              \
+        _Pragma("unroll") for (int r = 0; r < 4; ++r) v += fast_exp2(park_##J[r] - lh[r]);          \
+        v += __shfl_xor(v, 16);                                                                     \
+        if ((lg & 1) == 0) red[kvh * R + img_first(J) - r0 + tok_in_tile] = v;                      \
+        if ((J) + 1 >= nimg) goto fin_done;                                                         \
+    }
+
+// 16 bytes per lane from global memory straight into LDS: lane l's data lands at lds_base + 16 l
+// (lds_base is wave-uniform).  Completion is tracked by vmcnt like any other vector load, but the
+// compiler does not order later LDS reads after it: the reader waits for vmcnt itself.
+__device__ __forceinline__ void lds_dma16(const uint16_t *src, unsigned char *lds_base)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                     (__attribute__((address_space(3))) void *)lds_base, 16, 0, /*nt*/ 2);
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void *p)
+{
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)p;
+}
+
+bool resident_plan(const Shape &s, int num_cu, ResidentPlan *plan)
+{
+    const int Hkv = s.kv.n_kv_heads;
+    if (!s.fast || Hkv < 1 || s.n_q_heads % Hkv != 0) return false;
+    const int G = s.n_q_heads / Hkv;
+    if (G > 8 || s.n_q_heads > kResMaxHq) return false;
+    if (Hkv != 1 && Hkv != 2 && Hkv != 4 && Hkv != 8) return false;
+    if (s.batch < 1 || s.batch > num_cu) return false;
+    if (s.paged && s.kv.page_tokens < kResTile) return false;        // a tile may touch two pages at most
+    if (s.kv.stride_token > (1 << 24)) return false;                 // 32 rows of bytes must fit 32 bits
+    const int wpk = kResWaves / Hkv;
+    const int unit = kResTile * wpk;                       // tokens of one round of a head's waves
+    int nranges = num_cu / s.batch;
+    const int N = s.bv.max_vis_len;
+    int R = ((N + nranges - 1) / nranges + unit - 1) / unit * unit;
+    if (R < unit) R = unit;
+    if (R / unit > kResTmax) return false;
+    nranges = (N + R - 1) / R;
+    if (nranges < 1) nranges = 1;
+    plan->nranges = nranges;
+    plan->range_tokens = R;
+    plan->wpk = wpk;
+    return true;
+}
+
+size_t resident_workspace_bytes(const Shape &s, const ResidentPlan &p)
+{
+    size_t bytes = (size_t)s.batch * p.nranges * s.n_q_heads * 2 * sizeof(float);   // range statistics
+    bytes += (size_t)s.batch * p.nranges * sizeof(float);                              // image-mass partials
+    bytes += ((size_t)s.batch + 1) * sizeof(uint32_t);                                 // barrier counters + status
+    return bytes;
+}
+
+__global__ void resident_init_kernel(uint32_t *__restrict__ bar, int n)
+{
+    for (int i = threadIdx.x; i < n; i += blockDim.x) bar[i] = 0u;
+}
+
+template <bool PAGED>
+__global__ __launch_bounds__(kResThreads) void score_resident_kernel(
+    KvDev kv, BatchDev bv, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2,
+    int nranges, int R, float *part_ml, uint32_t *bar, long long spin_ticks,
+    float *__restrict__ scores, float *__restrict__ lse_out, float *__restrict__ mass_part)
+{
+    __shared__ __align__(16) unsigned char smem[kResWaves][2][8192];
+    __shared__ float sm_m[kResWaves][8], sm_z[kResWaves][8];
+    __shared__ float sm_lse[kResMaxHq];
+    __shared__ float sm_pm[kResWaves][64], sm_pz[kResWaves][64];
+    __shared__ float sm_red[kResWaves];
+    __shared__ int sm_met;
+
+    // wave-uniform quantities are kept in scalar registers: tile bookkeeping, addresses and loop
+    // exits then cost no vector instructions
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int li = lane & 15, lg = lane >> 4;
+    const int rng = blockIdx.x, b = blockIdx.y;
+    const int Hkv = kv.n_kv_heads;
+    const int wpk = kResWaves / Hkv;
+    const int kvh = wave % Hkv, sub = wave / Hkv;
+
+    const SeqGeom geo = seq_geom(bv, b);
+    const int S = geo.S, v0 = geo.v0, N = geo.N;
+    const int Tn = S - N;
+
+    // image tiles of this wave: tile ti = sub + j*wpk of the range, j = 0 .. nimg-1
+    const int r0 = rng * R, r1 = min(N, r0 + R);
+    const int nt_range = r1 > r0 ? (r1 - r0 + kResTile - 1) / kResTile : 0;
+    const int nimg = min(nt_range > sub ? (nt_range - sub + wpk - 1) / wpk : 0, kResTmax);
+    // text tiles of this wave: u = slot + i*nslots
+    const int ntt = (Tn + kResTile - 1) / kResTile;
+    const int slot = rng * wpk + sub, nslots = nranges * wpk;
+    const int ntext = ntt > slot ? (ntt - slot + nslots - 1) / nslots : 0;
+
+    // Q as the A operand (rows 0..7 for the tile's first 16 tokens, rows 8..15 for the second 16)
+    u32x4 qlo[4], qhi[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        qlo[kk] = u32x4{0u, 0u, 0u, 0u};
+        qhi[kk] = u32x4{0u, 0u, 0u, 0u};
+        const int hl = li, hh = li - 8;
+        if (hl < G && hl < 8)
+            qlo[kk] = *reinterpret_cast<const u32x4 *>(q + ((int64_t)b * Hq + (int64_t)kvh * G + hl) * 128 + 8 * (4 * kk + lg));
+        if (hh >= 0 && hh < G)
+            qhi[kk] = *reinterpret_cast<const u32x4 *>(q + ((int64_t)b * Hq + (int64_t)kvh * G + hh) * 128 + 8 * (4 * kk + lg));
+    }
+    const uint16_t *kbase = reinterpret_cast<const uint16_t *>(kv.k);
+
+    // The waves of the grid advance in lock step and their streams start at addresses that differ
+    // by large powers of two, so each wave walks its image tiles in a rotated order (park slot x
+    // holds tile x + rot) to spread the grid over the memory channels.
+    const int rot = nimg > 0 ? (wave * 5 + rng * 3 + b * 7) % nimg : 0;
+    auto img_first = [&](int x) {                                                  // span-relative
+        int j = x + rot;
+        j = j >= nimg ? j - nimg : j;
+        return r0 + (sub + j * wpk) * kResTile;
+    };
+    auto text_first = [&](int x) { return (slot + x * nslots) * kResTile; };       // text-relative
+
+    // A tile goes into LDS slot (sequence number & 1) of the wave: load e brings rows 4e .. 4e+3,
+    // lane (lg, li) the 16-byte chunk li ^ (row & 15) of row 4e + lg, which lands at
+    // slot + 1024 e + 16 lane.  Rows past the end of a ragged tile are clamped to its last row.
+    // Addresses are a wave-uniform 64-bit base (scalar registers) plus a 32-bit byte offset per lane.
+    const int64_t seq_base = row_offset<false>(kv, b, 0, kvh);
+    const uint32_t stride_b = (uint32_t)kv.stride_token * 2u;            // bytes; 32 rows fit 32 bits (host-checked)
+    const uint32_t rowoff_lg = (uint32_t)lg * stride_b;
+    uint32_t chunk_b[4];                                 // byte offset of this lane's chunk, by e & 3
+#pragma unroll
+    for (int k = 0; k < 4; ++k) chunk_b[k] = 16u * (uint32_t)((li ^ lg) ^ (4 * k));
+    const unsigned char *kbytes = reinterpret_cast<const unsigned char *>(kv.k);
+
+    // rows first_tok .. first_tok + rv - 1 of the sequence, contiguous token indices
+    auto issue_run = [&](int first_tok, int rv, int seq_no) {
+        unsigned char *dst = smem[wave][seq_no & 1];
+        const uint32_t limit = (uint32_t)(rv - 1) * stride_b;
+        if (PAGED) {
+            const int pt = kv.page_tokens;
+            const int pg0 = first_tok / pt, in0 = first_tok - pg0 * pt;
+            const int32_t *bt = kv.block_table + (int64_t)b * kv.max_pages;
+            const int64_t pa = bt[min(pg0, kv.max_pages - 1)], pb = bt[min(pg0 + 1, kv.max_pages - 1)];
+            // row r of the tile lives at base_a + r*stride while in0 + r < pt, else at base_b + r*stride
+            const unsigned char *base_a = kbytes + 2 * (pa * kv.stride_page + (int64_t)kvh * kv.stride_head + (int64_t)in0 * kv.stride_token);
+            const unsigned char *base_b = kbytes + 2 * (pb * kv.stride_page + (int64_t)kvh * kv.stride_head + (int64_t)(in0 - pt) * kv.stride_token);
+            const uint32_t split = (uint32_t)(pt - in0) * stride_b;      // first byte offset of the second page
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t ro = min(rowoff_lg + (uint32_t)(4 * e) * stride_b, limit);
+                const unsigned char *base = ro >= split ? base_b : base_a;
+                lds_dma16(reinterpret_cast<const uint16_t *>(base + (ro + chunk_b[e & 3])), dst + 1024 * e);
+            }
+        } else {
+            const unsigned char *base = kbytes + 2 * (seq_base + (int64_t)first_tok * kv.stride_token);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t ro = min(rowoff_lg + (uint32_t)(4 * e) * stride_b, limit);
+                lds_dma16(reinterpret_cast<const uint16_t *>(base + (ro + chunk_b[e & 3])), dst + 1024 * e);
+            }
+        }
+    };
+    // image tile x of the wave (past the last one the last is fetched again: it is still in cache,
+    // and the issue stays unconditional)
+    auto issue_img = [&](int x, int seq_no) {
+        const int jf = img_first(min(x, nimg - 1));
+        issue_run(v0 + jf, min(kResTile, r1 - jf), seq_no);
+    };
+    // text tile x of the wave: text positions map to tokens with a gap at the image span, so the
+    // rows are addressed one by one
+    auto issue_text = [&](int x, int seq_no) {
+        const int tf = text_first(min(x, ntext - 1));
+        unsigned char *dst = smem[wave][seq_no & 1];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int tc = min(tf + 4 * e + lg, Tn - 1);
+            const int tok = tc < v0 ? tc : tc + N;
+            lds_dma16(kbase + row_offset<PAGED>(kv, b, tok, kvh) + chunk_b[e & 3] / 2, dst + 1024 * e);
+        }
+    };
+
+    const int hbase = 4 * (lg & 1);
+    const int tok_in_tile = li + 16 * (lg >> 1);
+    float m[4], z[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) { m[r] = kMinusHuge; z[r] = 0.f; }
+
+    // LDS byte addresses of this lane's four B-operand chunks (rows li and 16 + li of slot 0)
+    uint32_t rd_addr[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        rd_addr[kk] = lds_address(&smem[wave][0][0]) + li * 256 + ((((4 * kk + lg) ^ li) & 15) << 4);
+
+    // Tile number seq_no of the wave has landed once at most the 8 loads of the next tile are
+    // outstanding; read it in the MFMA B layout.  The reads are written in assembly together with
+    // their waits: the compiler does not order LDS reads after loads that land in LDS by
+    // themselves (left to itself it waits for ALL outstanding loads, the prefetch included), and
+    // it must not move the products above the wait either.
+    auto wait_and_read = [&](int seq_no, u32x4(&kb)[8]) {
+        const uint32_t so = (seq_no & 1) * 8192;
+        asm volatile(
+            "s_waitcnt vmcnt(8)\n\t"
+            "ds_read_b128 %0, %8\n\t"
+            "ds_read_b128 %1, %9\n\t"
+            "ds_read_b128 %2, %10\n\t"
+            "ds_read_b128 %3, %11\n\t"
+            "ds_read_b128 %4, %8 offset:4096\n\t"
+            "ds_read_b128 %5, %9 offset:4096\n\t"
+            "ds_read_b128 %6, %10 offset:4096\n\t"
+            "ds_read_b128 %7, %11 offset:4096\n\t"
+            "s_waitcnt lgkmcnt(0)"
+            : "=&v"(kb[0]), "=&v"(kb[1]), "=&v"(kb[2]), "=&v"(kb[3]), "=&v"(kb[4]), "=&v"(kb[5]), "=&v"(kb[6]), "=&v"(kb[7])
+            : "v"(rd_addr[0] + so), "v"(rd_addr[1] + so), "v"(rd_addr[2] + so), "v"(rd_addr[3] + so)
+            : "memory");
+    };
+    // logits (log2 domain) of this lane's token for its 4 heads; dead positions come out -inf
+    auto logits_of = [&](u32x4(&kb)[8], bool live) -> f32x4 {
+        f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qlo[kk]),
+                                                        __builtin_bit_cast(bf16x8, kb[kk]), s, 0, 0, 0);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qhi[kk]),
+                                                        __builtin_bit_cast(bf16x8, kb[4 + kk]), s, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            s[r] = live ? s[r] * scale_log2 : -INFINITY;
+            const float mn = fmaxf(m[r], s[r]);
+            z[r] = z[r] * fast_exp2(m[r] - mn) + fast_exp2(s[r] - mn);
+            m[r] = mn;
+        }
+        return s;
+    };
+
+    // ---- stream: text tiles (statistics only), then image tiles (logits parked in registers) -----
+    // The wave's tiles are numbered 0 .. ntext + nimg - 1 in that order; tile n uses slot n & 1 and
+    // two tiles are always in flight.
+    RES_EACH_TILE(RES_DECLARE)
+    u32x4 kb[8];
+    if (ntext + nimg > 0) {
+        // the first two tiles
+        if (ntext > 0) issue_text(0, 0); else issue_img(0, 0);
+        if (ntext > 1) issue_text(1, 1); else if (nimg > 0) issue_img(1 - ntext, 1); else issue_text(1, 1);
+        for (int x = 0; x < ntext; ++x) {
+            wait_and_read(x, kb);
+            if (x + 2 < ntext || nimg == 0) issue_text(x + 2, x); else issue_img(x + 2 - ntext, x);
+            (void)logits_of(kb, text_first(x) + tok_in_tile < Tn);
+        }
+    }
+    if (nimg > 0) {
+        RES_EACH_TILE(RES_STREAM_STEP)
+    }
+img_done:
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the trailing refills must not land later
+
+    // ---- range statistics: lanes -> waves -> workgroup -> workspace ------------------------------
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) softmax_merge(m[r], z[r], __shfl_xor(m[r], o), __shfl_xor(z[r], o));
+        softmax_merge(m[r], z[r], __shfl_xor(m[r], 32), __shfl_xor(z[r], 32));
+    }
+    if (li == 0 && lg < 2) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) { sm_m[wave][hbase + r] = m[r]; sm_z[wave][hbase + r] = z[r]; }
+    }
+    __syncthreads();
+    // The statistics cross compute units (and XCDs, each with its own L2) through agent-scope
+    // atomic stores and loads, which go through to memory, instead of plain stores bracketed by
+    // release/acquire fences: a fence writes back or invalidates the XCD's whole L2 and costs
+    // microseconds here.  Order: each publishing thread waits until its stores are acknowledged,
+    // the workgroup barrier collects them, then thread 0 counts the range in.
+    unsigned long long *my_part = reinterpret_cast<unsigned long long *>(part_ml) + ((int64_t)b * nranges + rng) * Hq;
+    if ((int)threadIdx.x < Hq) {
+        const int h = threadIdx.x, g = h / G, x = h - g * G;
+        float M = kMinusHuge, Z = 0.f;
+        for (int sb = 0; sb < wpk; ++sb) softmax_merge(M, Z, sm_m[g + sb * Hkv][x], sm_z[g + sb * Hkv][x]);
+        const unsigned long long mz = (unsigned long long)__float_as_uint(M) | ((unsigned long long)__float_as_uint(Z) << 32);
+        __hip_atomic_store(&my_part[h], mz, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    // ---- per-sequence barrier: every range of the sequence has published its statistics ---------
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __hip_atomic_fetch_add(&bar[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const long long t_start = wall_clock64();
+        bool ok = true;
+        while (__hip_atomic_load(&bar[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (uint32_t)nranges) {
+            __builtin_amdgcn_s_sleep(1);
+            if (wall_clock64() - t_start > spin_ticks) { ok = false; break; }
+        }
+        if (!ok) __hip_atomic_fetch_or(&bar[gridDim.y], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sm_met = ok ? 1 : 0;
+    }
+    __syncthreads();
+    if (!sm_met) {
+        // the sequence's other ranges never arrived (the grid was not resident as a whole):
+        // poison this range's scores rather than publish numbers built on missing statistics
+        for (int i = threadIdx.x; i < r1 - r0; i += kResThreads)
+            scores[(int64_t)b * bv.max_vis_len + r0 + i] = __builtin_nanf("");
+        return;
+    }
+    // every head's log-sum-exp from the ranges' statistics: wave w merges ranges w, w+8, ..; lane = head
+    {
+        float M = kMinusHuge, Z = 0.f;
+        if (lane < Hq) {
+            const unsigned long long *pp = reinterpret_cast<const unsigned long long *>(part_ml) + (int64_t)b * nranges * Hq + lane;
+            for (int rr = wave; rr < nranges; rr += kResWaves) {
+                const unsigned long long mz = __hip_atomic_load(pp + (int64_t)rr * Hq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                softmax_merge(M, Z, __uint_as_float((uint32_t)mz), __uint_as_float((uint32_t)(mz >> 32)));
+            }
+        }
+        sm_pm[wave][lane] = M;
+        sm_pz[wave][lane] = Z;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < Hq) {
+        const int h = threadIdx.x;
+        float M = kMinusHuge, Z = 0.f;
+#pragma unroll
+        for (int w = 0; w < kResWaves; ++w) softmax_merge(M, Z, sm_pm[w][h], sm_pz[w][h]);
+        const float l2 = Z > 0.f ? M + log2f(Z) : -INFINITY;
+        sm_lse[h] = l2;
+        if (lse_out && rng == 0) lse_out[(int64_t)b * Hq + h] = l2 * kLn2;
+    }
+    __syncthreads();
+
+    // ---- probabilities of the parked logits, summed over the heads of each token ---------------
+    float lh[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) lh[r] = (hbase + r < G) ? sm_lse[kvh * G + hbase + r] : INFINITY;
+    float *red = reinterpret_cast<float *>(&smem[0][0][0]);          // [Hkv][R], at most 32 KB
+    if (nimg > 0) {
+        RES_EACH_TILE(RES_FINISH_STEP)
+    }
+fin_done:
+    __syncthreads();
+    float local = 0.f;
+    const float inv = 1.0f / (float)Hq;
+    for (int i = threadIdx.x; i < r1 - r0; i += kResThreads) {
+        float a = 0.f;
+        for (int g = 0; g < Hkv; ++g) a += red[g * R + i];
+        a *= inv;
+        scores[(int64_t)b * bv.max_vis_len + r0 + i] = a;
+        local += a;
+    }
+    if (mass_part) {
+        local = wave_sum(local);
+        if (lane == 0) sm_red[wave] = local;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float t = 0.f;
+            for (int w = 0; w < kResWaves; ++w) t += sm_red[w];
+            mass_part[(int64_t)b * nranges + rng] = t;
+        }
+    }
+}
+
+__global__ void resident_mass_kernel(const float *__restrict__ mass_part, int nranges, float *__restrict__ img_mass)
+{
+    const int b = blockIdx.x;
+    float t = 0.f;
+    for (int x = threadIdx.x; x < nranges; x += 64) t += mass_part[(int64_t)b * nranges + x];
+    t = wave_sum(t);
+    if (threadIdx.x == 0) img_mass[b] = t;
+}
+
+hipError_t launch_score_resident(const Shape &s, const ResidentPlan &p, const void *q, float scale, float *scores,
+                                 float *lse, float *img_mass, void *ws, hipStream_t stream)
+{
+    const size_t nstat = (size_t)s.batch * p.nranges * s.n_q_heads * 2;
+    float *part_ml = reinterpret_cast<float *>(ws);
+    float *mass_part = part_ml + nstat;
+    uint32_t *bar = reinterpret_cast<uint32_t *>(mass_part + (size_t)s.batch * p.nranges);
+    const float scale_log2 = scale * kLog2e;
+    const int G = s.n_q_heads / s.kv.n_kv_heads;
+    // a range waits at most this long for its sequence's other ranges (they run concurrently and
+    // finish within microseconds of each other); past it the call's scores are NaN but it ends
+    const long long spin_ticks = 100000000ll / 4;          // 0.25 s of the 100 MHz wall clock
+
+    resident_init_kernel<<<1, 256, 0, stream>>>(bar, s.batch + 1);
+    dim3 grid(p.nranges, s.batch), block(kResThreads);
+    if (s.paged)
+        FASTOCR_LAUNCH(K_SCORE_LOGITS, score_resident_kernel<true>, grid, block, 0, stream, s.kv, s.bv,
+                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, p.nranges, p.range_tokens, part_ml, bar,
+                       spin_ticks, scores, lse, img_mass ? mass_part : nullptr);
+    else
+        FASTOCR_LAUNCH(K_SCORE_LOGITS, score_resident_kernel<false>, grid, block, 0, stream, s.kv, s.bv,
+                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, p.nranges, p.range_tokens, part_ml, bar,
+                       spin_ticks, scores, lse, img_mass ? mass_part : nullptr);
+    if (img_mass) resident_mass_kernel<<<s.batch, 64, 0, stream>>>(mass_part, p.nranges, img_mass);
+    return hipGetLastError();
+}
+
+}  // namespace fastocr

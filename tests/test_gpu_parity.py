@@ -194,3 +194,76 @@ def test_degenerate_sequences():
     full_check(problem_from_case(case), 0.5, "degenerate fp32")
     out, _ = p.dense()
     assert torch.all(out[4] == 0)                      # an empty sequence attends nothing
+
+
+# ------------------------------------------------------------------ both scoring paths
+
+@pytest.mark.parametrize("resident", [1, 0])
+@pytest.mark.parametrize("Hq,Hkv", [(28, 4), (64, 8), (8, 1), (6, 2)])
+def test_scoring_paths_agree_with_the_oracle(resident, Hq, Hkv):
+    """Register-resident scoring (one kernel, per-sequence barrier) and the two-kernel path that
+    parks logits in the workspace, on a batch whose ranges hold several tiles per wave."""
+    fb.set_tuning("score_resident", resident)
+    try:
+        case = TinyCase(seed=200 + Hq, B=40, Hq=Hq, Hkv=Hkv, d=128, n_vis=[1500 + 37 * i for i in range(40)],
+                        pre=[i % 7 * 5 for i in range(40)], post=[(i * 13) % 90 for i in range(40)], dtype="bf16")
+        p = problem_from_case(case)
+        ref_sc, ref_lse, ref_mass = oracle.focal_score(*p.oracle_args())
+        sc, lse, mass = p.scores(want_lse=True, want_mass=True)
+        check_scores(sc, ref_sc, p.vis_len, f"resident={resident} scores")
+        assert np.allclose(lse.cpu().numpy(), ref_lse, rtol=2e-5, atol=2e-5)
+        assert np.allclose(mass.cpu().numpy(), ref_mass, atol=2e-5)
+    finally:
+        fb.set_tuning("score_resident", 1)
+
+
+@pytest.mark.parametrize("resident", [1, 0])
+def test_scoring_paths_paged(resident):
+    fb.set_tuning("score_resident", resident)
+    try:
+        wl = fs.config(5, batch=24, steps=4, n_visual=(600, 3000), grid_w=(20, 60), text_prefix=(3, 300), page_tokens=64)
+        bt = fs.make_batch(wl, device=DEV)
+        q = fs.queries_for_step(bt, 3, [x[2] for x in fs.centres(bt)])
+        p = GpuProblem(bt.k, bt.v, q, bt.seq_len(3), bt.vis_start, bt.n_vis, wl.head_dim ** -0.5,
+                       block_table=bt.block_table)
+        ref_sc, ref_lse, _ = oracle.focal_score(*p.oracle_args())
+        sc, lse, _ = p.scores(want_lse=True)
+        check_scores(sc, ref_sc, p.vis_len, f"paged resident={resident}")
+        assert np.allclose(lse.cpu().numpy(), ref_lse, rtol=2e-5, atol=2e-5)
+    finally:
+        fb.set_tuning("score_resident", 1)
+
+
+# ------------------------------------------------------------------ full size, the benchmark's launch configuration
+
+def test_config4_full_size_in_the_benchmark_launch_configuration():
+    """The metric workload at its full size (batch 16, Hq 64, Hkv 8, N = 16384) with the launch
+    shapes bench.py times (automatic splits, register-resident scoring at its full depth of 32
+    tiles per wave): every output of the three-step path and of the dense comparator against the
+    oracle, which needs a few seconds for this size."""
+    wl = fs.config(4, steps=16)
+    bt = fs.make_batch(wl, device=DEV)
+    t = 16
+    q = fs.queries_for_step(bt, t, [x[t - 1] for x in fs.centres(bt)])
+    p = GpuProblem(bt.k, bt.v, q, bt.seq_len(t), bt.vis_start, bt.n_vis, wl.head_dim ** -0.5)
+    oc = p.oracle_args()
+    ref_sc, ref_lse, ref_mass = oracle.focal_score(*oc)
+    sc, lse, mass = p.scores(want_lse=True, want_mass=True)
+    check_scores(sc, ref_sc, p.vis_len, "config4 scores")
+    assert np.allclose(lse.cpu().numpy(), ref_lse, rtol=2e-5, atol=2e-5)
+    assert np.allclose(mass.cpu().numpy(), ref_mass, atol=2e-5)
+    for tau in (0.05, 0.02):
+        ref_idx, ref_cnt = oracle.topk_fixation(ref_sc, p.vis_len, tau)
+        idx, cnt = p.topk(sc, tau)
+        idx_h, cnt_h, sc_h = idx.cpu().numpy(), cnt.cpu().numpy(), sc.cpu().numpy()
+        for b in range(p.B):
+            check_set_valid(idx_h[b], int(cnt_h[b]), ref_sc[b], int(ref_cnt[b]), f"config4 tau={tau} b={b}")
+            assert np.array_equal(idx_h[b, : cnt_h[b]], oracle.topk(sc_h[b], int(ref_cnt[b])))
+        # warm start from the other tau's set (wrong size) and from itself
+        idx2, cnt2 = p.topk(sc, tau, prev_idx=idx.clone(), prev_cnt=cnt.clone())
+        assert torch.equal(idx2, idx) and torch.equal(cnt2, cnt)
+        ref_sparse, _ = oracle.decode_attn(*oc, ref_idx, ref_cnt)
+        sel = torch.from_numpy(ref_idx).to(DEV).contiguous()
+        check_out(p.sparse(sel, torch.from_numpy(ref_cnt).to(DEV)), ref_sparse, f"config4 sparse tau={tau}")
+    ref_dense, _ = oracle.decode_attn(*oc)
+    check_out(p.dense()[0], ref_dense, "config4 dense")
