@@ -9,8 +9,8 @@
 
 namespace fastocr {
 
-int g_tune_k_via_lds = 1;
 static int g_tune_score_resident = 1;
+int g_tune_attn_waves = 4;
 static int g_tune_splits[4] = {0, 0, 0, 0};     // indexed by fastocr_op
 
 // ---- per-kernel timers ------------------------------------------------------------------
@@ -108,6 +108,9 @@ static int choose_splits(int op, const Shape &s, int max_positions)
         // unit (few, long, equally sized streams), the plain-FMA kernels with many small ones.
         const int target_wg = fast ? kNumCU : 8 * kNumCU;
         nsplit = (target_wg + streams - 1) / (streams > 0 ? streams : 1);
+        // attention with at least half a chip of streams: one eight-wave workgroup per stream writes
+        // the final output itself (no partials, no merge kernel)
+        if (fast && op == FASTOCR_OP_SPARSE_DECODE_ATTN && 2 * streams >= kNumCU) nsplit = 1;
     }
     if (nsplit > by_work) nsplit = by_work;
     if (nsplit > 256) nsplit = 256;
@@ -319,7 +322,7 @@ int fastocr_set_tuning(const char *key, int value)
     if (!strcmp(key, "splits_score")) g_tune_splits[FASTOCR_OP_FOCAL_SCORE] = value;
     else if (!strcmp(key, "splits_sparse")) g_tune_splits[FASTOCR_OP_SPARSE_DECODE_ATTN] = value;
     else if (!strcmp(key, "splits_dense")) g_tune_splits[FASTOCR_OP_DENSE_DECODE_ATTN] = value;
-    else if (!strcmp(key, "k_via_lds")) g_tune_k_via_lds = value ? 1 : 0;
+    else if (!strcmp(key, "attn_waves")) g_tune_attn_waves = value;
     else if (!strcmp(key, "score_resident")) g_tune_score_resident = value ? 1 : 0;
     else return FASTOCR_EINVAL;
     return FASTOCR_OK;

@@ -15,15 +15,15 @@
 // B layout the second one needs, so probabilities never cross lanes.  V rows are loaded
 // coalesced (16 lanes x 16 B = one 256 B row) and transposed in registers with v_perm_b32.
 // K is loaded the same coalesced way and re-laid to the A layout through a wave-private,
-// XOR-swizzled LDS tile (or loaded straight in A layout, 64 B per row per instruction).
+// XOR-swizzled LDS tile.
 #include "kernels.hpp"
 
 namespace fastocr {
 
-extern int g_tune_k_via_lds;
+extern int g_tune_attn_waves;
+
 
 constexpr int kTile = 32;          // tokens per wave tile (two 16-token MFMA tiles)
-constexpr int kWaves = 4;
 
 // Row of the 32-token tile that lane group `lg` holds as element e of its 8-token k-block:
 // elements 0..3 come from the first 16-token half, 4..7 from the second.
@@ -32,11 +32,14 @@ __device__ __forceinline__ int tile_row(int lg, int e) { return (e < 4) ? (4 * l
 // -----------------------------------------------------------------------------------------
 // MFMA kernel: bf16, head_dim = 128, G <= 16.
 // -----------------------------------------------------------------------------------------
-template <bool GATHER, bool PAGED, bool KLDS>
-__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
+// kWaves waves per workgroup walk the range; with DIRECT (a single range per stream) the merged
+// result is final and is written normalised to `out`, otherwise as an fp32 partial.
+template <bool GATHER, bool PAGED, int kWaves, bool DIRECT>
+__global__ __launch_bounds__(64 * kWaves, 8 / kWaves) void attn_mfma_kernel(
     KvDev kv, BatchDev bv, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2,
     const int32_t *__restrict__ sel_idx, const int32_t *__restrict__ sel_cnt, int64_t kmax,
-    float *__restrict__ part_o, float *__restrict__ part_ml, int nsplit)
+    float *__restrict__ part_o, float *__restrict__ part_ml, int nsplit, uint16_t *__restrict__ out,
+    float *__restrict__ lse)
 {
     __shared__ __align__(16) unsigned char smem[kWaves][8192];
     __shared__ float sm_m[kWaves][16], sm_z[kWaves][16];
@@ -87,19 +90,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
             if (GATHER || PAGED) ro = __shfl(off, r);
             else ro = seq_base + (int64_t)min(tile * kTile + r, L - 1) * kv.stride_token;
             V[e] = stream_load(vbase + ro + 8 * li);
-            if (KLDS) K[e] = stream_load(kbase + ro + 8 * li);
-        }
-        if (!KLDS) {
-#pragma unroll
-            for (int T = 0; T < 2; ++T) {
-                const int r = 16 * T + li;
-                int64_t ro;
-                if (GATHER || PAGED) ro = __shfl(off, r);
-                else ro = seq_base + (int64_t)min(tile * kTile + r, L - 1) * kv.stride_token;
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk)
-                    K[4 * T + kk] = stream_load(kbase + ro + 8 * (4 * kk + lg));
-            }
+            K[e] = stream_load(kbase + ro + 8 * li);
         }
     };
 
@@ -110,7 +101,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
 
     auto compute = [&](int tile, u32x4(&K)[8], u32x4(&V)[8]) {
         u32x4 ka[8];
-        if (KLDS) {
+        {
             unsigned char *sw = smem[wave];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -126,9 +117,6 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
                     ka[4 * T + kk] = *reinterpret_cast<const u32x4 *>(sw + (16 * T + li) * 256 + (((c ^ li) & 15) << 4));
                 }
             wave_lds_fence();
-        } else {
-#pragma unroll
-            for (int x = 0; x < 8; ++x) ka[x] = K[x];
         }
         f32x4 s0 = f32x4{0.f, 0.f, 0.f, 0.f}, s1 = s0;
 #pragma unroll
@@ -180,23 +168,44 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
         u32x4 KA[8], VA[8], KB[8], VB[8];
         int tile = t0 + wave;
         const int last = tile + (t1 - 1 - tile) / kWaves * kWaves;
-        int64_t off_a = 0, off_b = 0;
-        if (GATHER || PAGED) off_a = rowoff_of(tile);
-        load_tile(tile, off_a, KA, VA);
-        if (GATHER || PAGED) off_b = rowoff_of(min(tile + kWaves, last));
-        while (true) {
-            load_tile(min(tile + kWaves, last), off_b, KB, VB);
-            if (GATHER || PAGED) off_a = rowoff_of(min(tile + 2 * kWaves, last));
-            compute(tile, KA, VA);
-            tile += kWaves;
-            if (tile > last) break;
-            load_tile(min(tile + kWaves, last), off_a, KA, VA);
-            if (GATHER || PAGED) off_b = rowoff_of(min(tile + 2 * kWaves, last));
-            compute(tile, KB, VB);
-            tile += kWaves;
-            if (tile > last) break;
+        if (!(GATHER || PAGED)) {
+            load_tile(tile, 0, KA, VA);
+            while (true) {
+                load_tile(min(tile + kWaves, last), 0, KB, VB);
+                compute(tile, KA, VA);
+                tile += kWaves;
+                if (tile > last) break;
+                load_tile(min(tile + kWaves, last), 0, KA, VA);
+                compute(tile, KB, VB);
+                tile += kWaves;
+                if (tile > last) break;
+            }
+        } else {
+            // Row offsets come from memory (selected indices, block table).  They are fetched a
+            // whole group of tiles ahead and BEFORE that group's K/V loads are issued: loads return
+            // in order, so waiting for an offset never waits for a tile issued after it.
+            constexpr int kGroup = 4;
+            int64_t offc[kGroup], offn[kGroup];
+#pragma unroll
+            for (int i = 0; i < kGroup; ++i) offc[i] = rowoff_of(min(tile + i * kWaves, last));
+            load_tile(tile, offc[0], KA, VA);
+            while (true) {
+#pragma unroll
+                for (int i = 0; i < kGroup; ++i) offn[i] = rowoff_of(min(tile + (kGroup + i) * kWaves, last));
+#pragma unroll
+                for (int i = 0; i < kGroup; ++i) {
+                    const int64_t onext = (i + 1 < kGroup) ? offc[i + 1] : offn[0];
+                    if ((i & 1) == 0) { load_tile(min(tile + kWaves, last), onext, KB, VB); compute(tile, KA, VA); }
+                    else              { load_tile(min(tile + kWaves, last), onext, KA, VA); compute(tile, KB, VB); }
+                    tile += kWaves;
+                    if (tile > last) goto tiles_done;
+                }
+#pragma unroll
+                for (int i = 0; i < kGroup; ++i) offc[i] = offn[i];
+            }
         }
     }
+tiles_done:
 
     // ---- cross-wave merge through LDS -----------------------------------------------------
     zl += __shfl_xor(zl, 16);
@@ -209,7 +218,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
     if (lg == 0) { sm_m[wave][li] = m; sm_z[wave][li] = zl; }
     __syncthreads();
 
-    for (int idx = threadIdx.x; idx < G * 128; idx += 256) {
+    for (int idx = threadIdx.x; idx < G * 128; idx += 64 * kWaves) {
         const int hh = idx >> 7, c = idx & 127;
         float M = sm_m[0][hh];
 #pragma unroll
@@ -223,9 +232,15 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
                 Z += f * sm_z[w][hh];
             }
         }
-        const int64_t ph = ((int64_t)b * Hq + (int64_t)kvh * G + hh) * nsplit + split;
-        part_o[ph * 128 + c] = o;
-        if (c == 0) { part_ml[ph * 2] = M; part_ml[ph * 2 + 1] = Z; }
+        if (DIRECT) {
+            const int64_t bh = (int64_t)b * Hq + (int64_t)kvh * G + hh;
+            out[bh * 128 + c] = f32_to_bf16_bits(Z > 0.f ? o / Z : 0.f);
+            if (lse && c == 0) lse[bh] = Z > 0.f ? (M + log2f(Z)) * kLn2 : -INFINITY;
+        } else {
+            const int64_t ph = ((int64_t)b * Hq + (int64_t)kvh * G + hh) * nsplit + split;
+            part_o[ph * 128 + c] = o;
+            if (c == 0) { part_ml[ph * 2] = M; part_ml[ph * 2 + 1] = Z; }
+        }
     }
 }
 
@@ -329,7 +344,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(
 // -----------------------------------------------------------------------------------------
 // Host side
 // -----------------------------------------------------------------------------------------
-int attn_tile_tokens(const Shape &s) { return mfma_path(s) ? kTile * kWaves : 64; }
+int attn_tile_tokens(const Shape &s) { return mfma_path(s) ? kTile * 4 : 64; }
 
 size_t attn_workspace_bytes(const Shape &s, int nsplit)
 {
@@ -340,22 +355,23 @@ size_t attn_workspace_bytes(const Shape &s, int nsplit)
 template <bool GATHER, bool PAGED>
 static void launch_mfma(int kid, const Shape &s, const void *q, float scale_log2, const int32_t *sel_idx,
                         const int32_t *sel_cnt, int64_t kmax, float *part_o, float *part_ml,
-                        int nsplit, hipStream_t stream)
+                        int nsplit, void *out, float *lse, hipStream_t stream)
 {
     const int G = s.n_q_heads / s.kv.n_kv_heads;
-    dim3 grid(nsplit, s.kv.n_kv_heads, s.batch), block(256);
-    if (g_tune_k_via_lds)
-        FASTOCR_LAUNCH(kid, (attn_mfma_kernel<GATHER, PAGED, true>), grid, block, 0, stream,
-            s.kv, s.bv, (const uint16_t *)q, s.n_q_heads, G, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit);
-    else
-        FASTOCR_LAUNCH(kid, (attn_mfma_kernel<GATHER, PAGED, false>), grid, block, 0, stream,
-            s.kv, s.bv, (const uint16_t *)q, s.n_q_heads, G, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit);
+    dim3 grid(nsplit, s.kv.n_kv_heads, s.batch);
+#define FASTOCR_ATTN(W, D) FASTOCR_LAUNCH(kid, (attn_mfma_kernel<GATHER, PAGED, W, D>), grid, dim3(64 * W), 0, stream, \
+        s.kv, s.bv, (const uint16_t *)q, s.n_q_heads, G, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, \
+        (uint16_t *)out, lse)
+    if (nsplit == 1) FASTOCR_ATTN(8, true);          // one range per stream: eight waves, final output
+    else if (g_tune_attn_waves == 8) FASTOCR_ATTN(8, false);
+    else FASTOCR_ATTN(4, false);
+#undef FASTOCR_ATTN
 }
 
 template <typename T, bool GATHER, bool PAGED>
 static void launch_generic(int kid, const Shape &s, const void *q, float scale_log2, const int32_t *sel_idx,
                            const int32_t *sel_cnt, int64_t kmax, float *part_o, float *part_ml,
-                           int nsplit, hipStream_t stream)
+                           int nsplit, void *, float *, hipStream_t stream)
 {
     dim3 grid(nsplit, s.n_q_heads, s.batch), block(64);
     FASTOCR_LAUNCH(kid, (attn_generic_kernel<T, GATHER, PAGED>), grid, block, 0, stream,
@@ -375,10 +391,10 @@ hipError_t launch_attn(const Shape &s, const void *q, float scale, const int32_t
 
 #define FASTOCR_DISPATCH(FN, ...)                                                                      \
     do {                                                                                               \
-        if (gather) { if (s.paged) FN<__VA_ARGS__ true, true>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, stream); \
-                      else         FN<__VA_ARGS__ true, false>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, stream); } \
-        else        { if (s.paged) FN<__VA_ARGS__ false, true>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, stream); \
-                      else         FN<__VA_ARGS__ false, false>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, stream); } \
+        if (gather) { if (s.paged) FN<__VA_ARGS__ true, true>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, out, lse, stream); \
+                      else         FN<__VA_ARGS__ true, false>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, out, lse, stream); } \
+        else        { if (s.paged) FN<__VA_ARGS__ false, true>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, out, lse, stream); \
+                      else         FN<__VA_ARGS__ false, false>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, out, lse, stream); } \
     } while (0)
     if (mfma_path(s)) {
         FASTOCR_DISPATCH(launch_mfma, );
@@ -390,6 +406,7 @@ hipError_t launch_attn(const Shape &s, const void *q, float scale, const int32_t
 #undef FASTOCR_DISPATCH
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (mfma_path(s) && nsplit == 1) return hipSuccess;        // the kernel wrote the final output itself
 
     dim3 grid(s.n_q_heads, s.batch), block(256);
     if (s.dtype == DT_BF16)

@@ -89,16 +89,6 @@ def test_mfma_bf16_ragged_batch(Hq, Hkv):
     full_check(problem_from_case(case), 0.05, f"mfma Hq{Hq} Hkv{Hkv}")
 
 
-@pytest.mark.parametrize("k_via_lds", [1, 0])
-def test_mfma_both_key_load_paths(k_via_lds):
-    fb.set_tuning("k_via_lds", k_via_lds)
-    try:
-        case = TinyCase(seed=5, B=2, Hq=28, Hkv=4, d=128, n_vis=[900, 333], pre=[17, 3], post=[11, 64], dtype="bf16")
-        full_check(problem_from_case(case), 0.1, f"k_via_lds={k_via_lds}")
-    finally:
-        fb.set_tuning("k_via_lds", 1)
-
-
 @pytest.mark.parametrize("nsplit", [1, 2, 5, 64])
 def test_split_counts_give_the_same_result(nsplit):
     for key in ("splits_score", "splits_dense", "splits_sparse"):
