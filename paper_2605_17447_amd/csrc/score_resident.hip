@@ -21,6 +21,8 @@
 //     summed through LDS and the finished scores are written -- the only HBM writes.
 // Shapes that do not fit (group size > 8, Hkv not dividing 8, more sequences than compute
 // units, more than 32 tiles per wave, pages shorter than a tile) take the two-kernel path.
+#include <atomic>
+
 #include "kernels.hpp"
 
 namespace fastocr {
@@ -68,6 +70,15 @@ __device__ __forceinline__ uint32_t lds_address(const void *p)
     return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)p;
 }
 
+// Barrier state lives in static device memory (zero when the module is loaded) rather than in
+// the caller's workspace, which would have to be cleared by an extra launch before every call:
+// {arrived, left} per sequence.  The last range to leave a barrier resets both counts, so a slot
+// is clean again when its call ends; calls take slots round-robin, so up to kResSlots calls may
+// overlap on one GPU.  The last word of a slot is a sticky "a barrier timed out" flag.
+constexpr int kResSlots = 32;
+constexpr int kResMaxBatch = 256;
+__device__ uint32_t g_res_sync[kResSlots][2 * kResMaxBatch + 1];
+
 bool resident_plan(const Shape &s, int num_cu, ResidentPlan *plan)
 {
     const int Hkv = s.kv.n_kv_heads;
@@ -75,7 +86,7 @@ bool resident_plan(const Shape &s, int num_cu, ResidentPlan *plan)
     const int G = s.n_q_heads / Hkv;
     if (G > 8 || s.n_q_heads > kResMaxHq) return false;
     if (Hkv != 1 && Hkv != 2 && Hkv != 4 && Hkv != 8) return false;
-    if (s.batch < 1 || s.batch > num_cu) return false;
+    if (s.batch < 1 || s.batch > num_cu || s.batch > kResMaxBatch) return false;
     if (s.paged && s.kv.page_tokens < kResTile) return false;        // a tile may touch two pages at most
     if (s.kv.stride_token > (1 << 24)) return false;                 // 32 rows of bytes must fit 32 bits
     const int wpk = kResWaves / Hkv;
@@ -97,19 +108,13 @@ size_t resident_workspace_bytes(const Shape &s, const ResidentPlan &p)
 {
     size_t bytes = (size_t)s.batch * p.nranges * s.n_q_heads * 2 * sizeof(float);   // range statistics
     bytes += (size_t)s.batch * p.nranges * sizeof(float);                              // image-mass partials
-    bytes += ((size_t)s.batch + 1) * sizeof(uint32_t);                                 // barrier counters + status
     return bytes;
-}
-
-__global__ void resident_init_kernel(uint32_t *__restrict__ bar, int n)
-{
-    for (int i = threadIdx.x; i < n; i += blockDim.x) bar[i] = 0u;
 }
 
 template <bool PAGED>
 __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
     KvDev kv, BatchDev bv, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2,
-    int nranges, int R, float *part_ml, uint32_t *bar, long long spin_ticks,
+    int nranges, int R, float *part_ml, int sync_slot, long long spin_ticks,
     float *__restrict__ scores, float *__restrict__ lse_out, float *__restrict__ mass_part)
 {
     __shared__ __align__(16) unsigned char smem[kResWaves][2][8192];
@@ -330,16 +335,27 @@ img_done:
     }
     // ---- per-sequence barrier: every range of the sequence has published its statistics ---------
     __syncthreads();
+    uint32_t left_before = 0u;
+    uint32_t *arrived = &g_res_sync[sync_slot][2 * b], *left = arrived + 1;
+    // the last range to leave has seen every other one pass: it clears the counts for the next call
+    auto leave = [&]() {
+        if (threadIdx.x == 0 && left_before == (uint32_t)nranges - 1u) {
+            __hip_atomic_store(left, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    };
     if (threadIdx.x == 0) {
-        __hip_atomic_fetch_add(&bar[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const long long t_start = wall_clock64();
         bool ok = true;
-        while (__hip_atomic_load(&bar[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (uint32_t)nranges) {
+        while (__hip_atomic_load(arrived, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (uint32_t)nranges) {
             __builtin_amdgcn_s_sleep(1);
             if (wall_clock64() - t_start > spin_ticks) { ok = false; break; }
         }
-        if (!ok) __hip_atomic_fetch_or(&bar[gridDim.y], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (!ok) __hip_atomic_fetch_or(&g_res_sync[sync_slot][2 * kResMaxBatch], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         sm_met = ok ? 1 : 0;
+        // count this range out; the answer is only looked at when the kernel ends
+        left_before = __hip_atomic_fetch_add(left, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
     if (!sm_met) {
@@ -347,6 +363,7 @@ img_done:
         // poison this range's scores rather than publish numbers built on missing statistics
         for (int i = threadIdx.x; i < r1 - r0; i += kResThreads)
             scores[(int64_t)b * bv.max_vis_len + r0 + i] = __builtin_nanf("");
+        leave();
         return;
     }
     // every head's log-sum-exp from the ranges' statistics: wave w merges ranges w, w+8, ..; lane = head
@@ -403,6 +420,7 @@ fin_done:
             mass_part[(int64_t)b * nranges + rng] = t;
         }
     }
+    leave();
 }
 
 __global__ void resident_mass_kernel(const float *__restrict__ mass_part, int nranges, float *__restrict__ img_mass)
@@ -420,22 +438,22 @@ hipError_t launch_score_resident(const Shape &s, const ResidentPlan &p, const vo
     const size_t nstat = (size_t)s.batch * p.nranges * s.n_q_heads * 2;
     float *part_ml = reinterpret_cast<float *>(ws);
     float *mass_part = part_ml + nstat;
-    uint32_t *bar = reinterpret_cast<uint32_t *>(mass_part + (size_t)s.batch * p.nranges);
+    static std::atomic<unsigned> call_no{0};
+    const int sync_slot = (int)(call_no.fetch_add(1u) % (unsigned)kResSlots);
     const float scale_log2 = scale * kLog2e;
     const int G = s.n_q_heads / s.kv.n_kv_heads;
     // a range waits at most this long for its sequence's other ranges (they run concurrently and
     // finish within microseconds of each other); past it the call's scores are NaN but it ends
     const long long spin_ticks = 100000000ll / 4;          // 0.25 s of the 100 MHz wall clock
 
-    resident_init_kernel<<<1, 256, 0, stream>>>(bar, s.batch + 1);
     dim3 grid(p.nranges, s.batch), block(kResThreads);
     if (s.paged)
         FASTOCR_LAUNCH(K_SCORE_LOGITS, score_resident_kernel<true>, grid, block, 0, stream, s.kv, s.bv,
-                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, p.nranges, p.range_tokens, part_ml, bar,
+                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, p.nranges, p.range_tokens, part_ml, sync_slot,
                        spin_ticks, scores, lse, img_mass ? mass_part : nullptr);
     else
         FASTOCR_LAUNCH(K_SCORE_LOGITS, score_resident_kernel<false>, grid, block, 0, stream, s.kv, s.bv,
-                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, p.nranges, p.range_tokens, part_ml, bar,
+                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, p.nranges, p.range_tokens, part_ml, sync_slot,
                        spin_ticks, scores, lse, img_mass ? mass_part : nullptr);
     if (img_mass) resident_mass_kernel<<<s.batch, 64, 0, stream>>>(mass_part, p.nranges, img_mass);
     return hipGetLastError();

@@ -8,6 +8,8 @@
 // keys to a short candidate list bounded below by (a) the previous step's set -- the warm start:
 // its k tokens' smallest current key can only be at or below the new threshold -- and (b) a
 // sample of the scores; see topk_kernel.  The result never depends on either bound.
+#include <atomic>
+
 #include "kernels.hpp"
 
 namespace fastocr {
@@ -103,14 +105,16 @@ __device__ uint32_t radix_select(const uint32_t *keys, int n, int k, uint32_t *h
     return prefix;
 }
 
-// Workspace header of the multi-workgroup path, per sequence: candidate count and arrival count,
-// followed by the candidates themselves (key << 32 | index), kCandCap per sequence.
+// Per-sequence counters of the multi-workgroup path: candidates appended so far, workgroups
+// arrived.  They live in static device memory (zero when the module is loaded) rather than in the
+// caller's workspace, which would have to be cleared by an extra launch before every call; the
+// workgroup that arrives last is the only one still running for its sequence and clears them, so
+// a slot is clean again when its call ends.  Calls take slots round-robin: up to kTopkSlots calls
+// may overlap on one GPU.  Batches beyond kTopkMaxBatch use one workgroup per sequence.
 struct TopkCounters { uint32_t ncand, arrived; };
-
-__global__ void topk_init_kernel(TopkCounters *__restrict__ ctr, int n)
-{
-    for (int i = threadIdx.x; i < n; i += blockDim.x) { ctr[i].ncand = 0u; ctr[i].arrived = 0u; }
-}
+constexpr int kTopkSlots = 32;
+constexpr int kTopkMaxBatch = 1024;
+__device__ TopkCounters g_topk_ctr[kTopkSlots][kTopkMaxBatch];
 
 // Grid (parts, batch).  Every workgroup of a sequence derives the same lower bound theta0 of the
 // threshold for itself, filters its own slice of the scores against it and appends the survivors
@@ -126,8 +130,9 @@ __global__ void topk_init_kernel(TopkCounters *__restrict__ ctr, int n)
 __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
     const float *__restrict__ scores, BatchDev bv, double tau, const int32_t *prev_idx,
     const int32_t *prev_cnt, int32_t *sel_idx, int32_t *sel_cnt, int64_t kmax,
-    uint32_t *__restrict__ gkeys, int lds_keys, TopkCounters *ctr, unsigned long long *cand_list)
+    uint32_t *__restrict__ gkeys, int lds_keys, int sync_slot, unsigned long long *cand_list)
 {
+    TopkCounters *ctr = g_topk_ctr[sync_slot];
     extern __shared__ uint32_t dyn_keys[];
     __shared__ uint32_t hist[256];
     __shared__ uint32_t cand[kCandCap];
@@ -241,6 +246,11 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
 
         // ---- the last workgroup of the sequence selects among the candidates ----------------------
         const int nc = (int)__hip_atomic_load(&ctr[b].ncand, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (tid == 0) {                                    // clean for the next call on this slot
+            __hip_atomic_store(&ctr[b].ncand, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&ctr[b].arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         if (nc >= k && nc <= kCandCap) {
             for (int c = tid; c < nc; c += kTopkThreads) {
                 const unsigned long long e = __hip_atomic_load(&list[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -308,6 +318,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
         }
         __syncthreads();
         if (!s_last) return;
+        if (tid == 0) __hip_atomic_store(&ctr[b].arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 
     // ---- select over all N keys ---------------------------------------------------------------------
@@ -358,7 +369,6 @@ size_t topk_workspace_bytes(int batch, int max_vis_len)
     size_t bytes = 0;
     if (max_vis_len > kLdsKeyCap) bytes += (size_t)batch * (size_t)max_vis_len * sizeof(uint32_t);
     bytes = (bytes + 255) / 256 * 256;
-    bytes += ((size_t)batch * sizeof(TopkCounters) + 255) / 256 * 256;
     bytes += (size_t)batch * kCandCap * sizeof(unsigned long long);
     return bytes;
 }
@@ -385,13 +395,12 @@ hipError_t launch_topk(const float *scores, const BatchDev &bv, int batch, doubl
     size_t off = 0;
     if (bv.max_vis_len > kLdsKeyCap) off += (size_t)batch * (size_t)bv.max_vis_len * sizeof(uint32_t);
     off = (off + 255) / 256 * 256;
-    TopkCounters *ctr = reinterpret_cast<TopkCounters *>(p + off);
-    off += ((size_t)batch * sizeof(TopkCounters) + 255) / 256 * 256;
     unsigned long long *cand_list = reinterpret_cast<unsigned long long *>(p + off);
-    const int parts = topk_parts(bv.max_vis_len);
-    if (parts > 1) topk_init_kernel<<<1, 256, 0, stream>>>(ctr, batch);
+    const int parts = batch <= kTopkMaxBatch ? topk_parts(bv.max_vis_len) : 1;
+    static std::atomic<unsigned> call_no{0};
+    const int sync_slot = (int)(call_no.fetch_add(1u) % (unsigned)kTopkSlots);
     FASTOCR_LAUNCH(K_TOPK, topk_kernel, dim3(parts, batch), dim3(kTopkThreads), dyn, stream, scores, bv, tau, prev_idx,
-                   prev_cnt, sel_idx, sel_cnt, kmax, gkeys, lds_keys, ctr, cand_list);
+                   prev_cnt, sel_idx, sel_cnt, kmax, gkeys, lds_keys, sync_slot, cand_list);
     return hipGetLastError();
 }
 
