@@ -54,9 +54,11 @@ class FixationController:
         return self._ws
 
     def step(self, t: int, batch: "_b.SeqBatch", queries: Sequence[torch.Tensor],
-             outs: Sequence[torch.Tensor], stream=None) -> List[Tuple[int, str, Optional[object]]]:
+             outs: Sequence[torch.Tensor], stream=None, on_select=None) -> List[Tuple[int, str, Optional[object]]]:
         """Enqueue decode step t (1-based).  queries[l], outs[l]: [B, Hq, d] per layer.
-        Returns the schedule it ran as (layer, mode, kept-set source) triples."""
+        Returns the schedule it ran as (layer, mode, kept-set source) triples.
+        ``on_select(layer, scores, kept_idx, kept_cnt)`` is called right after a selecting layer
+        has been enqueued (the tensors are the controller's own buffers, valid in stream order)."""
         ops, trace = self.ops, []
         post_warmup = t > self.warmup
         if post_warmup and self.kept_from is not None:
@@ -77,6 +79,8 @@ class FixationController:
                                   prev_idx=self.kept_idx if warm else None,
                                   prev_cnt=self.kept_cnt if warm else None, stream=stream)
                 self.kept_from = l
+                if on_select is not None:
+                    on_select(l, self.scores, self.kept_idx, self.kept_cnt)
                 trace.append((l, "full+select", None))
             else:
                 ops.sparse_decode_attn(cache, batch, q, self.scale, self.kept_idx, self.kept_cnt, out, ws,
