@@ -165,6 +165,24 @@ int fastocr_dense_decode_attn(const fastocr_kv_view *kv, const fastocr_batch_vie
                               void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * Focal Layer Selection (Sec. 3.1.1; first block of Alg. 1).  HOST function, no GPU involved.
+ *   ratio  HOST fp32 [steps][layers][batch]: the image-attention ratio r_i^(t) of Eq. 1 of layer i
+ *          at warm-up step t for sequence b -- what fastocr_focal_score returns in img_mass
+ *          (the softmax runs over image and text positions together, so the ratio's
+ *          denominator is 1).
+ * Layers are ranked by the mean of their ratio over steps and batch (one focal set serves the
+ * whole batch), descending, equal means in layer order; they are taken greedily while fewer
+ * than floor(rho * layers) are taken and the layer is more than `gap` layers away from every
+ * layer already taken.  The chosen layers are written ascending to focal_out[0 .. *n_out)
+ * (HOST int32, room for `layers` entries).  The mean is formed in double; rho * layers within
+ * 1e-9 below an integer counts as that integer.
+ * Returns FASTOCR_EINVAL for null pointers, steps/layers/batch < 1, rho outside [0,1], gap < 0
+ * or a non-finite ratio.
+ */
+int fastocr_select_focal_layers(const float *ratio, int steps, int layers, int batch, double rho,
+                                int gap, int32_t *focal_out, int32_t *n_out);
+
+/*
  * Per-kernel timing with HIP events recorded on the stream the kernel is launched on.
  * fastocr_kernel_timer_enable(kernel, capacity) makes every later launch of that kernel
  * record a start/stop event pair (up to `capacity` launches; capacity 0 disables and

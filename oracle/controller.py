@@ -3,7 +3,10 @@
 Given the frozen focal layer set C, the warm-up length w and whether a focal
 token set survives from the previous step, say for every layer of decode step t
 what kind of attention it runs and whose focal token set it attends over.
-Written from the algorithm's three blocks in their order; no arithmetic here.
+Written from the algorithm's three blocks in their order.  ``select_focal_layers``
+is the Focal Layer Selection block (Sec. 3.1.1): rank layers by their mean
+image-attention ratio over the warm-up steps, then take them greedily while the
+budget floor(rho L) lasts and the focal gap to every layer already taken holds.
 """
 from __future__ import annotations
 
@@ -51,3 +54,25 @@ def plan_step(t: int, n_layers: int, focal_layers: Sequence[int], warmup: int,
         else:
             actions.append(LayerAction(i, "pruned", current))
     return StepPlan(actions, max(C))
+
+
+def select_focal_layers(ratios, rho: float, gap: int) -> List[int]:
+    """ratios[t][i]: image-attention ratio r_i^(t) of layer i at warm-up step t (Eq. 1), or
+    ratios[t][i][b] per sequence of a batch (then also averaged over the batch: one focal set
+    serves the whole batch).  Returns the focal layer set C, ascending."""
+    import numpy as np
+    r = np.asarray(ratios, dtype=np.float64)
+    if r.ndim == 3:
+        r = r.mean(axis=2)
+    if r.ndim != 2 or r.shape[0] < 1:
+        raise ValueError("ratios must be [steps][layers] or [steps][layers][batch]")
+    n_layers = r.shape[1]
+    mean = r.mean(axis=0)
+    # descending by mean ratio; equal means keep the lower layer first
+    ranked = sorted(range(n_layers), key=lambda i: (-mean[i], i))
+    budget = int(np.floor(rho * n_layers + 1e-9))
+    chosen: List[int] = []
+    for i in ranked:
+        if len(chosen) < budget and all(abs(i - j) > gap for j in chosen):
+            chosen.append(i)
+    return sorted(chosen)

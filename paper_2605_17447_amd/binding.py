@@ -25,7 +25,7 @@ OP_FOCAL_SCORE, OP_TOPK_FIXATION, OP_SPARSE_DECODE_ATTN, OP_DENSE_DECODE_ATTN = 
 EXPORTS = (
     "fastocr_keep_count", "fastocr_workspace_bytes", "fastocr_focal_score", "fastocr_topk_fixation",
     "fastocr_sparse_decode_attn", "fastocr_dense_decode_attn", "fastocr_kernel_timer_enable",
-    "fastocr_kernel_timer_read", "fastocr_stream_probe", "fastocr_set_tuning", "fastocr_strerror", "fastocr_version",
+    "fastocr_kernel_timer_read", "fastocr_select_focal_layers", "fastocr_stream_probe", "fastocr_set_tuning", "fastocr_strerror", "fastocr_version",
 )
 
 
@@ -81,6 +81,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.fastocr_dense_decode_attn.argtypes = [KV, BV, P, I, F, P, P, P, SZ, P]
     lib.fastocr_kernel_timer_enable.restype, lib.fastocr_kernel_timer_enable.argtypes = I, [I, I]
     lib.fastocr_kernel_timer_read.restype, lib.fastocr_kernel_timer_read.argtypes = I, [I, P, I]
+    lib.fastocr_select_focal_layers.restype = I
+    lib.fastocr_select_focal_layers.argtypes = [P, I, I, I, ctypes.c_double, I, P, P]
     lib.fastocr_stream_probe.restype, lib.fastocr_stream_probe.argtypes = I, [P, P, SZ, P, P]
     lib.fastocr_set_tuning.restype, lib.fastocr_set_tuning.argtypes = I, [ctypes.c_char_p, I]
     lib.fastocr_strerror.restype, lib.fastocr_strerror.argtypes = ctypes.c_char_p, [I]
@@ -259,6 +261,20 @@ def dense_decode_attn(cache: KvCache, batch: SeqBatch, q: torch.Tensor, scale: f
     _check(lib.fastocr_dense_decode_attn(ctypes.byref(kv), ctypes.byref(bv), _ptr(q), q.shape[1],
                                          float(scale), _ptr(out), _ptr(lse), _ptr(ws), ws.numel(),
                                          _stream_handle(stream)), "fastocr_dense_decode_attn")
+
+
+def select_focal_layers(ratio, rho: float, gap: int):
+    """fastocr_select_focal_layers on a host array [steps, layers, batch] (or [steps, layers])."""
+    import numpy as np
+    r = np.ascontiguousarray(np.asarray(ratio, dtype=np.float32))
+    if r.ndim == 2:
+        r = r[:, :, None]
+    steps, layers, batch = r.shape
+    out = np.zeros(layers, dtype=np.int32)
+    n = ctypes.c_int32(0)
+    _check(load_library().fastocr_select_focal_layers(r.ctypes.data, steps, layers, batch, float(rho), int(gap),
+                                                      out.ctypes.data, ctypes.byref(n)), "fastocr_select_focal_layers")
+    return [int(x) for x in out[: n.value]]
 
 
 def stream_probe(src: torch.Tensor, dst: Optional[torch.Tensor], sink: torch.Tensor, stream=None) -> None:

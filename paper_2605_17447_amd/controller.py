@@ -4,8 +4,11 @@ Implements the per-step control flow of Algorithm 1 (App. A) for a frozen focal 
 warm-up steps run full attention everywhere; afterwards a focal layer attends the full cache
 and refreshes the kept image tokens (Cross-Layer Propagation, Sec. 3.1.2), every other layer
 attends text + the kept tokens, and the set left by the deepest focal layer serves layer 0 of
-the next step (Cross-Step Fixation Reuse, Sec. 3.2).  No arithmetic happens here: the
-controller only owns device buffers and orders the four C-ABI calls on one stream.
+the next step (Cross-Step Fixation Reuse, Sec. 3.2).  When no focal layer set is given, the
+warm-up steps also record every layer's image-attention ratio (Eq. 1: the image mass that
+focal scoring returns) and the set is chosen after the last of them (Focal Layer Selection,
+Sec. 3.1.1) by the library's host routine.  No arithmetic happens here: the controller only
+owns device buffers and orders the C-ABI calls on one stream.
 """
 from __future__ import annotations
 
@@ -18,19 +21,30 @@ from . import binding as _b
 
 class FixationController:
     def __init__(self, caches: Sequence[_b.KvCache], n_q_heads: int, scale: float,
-                 focal_layers: Sequence[int], tau: float, warmup: int, max_seq_len: int,
-                 max_vis_len: int, batch_size: int, device, focal_gap: int = 1, ops=None):
+                 focal_layers: Optional[Sequence[int]], tau: float, warmup: int, max_seq_len: int,
+                 max_vis_len: int, batch_size: int, device, focal_gap: int = 1, ops=None,
+                 focal_ratio: float = 0.1):
         self.caches = list(caches)
         self.n_layers = len(self.caches)
-        self.focal = sorted(set(int(c) for c in focal_layers))
-        if not self.focal:
-            raise ValueError("the focal layer set must not be empty")
-        if self.focal[0] < 0 or self.focal[-1] >= self.n_layers:
-            raise ValueError("focal layer outside the stack")
-        # the focal gap is a spacing in layers between focal layers (Sec. 3.1.1)
-        for a, c in zip(self.focal, self.focal[1:]):
-            if c - a <= focal_gap:
-                raise ValueError(f"focal layers {a} and {c} are closer than the focal gap {focal_gap}")
+        self.focal_gap, self.focal_ratio = int(focal_gap), float(focal_ratio)
+        if focal_layers is None:
+            # chosen from the warm-up steps' image-attention ratios
+            if warmup < 1:
+                raise ValueError("focal layer selection needs at least one warm-up step")
+            if int(self.focal_ratio * self.n_layers + 1e-9) < 1:
+                raise ValueError("focal_ratio * layers must allow at least one focal layer")
+            self.focal = None
+            self.ratios = torch.zeros((warmup, self.n_layers, batch_size), dtype=torch.float32, device=device)
+        else:
+            self.focal = sorted(set(int(c) for c in focal_layers))
+            if not self.focal:
+                raise ValueError("the focal layer set must not be empty")
+            if self.focal[0] < 0 or self.focal[-1] >= self.n_layers:
+                raise ValueError("focal layer outside the stack")
+            # the focal gap is a spacing in layers between focal layers (Sec. 3.1.1)
+            for a, c in zip(self.focal, self.focal[1:]):
+                if c - a <= focal_gap:
+                    raise ValueError(f"focal layers {a} and {c} are closer than the focal gap {focal_gap}")
         if not (0.0 <= tau <= 1.0):
             raise ValueError("tau must lie in [0, 1]")
         self.tau, self.warmup, self.scale, self.n_q_heads = float(tau), int(warmup), float(scale), n_q_heads
@@ -61,6 +75,8 @@ class FixationController:
         has been enqueued (the tensors are the controller's own buffers, valid in stream order)."""
         ops, trace = self.ops, []
         post_warmup = t > self.warmup
+        if post_warmup and self.focal is None:
+            raise RuntimeError("the focal layer set is chosen at the last warm-up step: run steps 1..warmup first")
         if post_warmup and self.kept_from is not None:
             self.kept_from = "F_last"             # what the previous step left behind
         for l, cache in enumerate(self.caches):
@@ -68,6 +84,10 @@ class FixationController:
             q, out = queries[l], outs[l]
             if not post_warmup:
                 ops.dense_decode_attn(cache, batch, q, self.scale, out, ws, stream=stream)
+                if self.focal is None:
+                    # r_l^(t) of Eq. 1 for every sequence, kept on the device until the last warm-up step
+                    ops.focal_score(cache, batch, q, self.scale, self.scores, ws, img_mass=self.ratios[t - 1, l],
+                                    stream=stream)
                 trace.append((l, "full", None))
                 continue
             selects = (l in self.focal) or (l == 0 and self.kept_from is None)
@@ -86,5 +106,8 @@ class FixationController:
                 ops.sparse_decode_attn(cache, batch, q, self.scale, self.kept_idx, self.kept_cnt, out, ws,
                                        stream=stream)
                 trace.append((l, "pruned", self.kept_from))
+        if self.focal is None and t == self.warmup:
+            # Focal Layer Selection: one read-back of warmup x layers x batch ratios, ranked on the host
+            self.focal = ops.select_focal_layers(self.ratios.cpu().numpy(), self.focal_ratio, self.focal_gap)
         # after the last layer the kept set is the deepest focal layer's: it is next step's F_last
         return trace

@@ -2,7 +2,11 @@
 // choice and per-kernel event timers.  Every check happens before the first HIP call, so the
 // error paths can be exercised without a GPU.
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
+
+#include <algorithm>
+#include <vector>
 
 #include "fastocr.h"
 #include "kernels.hpp"
@@ -268,6 +272,37 @@ int fastocr_dense_decode_attn(const fastocr_kv_view *kv, const fastocr_batch_vie
 {
     return attn_common(FASTOCR_OP_DENSE_DECODE_ATTN, kv, bv, q, n_q_heads, scale, nullptr, nullptr, 0,
                        out, lse, ws, ws_bytes, hip_stream);
+}
+
+int fastocr_select_focal_layers(const float *ratio, int steps, int layers, int batch, double rho,
+                                int gap, int32_t *focal_out, int32_t *n_out)
+{
+    if (!ratio || !focal_out || !n_out || steps < 1 || layers < 1 || batch < 1 || gap < 0) return FASTOCR_EINVAL;
+    if (!(rho >= 0.0 && rho <= 1.0)) return FASTOCR_EINVAL;
+    std::vector<double> mean((size_t)layers, 0.0);
+    for (int t = 0; t < steps; ++t)
+        for (int i = 0; i < layers; ++i)
+            for (int b = 0; b < batch; ++b) {
+                const float r = ratio[((size_t)t * layers + i) * batch + b];
+                if (!isfinite(r)) return FASTOCR_EINVAL;
+                mean[i] += (double)r;
+            }
+    for (int i = 0; i < layers; ++i) mean[i] /= (double)steps * (double)batch;
+    std::vector<int> order((size_t)layers);
+    for (int i = 0; i < layers; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return mean[x] > mean[y]; });
+    const int budget = (int)floor(rho * (double)layers + 1e-9);
+    std::vector<int> taken;
+    for (int i : order) {
+        if ((int)taken.size() >= budget) break;
+        bool far = true;
+        for (int j : taken) far = far && abs(i - j) > gap;
+        if (far) taken.push_back(i);
+    }
+    std::sort(taken.begin(), taken.end());
+    for (size_t x = 0; x < taken.size(); ++x) focal_out[x] = taken[x];
+    *n_out = (int32_t)taken.size();
+    return FASTOCR_OK;
 }
 
 int fastocr_kernel_timer_enable(int kernel, int capacity)

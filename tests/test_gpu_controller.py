@@ -77,3 +77,48 @@ def test_stack_follows_algorithm_1(paged):
         if plan.save_from is not None:
             have_last = True
             assert ctl.kept_from == plan.save_from
+
+
+def test_focal_layers_are_chosen_from_the_warm_up_ratios():
+    """Focal Layer Selection on the GPU path: layers differ in how much attention mass their
+    queries put on the image (a per-layer gain on the fixation window), the controller records
+    each layer's image-attention ratio during warm-up and picks the focal set; ratios and set
+    must match the oracle's."""
+    import dataclasses
+    L, warmup, tau, rho, gap = 8, 3, 0.1, 0.4, 1
+    gains = [0.6, 3.0, 2.0, 0.8, 1.0, 3.5, 0.7, 1.5]             # ranked: 5, 1, 2, 7, ... -> with gap 1: {1, 5, 7}
+    base = fs.config(3, batch=2, n_layers=L, steps=warmup + 1, warmup=warmup, n_visual=(576, 576), grid_w=(24, 24),
+                     text_prefix=(400, 400))
+    bts = [fs.make_batch(dataclasses.replace(base, beta=g), device=DEV, layer=l) for l, g in enumerate(gains)]
+    bt = bts[0]
+    cs = fs.centres(bt)
+    B, Hq, d = base.batch, base.n_q_heads, base.head_dim
+    scale = float(np.float32(d ** -0.5))
+    caches = [fo.KvCache(x.k, x.v) for x in bts]
+    ctl = fo.FixationController(caches, Hq, scale, None, tau, warmup, max(bt.seq_len(warmup + 1)), max(bt.n_vis), B, DEV,
+                                focal_gap=gap, focal_ratio=rho)
+    ref = np.zeros((warmup, L, B))
+    for t in range(1, warmup + 1):
+        seq_len = bt.seq_len(t)
+        batch = fo.SeqBatch.from_lists(seq_len, bt.vis_start, bt.n_vis, DEV)
+        qs = [fs.queries_for_step(bts[l], t, [c[t - 1] for c in cs]) for l in range(L)]
+        outs = [torch.zeros_like(q) for q in qs]
+        ctl.step(t, batch, qs, outs)
+        for l in range(L):
+            oc = oracle.Cache.from_bhsd(fs.to_oracle_array(bts[l].k), fs.to_oracle_array(bts[l].v))
+            _, _, mass = oracle.focal_score(oc, seq_len, bt.vis_start, bt.n_vis, fs.to_oracle_array(qs[l]), scale)
+            ref[t - 1, l] = mass
+    torch.cuda.synchronize()
+    got = ctl.ratios.cpu().numpy()
+    assert np.abs(got - ref).max() <= 2e-5, "image-attention ratios differ from the oracle"
+    from oracle.controller import select_focal_layers
+    want = select_focal_layers(ref, rho, gap)
+    assert ctl.focal == want and len(want) == 3
+    # the ranking is not an accident of noise: the chosen layers are those with the largest gains allowed by the gap
+    assert want == [1, 5, 7]
+    # and the next step runs with the chosen set
+    t = warmup + 1
+    batch = fo.SeqBatch.from_lists(bt.seq_len(t), bt.vis_start, bt.n_vis, DEV)
+    qs = [fs.queries_for_step(bts[l], t, [c[t - 1] for c in cs]) for l in range(L)]
+    trace = ctl.step(t, batch, qs, [torch.zeros_like(q) for q in qs])
+    assert [tuple(a) for a in plan_step(t, L, want, warmup, False).actions] == trace
