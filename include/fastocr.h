@@ -23,6 +23,10 @@
  *     reported here.
  *   - `ws` is caller-provided device scratch of at least fastocr_workspace_bytes(...)
  *     bytes, 256-byte aligned, private to the call until the stream reaches its end.
+ *   - fastocr_focal_score and fastocr_topk_fixation keep a few synchronisation counters in
+ *     static device memory (cleared by the kernels themselves when they end); calls take one
+ *     of 32 slots in turn, so at most 32 calls of each kind may be in flight on one GPU at a
+ *     time (more would share a slot and corrupt each other's results).
  *   - Sequences are independent.  Sequence b holds seq_len[b] tokens; its image tokens
  *     are the contiguous span [vis_start[b], vis_start[b] + vis_len[b]); every other
  *     position (text before, text after, generated tokens, the current token) is text.
