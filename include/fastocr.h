@@ -106,8 +106,9 @@ typedef struct {
 int64_t fastocr_keep_count(int64_t n_visual, double tau);
 
 /* Bytes of device scratch `op` needs for these shapes (host function; only the host
- * fields of the views are read).  kmax is ignored except for the top-k.  Returns 0 on
- * invalid arguments. */
+ * fields of the views are read).  kmax is the row pitch of the selected sets: it sizes the
+ * top-k's workspace and bounds the positions pruned attention can attend (a size obtained with a
+ * larger kmax, or with kmax = 0, also suffices).  Returns 0 on invalid arguments. */
 size_t fastocr_workspace_bytes(int op, const fastocr_kv_view *kv, const fastocr_batch_view *bv,
                                int n_q_heads, int64_t kmax);
 

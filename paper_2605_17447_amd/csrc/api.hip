@@ -112,14 +112,23 @@ static int choose_splits(int op, const Shape &s, int max_positions)
         // unit (few, long, equally sized streams), the plain-FMA kernels with many small ones.
         const int target_wg = fast ? kNumCU : 8 * kNumCU;
         nsplit = (target_wg + streams - 1) / (streams > 0 ? streams : 1);
-        // attention with at least half a chip of streams: one eight-wave workgroup per stream writes
-        // the final output itself (no partials, no merge kernel)
-        if (fast && op == FASTOCR_OP_SPARSE_DECODE_ATTN && 2 * streams >= kNumCU) nsplit = 1;
+        // pruned attention is short: when eight waves get at most eight tiles each, or at least half
+        // a chip of streams exists, one eight-wave workgroup per stream writes the final output
+        // itself (no partials, no merge kernel -- a second launch costs more than it saves here)
+        if (fast && op == FASTOCR_OP_SPARSE_DECODE_ATTN && (2 * streams >= kNumCU || ntile <= 64)) nsplit = 1;
     }
     if (nsplit > by_work) nsplit = by_work;
     if (nsplit > 256) nsplit = 256;
     if (nsplit < 1) nsplit = 1;
     return nsplit;
+}
+
+// Upper bound of the positions a pruned-attention call attends: all text plus kmax image tokens
+// (kmax <= 0: unknown, the whole sequence).
+static int sparse_positions(const fastocr_batch_view *bv, int64_t kmax)
+{
+    if (kmax <= 0 || kmax >= bv->max_vis_len) return bv->max_seq_len;
+    return bv->max_seq_len - bv->max_vis_len + (int)kmax;
 }
 
 // Compute units of the current device (queried once per device).
@@ -156,7 +165,6 @@ int64_t fastocr_keep_count(int64_t n_visual, double tau)
 size_t fastocr_workspace_bytes(int op, const fastocr_kv_view *kv, const fastocr_batch_view *bv,
                                int n_q_heads, int64_t kmax)
 {
-    (void)kmax;
     if (op == FASTOCR_OP_TOPK_FIXATION) {
         if (!bv || bv->batch < 0 || bv->max_vis_len < 0) return 0;
         return round256(topk_workspace_bytes(bv->batch, bv->max_vis_len));
@@ -164,8 +172,8 @@ size_t fastocr_workspace_bytes(int op, const fastocr_kv_view *kv, const fastocr_
     if (op < 0 || op > FASTOCR_OP_DENSE_DECODE_ATTN) return 0;
     if (check_views(kv, bv, n_q_heads) != FASTOCR_OK) return 0;
     Shape s = make_shape(kv, bv, n_q_heads);
-    // the sparse path may be asked to attend everything (tau = 1): size for the whole sequence
-    const int nsplit = choose_splits(op, s, bv->max_seq_len);
+    // fewer positions never need more ranges, so a bound taken with a larger kmax (or none) also covers
+    const int nsplit = choose_splits(op, s, op == FASTOCR_OP_SPARSE_DECODE_ATTN ? sparse_positions(bv, kmax) : bv->max_seq_len);
     if (op == FASTOCR_OP_FOCAL_SCORE) {
         // sized for either scoring path, so that the choice can be made at launch
         size_t need = score_workspace_bytes(s, nsplit);
@@ -253,7 +261,7 @@ static int attn_common(int op, const fastocr_kv_view *kv, const fastocr_batch_vi
     if (rc != FASTOCR_OK) return rc;
     if (bv->batch == 0) return FASTOCR_OK;
     Shape s = make_shape(kv, bv, n_q_heads);
-    const int nsplit = choose_splits(op, s, bv->max_seq_len);
+    const int nsplit = choose_splits(op, s, op == FASTOCR_OP_SPARSE_DECODE_ATTN ? sparse_positions(bv, kmax) : bv->max_seq_len);
     hipError_t e = launch_attn(s, q, scale, sel_idx, sel_cnt, kmax, out, lse, ws, nsplit, (hipStream_t)hip_stream);
     return e == hipSuccess ? FASTOCR_OK : FASTOCR_EHIP;
 }

@@ -122,3 +122,65 @@ def test_focal_layers_are_chosen_from_the_warm_up_ratios():
     qs = [fs.queries_for_step(bts[l], t, [c[t - 1] for c in cs]) for l in range(L)]
     trace = ctl.step(t, batch, qs, [torch.zeros_like(q) for q in qs])
     assert [tuple(a) for a in plan_step(t, L, want, warmup, False).actions] == trace
+
+
+def test_a_captured_decode_step_replays_like_the_eager_one():
+    """The four calls allocate nothing and never synchronise, so a whole decode step of the
+    controller can be captured in a HIP graph (launch-bound small shapes).  Every replay, with
+    fresh queries and a longer sequence, must match the eager controller bit for bit; eager work
+    and synchronisations sit between the replays."""
+    L, focal, tau, steps = 5, (1, 3), 0.1, 10
+    wl = fs.config(3, batch=2, n_layers=L, focal_layers=focal, steps=steps, warmup=0, n_visual=(1024, 1024),
+                   grid_w=(32, 32), text_prefix=(30, 30))
+    bts = [fs.make_batch(wl, device=DEV, layer=l) for l in range(L)]
+    bt = bts[0]
+    cs = fs.centres(bt)
+    B, Hq, d = wl.batch, wl.n_q_heads, wl.head_dim
+    scale = float(np.float32(d ** -0.5))
+    caches = [fo.KvCache(x.k, x.v) for x in bts]
+    max_seq, max_vis = max(bt.seq_len(steps)), max(bt.n_vis)
+    mk = lambda: fo.FixationController(caches, Hq, scale, focal, tau, 0, max_seq, max_vis, B, DEV, focal_gap=1)
+    eager, graphed = mk(), mk()
+    queries = lambda t: [fs.queries_for_step(bts[l], t, [c[t - 1] for c in cs]) for l in range(L)]
+    vis_start = torch.tensor(bt.vis_start, dtype=torch.int32, device=DEV)
+    vis_len = torch.tensor(bt.n_vis, dtype=torch.int32, device=DEV)
+    # static inputs of the graph; host-side bounds are those of the last step
+    seq_len_g = torch.tensor(bt.seq_len(1), dtype=torch.int32, device=DEV)
+    batch_g = fo.SeqBatch(seq_len_g, vis_start, vis_len, max_seq, max_vis)
+    qs_g = [q.clone() for q in queries(1)]
+    outs_g = [torch.zeros_like(q) for q in qs_g]
+
+    def eager_step(t):
+        batch = fo.SeqBatch.from_lists(bt.seq_len(t), bt.vis_start, bt.n_vis, DEV)
+        batch.max_seq_len = max_seq
+        outs = [torch.zeros_like(q) for q in qs_g]
+        eager.step(t, batch, queries(t), outs)
+        return outs
+
+    def load_inputs(t):
+        seq_len_g.copy_(torch.tensor(bt.seq_len(t), dtype=torch.int32))
+        for dst, src in zip(qs_g, queries(t)):
+            dst.copy_(src)
+
+    # steps 1, 2 eagerly on both (step 1 takes the fallback path; step 2 is the steady-state schedule)
+    for t in (1, 2):
+        ref = eager_step(t)
+        load_inputs(t)
+        graphed.step(t, batch_g, qs_g, outs_g)
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(ref, outs_g))
+    # capture step 3's schedule (the same for every later step)
+    load_inputs(3)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        graphed.step(3, batch_g, qs_g, outs_g)
+    for t in range(3, steps + 1):
+        ref = eager_step(t)
+        load_inputs(t)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for l, (a, b) in enumerate(zip(ref, outs_g)):
+            assert torch.equal(a, b), f"step {t} layer {l}: replay differs from the eager step"
+        assert torch.equal(eager.kept_idx, graphed.kept_idx) and torch.equal(eager.kept_cnt, graphed.kept_cnt)
