@@ -212,10 +212,18 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
             }
         }
     };
-    // image tile x of the wave (past the last one the last is fetched again: it is still in cache,
-    // and the issue stays unconditional)
+    // image tile x of the wave.  Past the last one the issue stays unconditional (the reader's
+    // "at most 8 loads outstanding" wait counts on it) but fetches 256 bytes of the query, which
+    // are in cache, instead of cache rows that nobody will use.
+    const uint16_t *qrow = q + ((int64_t)b * Hq + (int64_t)kvh * G) * 128;
     auto issue_img = [&](int x, int seq_no) {
-        const int jf = img_first(min(x, nimg - 1));
+        if (x >= nimg) {
+            unsigned char *dst = smem[wave][seq_no & 1];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) lds_dma16(qrow + chunk_b[e & 3] / 2, dst + 1024 * e);
+            return;
+        }
+        const int jf = img_first(x);
         issue_run(v0 + jf, min(kResTile, r1 - jf), seq_no);
     };
     // text tile x of the wave: text positions map to tokens with a gap at the image span, so the
