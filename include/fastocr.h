@@ -57,7 +57,8 @@ typedef enum {
     FASTOCR_OP_FOCAL_SCORE = 0,
     FASTOCR_OP_TOPK_FIXATION = 1,
     FASTOCR_OP_SPARSE_DECODE_ATTN = 2,
-    FASTOCR_OP_DENSE_DECODE_ATTN = 3
+    FASTOCR_OP_DENSE_DECODE_ATTN = 3,
+    FASTOCR_OP_FOCAL_ATTN_SCORE = 4
 } fastocr_op;
 
 /*
@@ -170,6 +171,20 @@ int fastocr_dense_decode_attn(const fastocr_kv_view *kv, const fastocr_batch_vie
                               void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * A focal layer in one call (Alg. 1, focal branch; Eq. 1 and Eq. 2 with the full cache): the
+ * dense attention output of fastocr_dense_decode_attn AND the scores, lse and img_mass of
+ * fastocr_focal_score for the same q, computed from a single pass over K and V where the
+ * shape allows it (bf16, head_dim 128, group size <= 8, 1/2/4/8 KV heads, batch <= compute
+ * units, at most 32 tiles of 32 image tokens per wave); other shapes run the two separate
+ * kernels one after the other on the same stream, with identical results up to rounding order.
+ * Arguments as in those two calls; out and scores are both required, lse and img_mass optional.
+ * Workspace: fastocr_workspace_bytes(FASTOCR_OP_FOCAL_ATTN_SCORE, ...).
+ */
+int fastocr_focal_attn_score(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
+                             int n_q_heads, float scale, void *out, float *scores, float *lse,
+                             float *img_mass, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * Focal Layer Selection (Sec. 3.1.1; first block of Alg. 1).  HOST function, no GPU involved.
  *   ratio  HOST fp32 [steps][layers][batch]: the image-attention ratio r_i^(t) of Eq. 1 of layer i
  *          at warm-up step t for sequence b -- what fastocr_focal_score returns in img_mass
@@ -202,7 +217,8 @@ typedef enum {
     FASTOCR_KERNEL_SPARSE_ATTN = 3,
     FASTOCR_KERNEL_DENSE_ATTN = 4,
     FASTOCR_KERNEL_ATTN_COMBINE = 5,
-    FASTOCR_KERNEL_COUNT = 6
+    FASTOCR_KERNEL_FOCAL_FUSED = 6,    /* one pass over K and V: attention partials + scores */
+    FASTOCR_KERNEL_COUNT = 7
 } fastocr_kernel;
 
 int fastocr_kernel_timer_enable(int kernel, int capacity);
@@ -218,7 +234,8 @@ int fastocr_kernel_timer_read(int kernel, float *ms_out, int max_out);
 int fastocr_stream_probe(const void *src, void *dst, size_t bytes, void *sink, void *hip_stream);
 
 /* Launch-shape overrides for measurement sweeps: key "splits_score" | "splits_dense" |
- * "splits_sparse" (0 = automatic).  Returns FASTOCR_EINVAL for an unknown key. */
+ * "splits_sparse" (0 = automatic), "score_resident" | "focal_fused" (0 = use the separate
+ * kernels instead), "attn_waves" (4 | 8).  Returns FASTOCR_EINVAL for an unknown key. */
 int fastocr_set_tuning(const char *key, int value);
 
 const char *fastocr_strerror(int status);

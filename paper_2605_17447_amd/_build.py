@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libfastocr.so")
-SOURCES = ["api.hip", "attn.hip", "score.hip", "score_resident.hip", "topk.hip", "probe.hip"]
+SOURCES = ["api.hip", "attn.hip", "score.hip", "score_resident.hip", "focal_fused.hip", "topk.hip", "probe.hip"]
 
 # Packed-FP32 VALU forms are switched off for all device code (they have given silently wrong
 # results on these machines); hipcc's host pass does not know the feature and says so.

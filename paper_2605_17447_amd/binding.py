@@ -18,13 +18,13 @@ LIB_PATH = os.path.join(_HERE, "libfastocr.so")
 
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 F32, BF16 = 0, 1
-OP_FOCAL_SCORE, OP_TOPK_FIXATION, OP_SPARSE_DECODE_ATTN, OP_DENSE_DECODE_ATTN = 0, 1, 2, 3
+OP_FOCAL_SCORE, OP_TOPK_FIXATION, OP_SPARSE_DECODE_ATTN, OP_DENSE_DECODE_ATTN, OP_FOCAL_ATTN_SCORE = 0, 1, 2, 3, 4
 (KERNEL_SCORE_LOGITS, KERNEL_SCORE_FINALIZE, KERNEL_TOPK, KERNEL_SPARSE_ATTN, KERNEL_DENSE_ATTN,
- KERNEL_ATTN_COMBINE) = range(6)
+ KERNEL_ATTN_COMBINE, KERNEL_FOCAL_FUSED) = range(7)
 
 EXPORTS = (
     "fastocr_keep_count", "fastocr_workspace_bytes", "fastocr_focal_score", "fastocr_topk_fixation",
-    "fastocr_sparse_decode_attn", "fastocr_dense_decode_attn", "fastocr_kernel_timer_enable",
+    "fastocr_sparse_decode_attn", "fastocr_dense_decode_attn", "fastocr_focal_attn_score", "fastocr_kernel_timer_enable",
     "fastocr_kernel_timer_read", "fastocr_select_focal_layers", "fastocr_stream_probe", "fastocr_set_tuning", "fastocr_strerror", "fastocr_version",
 )
 
@@ -79,6 +79,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.fastocr_sparse_decode_attn.argtypes = [KV, BV, P, I, F, P, P, I64, P, P, SZ, P]
     lib.fastocr_dense_decode_attn.restype = I
     lib.fastocr_dense_decode_attn.argtypes = [KV, BV, P, I, F, P, P, P, SZ, P]
+    lib.fastocr_focal_attn_score.restype = I
+    lib.fastocr_focal_attn_score.argtypes = [KV, BV, P, I, F, P, P, P, P, P, SZ, P]
     lib.fastocr_kernel_timer_enable.restype, lib.fastocr_kernel_timer_enable.argtypes = I, [I, I]
     lib.fastocr_kernel_timer_read.restype, lib.fastocr_kernel_timer_read.argtypes = I, [I, P, I]
     lib.fastocr_select_focal_layers.restype = I
@@ -261,6 +263,20 @@ def dense_decode_attn(cache: KvCache, batch: SeqBatch, q: torch.Tensor, scale: f
     _check(lib.fastocr_dense_decode_attn(ctypes.byref(kv), ctypes.byref(bv), _ptr(q), q.shape[1],
                                          float(scale), _ptr(out), _ptr(lse), _ptr(ws), ws.numel(),
                                          _stream_handle(stream)), "fastocr_dense_decode_attn")
+
+
+def focal_attn_score(cache: KvCache, batch: SeqBatch, q: torch.Tensor, scale: float, out: torch.Tensor,
+                     scores: torch.Tensor, ws: torch.Tensor, lse: Optional[torch.Tensor] = None,
+                     img_mass: Optional[torch.Tensor] = None, stream=None) -> None:
+    """fastocr_focal_attn_score: dense output [B,Hq,d] and scores fp32 [B, max_vis_len] in one call."""
+    lib = load_library()
+    kv, bv = cache.view(), batch.view()
+    assert q.is_contiguous() and out.is_contiguous() and out.shape == q.shape and out.dtype == q.dtype
+    assert scores.is_contiguous() and scores.dtype == torch.float32
+    assert scores.shape[0] == bv.batch and (scores.shape[1] == bv.max_vis_len or bv.batch == 0)
+    _check(lib.fastocr_focal_attn_score(ctypes.byref(kv), ctypes.byref(bv), _ptr(q), q.shape[1], float(scale),
+                                        _ptr(out), _ptr(scores), _ptr(lse), _ptr(img_mass), _ptr(ws), ws.numel(),
+                                        _stream_handle(stream)), "fastocr_focal_attn_score")
 
 
 def select_focal_layers(ratio, rho: float, gap: int):

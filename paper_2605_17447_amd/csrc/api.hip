@@ -14,6 +14,7 @@
 namespace fastocr {
 
 static int g_tune_score_resident = 1;
+static int g_tune_focal_fused = 1;
 int g_tune_attn_waves = 4;
 static int g_tune_splits[4] = {0, 0, 0, 0};     // indexed by fastocr_op
 
@@ -169,9 +170,21 @@ size_t fastocr_workspace_bytes(int op, const fastocr_kv_view *kv, const fastocr_
         if (!bv || bv->batch < 0 || bv->max_vis_len < 0) return 0;
         return round256(topk_workspace_bytes(bv->batch, bv->max_vis_len));
     }
-    if (op < 0 || op > FASTOCR_OP_DENSE_DECODE_ATTN) return 0;
+    if (op < 0 || op > FASTOCR_OP_FOCAL_ATTN_SCORE) return 0;
     if (check_views(kv, bv, n_q_heads) != FASTOCR_OK) return 0;
     Shape s = make_shape(kv, bv, n_q_heads);
+    if (op == FASTOCR_OP_FOCAL_ATTN_SCORE) {
+        // the one-pass kernel, or the two separate calls one after the other in the same buffer
+        size_t need = fastocr_workspace_bytes(FASTOCR_OP_FOCAL_SCORE, kv, bv, n_q_heads, 0);
+        const size_t dense = fastocr_workspace_bytes(FASTOCR_OP_DENSE_DECODE_ATTN, kv, bv, n_q_heads, 0);
+        need = need > dense ? need : dense;
+        ResidentPlan rp;
+        if (resident_plan(s, kNumCU, &rp)) {
+            const size_t fused = round256(focal_fused_workspace_bytes(s, rp) + 256);
+            need = need > fused ? need : fused;
+        }
+        return need;
+    }
     // fewer positions never need more ranges, so a bound taken with a larger kmax (or none) also covers
     const int nsplit = choose_splits(op, s, op == FASTOCR_OP_SPARSE_DECODE_ATTN ? sparse_positions(bv, kmax) : bv->max_seq_len);
     if (op == FASTOCR_OP_FOCAL_SCORE) {
@@ -282,6 +295,31 @@ int fastocr_dense_decode_attn(const fastocr_kv_view *kv, const fastocr_batch_vie
                        out, lse, ws, ws_bytes, hip_stream);
 }
 
+int fastocr_focal_attn_score(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
+                             int n_q_heads, float scale, void *out, float *scores, float *lse,
+                             float *img_mass, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_views(kv, bv, n_q_heads);
+    if (rc != FASTOCR_OK) return rc;
+    if (!out) return FASTOCR_EINVAL;
+    rc = check_qo(kv, q, out, scale);
+    if (rc != FASTOCR_OK) return rc;
+    if (!scores && bv->max_vis_len > 0 && bv->batch > 0) return FASTOCR_EINVAL;
+    const size_t need = fastocr_workspace_bytes(FASTOCR_OP_FOCAL_ATTN_SCORE, kv, bv, n_q_heads, 0);
+    rc = check_ws(ws, ws_bytes, need);
+    if (rc != FASTOCR_OK) return rc;
+    if (bv->batch == 0) return FASTOCR_OK;
+    Shape s = make_shape(kv, bv, n_q_heads);
+    ResidentPlan rp;
+    if (g_tune_focal_fused && resident_plan(s, kNumCU, &rp) && rp.nranges * s.batch <= device_cu_count()) {
+        hipError_t e = launch_focal_fused(s, rp, q, scale, out, scores, lse, img_mass, ws, (hipStream_t)hip_stream);
+        return e == hipSuccess ? FASTOCR_OK : FASTOCR_EHIP;
+    }
+    rc = fastocr_dense_decode_attn(kv, bv, q, n_q_heads, scale, out, nullptr, ws, ws_bytes, hip_stream);
+    if (rc != FASTOCR_OK) return rc;
+    return fastocr_focal_score(kv, bv, q, n_q_heads, scale, scores, lse, img_mass, ws, ws_bytes, hip_stream);
+}
+
 int fastocr_select_focal_layers(const float *ratio, int steps, int layers, int batch, double rho,
                                 int gap, int32_t *focal_out, int32_t *n_out)
 {
@@ -367,6 +405,7 @@ int fastocr_set_tuning(const char *key, int value)
     else if (!strcmp(key, "splits_dense")) g_tune_splits[FASTOCR_OP_DENSE_DECODE_ATTN] = value;
     else if (!strcmp(key, "attn_waves")) g_tune_attn_waves = value;
     else if (!strcmp(key, "score_resident")) g_tune_score_resident = value ? 1 : 0;
+    else if (!strcmp(key, "focal_fused")) g_tune_focal_fused = value ? 1 : 0;
     else return FASTOCR_EINVAL;
     return FASTOCR_OK;
 }

@@ -408,6 +408,13 @@ hipError_t launch_attn(const Shape &s, const void *q, float scale, const int32_t
     if (e != hipSuccess) return e;
     if (mfma_path(s) && nsplit == 1) return hipSuccess;        // the kernel wrote the final output itself
 
+    return launch_attn_combine(s, part_o, part_ml, nsplit, out, lse, stream);
+}
+
+hipError_t launch_attn_combine(const Shape &s, const float *part_o, const float *part_ml, int nsplit,
+                               void *out, float *lse, hipStream_t stream)
+{
+    const int d = s.kv.head_dim;
     dim3 grid(s.n_q_heads, s.batch), block(256);
     if (s.dtype == DT_BF16)
         FASTOCR_LAUNCH(K_ATTN_COMBINE, attn_combine_kernel<uint16_t>, grid, block, 0, stream, part_o, part_ml, nsplit, d, (uint16_t *)out, lse);

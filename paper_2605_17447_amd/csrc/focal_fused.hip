@@ -1,0 +1,484 @@
+// Focal layer in one pass (Sec. 3.1.1, Eq. 1; Alg. 1, focal branch): the layer's dense decode
+// attention output AND the head-averaged focal scores of the image tokens from a single read
+// of K and V.  A focal layer needs both -- its own attention output over the full cache and the
+// scores that the following layers' fixation sets are cut from -- and K is the larger part of
+// either computation's traffic, so reading it twice (dense attention, then scoring) wastes a
+// third of the bytes.
+//
+// Structure (shared with the scoring-only kernel in score_resident.hip):
+//   - one 512-thread workgroup per (image-token range, sequence), at most one per compute unit,
+//     so the whole grid is resident; wave w streams KV head w % Hkv in 32-token tiles;
+//   - K and V tiles travel HBM -> LDS directly (one 8 KB slot each per wave); the next K tile is
+//     requested as soon as the current one has been read into registers, likewise for V, so one
+//     tile of each is always in flight while the other is being consumed;
+//   - logits are produced transposed, C[token][column]: columns 0..7 are the group's heads for
+//     the tile's first 16 tokens, columns 8..15 the same heads for its last 16 (two accumulators,
+//     one select), so every lane holds 4 logits of ONE head; they stay in 4 VGPRs named for the
+//     tile until the normalisers are known;
+//   - the same layout serves P*V: with P masked to "first-half tokens in columns 0..7, second-half
+//     tokens in columns 8..15" one v_mfma_f32_16x16x32_bf16 per 16 output dims accumulates
+//     O^T[dim][column]; columns n and n+8 are the two halves' partial sums of head n and are added
+//     at the end.  The running maximum of a head is uniform over the wave (it scales whole
+//     accumulator columns); rescaling happens only in tiles where some head's maximum grew;
+//   - each wave leaves an attention partial (accumulator, max, sum) in the workspace for the
+//     split-merge kernel of attn.hip; the ranges then exchange their softmax statistics, meet at
+//     the per-sequence barrier and turn the parked logits into scores exactly as the
+//     scoring-only kernel does.
+#include <atomic>
+
+#include "kernels.hpp"
+#include "resident.hpp"
+
+namespace fastocr {
+
+#define FUS_DECLARE(J) f32x4 park_##J;
+// image tile J of the wave; the K and V slots are refilled with tile J + 1
+#define FUS_STREAM_STEP(J)                                                                          \
+    {                                                                                               \
+        park_##J = tile_step(r1 - img_first(J), [&]() { issue_img((J) + 1, false); },               \
+                             [&]() { issue_img((J) + 1, true); });                                  \
+        if ((J) + 1 >= nimg) goto img_done;                                                         \
+    }
+// tile J after the barrier: this lane's 4 tokens, one head each on 8 neighbouring lanes
+#define FUS_FINISH_STEP(J)                                                                          \
+    {                                                                                               \
+        f32x4 v;                                                                                    \
+        _Pragma("unroll") for (int r = 0; r < 4; ++r) {                                             \
+            float x = fast_exp2(park_##J[r] - lh);                                                  \
+            x += dpp_move<kDppXor1>(x);                                                             \
+            x += dpp_move<kDppXor2>(x);                                                             \
+            x += dpp_move<kDppHalfMirror>(x);                                                       \
+            v[r] = x;                                                                               \
+        }                                                                                           \
+        if ((li & 7) == 0) *reinterpret_cast<f32x4 *>(&red[kvh * R + img_first(J) - r0 + tt0]) = v; \
+        if ((J) + 1 >= nimg) goto fin_done;                                                         \
+    }
+
+// {arrived, left} per sequence and a sticky time-out flag per slot; see score_resident.hip
+__device__ uint32_t g_fus_sync[kResSlots][2 * kResMaxBatch + 1];
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+template <bool PAGED>
+__global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
+    KvDev kv, BatchDev bv, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2,
+    int nranges, int R, float *part_ml, int sync_slot, long long spin_ticks,
+    float *__restrict__ scores, float *__restrict__ lse_out, float *__restrict__ mass_part,
+    float *__restrict__ att_o, float *__restrict__ att_ml)
+{
+    __shared__ __align__(16) unsigned char smem[kResWaves][2][8192];      // [wave][K, V]
+    __shared__ float sm_m[kResWaves][8], sm_z[kResWaves][8];
+    __shared__ float sm_lse[kResMaxHq];
+    __shared__ float sm_pm[kResWaves][64], sm_pz[kResWaves][64];
+    __shared__ float sm_red[kResWaves];
+    __shared__ int sm_met;
+
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int li = lane & 15, lg = lane >> 4;
+    const int rng = blockIdx.x, b = blockIdx.y;
+    const int Hkv = kv.n_kv_heads;
+    const int wpk = kResWaves / Hkv;
+    const int kvh = wave % Hkv, sub = wave / Hkv;
+
+    const SeqGeom geo = seq_geom(bv, b);
+    const int S = geo.S, v0 = geo.v0, N = geo.N;
+    const int Tn = S - N;
+
+    // image tiles of this wave: tile ti = sub + j*wpk of the range, j = 0 .. nimg-1
+    const int r0 = rng * R, r1 = min(N, r0 + R);
+    const int nt_range = r1 > r0 ? (r1 - r0 + kResTile - 1) / kResTile : 0;
+    const int nimg = min(nt_range > sub ? (nt_range - sub + wpk - 1) / wpk : 0, kResTmax);
+    // text tiles of this wave: u = slot + i*nslots
+    const int ntt = (Tn + kResTile - 1) / kResTile;
+    const int slot = rng * wpk + sub, nslots = nranges * wpk;
+    const int ntext = ntt > slot ? (ntt - slot + nslots - 1) / nslots : 0;
+
+    // Q as the B operand of the logits: column n = li holds head n & 7 of the group
+    const int hcol = li & 7;
+    const bool hi = li >= 8;                     // this lane's logits belong to the tile's last 16 tokens
+    u32x4 qq[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        qq[kk] = u32x4{0u, 0u, 0u, 0u};
+        if (hcol < G)
+            qq[kk] = *reinterpret_cast<const u32x4 *>(q + ((int64_t)b * Hq + (int64_t)kvh * G + hcol) * 128 + 8 * (4 * kk + lg));
+    }
+    // the query has arrived before the first tile is requested: the waits further down count
+    // tile loads only
+    asm volatile("" ::"v"(qq[0]), "v"(qq[1]), "v"(qq[2]), "v"(qq[3]));
+    const uint16_t *kbase = reinterpret_cast<const uint16_t *>(kv.k);
+    const uint16_t *vbase = reinterpret_cast<const uint16_t *>(kv.v);
+
+    const int rot = nimg > 0 ? (wave * 5 + rng * 3 + b * 7) % nimg : 0;
+    auto img_first = [&](int x) {                                                  // span-relative
+        int j = x + rot;
+        j = j >= nimg ? j - nimg : j;
+        return r0 + (sub + j * wpk) * kResTile;
+    };
+    auto text_first = [&](int x) { return (slot + x * nslots) * kResTile; };       // text-relative
+
+    // A tile goes into the wave's K or V slot: load e brings rows 4e .. 4e+3, lane (lg, li) one
+    // 16-byte chunk of row 4e + lg, which lands at slot + 1024 e + 16 lane.  For K the chunk is
+    // li ^ (row & 15) (the swizzle that makes the MFMA operand reads conflict-free); V stays
+    // row-major (chunk li).  Rows past the end of a ragged tile are clamped to its last row.
+    const int64_t seq_base = row_offset<false>(kv, b, 0, kvh);
+    const uint32_t stride_b = (uint32_t)kv.stride_token * 2u;            // bytes; 32 rows fit 32 bits (host-checked)
+    const uint32_t rowoff_lg = (uint32_t)lg * stride_b;
+    uint32_t chunk_k[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) chunk_k[k] = 16u * (uint32_t)((li ^ lg) ^ (4 * k));
+    const uint32_t chunk_v = 16u * (uint32_t)li;
+    const unsigned char *kbytes = reinterpret_cast<const unsigned char *>(kv.k);
+    const unsigned char *vbytes = reinterpret_cast<const unsigned char *>(kv.v);
+
+    auto issue_run = [&](int first_tok, int rv, bool isv) {
+        unsigned char *dst = smem[wave][isv ? 1 : 0];
+        const unsigned char *bytes = isv ? vbytes : kbytes;
+        const uint32_t limit = (uint32_t)(rv - 1) * stride_b;
+        if (PAGED) {
+            const int pt = kv.page_tokens;
+            const int pg0 = first_tok / pt, in0 = first_tok - pg0 * pt;
+            const int32_t *bt = kv.block_table + (int64_t)b * kv.max_pages;
+            const int64_t pa = bt[min(pg0, kv.max_pages - 1)], pb = bt[min(pg0 + 1, kv.max_pages - 1)];
+            const unsigned char *base_a = bytes + 2 * (pa * kv.stride_page + (int64_t)kvh * kv.stride_head + (int64_t)in0 * kv.stride_token);
+            const unsigned char *base_b = bytes + 2 * (pb * kv.stride_page + (int64_t)kvh * kv.stride_head + (int64_t)(in0 - pt) * kv.stride_token);
+            const uint32_t split = (uint32_t)(pt - in0) * stride_b;      // first byte offset of the second page
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t ro = min(rowoff_lg + (uint32_t)(4 * e) * stride_b, limit);
+                const unsigned char *base = ro >= split ? base_b : base_a;
+                lds_dma16(reinterpret_cast<const uint16_t *>(base + (ro + (isv ? chunk_v : chunk_k[e & 3]))), dst + 1024 * e);
+            }
+        } else {
+            const unsigned char *base = bytes + 2 * (seq_base + (int64_t)first_tok * kv.stride_token);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t ro = min(rowoff_lg + (uint32_t)(4 * e) * stride_b, limit);
+                lds_dma16(reinterpret_cast<const uint16_t *>(base + (ro + (isv ? chunk_v : chunk_k[e & 3]))), dst + 1024 * e);
+            }
+        }
+    };
+    // Past the wave's last tile the refill stays unconditional (the readers' "at most 8 loads
+    // outstanding" waits count on it) but fetches 256 bytes of the query, which are in cache.
+    const uint16_t *qrow = q + ((int64_t)b * Hq + (int64_t)kvh * G) * 128;
+    auto issue_dummy = [&](bool isv) {
+        unsigned char *dst = smem[wave][isv ? 1 : 0];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) lds_dma16(qrow + chunk_v / 2, dst + 1024 * e);
+    };
+    auto issue_img = [&](int x, bool isv) {
+        if (x >= nimg) { issue_dummy(isv); return; }
+        const int jf = img_first(x);
+        issue_run(v0 + jf, min(kResTile, r1 - jf), isv);
+    };
+    // text positions map to tokens with a gap at the image span, so the rows are addressed one by one
+    auto issue_text = [&](int x, bool isv) {
+        const int tf = text_first(x);
+        unsigned char *dst = smem[wave][isv ? 1 : 0];
+        const uint16_t *base = isv ? vbase : kbase;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int tc = min(tf + 4 * e + lg, Tn - 1);
+            const int tok = tc < v0 ? tc : tc + N;
+            lds_dma16(base + row_offset<PAGED>(kv, b, tok, kvh) + (isv ? chunk_v : chunk_k[e & 3]) / 2, dst + 1024 * e);
+        }
+    };
+    // tile number n of the wave (text tiles first, then image tiles), or the dummy past the end
+    auto issue_any = [&](int n, bool isv) {
+        if (n < ntext) issue_text(n, isv);
+        else issue_img(n - ntext, isv);
+    };
+
+    const int tt0 = 16 * (li >> 3) + 4 * lg;        // tile-relative token of this lane's first logit
+    float m = kMinusHuge, z = 0.f;                  // running max (uniform over the head's lanes), this lane's sum
+    f32x4 acc[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // LDS byte addresses: K rows li and 16 + li as the A operand, V rows 4lg.. and 16 + 4lg..
+    uint32_t rd_addr[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        rd_addr[kk] = lds_address(&smem[wave][0][0]) + li * 256 + ((((4 * kk + lg) ^ li) & 15) << 4);
+    const uint32_t rd_v = lds_address(&smem[wave][1][0]) + (4 * lg) * 256 + li * 16;
+
+    // The newest outstanding loads are always the 8 of the other slot's refill, so "at most 8
+    // outstanding" means the tile wanted here has landed.  Reads and waits are written in assembly:
+    // the compiler neither orders LDS reads after loads that land in LDS by themselves without
+    // draining ALL of them, nor may it move the products above the wait.
+    auto read_k = [&](u32x4(&kb)[8]) {
+        asm volatile(
+            "s_waitcnt vmcnt(8)\n\t"
+            "ds_read_b128 %0, %8\n\t"
+            "ds_read_b128 %1, %9\n\t"
+            "ds_read_b128 %2, %10\n\t"
+            "ds_read_b128 %3, %11\n\t"
+            "ds_read_b128 %4, %8 offset:4096\n\t"
+            "ds_read_b128 %5, %9 offset:4096\n\t"
+            "ds_read_b128 %6, %10 offset:4096\n\t"
+            "ds_read_b128 %7, %11 offset:4096\n\t"
+            "s_waitcnt lgkmcnt(0)"
+            : "=&v"(kb[0]), "=&v"(kb[1]), "=&v"(kb[2]), "=&v"(kb[3]), "=&v"(kb[4]), "=&v"(kb[5]), "=&v"(kb[6]), "=&v"(kb[7])
+            : "v"(rd_addr[0]), "v"(rd_addr[1]), "v"(rd_addr[2]), "v"(rd_addr[3])
+            : "memory");
+    };
+    // vv[e]: dims 8li .. 8li+7 of token 4lg + e (e < 4) or 16 + 4lg + e - 4 of the tile
+    auto read_v = [&](u32x4(&vv)[8]) {
+        asm volatile(
+            "s_waitcnt vmcnt(8)\n\t"
+            "ds_read_b128 %0, %8\n\t"
+            "ds_read_b128 %1, %8 offset:256\n\t"
+            "ds_read_b128 %2, %8 offset:512\n\t"
+            "ds_read_b128 %3, %8 offset:768\n\t"
+            "ds_read_b128 %4, %8 offset:4096\n\t"
+            "ds_read_b128 %5, %8 offset:4352\n\t"
+            "ds_read_b128 %6, %8 offset:4608\n\t"
+            "ds_read_b128 %7, %8 offset:4864\n\t"
+            "s_waitcnt lgkmcnt(0)"
+            : "=&v"(vv[0]), "=&v"(vv[1]), "=&v"(vv[2]), "=&v"(vv[3]), "=&v"(vv[4]), "=&v"(vv[5]), "=&v"(vv[6]), "=&v"(vv[7])
+            : "v"(rd_v)
+            : "memory");
+    };
+
+    // One tile: logits, online softmax, P*V.  nlive = tokens of the tile that exist (may exceed 32).
+    // Returns this lane's 4 logits (log2 domain; -inf for tokens past the end).
+    auto tile_step = [&](int nlive, auto &&next_k, auto &&next_v) -> f32x4 {
+        u32x4 kb[8];
+        read_k(kb);
+        next_k();
+        f32x4 c0 = f32x4{0.f, 0.f, 0.f, 0.f}, c1 = c0;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            c0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[kk]),
+                                                         __builtin_bit_cast(bf16x8, qq[kk]), c0, 0, 0, 0);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            c1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[4 + kk]),
+                                                         __builtin_bit_cast(bf16x8, qq[kk]), c1, 0, 0, 0);
+        f32x4 s;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float x = hi ? c1[r] : c0[r];
+            s[r] = (tt0 + r < nlive) ? x * scale_log2 : -INFINITY;
+        }
+        float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+        mx = fmaxf(mx, dpp_move<kDppRor8>(mx));
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m, mx);
+        if (__builtin_amdgcn_ballot_w64(m_new != m) != 0ull) {
+            const float alpha = fast_exp2(m - m_new);
+            z *= alpha;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) acc[t] *= alpha;
+            m = m_new;
+        }
+        float p[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) p[r] = fast_exp2(s[r] - m);
+        z += (p[0] + p[1]) + (p[2] + p[3]);
+        const uint32_t w0 = __builtin_bit_cast(uint32_t, bf16x2{(__bf16)p[0], (__bf16)p[1]});
+        const uint32_t w1 = __builtin_bit_cast(uint32_t, bf16x2{(__bf16)p[2], (__bf16)p[3]});
+        // contraction slots of lane group lg: tokens 4lg..4lg+3, then 16+4lg..16+4lg+3
+        const u32x4 pb = u32x4{hi ? 0u : w0, hi ? 0u : w1, hi ? w0 : 0u, hi ? w1 : 0u};
+
+        u32x4 vv[8];
+        read_v(vv);
+        next_v();
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int w = t >> 1;
+            const uint32_t selb = (t & 1) ? 0x07060302u : 0x05040100u;
+            u32x4 a;
+#pragma unroll
+            for (int pp = 0; pp < 4; ++pp) a[pp] = __builtin_amdgcn_perm(vv[2 * pp + 1][w], vv[2 * pp][w], selb);
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                             __builtin_bit_cast(bf16x8, pb), acc[t], 0, 0, 0);
+        }
+        return s;
+    };
+
+    // ---- stream: text tiles, then image tiles (logits parked in registers) ----------------------
+    RES_EACH_TILE(FUS_DECLARE)
+    if (ntext + nimg > 0) {
+        issue_any(0, false);
+        issue_any(0, true);
+        for (int x = 0; x < ntext; ++x)
+            (void)tile_step(Tn - text_first(x), [&]() { issue_any(x + 1, false); }, [&]() { issue_any(x + 1, true); });
+    }
+    if (nimg > 0) {
+        RES_EACH_TILE(FUS_STREAM_STEP)
+    }
+img_done:
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the trailing refills must not land later
+
+    // ---- attention partial of this wave: O^T columns n and n + 8 are the same head's halves -----
+    z += dpp_move<kDppRor8>(z);
+    z += __shfl_xor(z, 16);
+    z += __shfl_xor(z, 32);
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[t][r] += dpp_move<kDppRor8>(acc[t][r]);
+    if (li < 8 && li < G) {
+        // lane (head li, group lg) holds dims 32lg + 8r + t in acc[t][r]
+        const int64_t row = ((int64_t)b * Hq + (int64_t)kvh * G + li) * nslots + slot;
+        float *po = att_o + row * 128 + 32 * lg;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            *reinterpret_cast<f32x4 *>(po + 8 * r) = f32x4{acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
+            *reinterpret_cast<f32x4 *>(po + 8 * r + 4) = f32x4{acc[4][r], acc[5][r], acc[6][r], acc[7][r]};
+        }
+        if (lg == 0) {
+            att_ml[2 * row] = m;
+            att_ml[2 * row + 1] = z;
+            sm_m[wave][li] = m;
+            sm_z[wave][li] = z;
+        }
+    }
+    __syncthreads();
+
+    // ---- range statistics to the workspace (agent-scope atomics: see score_resident.hip) ---------
+    unsigned long long *my_part = reinterpret_cast<unsigned long long *>(part_ml) + ((int64_t)b * nranges + rng) * Hq;
+    if ((int)threadIdx.x < Hq) {
+        const int h = threadIdx.x, g = h / G, x = h - g * G;
+        float M = kMinusHuge, Z = 0.f;
+        for (int sb = 0; sb < wpk; ++sb) softmax_merge(M, Z, sm_m[g + sb * Hkv][x], sm_z[g + sb * Hkv][x]);
+        const unsigned long long mz = (unsigned long long)__float_as_uint(M) | ((unsigned long long)__float_as_uint(Z) << 32);
+        __hip_atomic_store(&my_part[h], mz, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    // ---- per-sequence barrier: every range of the sequence has published its statistics ---------
+    __syncthreads();
+    uint32_t left_before = 0u;
+    uint32_t *arrived = &g_fus_sync[sync_slot][2 * b], *left = arrived + 1;
+    auto leave = [&]() {
+        if (threadIdx.x == 0 && left_before == (uint32_t)nranges - 1u) {
+            __hip_atomic_store(left, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    };
+    if (threadIdx.x == 0) {
+        __hip_atomic_fetch_add(arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const long long t_start = wall_clock64();
+        bool ok = true;
+        while (__hip_atomic_load(arrived, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (uint32_t)nranges) {
+            __builtin_amdgcn_s_sleep(1);
+            if (wall_clock64() - t_start > spin_ticks) { ok = false; break; }
+        }
+        if (!ok) __hip_atomic_fetch_or(&g_fus_sync[sync_slot][2 * kResMaxBatch], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sm_met = ok ? 1 : 0;
+        left_before = __hip_atomic_fetch_add(left, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (!sm_met) {
+        // the sequence's other ranges never arrived: poison this range's scores
+        for (int i = threadIdx.x; i < r1 - r0; i += kResThreads)
+            scores[(int64_t)b * bv.max_vis_len + r0 + i] = __builtin_nanf("");
+        leave();
+        return;
+    }
+    // every head's log-sum-exp from the ranges' statistics: wave w merges ranges w, w+8, ..; lane = head
+    {
+        float M = kMinusHuge, Z = 0.f;
+        if (lane < Hq) {
+            const unsigned long long *pp = reinterpret_cast<const unsigned long long *>(part_ml) + (int64_t)b * nranges * Hq + lane;
+            for (int rr = wave; rr < nranges; rr += kResWaves) {
+                const unsigned long long mz = __hip_atomic_load(pp + (int64_t)rr * Hq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                softmax_merge(M, Z, __uint_as_float((uint32_t)mz), __uint_as_float((uint32_t)(mz >> 32)));
+            }
+        }
+        sm_pm[wave][lane] = M;
+        sm_pz[wave][lane] = Z;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < Hq) {
+        const int h = threadIdx.x;
+        float M = kMinusHuge, Z = 0.f;
+#pragma unroll
+        for (int w = 0; w < kResWaves; ++w) softmax_merge(M, Z, sm_pm[w][h], sm_pz[w][h]);
+        const float l2 = Z > 0.f ? M + log2f(Z) : -INFINITY;
+        sm_lse[h] = l2;
+        if (lse_out && rng == 0) lse_out[(int64_t)b * Hq + h] = l2 * kLn2;
+    }
+    __syncthreads();
+
+    // ---- probabilities of the parked logits, summed over the heads of each token ---------------
+    const float lh = hcol < G ? sm_lse[kvh * G + hcol] : INFINITY;
+    float *red = reinterpret_cast<float *>(&smem[0][0][0]);          // [Hkv][R], at most 32 KB
+    if (nimg > 0) {
+        RES_EACH_TILE(FUS_FINISH_STEP)
+    }
+fin_done:
+    __syncthreads();
+    float local = 0.f;
+    const float inv = 1.0f / (float)Hq;
+    for (int i = threadIdx.x; i < r1 - r0; i += kResThreads) {
+        float a = 0.f;
+        for (int g = 0; g < Hkv; ++g) a += red[g * R + i];
+        a *= inv;
+        scores[(int64_t)b * bv.max_vis_len + r0 + i] = a;
+        local += a;
+    }
+    if (mass_part) {
+        local = wave_sum(local);
+        if (lane == 0) sm_red[wave] = local;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float t = 0.f;
+            for (int w = 0; w < kResWaves; ++w) t += sm_red[w];
+            mass_part[(int64_t)b * nranges + rng] = t;
+        }
+    }
+    leave();
+}
+
+__global__ void fused_mass_kernel(const float *__restrict__ mass_part, int nranges, float *__restrict__ img_mass)
+{
+    const int b = blockIdx.x;
+    float t = 0.f;
+    for (int x = threadIdx.x; x < nranges; x += 64) t += mass_part[(int64_t)b * nranges + x];
+    t = wave_sum(t);
+    if (threadIdx.x == 0) img_mass[b] = t;
+}
+
+// Workspace: attention partials fp32 [B][Hq][nsp][128] and [B][Hq][nsp][2] with
+// nsp = nranges * wpk, range statistics fp32 [B][nranges][Hq][2], image-mass partials [B][nranges].
+size_t focal_fused_workspace_bytes(const Shape &s, const ResidentPlan &p)
+{
+    const size_t nsp = (size_t)p.nranges * p.wpk;
+    size_t bytes = (size_t)s.batch * s.n_q_heads * nsp * (128 + 2) * sizeof(float);
+    bytes += (size_t)s.batch * p.nranges * s.n_q_heads * 2 * sizeof(float);
+    bytes += (size_t)s.batch * p.nranges * sizeof(float);
+    return bytes;
+}
+
+hipError_t launch_focal_fused(const Shape &s, const ResidentPlan &p, const void *q, float scale, void *out,
+                              float *scores, float *lse, float *img_mass, void *ws, hipStream_t stream)
+{
+    const int nsp = p.nranges * p.wpk;
+    float *att_o = reinterpret_cast<float *>(ws);
+    float *att_ml = att_o + (size_t)s.batch * s.n_q_heads * nsp * 128;
+    float *part_ml = att_ml + (size_t)s.batch * s.n_q_heads * nsp * 2;
+    float *mass_part = part_ml + (size_t)s.batch * p.nranges * s.n_q_heads * 2;
+    static std::atomic<unsigned> call_no{0};
+    const int sync_slot = (int)(call_no.fetch_add(1u) % (unsigned)kResSlots);
+    const float scale_log2 = scale * kLog2e;
+    const int G = s.n_q_heads / s.kv.n_kv_heads;
+    const long long spin_ticks = 100000000ll / 4;          // 0.25 s of the 100 MHz wall clock
+
+    dim3 grid(p.nranges, s.batch), block(kResThreads);
+    if (s.paged)
+        FASTOCR_LAUNCH(K_FOCAL_FUSED, focal_fused_kernel<true>, grid, block, 0, stream, s.kv, s.bv,
+                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, p.nranges, p.range_tokens, part_ml, sync_slot,
+                       spin_ticks, scores, lse, img_mass ? mass_part : nullptr, att_o, att_ml);
+    else
+        FASTOCR_LAUNCH(K_FOCAL_FUSED, focal_fused_kernel<false>, grid, block, 0, stream, s.kv, s.bv,
+                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, p.nranges, p.range_tokens, part_ml, sync_slot,
+                       spin_ticks, scores, lse, img_mass ? mass_part : nullptr, att_o, att_ml);
+    if (img_mass) fused_mass_kernel<<<s.batch, 64, 0, stream>>>(mass_part, p.nranges, img_mass);
+    return launch_attn_combine(s, att_o, att_ml, nsp, out, nullptr, stream);
+}
+
+}  // namespace fastocr

@@ -9,7 +9,7 @@ namespace fastocr {
 // Kernel ids mirror fastocr_kernel in fastocr.h (used by the per-kernel timers).
 enum KernelId {
     K_SCORE_LOGITS = 0, K_SCORE_FINALIZE = 1, K_TOPK = 2, K_SPARSE_ATTN = 3, K_DENSE_ATTN = 4,
-    K_ATTN_COMBINE = 5, K_COUNT = 6
+    K_ATTN_COMBINE = 5, K_FOCAL_FUSED = 6, K_COUNT = 7
 };
 
 // Per-kernel timing (api.hip): when a timer is enabled for `kernel`, the next launch gets a pair of
@@ -47,6 +47,9 @@ size_t attn_workspace_bytes(const Shape &s, int nsplit);
 hipError_t launch_attn(const Shape &s, const void *q, float scale, const int32_t *sel_idx,
                        const int32_t *sel_cnt, int64_t kmax, void *out, float *lse, void *ws,
                        int nsplit, hipStream_t stream);
+// merge of nsplit partials per (sequence, head) in the layout above into the final output
+hipError_t launch_attn_combine(const Shape &s, const float *part_o, const float *part_ml, int nsplit,
+                               void *out, float *lse, hipStream_t stream);
 
 // ---- focal scoring (score.hip) ----------------------------------------------------------
 // Workspace: logits fp32 [B][Hq][pitch], part_ml fp32 [B][Hq][nsplit][2], mass partials.
@@ -63,6 +66,12 @@ bool resident_plan(const Shape &s, int num_cu, ResidentPlan *plan);
 size_t resident_workspace_bytes(const Shape &s, const ResidentPlan &p);
 hipError_t launch_score_resident(const Shape &s, const ResidentPlan &p, const void *q, float scale, float *scores,
                                  float *lse, float *img_mass, void *ws, hipStream_t stream);
+
+// ---- focal layer in one pass: dense attention output + scores (focal_fused.hip) -----------
+// Uses the same plan as the register-resident scoring kernel.
+size_t focal_fused_workspace_bytes(const Shape &s, const ResidentPlan &p);
+hipError_t launch_focal_fused(const Shape &s, const ResidentPlan &p, const void *q, float scale, void *out,
+                              float *scores, float *lse, float *img_mass, void *ws, hipStream_t stream);
 
 // ---- top-k (topk.hip) -------------------------------------------------------------------
 size_t topk_workspace_bytes(int batch, int max_vis_len);

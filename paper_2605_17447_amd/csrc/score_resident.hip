@@ -24,19 +24,10 @@
 #include <atomic>
 
 #include "kernels.hpp"
+#include "resident.hpp"
 
 namespace fastocr {
 
-constexpr int kResWaves = 8;
-constexpr int kResThreads = 64 * kResWaves;
-constexpr int kResTmax = 32;          // image tiles per wave held in registers
-constexpr int kResTile = 32;
-constexpr int kResMaxHq = 64;
-
-#define RES_EACH_TILE(M)                                                                            \
-    M(0) M(1) M(2) M(3) M(4) M(5) M(6) M(7) M(8) M(9) M(10) M(11) M(12) M(13) M(14) M(15)               \
-    M(16) M(17) M(18) M(19) M(20) M(21) M(22) M(23) M(24) M(25) M(26) M(27) M(28) M(29) M(30) M(31)
-static_assert(kResTmax == 32, "RES_EACH_TILE lists kResTmax tiles");
 #define RES_DECLARE(J) f32x4 park_##J;
 // image tile J of the wave: multiply, keep the logits, refill the tile's LDS slot
 #define RES_STREAM_STEP(J)                                                                          \
@@ -56,27 +47,11 @@ static_assert(kResTmax == 32, "RES_EACH_TILE lists kResTmax tiles");
         if ((J) + 1 >= nimg) goto fin_done;                                                         \
     }
 
-// 16 bytes per lane from global memory straight into LDS: lane l's data lands at lds_base + 16 l
-// (lds_base is wave-uniform).  Completion is tracked by vmcnt like any other vector load, but the
-// compiler does not order later LDS reads after it: the reader waits for vmcnt itself.
-__device__ __forceinline__ void lds_dma16(const uint16_t *src, unsigned char *lds_base)
-{
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                     (__attribute__((address_space(3))) void *)lds_base, 16, 0, /*nt*/ 2);
-}
-
-__device__ __forceinline__ uint32_t lds_address(const void *p)
-{
-    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)p;
-}
-
 // Barrier state lives in static device memory (zero when the module is loaded) rather than in
 // the caller's workspace, which would have to be cleared by an extra launch before every call:
 // {arrived, left} per sequence.  The last range to leave a barrier resets both counts, so a slot
 // is clean again when its call ends; calls take slots round-robin, so up to kResSlots calls may
 // overlap on one GPU.  The last word of a slot is a sticky "a barrier timed out" flag.
-constexpr int kResSlots = 32;
-constexpr int kResMaxBatch = 256;
 __device__ uint32_t g_res_sync[kResSlots][2 * kResMaxBatch + 1];
 
 bool resident_plan(const Shape &s, int num_cu, ResidentPlan *plan)

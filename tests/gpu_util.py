@@ -83,6 +83,16 @@ class GpuProblem:
         fo.dense_decode_attn(self.cache, self.batch, self.q, self.scale, out, self.ws(fb.OP_DENSE_DECODE_ATTN), lse)
         return out, lse
 
+    def focal_attn(self, want_lse=False, want_mass=False):
+        """Dense output and scores from the one-call focal layer."""
+        out = torch.full_like(self.q, 3.0)
+        sc = torch.full((self.B, self.batch.max_vis_len), -7.0, dtype=torch.float32, device=DEV)
+        lse = torch.zeros((self.B, self.Hq), dtype=torch.float32, device=DEV) if want_lse else None
+        mass = torch.zeros((self.B,), dtype=torch.float32, device=DEV) if want_mass else None
+        fo.focal_attn_score(self.cache, self.batch, self.q, self.scale, out, sc, self.ws(fb.OP_FOCAL_ATTN_SCORE),
+                            lse, mass)
+        return out, sc, lse, mass
+
     # ---- the same problem for the oracle -------------------------------------------------
     def oracle_cache(self) -> oracle.Cache:
         k, v = to_np(self.k), to_np(self.v)

@@ -51,6 +51,13 @@ def full_check(p: "GpuProblem", tau: float, what: str, exact_topk=True):
     check_out(out, ref_dense, what + " dense")
     assert np.allclose(dl.cpu().numpy()[nz], ref_dlse[nz], rtol=2e-5, atol=2e-5), what + " dense lse"
 
+    # the focal layer in one call: the dense output and the scores together
+    out, sc, lse, mass = p.focal_attn(want_lse=True, want_mass=True)
+    check_out(out, ref_dense, what + " focal-layer output")
+    check_scores(sc, ref_sc, p.vis_len, what + " focal-layer scores")
+    assert np.allclose(lse.cpu().numpy()[nz], ref_lse[nz], rtol=2e-5, atol=2e-5), what + " focal-layer lse"
+    assert np.allclose(mass.cpu().numpy(), ref_mass, atol=2e-5), what + " focal-layer image mass"
+
 
 # ------------------------------------------------------------------ config 1 (fp32, tiny)
 
@@ -224,6 +231,58 @@ def test_scoring_paths_paged(resident):
         fb.set_tuning("score_resident", 1)
 
 
+# ------------------------------------------------------------------ the focal layer in one pass
+
+@pytest.mark.parametrize("fused", [1, 0])
+@pytest.mark.parametrize("Hq,Hkv", [(28, 4), (64, 8), (8, 1), (6, 2)])
+def test_focal_layer_one_pass_against_the_oracle(fused, Hq, Hkv):
+    """Dense output and scores from one pass over K and V (and from the two separate kernels the
+    call falls back to), on a batch whose ranges hold several tiles per wave."""
+    fb.set_tuning("focal_fused", fused)
+    try:
+        case = TinyCase(seed=300 + Hq, B=40, Hq=Hq, Hkv=Hkv, d=128, n_vis=[1500 + 37 * i for i in range(40)],
+                        pre=[i % 7 * 5 for i in range(40)], post=[(i * 13) % 90 for i in range(40)], dtype="bf16")
+        p = problem_from_case(case)
+        oc = p.oracle_args()
+        ref_sc, ref_lse, ref_mass = oracle.focal_score(*oc)
+        ref_dense, _ = oracle.decode_attn(*oc)
+        out, sc, lse, mass = p.focal_attn(want_lse=True, want_mass=True)
+        check_out(out, ref_dense, f"fused={fused} output")
+        check_scores(sc, ref_sc, p.vis_len, f"fused={fused} scores")
+        assert np.allclose(lse.cpu().numpy(), ref_lse, rtol=2e-5, atol=2e-5)
+        assert np.allclose(mass.cpu().numpy(), ref_mass, atol=2e-5)
+        # twice the same call: bit-identical (no atomics in the arithmetic)
+        out2, sc2, _, _ = p.focal_attn()
+        assert torch.equal(out, out2) and torch.equal(sc, sc2)
+    finally:
+        fb.set_tuning("focal_fused", 1)
+
+
+def test_focal_layer_one_pass_paged_and_long_text():
+    wl = fs.config(5, batch=24, steps=4, n_visual=(600, 3000), grid_w=(20, 60), text_prefix=(3, 300), page_tokens=64)
+    bt = fs.make_batch(wl, device=DEV)
+    q = fs.queries_for_step(bt, 3, [x[2] for x in fs.centres(bt)])
+    p = GpuProblem(bt.k, bt.v, q, bt.seq_len(3), bt.vis_start, bt.n_vis, wl.head_dim ** -0.5,
+                   block_table=bt.block_table)
+    oc = p.oracle_args()
+    ref_sc, ref_lse, _ = oracle.focal_score(*oc)
+    ref_dense, _ = oracle.decode_attn(*oc)
+    out, sc, lse, _ = p.focal_attn(want_lse=True)
+    check_out(out, ref_dense, "paged one-pass output")
+    check_scores(sc, ref_sc, p.vis_len, "paged one-pass scores")
+    assert np.allclose(lse.cpu().numpy(), ref_lse, rtol=2e-5, atol=2e-5)
+    # text much longer than the image span: most tiles are text tiles
+    case = TinyCase(seed=77, B=3, Hq=28, Hkv=4, d=128, n_vis=[64, 200, 33], pre=[3000, 1500, 0],
+                    post=[500, 2100, 4000], dtype="bf16")
+    p = problem_from_case(case)
+    oc = p.oracle_args()
+    ref_sc, _, _ = oracle.focal_score(*oc)
+    ref_dense, _ = oracle.decode_attn(*oc)
+    out, sc, _, _ = p.focal_attn()
+    check_out(out, ref_dense, "long-text one-pass output")
+    check_scores(sc, ref_sc, p.vis_len, "long-text one-pass scores")
+
+
 # ------------------------------------------------------------------ full size, the benchmark's launch configuration
 
 def test_config4_full_size_in_the_benchmark_launch_configuration():
@@ -257,3 +316,8 @@ def test_config4_full_size_in_the_benchmark_launch_configuration():
         check_out(p.sparse(sel, torch.from_numpy(ref_cnt).to(DEV)), ref_sparse, f"config4 sparse tau={tau}")
     ref_dense, _ = oracle.decode_attn(*oc)
     check_out(p.dense()[0], ref_dense, "config4 dense")
+    out, sc1, lse1, mass1 = p.focal_attn(want_lse=True, want_mass=True)
+    check_out(out, ref_dense, "config4 focal-layer output")
+    check_scores(sc1, ref_sc, p.vis_len, "config4 focal-layer scores")
+    assert np.allclose(lse1.cpu().numpy(), ref_lse, rtol=2e-5, atol=2e-5)
+    assert np.allclose(mass1.cpu().numpy(), ref_mass, atol=2e-5)
