@@ -151,7 +151,7 @@ def main():
     cache = layer_caches[0]
     scale = float(np.float32(d ** -0.5))
     kmax = max(1, fo.keep_count(max_vis, tau))
-    need = max(fo.workspace_bytes(op, cache, batches[-1], Hq, kmax) for op in range(4))
+    need = max(fo.workspace_bytes(op, cache, batches[-1], Hq, kmax) for op in range(5))
     ws = torch.empty(need, dtype=torch.uint8, device=dev)
     scores = torch.zeros((B, max_vis), dtype=torch.float32, device=dev)
     idx = torch.zeros((B, kmax), dtype=torch.int32, device=dev)
@@ -236,7 +236,7 @@ def main():
     if not args.no_extras:
         names = {fb.KERNEL_SCORE_LOGITS: "score_logits", fb.KERNEL_SCORE_FINALIZE: "score_finalize",
                  fb.KERNEL_TOPK: "topk", fb.KERNEL_SPARSE_ATTN: "sparse_attn", fb.KERNEL_DENSE_ATTN: "dense_attn",
-                 fb.KERNEL_ATTN_COMBINE: "attn_combine"}
+                 fb.KERNEL_ATTN_COMBINE: "attn_combine", fb.KERNEL_FOCAL_FUSED: "focal_fused"}
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(n_warm, total):
@@ -248,11 +248,22 @@ def main():
             fo.sparse_decode_attn(caches[i], batches[i], qs[i], scale, idx, cnt, out, ws)
         torch.cuda.synchronize()
         sparse_ms = (time.perf_counter() - t0) * 1e3 / n_steps
+        # a focal layer as the controller runs it: dense output + scores from one pass, then top-k
+        for i in range(n_warm):
+            fo.focal_attn_score(caches[i], batches[i], qs[i], scale, out_dense, scores, ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n_warm, total):
+            fo.focal_attn_score(caches[i], batches[i], qs[i], scale, out_dense, scores, ws)
+            fo.topk_fixation(scores, batches[i], tau, idx, cnt, ws, prev_idx=idx, prev_cnt=cnt)
+        torch.cuda.synchronize()
+        focal_ms = (time.perf_counter() - t0) * 1e3 / n_steps
         for kid in names:
             fb.kernel_timer_enable(kid, 4 * n_steps)
         for i in range(n_warm, total):
             three_step(i)
             fo.dense_decode_attn(caches[i], batches[i], qs[i], scale, out_dense, ws)
+            fo.focal_attn_score(caches[i], batches[i], qs[i], scale, out_dense, scores, ws)
         torch.cuda.synchronize()
         kernels_us = {}
         for kid, nm in names.items():
@@ -262,11 +273,14 @@ def main():
         mean_T = mean_S - max_vis
         dense_bytes = B * (mean_S * 2 * R + 2 * Hq * d * e)
         sparse_bytes = B * ((kmax + mean_T) * 2 * R + 4 * kmax + 2 * Hq * d * e)
-        focal_ms = ms_per_step - sparse_ms + dense_ms            # dense output + score + top-k
+        focal_separate_ms = ms_per_step - sparse_ms + dense_ms   # dense output, scores and top-k as three calls
         blend = lambda f: f * focal_ms + (1 - f) * sparse_ms
         result["extras"] = {
             "dense_ms_per_layer_step": round(dense_ms, 5),
             "sparse_ms_per_layer_step": round(sparse_ms, 5),
+            "focal_layer_ms_per_layer_step": round(focal_ms, 5),
+            "focal_layer_ms_as_separate_calls": round(focal_separate_ms, 5),
+            "focal_layer_achieved_GBs": round(dense_bytes / (focal_ms * 1e-3) / 1e9, 1),
             "dense_layer_steps_per_s": round(1e3 / dense_ms, 2),
             "speedup_three_step_vs_dense": round(dense_ms / ms_per_step, 3),
             "speedup_sparse_vs_dense": round(dense_ms / sparse_ms, 3),

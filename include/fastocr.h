@@ -234,8 +234,9 @@ int fastocr_kernel_timer_read(int kernel, float *ms_out, int max_out);
 int fastocr_stream_probe(const void *src, void *dst, size_t bytes, void *sink, void *hip_stream);
 
 /* Launch-shape overrides for measurement sweeps: key "splits_score" | "splits_dense" |
- * "splits_sparse" (0 = automatic), "score_resident" | "focal_fused" (0 = use the separate
- * kernels instead), "attn_waves" (4 | 8).  Returns FASTOCR_EINVAL for an unknown key. */
+ * "splits_sparse" (0 = automatic), "score_resident" | "focal_fused" (0 = always the separate
+ * kernels, 1 = chosen by size (default), 2 = the single-kernel form whenever the shape fits),
+ * "attn_waves" (4 | 8).  Returns FASTOCR_EINVAL for an unknown key. */
 int fastocr_set_tuning(const char *key, int value);
 
 const char *fastocr_strerror(int status);

@@ -7,8 +7,9 @@ attends text + the kept tokens, and the set left by the deepest focal layer serv
 the next step (Cross-Step Fixation Reuse, Sec. 3.2).  When no focal layer set is given, the
 warm-up steps also record every layer's image-attention ratio (Eq. 1: the image mass that
 focal scoring returns) and the set is chosen after the last of them (Focal Layer Selection,
-Sec. 3.1.1) by the library's host routine.  No arithmetic happens here: the controller only
-owns device buffers and orders the C-ABI calls on one stream.
+Sec. 3.1.1) by the library's host routine.  A layer that needs both its full-cache output and
+the image scores gets them from one call (one pass over K and V).  No arithmetic happens here:
+the controller only owns device buffers and orders the C-ABI calls on one stream.
 """
 from __future__ import annotations
 
@@ -60,7 +61,7 @@ class FixationController:
 
     def _workspace(self, cache, batch):
         need = 0
-        for op in (_b.OP_FOCAL_SCORE, _b.OP_TOPK_FIXATION, _b.OP_SPARSE_DECODE_ATTN, _b.OP_DENSE_DECODE_ATTN):
+        for op in (_b.OP_FOCAL_ATTN_SCORE, _b.OP_TOPK_FIXATION, _b.OP_SPARSE_DECODE_ATTN, _b.OP_DENSE_DECODE_ATTN):
             need = max(need, self.ops.workspace_bytes(op, cache, batch, self.n_q_heads, self.kmax))
         if self._ws is None or self._ws_bytes < need:
             self._ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
@@ -83,17 +84,19 @@ class FixationController:
             ws = self._workspace(cache, batch)
             q, out = queries[l], outs[l]
             if not post_warmup:
-                ops.dense_decode_attn(cache, batch, q, self.scale, out, ws, stream=stream)
                 if self.focal is None:
-                    # r_l^(t) of Eq. 1 for every sequence, kept on the device until the last warm-up step
-                    ops.focal_score(cache, batch, q, self.scale, self.scores, ws, img_mass=self.ratios[t - 1, l],
-                                    stream=stream)
+                    # full attention plus r_l^(t) of Eq. 1 for every sequence from the same pass over the
+                    # cache; the ratios stay on the device until the last warm-up step
+                    ops.focal_attn_score(cache, batch, q, self.scale, out, self.scores, ws,
+                                         img_mass=self.ratios[t - 1, l], stream=stream)
+                else:
+                    ops.dense_decode_attn(cache, batch, q, self.scale, out, ws, stream=stream)
                 trace.append((l, "full", None))
                 continue
             selects = (l in self.focal) or (l == 0 and self.kept_from is None)
             if selects:
-                ops.dense_decode_attn(cache, batch, q, self.scale, out, ws, stream=stream)
-                ops.focal_score(cache, batch, q, self.scale, self.scores, ws, stream=stream)
+                # the layer's own output over the full cache and the scores its successors are pruned by
+                ops.focal_attn_score(cache, batch, q, self.scale, out, self.scores, ws, stream=stream)
                 warm = self.kept_from is not None
                 ops.topk_fixation(self.scores, batch, self.tau, self.kept_idx, self.kept_cnt, ws,
                                   prev_idx=self.kept_idx if warm else None,

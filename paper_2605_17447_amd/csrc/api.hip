@@ -212,6 +212,23 @@ static int check_qo(const fastocr_kv_view *kv, const void *q, const void *out, f
     return FASTOCR_OK;
 }
 
+// The register-resident kernels (scoring alone, or fused with the dense output) pay a fixed price
+// of 10-15 microseconds for their grid-wide exchange (statistics written through to memory, a
+// per-sequence barrier, partials read back); the paths built from separate kernels pay a second
+// read of K or a round trip of the logits through memory instead.  Measured crossovers on MI355X,
+// in image tiles per wave: scoring about 3, the fused focal layer about 12 (it saves one K read
+// but adds the merge of its attention partials).  mode 0 = never, 1 = by that rule, 2 = whenever
+// the shape fits.
+constexpr int kResidentMinTiles = 3;
+constexpr int kFusedMinTiles = 12;
+
+static bool use_resident(int mode, const Shape &s, ResidentPlan *rp, int min_tiles)
+{
+    if (mode == 0 || !resident_plan(s, kNumCU, rp)) return false;
+    if (rp->nranges * s.batch > device_cu_count()) return false;
+    return mode == 2 || rp->range_tokens / (32 * rp->wpk) >= min_tiles;
+}
+
 int fastocr_focal_score(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
                         int n_q_heads, float scale, float *scores, float *lse, float *img_mass,
                         void *ws, size_t ws_bytes, void *hip_stream)
@@ -229,7 +246,7 @@ int fastocr_focal_score(const fastocr_kv_view *kv, const fastocr_batch_view *bv,
     const int nsplit = choose_splits(FASTOCR_OP_FOCAL_SCORE, s, bv->max_seq_len);
     ResidentPlan rp;
     hipError_t e;
-    if (g_tune_score_resident && resident_plan(s, kNumCU, &rp) && rp.nranges * s.batch <= device_cu_count())
+    if (use_resident(g_tune_score_resident, s, &rp, kResidentMinTiles))
         e = launch_score_resident(s, rp, q, scale, scores, lse, img_mass, ws, (hipStream_t)hip_stream);
     else
         e = launch_score(s, q, scale, scores, lse, img_mass, ws, nsplit, (hipStream_t)hip_stream);
@@ -311,7 +328,7 @@ int fastocr_focal_attn_score(const fastocr_kv_view *kv, const fastocr_batch_view
     if (bv->batch == 0) return FASTOCR_OK;
     Shape s = make_shape(kv, bv, n_q_heads);
     ResidentPlan rp;
-    if (g_tune_focal_fused && resident_plan(s, kNumCU, &rp) && rp.nranges * s.batch <= device_cu_count()) {
+    if (use_resident(g_tune_focal_fused, s, &rp, kFusedMinTiles)) {
         hipError_t e = launch_focal_fused(s, rp, q, scale, out, scores, lse, img_mass, ws, (hipStream_t)hip_stream);
         return e == hipSuccess ? FASTOCR_OK : FASTOCR_EHIP;
     }
@@ -404,8 +421,8 @@ int fastocr_set_tuning(const char *key, int value)
     else if (!strcmp(key, "splits_sparse")) g_tune_splits[FASTOCR_OP_SPARSE_DECODE_ATTN] = value;
     else if (!strcmp(key, "splits_dense")) g_tune_splits[FASTOCR_OP_DENSE_DECODE_ATTN] = value;
     else if (!strcmp(key, "attn_waves")) g_tune_attn_waves = value;
-    else if (!strcmp(key, "score_resident")) g_tune_score_resident = value ? 1 : 0;
-    else if (!strcmp(key, "focal_fused")) g_tune_focal_fused = value ? 1 : 0;
+    else if (!strcmp(key, "score_resident") && value >= 0 && value <= 2) g_tune_score_resident = value;
+    else if (!strcmp(key, "focal_fused") && value >= 0 && value <= 2) g_tune_focal_fused = value;
     else return FASTOCR_EINVAL;
     return FASTOCR_OK;
 }

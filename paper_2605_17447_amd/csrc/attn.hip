@@ -341,6 +341,58 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(
     if (lse && c == 0) lse[bh] = Z > 0.f ? (M + log2f(Z)) * kLn2 : -INFINITY;
 }
 
+// The same merge for many partials per head (head_dim a multiple of 4).  A thread is (split lane,
+// dim lane): it walks every SL-th partial with 16-byte loads, four of them in flight, and the
+// split lanes are then added through LDS in a fixed order -- the serial walk of the kernel above
+// is bound by memory latency once a head has more than a handful of partials.
+template <typename T>
+__global__ __launch_bounds__(256) void attn_combine_wide_kernel(
+    const float *__restrict__ part_o, const float *__restrict__ part_ml, int nsplit, int d,
+    T *__restrict__ out, float *__restrict__ lse)
+{
+    __shared__ float sm_max[4];
+    __shared__ float sm_z[256];
+    __shared__ __align__(16) float sm_o[1024];         // [split lane][d]: SL * d <= 1024 as DL >= d/4
+    const int64_t bh = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;    // b*Hq + h
+    const int t = threadIdx.x;
+    const float *ml = part_ml + bh * nsplit * 2;
+    // dim lanes: the power of two covering d/4 (1 .. 64); split lanes: the rest of the 256 threads
+    const int nd4 = d / 4;
+    int DL = 1;
+    while (DL < nd4) DL <<= 1;
+    const int SL = 256 / DL;
+    const int dl = t & (DL - 1), sl = t / DL;
+
+    float mloc = -INFINITY;
+    for (int s = t; s < nsplit; s += 256) mloc = fmaxf(mloc, ml[2 * s]);
+    mloc = wave_max(mloc);
+    if ((t & 63) == 0) sm_max[t >> 6] = mloc;
+    __syncthreads();
+    const float M = fmaxf(fmaxf(sm_max[0], sm_max[1]), fmaxf(sm_max[2], sm_max[3]));
+
+    float Z = 0.f;
+    f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (M > -INFINITY && dl < nd4) {
+        const f32x4 *po = reinterpret_cast<const f32x4 *>(part_o + bh * nsplit * d) + dl;
+#pragma unroll 4
+        for (int s = sl; s < nsplit; s += SL) {
+            const float f = fast_exp2(ml[2 * s] - M);
+            Z += f * ml[2 * s + 1];
+            const f32x4 a = po[(int64_t)s * nd4];
+            o += a * f;
+        }
+    }
+    if (dl < nd4) *reinterpret_cast<f32x4 *>(&sm_o[sl * d + 4 * dl]) = o;
+    if (dl == 0) sm_z[sl] = Z;
+    __syncthreads();
+    if (t < d) {
+        float acc = 0.f, zt = 0.f;
+        for (int x = 0; x < SL; ++x) { acc += sm_o[x * d + t]; zt += sm_z[x]; }
+        store_elem<T>(out + bh * d + t, zt > 0.f ? acc / zt : 0.f);
+        if (lse && t == 0) lse[bh] = zt > 0.f ? (M + log2f(zt)) * kLn2 : -INFINITY;
+    }
+}
+
 // -----------------------------------------------------------------------------------------
 // Host side
 // -----------------------------------------------------------------------------------------
@@ -416,6 +468,14 @@ hipError_t launch_attn_combine(const Shape &s, const float *part_o, const float 
 {
     const int d = s.kv.head_dim;
     dim3 grid(s.n_q_heads, s.batch), block(256);
+    if (d % 4 == 0 && nsplit > 2) {
+        // several partials per head: spread them over the workgroup's threads
+        if (s.dtype == DT_BF16)
+            FASTOCR_LAUNCH(K_ATTN_COMBINE, attn_combine_wide_kernel<uint16_t>, grid, block, 0, stream, part_o, part_ml, nsplit, d, (uint16_t *)out, lse);
+        else
+            FASTOCR_LAUNCH(K_ATTN_COMBINE, attn_combine_wide_kernel<float>, grid, block, 0, stream, part_o, part_ml, nsplit, d, (float *)out, lse);
+        return hipGetLastError();
+    }
     if (s.dtype == DT_BF16)
         FASTOCR_LAUNCH(K_ATTN_COMBINE, attn_combine_kernel<uint16_t>, grid, block, 0, stream, part_o, part_ml, nsplit, d, (uint16_t *)out, lse);
     else

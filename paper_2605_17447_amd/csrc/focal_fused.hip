@@ -31,33 +31,15 @@
 
 namespace fastocr {
 
-#define FUS_DECLARE(J) f32x4 park_##J;
-// image tile J of the wave; the K and V slots are refilled with tile J + 1
-#define FUS_STREAM_STEP(J)                                                                          \
-    {                                                                                               \
-        park_##J = tile_step(r1 - img_first(J), [&]() { issue_img((J) + 1, false); },               \
-                             [&]() { issue_img((J) + 1, true); });                                  \
-        if ((J) + 1 >= nimg) goto img_done;                                                         \
-    }
-// tile J after the barrier: this lane's 4 tokens, one head each on 8 neighbouring lanes
-#define FUS_FINISH_STEP(J)                                                                          \
-    {                                                                                               \
-        f32x4 v;                                                                                    \
-        _Pragma("unroll") for (int r = 0; r < 4; ++r) {                                             \
-            float x = fast_exp2(park_##J[r] - lh);                                                  \
-            x += dpp_move<kDppXor1>(x);                                                             \
-            x += dpp_move<kDppXor2>(x);                                                             \
-            x += dpp_move<kDppHalfMirror>(x);                                                       \
-            v[r] = x;                                                                               \
-        }                                                                                           \
-        if ((li & 7) == 0) *reinterpret_cast<f32x4 *>(&red[kvh * R + img_first(J) - r0 + tt0]) = v; \
-        if ((J) + 1 >= nimg) goto fin_done;                                                         \
-    }
-
 // {arrived, left} per sequence and a sticky time-out flag per slot; see score_resident.hip
 __device__ uint32_t g_fus_sync[kResSlots][2 * kResMaxBatch + 1];
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+// One logit per image tile of the wave, indexed by the (wave-uniform) tile number: the compiler
+// keeps such a vector in 32 consecutive VGPRs and addresses it through the register-index mode,
+// so the tile loop stays a loop instead of 32 unrolled copies that overflow the instruction cache.
+typedef float f32x32 __attribute__((ext_vector_type(32)));
+static_assert(kResTmax == 32, "one f32x32 per logit row holds kResTmax tiles");
 
 template <bool PAGED>
 __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
@@ -300,17 +282,20 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
     };
 
     // ---- stream: text tiles, then image tiles (logits parked in registers) ----------------------
-    RES_EACH_TILE(FUS_DECLARE)
+    f32x32 park0, park1, park2, park3;          // logit r of image tile J in park<r>[J]
     if (ntext + nimg > 0) {
         issue_any(0, false);
         issue_any(0, true);
         for (int x = 0; x < ntext; ++x)
             (void)tile_step(Tn - text_first(x), [&]() { issue_any(x + 1, false); }, [&]() { issue_any(x + 1, true); });
+        for (int J = 0; J < nimg; ++J) {
+            const f32x4 s = tile_step(r1 - img_first(J), [&]() { issue_img(J + 1, false); }, [&]() { issue_img(J + 1, true); });
+            park0[J] = s[0];
+            park1[J] = s[1];
+            park2[J] = s[2];
+            park3[J] = s[3];
+        }
     }
-    if (nimg > 0) {
-        RES_EACH_TILE(FUS_STREAM_STEP)
-    }
-img_done:
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the trailing refills must not land later
 
     // ---- attention partial of this wave: O^T columns n and n + 8 are the same head's halves -----
@@ -407,10 +392,19 @@ img_done:
     // ---- probabilities of the parked logits, summed over the heads of each token ---------------
     const float lh = hcol < G ? sm_lse[kvh * G + hcol] : INFINITY;
     float *red = reinterpret_cast<float *>(&smem[0][0][0]);          // [Hkv][R], at most 32 KB
-    if (nimg > 0) {
-        RES_EACH_TILE(FUS_FINISH_STEP)
+    for (int J = 0; J < nimg; ++J) {
+        // this lane's 4 tokens of tile J, one head each on 8 neighbouring lanes
+        f32x4 v = f32x4{park0[J], park1[J], park2[J], park3[J]};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            float x = fast_exp2(v[r] - lh);
+            x += dpp_move<kDppXor1>(x);
+            x += dpp_move<kDppXor2>(x);
+            x += dpp_move<kDppHalfMirror>(x);
+            v[r] = x;
+        }
+        if ((li & 7) == 0) *reinterpret_cast<f32x4 *>(&red[kvh * R + img_first(J) - r0 + tt0]) = v;
     }
-fin_done:
     __syncthreads();
     float local = 0.f;
     const float inv = 1.0f / (float)Hq;

@@ -22,8 +22,8 @@ class Recorder:
     def dense_decode_attn(self, cache, batch, q, scale, out, ws, **kw):
         self.calls.append(("dense", cache))
 
-    def focal_score(self, cache, batch, q, scale, scores, ws, **kw):
-        self.calls.append(("score", cache))
+    def focal_attn_score(self, cache, batch, q, scale, out, scores, ws, **kw):
+        self.calls.append(("dense+score", cache))
 
     def topk_fixation(self, scores, batch, tau, sel_idx, sel_cnt, ws, prev_idx=None, prev_cnt=None, **kw):
         self.calls.append(("topk", prev_idx is not None))
@@ -48,7 +48,7 @@ def _run(n_layers, focal, warmup, steps):
             if mode == "full":
                 expect.append("dense")
             elif mode == "full+select":
-                expect += ["dense", "score", "topk"]
+                expect += ["dense+score", "topk"]
             else:
                 expect.append("sparse")
         assert [c[0] for c in rec.calls] == expect

@@ -100,8 +100,8 @@ class _Recorder:
     def dense_decode_attn(self, *a, **k):
         self.calls.append("dense")
 
-    def focal_score(self, cache, batch, q, scale, scores, ws, img_mass=None, **k):
-        self.calls.append(("score", img_mass is not None))
+    def focal_attn_score(self, cache, batch, q, scale, out, scores, ws, img_mass=None, **k):
+        self.calls.append(("dense+score", img_mass is not None))
 
     def topk_fixation(self, *a, **k):
         self.calls.append("topk")
@@ -122,7 +122,7 @@ def test_controller_profiles_during_warm_up_and_then_uses_the_chosen_set():
     with pytest.raises(RuntimeError):
         ctl.step(3, None, q, q)                       # selection has not happened yet
     ctl.step(1, None, q, q)
-    assert rec.calls == ["dense", ("score", True)] * 4 and ctl.focal is None
+    assert rec.calls == [("dense+score", True)] * 4 and ctl.focal is None
     rec.calls.clear()
     ctl.step(2, None, q, q)
     assert rec.calls[-1] == ("select", (2, 4, 3), 0.5, 1) and ctl.focal == [1, 3]

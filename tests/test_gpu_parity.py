@@ -19,14 +19,21 @@ if torch.cuda.is_available():
 
 
 def full_check(p: "GpuProblem", tau: float, what: str, exact_topk=True):
-    """All four calls of one problem against the oracle."""
+    """All calls of one problem against the oracle.  Scoring and the one-call focal layer run in
+    both of their forms: the single register-resident kernel wherever the shape fits it (mode 2)
+    and the separate kernels (mode 0); the size rule in between only picks one of the two."""
     oc = p.oracle_args()
     ref_sc, ref_lse, ref_mass = oracle.focal_score(*oc)
-    sc, lse, mass = p.scores(want_lse=True, want_mass=True)
-    check_scores(sc, ref_sc, p.vis_len, what + " scores")
     nz = [b for b in range(p.B) if p.seq_len[b] > 0]
-    assert np.allclose(lse.cpu().numpy()[nz], ref_lse[nz], rtol=2e-5, atol=2e-5), what + " lse"
-    assert np.allclose(mass.cpu().numpy(), ref_mass, atol=2e-5), what + " image mass"
+    try:
+        for mode in (0, 2):
+            fb.set_tuning("score_resident", mode)
+            sc, lse, mass = p.scores(want_lse=True, want_mass=True)
+            check_scores(sc, ref_sc, p.vis_len, f"{what} scores (mode {mode})")
+            assert np.allclose(lse.cpu().numpy()[nz], ref_lse[nz], rtol=2e-5, atol=2e-5), what + " lse"
+            assert np.allclose(mass.cpu().numpy(), ref_mass, atol=2e-5), what + " image mass"
+    finally:
+        fb.set_tuning("score_resident", 1)
 
     ref_idx, ref_cnt = oracle.topk_fixation(ref_sc, p.vis_len, tau)
     idx, cnt = p.topk(sc, tau)
@@ -52,11 +59,16 @@ def full_check(p: "GpuProblem", tau: float, what: str, exact_topk=True):
     assert np.allclose(dl.cpu().numpy()[nz], ref_dlse[nz], rtol=2e-5, atol=2e-5), what + " dense lse"
 
     # the focal layer in one call: the dense output and the scores together
-    out, sc, lse, mass = p.focal_attn(want_lse=True, want_mass=True)
-    check_out(out, ref_dense, what + " focal-layer output")
-    check_scores(sc, ref_sc, p.vis_len, what + " focal-layer scores")
-    assert np.allclose(lse.cpu().numpy()[nz], ref_lse[nz], rtol=2e-5, atol=2e-5), what + " focal-layer lse"
-    assert np.allclose(mass.cpu().numpy(), ref_mass, atol=2e-5), what + " focal-layer image mass"
+    try:
+        for mode in (0, 2):
+            fb.set_tuning("focal_fused", mode)
+            out, sc, lse, mass = p.focal_attn(want_lse=True, want_mass=True)
+            check_out(out, ref_dense, f"{what} focal-layer output (mode {mode})")
+            check_scores(sc, ref_sc, p.vis_len, f"{what} focal-layer scores (mode {mode})")
+            assert np.allclose(lse.cpu().numpy()[nz], ref_lse[nz], rtol=2e-5, atol=2e-5), what + " focal-layer lse"
+            assert np.allclose(mass.cpu().numpy(), ref_mass, atol=2e-5), what + " focal-layer image mass"
+    finally:
+        fb.set_tuning("focal_fused", 1)
 
 
 # ------------------------------------------------------------------ config 1 (fp32, tiny)
@@ -195,7 +207,7 @@ def test_degenerate_sequences():
 
 # ------------------------------------------------------------------ both scoring paths
 
-@pytest.mark.parametrize("resident", [1, 0])
+@pytest.mark.parametrize("resident", [2, 0])
 @pytest.mark.parametrize("Hq,Hkv", [(28, 4), (64, 8), (8, 1), (6, 2)])
 def test_scoring_paths_agree_with_the_oracle(resident, Hq, Hkv):
     """Register-resident scoring (one kernel, per-sequence barrier) and the two-kernel path that
@@ -214,7 +226,7 @@ def test_scoring_paths_agree_with_the_oracle(resident, Hq, Hkv):
         fb.set_tuning("score_resident", 1)
 
 
-@pytest.mark.parametrize("resident", [1, 0])
+@pytest.mark.parametrize("resident", [2, 0])
 def test_scoring_paths_paged(resident):
     fb.set_tuning("score_resident", resident)
     try:
@@ -233,7 +245,7 @@ def test_scoring_paths_paged(resident):
 
 # ------------------------------------------------------------------ the focal layer in one pass
 
-@pytest.mark.parametrize("fused", [1, 0])
+@pytest.mark.parametrize("fused", [2, 0])
 @pytest.mark.parametrize("Hq,Hkv", [(28, 4), (64, 8), (8, 1), (6, 2)])
 def test_focal_layer_one_pass_against_the_oracle(fused, Hq, Hkv):
     """Dense output and scores from one pass over K and V (and from the two separate kernels the
@@ -259,28 +271,32 @@ def test_focal_layer_one_pass_against_the_oracle(fused, Hq, Hkv):
 
 
 def test_focal_layer_one_pass_paged_and_long_text():
-    wl = fs.config(5, batch=24, steps=4, n_visual=(600, 3000), grid_w=(20, 60), text_prefix=(3, 300), page_tokens=64)
-    bt = fs.make_batch(wl, device=DEV)
-    q = fs.queries_for_step(bt, 3, [x[2] for x in fs.centres(bt)])
-    p = GpuProblem(bt.k, bt.v, q, bt.seq_len(3), bt.vis_start, bt.n_vis, wl.head_dim ** -0.5,
-                   block_table=bt.block_table)
-    oc = p.oracle_args()
-    ref_sc, ref_lse, _ = oracle.focal_score(*oc)
-    ref_dense, _ = oracle.decode_attn(*oc)
-    out, sc, lse, _ = p.focal_attn(want_lse=True)
-    check_out(out, ref_dense, "paged one-pass output")
-    check_scores(sc, ref_sc, p.vis_len, "paged one-pass scores")
-    assert np.allclose(lse.cpu().numpy(), ref_lse, rtol=2e-5, atol=2e-5)
-    # text much longer than the image span: most tiles are text tiles
-    case = TinyCase(seed=77, B=3, Hq=28, Hkv=4, d=128, n_vis=[64, 200, 33], pre=[3000, 1500, 0],
-                    post=[500, 2100, 4000], dtype="bf16")
-    p = problem_from_case(case)
-    oc = p.oracle_args()
-    ref_sc, _, _ = oracle.focal_score(*oc)
-    ref_dense, _ = oracle.decode_attn(*oc)
-    out, sc, _, _ = p.focal_attn()
-    check_out(out, ref_dense, "long-text one-pass output")
-    check_scores(sc, ref_sc, p.vis_len, "long-text one-pass scores")
+    fb.set_tuning("focal_fused", 2)
+    try:
+        wl = fs.config(5, batch=24, steps=4, n_visual=(600, 3000), grid_w=(20, 60), text_prefix=(3, 300), page_tokens=64)
+        bt = fs.make_batch(wl, device=DEV)
+        q = fs.queries_for_step(bt, 3, [x[2] for x in fs.centres(bt)])
+        p = GpuProblem(bt.k, bt.v, q, bt.seq_len(3), bt.vis_start, bt.n_vis, wl.head_dim ** -0.5,
+                       block_table=bt.block_table)
+        oc = p.oracle_args()
+        ref_sc, ref_lse, _ = oracle.focal_score(*oc)
+        ref_dense, _ = oracle.decode_attn(*oc)
+        out, sc, lse, _ = p.focal_attn(want_lse=True)
+        check_out(out, ref_dense, "paged one-pass output")
+        check_scores(sc, ref_sc, p.vis_len, "paged one-pass scores")
+        assert np.allclose(lse.cpu().numpy(), ref_lse, rtol=2e-5, atol=2e-5)
+        # text much longer than the image span: most tiles are text tiles
+        case = TinyCase(seed=77, B=3, Hq=28, Hkv=4, d=128, n_vis=[64, 200, 33], pre=[3000, 1500, 0],
+                        post=[500, 2100, 4000], dtype="bf16")
+        p = problem_from_case(case)
+        oc = p.oracle_args()
+        ref_sc, _, _ = oracle.focal_score(*oc)
+        ref_dense, _ = oracle.decode_attn(*oc)
+        out, sc, _, _ = p.focal_attn()
+        check_out(out, ref_dense, "long-text one-pass output")
+        check_scores(sc, ref_sc, p.vis_len, "long-text one-pass scores")
+    finally:
+        fb.set_tuning("focal_fused", 1)
 
 
 # ------------------------------------------------------------------ full size, the benchmark's launch configuration
