@@ -105,6 +105,20 @@ __device__ __forceinline__ float wave_sum(float x)
     return x;
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves (shifts
+// within rows of 16 lanes, then the last lane of a row broadcast into the following rows): six
+// full-rate VALU additions instead of six round trips through the LDS crossbar.
+__device__ __forceinline__ int wave_scan_incl(int x)
+{
+    x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, false);      // row_shr:1
+    x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, false);      // row_shr:2
+    x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, false);      // row_shr:4
+    x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, false);      // row_shr:8
+    x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, false);      // row_bcast:15 into rows 1 and 3
+    x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, false);      // row_bcast:31 into rows 2 and 3
+    return x;
+}
+
 // exp2 with exp2(-inf) = 0 and no NaN for (-inf) - (-inf) handled by the callers
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 

@@ -3,12 +3,11 @@
 //
 // The scores become order-preserving 32-bit keys.  The k-th largest key (the threshold) is found
 // by an MSB-first 8-bit radix select in LDS; everything above it, plus the lowest-index keys equal
-// to it until k, is written in ascending index order.  To keep the select short and the whole
-// chip busy, a sequence is spread over several 1024-thread workgroups that first reduce the N
-// keys to a short candidate list bounded below by (a) the previous step's set -- the warm start:
-// its k tokens' smallest current key can only be at or below the new threshold -- and (b) a
-// sample of the scores; see topk_kernel.  The result never depends on either bound.
-#include <atomic>
+// to it until k, is written in ascending index order.  The select is shortened by first reducing
+// the N keys to a short candidate list bounded below by (a) the previous step's set -- the warm
+// start: its k tokens' smallest current key can only be at or below the new threshold -- and (b)
+// a sample of the scores; the writing is spread over several 1024-thread workgroups per
+// sequence; see topk_kernel.  The result never depends on either bound.
 
 #include "kernels.hpp"
 
@@ -18,7 +17,6 @@ constexpr int kTopkThreads = 1024;
 constexpr int kTopkWaves = kTopkThreads / 64;
 constexpr int kCandCap = 4096;
 constexpr int kLdsKeyCap = 24576;
-constexpr int kBitmapWords = 1024;        // candidates path: image spans of up to 32768 tokens
 
 __device__ __forceinline__ uint32_t order_key(float x)
 {
@@ -41,15 +39,19 @@ __device__ __forceinline__ int keep_count_dev(int n, double tau)
 // *ties_needed, how many keys equal to it belong to the top k.  All threads must call.
 // With stop_shift > 0 only the bits at and above it are resolved: the result is the k-th largest
 // key with its low bits cleared, a lower bound of it (and *ties_needed is meaningless).
-__device__ uint32_t radix_select(const uint32_t *keys, int n, int k, uint32_t *hist, int *s_pick,
+// Two histograms alternate between the passes (the idle one is cleared while the other is being
+// filled), which leaves two workgroup barriers per 8-bit pass.
+__device__ uint32_t radix_select(const uint32_t *keys, int n, int k, uint32_t (*hist)[256], int *s_pick,
                                  int *ties_needed, int stop_shift = 0)
 {
     const int tid = threadIdx.x, lane = tid & 63;
     uint32_t prefix = 0u, mask = 0u;
-    int kk = k;
+    int kk = k, cur = 0;
+    if (tid < 256) hist[0][tid] = 0u;
+    __syncthreads();
     for (int shift = 24; shift >= stop_shift; shift -= 8) {
-        if (tid < 256) hist[tid] = 0u;
-        __syncthreads();
+        uint32_t *h = hist[cur];
+        if (tid < 256) hist[cur ^ 1][tid] = 0u;
         for (int i0 = 0; i0 < n; i0 += kTopkThreads) {
             const int i = i0 + tid;
             const bool in = i < n;
@@ -59,13 +61,13 @@ __device__ uint32_t radix_select(const uint32_t *keys, int n, int k, uint32_t *h
             // a whole wave on one digit (the usual case for the exponent byte) adds once
             const uint64_t live_mask = __ballot(live);
             if (live_mask) {
-                const int first = __ffsll((long long)live_mask) - 1;
-                const uint32_t d0 = __shfl(dgt, first);
+                const int first = __builtin_amdgcn_readfirstlane(__ffsll((long long)live_mask) - 1);
+                const uint32_t d0 = (uint32_t)__builtin_amdgcn_readlane((int)dgt, first);
                 const uint64_t same = __ballot(live && dgt == d0);
                 if (same == live_mask) {
-                    if (lane == first) atomicAdd(&hist[d0], (uint32_t)__popcll(live_mask));
+                    if (lane == first) atomicAdd(&h[d0], (uint32_t)__popcll(live_mask));
                 } else if (live) {
-                    atomicAdd(&hist[dgt], 1u);
+                    atomicAdd(&h[dgt], 1u);
                 }
             }
         }
@@ -74,13 +76,8 @@ __device__ uint32_t radix_select(const uint32_t *keys, int n, int k, uint32_t *h
             // lane owns digits 255-4*lane .. 252-4*lane (descending)
             uint32_t c[4], tot = 0u;
 #pragma unroll
-            for (int x = 0; x < 4; ++x) { c[x] = hist[255 - (4 * lane + x)]; tot += c[x]; }
-            uint32_t incl = tot;
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                const uint32_t t = __shfl_up(incl, o);
-                if (lane >= o) incl += t;
-            }
+            for (int x = 0; x < 4; ++x) { c[x] = h[255 - (4 * lane + x)]; tot += c[x]; }
+            const uint32_t incl = (uint32_t)wave_scan_incl((int)tot);
             const uint32_t above = incl - tot;           // keys in strictly larger digits
             if (above < (uint32_t)kk && incl >= (uint32_t)kk) {
                 // the k-th key falls into one of this lane's four digits
@@ -96,51 +93,47 @@ __device__ uint32_t radix_select(const uint32_t *keys, int n, int k, uint32_t *h
             }
         }
         __syncthreads();
+        // the next pass writes s_pick only after its own first barrier, which every thread
+        // reaches after this read
         prefix |= ((uint32_t)s_pick[0]) << shift;
         mask |= 255u << shift;
         kk = s_pick[1];
-        __syncthreads();
+        cur ^= 1;
     }
+    __syncthreads();          // callers may reuse keys, hist and s_pick right away
     *ties_needed = kk;
     return prefix;
 }
 
-// Per-sequence counters of the multi-workgroup path: candidates appended so far, workgroups
-// arrived.  They live in static device memory (zero when the module is loaded) rather than in the
-// caller's workspace, which would have to be cleared by an extra launch before every call; the
-// workgroup that arrives last is the only one still running for its sequence and clears them, so
-// a slot is clean again when its call ends.  Calls take slots round-robin: up to kTopkSlots calls
-// may overlap on one GPU.  Batches beyond kTopkMaxBatch use one workgroup per sequence.
-struct TopkCounters { uint32_t ncand, arrived; };
-constexpr int kTopkSlots = 32;
-constexpr int kTopkMaxBatch = 1024;
-__device__ TopkCounters g_topk_ctr[kTopkSlots][kTopkMaxBatch];
-
-// Grid (parts, batch).  Every workgroup of a sequence derives the same lower bound theta0 of the
-// threshold for itself, filters its own slice of the scores against it and appends the survivors
-// to the sequence's candidate list; the workgroup that arrives last selects among the candidates.
+// General form, for image spans beyond the register-resident kernel below.
+// Grid (parts, batch).  The workgroups of a sequence do not talk to each other: each one loads ALL
+// of the sequence's keys into LDS (64 KB at N = 16384, read from cache), finds the exact threshold
+// for itself and writes only its own contiguous segment of the ascending result, at the position
+// that the count of selected tokens before the segment gives.  Redundant arithmetic is cheap here;
+// a candidate list handed from workgroup to workgroup through memory costs several dependent
+// round trips.  The threshold search is shortened by a lower bound theta0 of the threshold:
 //   theta0 = max(bound from the previous set, bound from a sample)
 //   previous set (warm start): the smallest current key among its k tokens -- a certain bound
 //     (k tokens reach it), tight when the fixation moved little;
 //   sample: the r-th largest of 1024 evenly spaced scores, r chosen so that about 1.5 k tokens
-//     reach it -- a likely bound only, so the last workgroup checks that at least k candidates came
-//     in.  If they did, the k largest overall are among them and the result is exact.
-// If fewer than k or more than kCandCap candidates came in, the last workgroup selects over all N
-// keys on its own: the result is the same in every case.
-__global__ __launch_bounds__(kTopkThreads) void topk_kernel(
+//     reach it -- a likely bound only.
+// Keys at or above theta0 are compacted into a candidate list; if at least k and at most kCandCap
+// came in, the k largest overall are among them and the radix select runs over the candidates,
+// otherwise over all N keys: the result is the same in every case.
+// Image spans whose keys do not fit LDS run as one workgroup per sequence with the keys in the
+// workspace.
+__global__ __launch_bounds__(kTopkThreads) void topk_general_kernel(
     const float *__restrict__ scores, BatchDev bv, double tau, const int32_t *prev_idx,
     const int32_t *prev_cnt, int32_t *sel_idx, int32_t *sel_cnt, int64_t kmax,
-    uint32_t *__restrict__ gkeys, int lds_keys, int sync_slot, unsigned long long *cand_list)
+    uint32_t *__restrict__ gkeys, int lds_keys)
 {
-    TopkCounters *ctr = g_topk_ctr[sync_slot];
     extern __shared__ uint32_t dyn_keys[];
-    __shared__ uint32_t hist[256];
+    __shared__ uint32_t hist[2][256];
     __shared__ uint32_t cand[kCandCap];
     __shared__ uint32_t cand_i[kCandCap];
-    __shared__ uint32_t bitmap[kBitmapWords], bitmap_eq[kBitmapWords];
     __shared__ int s_pick[2];
     __shared__ uint32_t s_theta_prev;
-    __shared__ int s_bad, s_ncand, s_base, s_last;
+    __shared__ int s_bad, s_ncand;
     __shared__ int w_gt[kTopkWaves], w_eq[kTopkWaves];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -162,30 +155,32 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
         return;
     }
 
-    if (tid == 0) { s_theta_prev = 0xffffffffu; s_bad = 0; s_ncand = 0; s_last = 0; }
+    if (tid == 0) { s_theta_prev = 0xffffffffu; s_bad = 0; s_ncand = 0; }
+    const bool in_lds = N <= lds_keys;
+    uint32_t *keys = in_lds ? dyn_keys : (gkeys + (int64_t)b * bv.max_vis_len);
+    for (int i = tid; i < N; i += kTopkThreads) keys[i] = order_key(srow[i]);
+    // ---- bound from the previous set: k distinct valid tokens (strictly ascending) or ignored ----
+    const bool have_prev = in_lds && prev_idx && pcnt == k;
+    uint32_t lo = 0xffffffffu;
+    int bad = 0;
+    if (have_prev) {
+        const int32_t *prev = prev_idx + (int64_t)b * kmax;
+        for (int r = tid; r < k; r += kTopkThreads) {
+            const int i = prev[r];
+            const int nx = (r + 1 < k) ? prev[r + 1] : 0x7fffffff;
+            if (i < 0 || i >= N || i >= nx) bad = 1;
+            else lo = min(lo, order_key(srow[i]));
+        }
+    }
     __syncthreads();
 
     uint32_t theta;
     int ties;
-    const bool filtered = nparts > 1 && N <= kBitmapWords * 32;
-    if (filtered) {
-        // the three independent gathers (sample, own slice, previous set) are issued together
-        const int ns = min(N, kTopkThreads);
-        const float sample_v = tid < ns ? srow[(int)(((int64_t)tid * N) / ns)] : 0.f;
-        const int own_i = part * kTopkThreads + tid;
-        const float own_v = own_i < N ? srow[own_i] : 0.f;
-        // ---- bound from the previous set: k distinct valid tokens (strictly ascending) or ignored ----
+    bool from_cand = false;
+    int nc = 0;
+    if (in_lds) {
         uint32_t theta0 = 0u;
-        if (prev_idx && pcnt == k) {
-            const int32_t *prev = prev_idx + (int64_t)b * kmax;
-            uint32_t lo = 0xffffffffu;
-            int bad = 0;
-            for (int r = tid; r < k; r += kTopkThreads) {
-                const int i = prev[r];
-                const int nx = (r + 1 < k) ? prev[r + 1] : 0x7fffffff;
-                if (i < 0 || i >= N || i >= nx) bad = 1;
-                else lo = min(lo, order_key(srow[i]));
-            }
+        if (have_prev) {
             if (bad) s_bad = 1;
 #pragma unroll
             for (int o = 32; o > 0; o >>= 1) lo = min(lo, (uint32_t)__shfl_xor((int)lo, o));
@@ -195,7 +190,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
         }
         // ---- bound from a sample of kTopkThreads evenly spaced scores -----------------------------
         {
-            if (tid < ns) cand[tid] = order_key(sample_v);
+            const int ns = min(N, kTopkThreads);
+            if (tid < ns) cand[tid] = keys[(int)(((int64_t)tid * N) / ns)];
             __syncthreads();
             // about 1.5 k of the N tokens should reach the bound: rank 1.5 k ns / N in the sample, plus slack
             const int r = (int)(((int64_t)3 * k * ns) / ((int64_t)2 * N)) + 24;
@@ -207,10 +203,11 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
             }
             __syncthreads();
         }
-        // ---- filter the own slice, append the survivors to the sequence's list --------------------
-        for (int ii = own_i; ii < N; ii += nparts * kTopkThreads) {
-            const uint32_t key = order_key(ii == own_i ? own_v : srow[ii]);
-            const bool c = key >= theta0;
+        // ---- candidates: every key of the sequence at or above the bound ---------------------------
+        for (int i0 = 0; i0 < N; i0 += kTopkThreads) {
+            const int ii = i0 + tid;
+            const uint32_t key = ii < N ? keys[ii] : 0u;
+            const bool c = ii < N && key >= theta0;
             const uint64_t mk = __ballot(c);
             int base = 0;
             if (lane == 0 && mk) base = atomicAdd(&s_ncand, __popcll(mk));
@@ -221,116 +218,42 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
             }
         }
         __syncthreads();
-        const int mine = s_ncand;
-        if (tid == 0)
-            s_base = mine > 0 ? (int)__hip_atomic_fetch_add(&ctr[b].ncand, (uint32_t)mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
-        __syncthreads();
-        // The list crosses compute units through agent-scope atomic stores (written through to
-        // memory); each thread waits for its stores to be acknowledged before the workgroup is
-        // counted in.
-        unsigned long long *list = cand_list + (int64_t)b * kCandCap;
-        for (int c = tid; c < min(mine, kCandCap); c += kTopkThreads) {
-            const int pos = s_base + c;
-            if (pos < kCandCap)
-                __hip_atomic_store(&list[pos], ((unsigned long long)cand[c] << 32) | cand_i[c], __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-        }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (tid == 0) {
-            const uint32_t old = __hip_atomic_fetch_add(&ctr[b].arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_last = old == (uint32_t)nparts - 1u;
-        }
-        __syncthreads();
-        if (!s_last) return;
-
-        // ---- the last workgroup of the sequence selects among the candidates ----------------------
-        const int nc = (int)__hip_atomic_load(&ctr[b].ncand, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __syncthreads();
-        if (tid == 0) {                                    // clean for the next call on this slot
-            __hip_atomic_store(&ctr[b].ncand, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&ctr[b].arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        if (nc >= k && nc <= kCandCap) {
-            for (int c = tid; c < nc; c += kTopkThreads) {
-                const unsigned long long e = __hip_atomic_load(&list[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                cand[c] = (uint32_t)(e >> 32);
-                cand_i[c] = (uint32_t)e;
-            }
-            for (int w = tid; w < kBitmapWords; w += kTopkThreads) { bitmap[w] = 0u; bitmap_eq[w] = 0u; }
-            __syncthreads();
-            theta = radix_select(cand, nc, k, hist, s_pick, &ties);
-            // mark the keys above the threshold, and separately those equal to it
-            for (int c = tid; c < nc; c += kTopkThreads) {
-                const uint32_t key = cand[c], i = cand_i[c];
-                if (key > theta) atomicOr(&bitmap[i >> 5], 1u << (i & 31));
-                else if (key == theta) atomicOr(&bitmap_eq[i >> 5], 1u << (i & 31));
-            }
-            __syncthreads();
-            // ordered emission: word w of the bitmaps belongs to thread w; ties go to the lowest indices
-            const int nwords = (N + 31) / 32;
-            int eq_before = 0, out_before = 0;
-            for (int w0 = 0; w0 < nwords; w0 += kTopkThreads) {
-                const int w = w0 + tid;
-                const uint32_t g = w < nwords ? bitmap[w] : 0u, e = w < nwords ? bitmap_eq[w] : 0u;
-                const int ne = __popc(e);
-                int ne_incl = ne;
-#pragma unroll
-                for (int o = 1; o < 64; o <<= 1) { const int t = __shfl_up(ne_incl, o); if (lane >= o) ne_incl += t; }
-                if (lane == 63) w_eq[wave] = ne_incl;
-                __syncthreads();
-                int eq_off = eq_before;
-                for (int x = 0; x < wave; ++x) eq_off += w_eq[x];
-                int eq_tot = 0;
-                for (int x = 0; x < kTopkWaves; ++x) eq_tot += w_eq[x];
-                const int eq_excl = eq_off + ne_incl - ne;
-                // ties of this word that are still wanted: its first (ties - eq_excl) set bits
-                uint32_t take_eq = 0u;
-                int want = min(max(ties - eq_excl, 0), ne);
-                uint32_t rest = e;
-                while (want > 0) { const uint32_t low = rest & (0u - rest); take_eq |= low; rest ^= low; --want; }
-                const uint32_t sel = g | take_eq;
-                const int nsel = __popc(sel);
-                int ns_incl = nsel;
-#pragma unroll
-                for (int o = 1; o < 64; o <<= 1) { const int t = __shfl_up(ns_incl, o); if (lane >= o) ns_incl += t; }
-                if (lane == 63) w_gt[wave] = ns_incl;
-                __syncthreads();
-                int pos = out_before;
-                for (int x = 0; x < wave; ++x) pos += w_gt[x];
-                int out_tot = 0;
-                for (int x = 0; x < kTopkWaves; ++x) out_tot += w_gt[x];
-                pos += ns_incl - nsel;
-                uint32_t bits = sel;
-                while (bits) { const int bit = __ffs((int)bits) - 1; out[pos++] = w * 32 + bit; bits &= bits - 1u; }
-                eq_before += eq_tot;
-                out_before += out_tot;
-                __syncthreads();
-            }
-            if (tid == 0) sel_cnt[b] = k;
-            return;
-        }
-    } else if (nparts > 1) {
-        // image span too long for the bitmaps: only the last workgroup works
-        if (tid == 0) {
-            const uint32_t old = __hip_atomic_fetch_add(&ctr[b].arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_last = old == (uint32_t)nparts - 1u;
-        }
-        __syncthreads();
-        if (!s_last) return;
-        if (tid == 0) __hip_atomic_store(&ctr[b].arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        nc = s_ncand;
+        from_cand = nc >= k && nc <= kCandCap;
     }
+    if (from_cand) theta = radix_select(cand, nc, k, hist, s_pick, &ties);
+    else theta = radix_select(keys, N, k, hist, s_pick, &ties);
 
-    // ---- select over all N keys ---------------------------------------------------------------------
-    uint32_t *keys = (N <= lds_keys) ? dyn_keys : (gkeys + (int64_t)b * bv.max_vis_len);
-    for (int i = tid; i < N; i += kTopkThreads) keys[i] = order_key(srow[i]);
-    __syncthreads();
-    theta = radix_select(keys, N, k, hist, s_pick, &ties);
-
-    // ordered compaction: each wave owns a contiguous index segment
-    const int seg = ((N + kTopkWaves - 1) / kTopkWaves + 63) / 64 * 64;
-    const int s0 = wave * seg, s1 = min(N, s0 + seg);
+    // ---- this workgroup's segment of the token range, and how much of the result precedes it ------
+    const int seg = ((N + nparts - 1) / nparts + 63) / 64 * 64;
+    const int p0 = min(N, part * seg), p1 = min(N, p0 + seg);
     int ngt = 0, neq = 0;
+    if (from_cand) {
+        for (int c = tid; c < nc; c += kTopkThreads) {
+            const bool before = (int)cand_i[c] < p0;
+            ngt += before && cand[c] > theta;
+            neq += before && cand[c] == theta;
+        }
+    } else {
+        for (int i = tid; i < p0; i += kTopkThreads) {
+            const uint32_t key = keys[i];
+            ngt += key > theta;
+            neq += key == theta;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { ngt += __shfl_xor(ngt, o); neq += __shfl_xor(neq, o); }
+    if (lane == 0) { w_gt[wave] = ngt; w_eq[wave] = neq; }
+    __syncthreads();
+    int gt_before = 0, eq_before = 0;
+    for (int w = 0; w < kTopkWaves; ++w) { gt_before += w_gt[w]; eq_before += w_eq[w]; }
+    __syncthreads();
+
+    // ---- ordered compaction of the segment: each wave owns a contiguous piece of it ---------------
+    const int wseg = ((p1 - p0 + kTopkWaves - 1) / kTopkWaves + 63) / 64 * 64;
+    const int s0 = min(p1, p0 + wave * wseg), s1 = min(p1, s0 + wseg);
+    ngt = 0;
+    neq = 0;
     for (int i = s0 + lane; i < s1; i += 64) {
         const uint32_t key = keys[i];
         ngt += key > theta;
@@ -340,7 +263,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
     for (int o = 32; o > 0; o >>= 1) { ngt += __shfl_xor(ngt, o); neq += __shfl_xor(neq, o); }
     if (lane == 0) { w_gt[wave] = ngt; w_eq[wave] = neq; }
     __syncthreads();
-    int eq_seen = 0, out_pos = 0;
+    // ties go to the lowest indices: the first `ties` keys equal to the threshold are taken
+    int eq_seen = eq_before, out_pos = gt_before + min(ties, eq_before);
     for (int w = 0; w < wave; ++w) {
         out_pos += w_gt[w] + min(max(ties - eq_seen, 0), w_eq[w]);
         eq_seen += w_eq[w];
@@ -358,19 +282,187 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
         eq_seen += __popcll(eq_mask);
         out_pos += __popcll(tk_mask);
     }
+    if (part == 0 && tid == 0) sel_cnt[b] = k;
+}
+
+// Image spans of up to kTopkRegKeys tokens: one workgroup per sequence, thread t keeps the keys of
+// tokens 16t .. 16t+15 in registers.  The candidate list (keys at or above the bound theta0, see
+// above) and the result are both written in index order through block-wide prefix sums, so no
+// atomics or index arrays are needed, and the scores are read exactly once.
+constexpr int kTopkPer = 16;
+constexpr int kTopkRegKeys = kTopkThreads * kTopkPer;
+
+// exclusive prefix sums of (a, c) over the 1024 threads; totals through *ta, *tc.  All threads call.
+// w_ac: 2 x 16 wave totals, 16-byte aligned.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void block_scan2(int a, int c, int *w_ac, int &a_excl, int &c_excl, int *ta, int *tc)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int ai = wave_scan_incl(a), ci = wave_scan_incl(c);
+    if (lane == 63) { w_ac[wave] = ai; w_ac[kTopkWaves + wave] = ci; }
+    __syncthreads();
+    int ab = 0, cb = 0, at = 0, ct = 0;
+#pragma unroll
+    for (int v = 0; v < kTopkWaves / 4; ++v) {
+        const i32x4 x = reinterpret_cast<const i32x4 *>(w_ac)[v], y = reinterpret_cast<const i32x4 *>(w_ac)[kTopkWaves / 4 + v];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (4 * v + e < wave) { ab += x[e]; cb += y[e]; }
+            at += x[e];
+            ct += y[e];
+        }
+    }
+    a_excl = ab + ai - a;
+    c_excl = cb + ci - c;
+    *ta = at;
+    *tc = ct;
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(
+    const float *__restrict__ scores, BatchDev bv, double tau, const int32_t *prev_idx,
+    const int32_t *prev_cnt, int32_t *sel_idx, int32_t *sel_cnt, int64_t kmax)
+{
+    extern __shared__ uint32_t dyn_keys[];          // all keys, only when the candidate list fails
+    __shared__ uint32_t hist[2][256];
+    __shared__ uint32_t cand[kCandCap];
+    __shared__ int s_pick[2];
+    __shared__ uint32_t s_theta_prev;
+    __shared__ int s_bad;
+    __shared__ __align__(16) int w_ac[2 * kTopkWaves];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int b = blockIdx.x;
+    const SeqGeom geo = seq_geom(bv, b);
+    const int N = geo.N;
+    const int k = (int)min((int64_t)keep_count_dev(N, tau), kmax);
+    const int pcnt = prev_cnt ? prev_cnt[b] : -1;
+    int32_t *out = sel_idx + (int64_t)b * kmax;
+    const float *srow = scores + (int64_t)b * bv.max_vis_len;
+
+    if (k <= 0 || k >= N) {
+        if (k >= N && k > 0)
+            for (int i = tid; i < N; i += kTopkThreads) out[i] = i;
+        if (tid == 0) sel_cnt[b] = k <= 0 ? 0 : N;
+        return;
+    }
+    if (tid == 0) { s_theta_prev = 0xffffffffu; s_bad = 0; }
+
+    // ---- the thread's 16 keys; tokens past N get key 0 and are never counted ----------------------
+    const int base = tid * kTopkPer;
+    const int nvalid = min(max(N - base, 0), kTopkPer);
+    uint32_t key[kTopkPer];
+    if (nvalid == kTopkPer && (reinterpret_cast<uintptr_t>(srow + base) & 15u) == 0) {
+#pragma unroll
+        for (int v = 0; v < kTopkPer / 4; ++v) {
+            const f32x4 x = *reinterpret_cast<const f32x4 *>(srow + base + 4 * v);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) key[4 * v + e] = order_key(x[e]);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < kTopkPer; ++j) key[j] = j < nvalid ? order_key(srow[base + j]) : 0u;
+    }
+    // ---- bound from the previous set: k distinct valid tokens (strictly ascending) or ignored ----
+    const bool have_prev = prev_idx && pcnt == k;
+    uint32_t lo = 0xffffffffu;
+    int bad = 0;
+    if (have_prev) {
+        const int32_t *prev = prev_idx + (int64_t)b * kmax;
+        for (int r = tid; r < k; r += kTopkThreads) {
+            const int i = prev[r];
+            const int nx = (r + 1 < k) ? prev[r + 1] : 0x7fffffff;
+            if (i < 0 || i >= N || i >= nx) bad = 1;
+            else lo = min(lo, order_key(srow[i]));
+        }
+    }
+    // ---- bound from a sample: the first key of every thread (every 16th token) ---------------------
+    const int ns = (N + kTopkPer - 1) / kTopkPer;
+    if (tid < ns) cand[tid] = key[0];
+    __syncthreads();
+    uint32_t theta0 = 0u;
+    if (have_prev) {
+        if (bad) s_bad = 1;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) lo = min(lo, (uint32_t)__shfl_xor((int)lo, o));
+        if (lane == 0) atomicMin(&s_theta_prev, lo);
+        __syncthreads();
+        if (!s_bad) theta0 = s_theta_prev;
+    }
+    {
+        // about 1.5 k of the N tokens should reach the bound: rank 1.5 k ns / N in the sample, plus slack
+        const int r = (int)(((int64_t)3 * k * ns) / ((int64_t)2 * N)) + 24;
+        if (r < ns) {
+            int unused;
+            // the upper 16 bits are enough for a bound (fp32: sign, exponent, 7 mantissa bits)
+            const uint32_t ths = radix_select(cand, ns, r, hist, s_pick, &unused, 16);
+            theta0 = max(theta0, ths);
+        }
+        __syncthreads();
+    }
+    // ---- candidates, compacted in index order --------------------------------------------------------
+    int mine = 0;
+#pragma unroll
+    for (int j = 0; j < kTopkPer; ++j) mine += (j < nvalid && key[j] >= theta0) ? 1 : 0;
+    int pos, unused_excl, nc, unused_tot;
+    block_scan2(mine, 0, w_ac, pos, unused_excl, &nc, &unused_tot);
+    const bool from_cand = nc >= k && nc <= kCandCap;
+    uint32_t theta;
+    int ties;
+    if (from_cand) {
+#pragma unroll
+        for (int j = 0; j < kTopkPer; ++j)
+            if (j < nvalid && key[j] >= theta0) cand[pos++] = key[j];
+        __syncthreads();
+        theta = radix_select(cand, nc, k, hist, s_pick, &ties);
+    } else {
+#pragma unroll
+        for (int j = 0; j < kTopkPer; ++j)
+            if (j < nvalid) dyn_keys[base + j] = key[j];
+        __syncthreads();
+        theta = radix_select(dyn_keys, N, k, hist, s_pick, &ties);
+    }
+    // ---- the result in ascending index order; ties go to the lowest indices ------------------------
+    // bit j of the masks: key j of this thread lies above / on the threshold
+    uint32_t m_gt = 0u, m_eq = 0u;
+#pragma unroll
+    for (int j = 0; j < kTopkPer; ++j) {
+        m_gt |= (j < nvalid && key[j] > theta) ? (1u << j) : 0u;
+        m_eq |= (j < nvalid && key[j] == theta) ? (1u << j) : 0u;
+    }
+    int gt_excl, eq_excl, gt_tot, eq_tot;
+    block_scan2(__popc(m_gt), __popc(m_eq), w_ac, gt_excl, eq_excl, &gt_tot, &eq_tot);
+    // of this thread's keys on the threshold, the first (ties - eq_excl) are still wanted
+    uint32_t take = m_gt;
+    {
+        int want = min(max(ties - eq_excl, 0), __popc(m_eq));
+        uint32_t rest = m_eq;
+        while (want > 0) { const uint32_t low = rest & (0u - rest); take |= low; rest ^= low; --want; }
+    }
+    int opos = gt_excl + min(ties, eq_excl);
+    while (take) {
+        out[opos++] = base + __ffs((int)take) - 1;
+        take &= take - 1u;
+    }
     if (tid == 0) sel_cnt[b] = k;
 }
 
-// parts per sequence: one 1024-token slice each, at most 64
-static int topk_parts(int max_vis_len) { return max(1, min(64, (max_vis_len + kTopkThreads - 1) / kTopkThreads)); }
+// Workgroups per sequence: one per 1024 image tokens, as long as the grid still fits the chip in
+// one round (each workgroup occupies a compute unit with its keys in LDS).
+static int topk_parts(int batch, int max_vis_len)
+{
+    if (max_vis_len > kLdsKeyCap) return 1;
+    const int by_size = (max_vis_len + kTopkThreads - 1) / kTopkThreads;
+    const int by_chip = 256 / max(1, batch);
+    return max(1, min(by_size, by_chip));
+}
 
+// Workspace: the keys of image spans that do not fit LDS, uint32 [batch][max_vis_len].
 size_t topk_workspace_bytes(int batch, int max_vis_len)
 {
     size_t bytes = 0;
     if (max_vis_len > kLdsKeyCap) bytes += (size_t)batch * (size_t)max_vis_len * sizeof(uint32_t);
-    bytes = (bytes + 255) / 256 * 256;
-    bytes += (size_t)batch * kCandCap * sizeof(unsigned long long);
-    return bytes;
+    return (bytes + 255) / 256 * 256;
 }
 
 hipError_t launch_topk(const float *scores, const BatchDev &bv, int batch, double tau,
@@ -382,25 +474,32 @@ hipError_t launch_topk(const float *scores, const BatchDev &bv, int batch, doubl
     static bool attr_set = false;
     if (!attr_set) {
         // gfx950 has 160 KB of LDS per workgroup; the keys of up to 24576 tokens take 96 KB next to
-        // the static candidate and bitmap arrays.  If the runtime refuses the opt-in, a launch
-        // that needs it reports the error itself.
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(topk_kernel),
+        // the static candidate arrays.  If the runtime refuses the opt-in, a launch that needs it
+        // reports the error itself.
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(topk_general_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kLdsKeyCap * (int)sizeof(uint32_t)) != hipSuccess)
             (void)hipGetLastError();
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(topk_reg_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kTopkRegKeys * (int)sizeof(uint32_t)) != hipSuccess)
+            (void)hipGetLastError();
         attr_set = true;
     }
-    unsigned char *p = reinterpret_cast<unsigned char *>(ws);
-    uint32_t *gkeys = reinterpret_cast<uint32_t *>(p);
-    size_t off = 0;
-    if (bv.max_vis_len > kLdsKeyCap) off += (size_t)batch * (size_t)bv.max_vis_len * sizeof(uint32_t);
-    off = (off + 255) / 256 * 256;
-    unsigned long long *cand_list = reinterpret_cast<unsigned long long *>(p + off);
-    const int parts = batch <= kTopkMaxBatch ? topk_parts(bv.max_vis_len) : 1;
-    static std::atomic<unsigned> call_no{0};
-    const int sync_slot = (int)(call_no.fetch_add(1u) % (unsigned)kTopkSlots);
-    FASTOCR_LAUNCH(K_TOPK, topk_kernel, dim3(parts, batch), dim3(kTopkThreads), dyn, stream, scores, bv, tau, prev_idx,
-                   prev_cnt, sel_idx, sel_cnt, kmax, gkeys, lds_keys, sync_slot, cand_list);
+    if (bv.max_vis_len <= kTopkRegKeys) {
+        // the dynamic LDS (all keys) is only touched when the candidate list fails
+        FASTOCR_LAUNCH(K_TOPK, topk_reg_kernel, dim3(batch), dim3(kTopkThreads), (size_t)bv.max_vis_len * sizeof(uint32_t),
+                       stream, scores, bv, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax);
+        return hipGetLastError();
+    }
+    uint32_t *gkeys = reinterpret_cast<uint32_t *>(ws);
+    // Several workgroups per sequence write their segments while others may still be reading the
+    // previous set: not when that set lives in the buffer being written.
+    const size_t span = (size_t)batch * (size_t)kmax;
+    const bool aliased = prev_idx && prev_idx < sel_idx + span && sel_idx < prev_idx + span;
+    const int parts = aliased ? 1 : topk_parts(batch, bv.max_vis_len);
+    FASTOCR_LAUNCH(K_TOPK, topk_general_kernel, dim3(parts, batch), dim3(kTopkThreads), dyn, stream, scores, bv, tau, prev_idx,
+                   prev_cnt, sel_idx, sel_cnt, kmax, gkeys, lds_keys);
     return hipGetLastError();
 }
 
