@@ -44,6 +44,10 @@ def parse_args():
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch the plain copy / read probe kernels of known size (1 GiB) three times "
                          "each, so that a profiler's byte counters can be scaled against them")
+    ap.add_argument("--step", choices=["three_step", "focal_layer"], default="three_step",
+                    help="what one timed step is: the metric's three-step path (default), or a focal layer as "
+                         "the controller runs it (dense output + scores from one pass over K and V, then top-k); "
+                         "the roofline object then describes the fused kernel")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
                     help="launch-shape override passed to fastocr_set_tuning (measurement sweeps)")
     return ap.parse_args()
@@ -170,19 +174,31 @@ def main():
             state["have_prev"] = True
         fo.sparse_decode_attn(cache, batches[i], qs[i], scale, idx, cnt, out, ws)
 
+    def focal_layer_step(i):
+        fo.focal_attn_score(caches[i], batches[i], qs[i], scale, out_dense, scores, ws)
+        if state["have_prev"]:
+            fo.topk_fixation(scores, batches[i], tau, idx, cnt, ws, prev_idx=idx, prev_cnt=cnt)
+        else:
+            fo.topk_fixation(scores, batches[i], tau, idx, cnt, ws)
+            state["have_prev"] = True
+
+    focal_mode = args.step == "focal_layer"
+    step_fn = focal_layer_step if focal_mode else three_step
+    timed_kernel = fb.KERNEL_FOCAL_FUSED if focal_mode else fb.KERNEL_SCORE_LOGITS
+
     # ---- timed region ------------------------------------------------------------------------
     for i in range(n_warm):
-        three_step(i)
+        step_fn(i)
     torch.cuda.synchronize()
-    fb.kernel_timer_enable(fb.KERNEL_SCORE_LOGITS, n_steps)
+    fb.kernel_timer_enable(timed_kernel, n_steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(n_warm, total):
-        three_step(i)
+        step_fn(i)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    logits_ms = fb.kernel_timer_read(fb.KERNEL_SCORE_LOGITS)
-    fb.kernel_timer_enable(fb.KERNEL_SCORE_LOGITS, 0)
+    logits_ms = fb.kernel_timer_read(timed_kernel)
+    fb.kernel_timer_enable(timed_kernel, 0)
 
     if args.calibrate:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -203,24 +219,28 @@ def main():
     R = Hkv * d * e
     mean_S = float(seq_lens[n_warm:].float().mean().item())
     score_bytes = B * (mean_S * R + Hq * d * e)                 # K rows of every cached token + the queries
+    if focal_mode:
+        score_bytes = B * (mean_S * 2 * R + 2 * Hq * d * e)     # K and V rows, queries in, outputs out
     k_ms = float(np.mean(logits_ms)) if logits_ms else float("nan")
     achieved = score_bytes / (k_ms * 1e-3) / 1e9
     traffic = None
-    prof = os.path.join(ROOT, "profiles", "three_step_config4_tau0.05.md")
+    prof = os.path.join(ROOT, "profiles", "focal_layer_config4_tau0.05.md" if focal_mode else "three_step_config4_tau0.05.md")
     if wl.config_id == 4 and abs(tau - 0.05) < 1e-12 and not args.batch and os.path.exists(prof):
         # HBM bytes per launch of this kernel from the committed rocprofv3 --pmc summary of this command
         for line in open(prof):
             if line.startswith("machine-readable:"):
                 traffic = json.loads(line.split(":", 1)[1])["traffic_bytes_per_launch"]
-    roofline = {"bound": "hbm", "kernel": "score_resident_kernel (focal scoring: K stream, logits kept in registers)",
+    roofline = {"bound": "hbm", "kernel": "focal_fused_kernel (focal layer: K and V stream, dense output and scores)" if focal_mode
+                else "score_resident_kernel (focal scoring: K stream, logits kept in registers)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "algorithmic_bytes": int(score_bytes), "avg_launch_us": round(k_ms * 1e3, 2),
                 "launches": len(logits_ms)}
 
     result = {
-        "metric": "decode attn layer-steps/s (focal score + top-k + sparse attention) at N=%d, tau=%g"
-                  % (max_vis, tau),
+        "metric": ("decode attn layer-steps/s (focal layer: dense attention + focal score in one pass, + top-k) at N=%d, tau=%g"
+                   if focal_mode else
+                   "decode attn layer-steps/s (focal score + top-k + sparse attention) at N=%d, tau=%g") % (max_vis, tau),
         "value": round(value, 2), "unit": "layer-steps/s", "n_gpus": 1, "steps": n_steps, "warmup": n_warm,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
@@ -233,7 +253,7 @@ def main():
     }
 
     # ---- extras: comparator and per-kernel breakdown (outside the timed region) ---------------
-    if not args.no_extras:
+    if not args.no_extras and not focal_mode:
         names = {fb.KERNEL_SCORE_LOGITS: "score_logits", fb.KERNEL_SCORE_FINALIZE: "score_finalize",
                  fb.KERNEL_TOPK: "topk", fb.KERNEL_SPARSE_ATTN: "sparse_attn", fb.KERNEL_DENSE_ATTN: "dense_attn",
                  fb.KERNEL_ATTN_COMBINE: "attn_combine", fb.KERNEL_FOCAL_FUSED: "focal_fused"}
@@ -295,7 +315,7 @@ def main():
         }
 
     # ---- the oracle timed on this machine's host cores (a baseline, not a target) -----------------
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not focal_mode:
         import oracle
         threads = oracle.max_threads()
         n_seq, cpu_s, n_steps_cpu = 0, 0.0, 0

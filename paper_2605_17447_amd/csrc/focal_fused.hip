@@ -189,19 +189,28 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
     // outstanding" means the tile wanted here has landed.  Reads and waits are written in assembly:
     // the compiler neither orders LDS reads after loads that land in LDS by themselves without
     // draining ALL of them, nor may it move the products above the wait.
-    auto read_k = [&](u32x4(&kb)[8]) {
+    // rows li (first call) and 16 + li (second call) of the K tile, in two halves so that only
+    // four operand registers are live at a time
+    auto read_k_lo = [&](u32x4(&kb)[4]) {
         asm volatile(
             "s_waitcnt vmcnt(8)\n\t"
-            "ds_read_b128 %0, %8\n\t"
-            "ds_read_b128 %1, %9\n\t"
-            "ds_read_b128 %2, %10\n\t"
-            "ds_read_b128 %3, %11\n\t"
-            "ds_read_b128 %4, %8 offset:4096\n\t"
-            "ds_read_b128 %5, %9 offset:4096\n\t"
-            "ds_read_b128 %6, %10 offset:4096\n\t"
-            "ds_read_b128 %7, %11 offset:4096\n\t"
+            "ds_read_b128 %0, %4\n\t"
+            "ds_read_b128 %1, %5\n\t"
+            "ds_read_b128 %2, %6\n\t"
+            "ds_read_b128 %3, %7\n\t"
             "s_waitcnt lgkmcnt(0)"
-            : "=&v"(kb[0]), "=&v"(kb[1]), "=&v"(kb[2]), "=&v"(kb[3]), "=&v"(kb[4]), "=&v"(kb[5]), "=&v"(kb[6]), "=&v"(kb[7])
+            : "=&v"(kb[0]), "=&v"(kb[1]), "=&v"(kb[2]), "=&v"(kb[3])
+            : "v"(rd_addr[0]), "v"(rd_addr[1]), "v"(rd_addr[2]), "v"(rd_addr[3])
+            : "memory");
+    };
+    auto read_k_hi = [&](u32x4(&kb)[4]) {
+        asm volatile(
+            "ds_read_b128 %0, %4 offset:4096\n\t"
+            "ds_read_b128 %1, %5 offset:4096\n\t"
+            "ds_read_b128 %2, %6 offset:4096\n\t"
+            "ds_read_b128 %3, %7 offset:4096\n\t"
+            "s_waitcnt lgkmcnt(0)"
+            : "=&v"(kb[0]), "=&v"(kb[1]), "=&v"(kb[2]), "=&v"(kb[3])
             : "v"(rd_addr[0]), "v"(rd_addr[1]), "v"(rd_addr[2]), "v"(rd_addr[3])
             : "memory");
     };
@@ -226,17 +235,18 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
     // One tile: logits, online softmax, P*V.  nlive = tokens of the tile that exist (may exceed 32).
     // Returns this lane's 4 logits (log2 domain; -inf for tokens past the end).
     auto tile_step = [&](int nlive, auto &&next_k, auto &&next_v) -> f32x4 {
-        u32x4 kb[8];
-        read_k(kb);
-        next_k();
+        u32x4 kb[4];
         f32x4 c0 = f32x4{0.f, 0.f, 0.f, 0.f}, c1 = c0;
+        read_k_lo(kb);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
             c0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[kk]),
                                                          __builtin_bit_cast(bf16x8, qq[kk]), c0, 0, 0, 0);
+        read_k_hi(kb);
+        next_k();
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
-            c1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[4 + kk]),
+            c1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[kk]),
                                                          __builtin_bit_cast(bf16x8, qq[kk]), c1, 0, 0, 0);
         f32x4 s;
 #pragma unroll
@@ -298,6 +308,13 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the trailing refills must not land later
 
+    // Lane coordinates are derived afresh for the rest of the kernel: carried across the tile loop
+    // they would occupy registers it has no room for.
+    int tx_p = threadIdx.x;
+    asm volatile("" : "+v"(tx_p));
+    const int lane_p = tx_p & 63, li_p = lane_p & 15, lg_p = lane_p >> 4, hcol_p = li_p & 7;
+    const int tt0_p = 16 * (li_p >> 3) + 4 * lg_p;
+
     // ---- attention partial of this wave: O^T columns n and n + 8 are the same head's halves -----
     z += dpp_move<kDppRor8>(z);
     z += __shfl_xor(z, 16);
@@ -306,20 +323,20 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
     for (int t = 0; t < 8; ++t)
 #pragma unroll
         for (int r = 0; r < 4; ++r) acc[t][r] += dpp_move<kDppRor8>(acc[t][r]);
-    if (li < 8 && li < G) {
-        // lane (head li, group lg) holds dims 32lg + 8r + t in acc[t][r]
-        const int64_t row = ((int64_t)b * Hq + (int64_t)kvh * G + li) * nslots + slot;
-        float *po = att_o + row * 128 + 32 * lg;
+    if (li_p < 8 && li_p < G) {
+        // lane_p (head li_p, group lg_p) holds dims 32lg + 8r + t in acc[t][r]
+        const int64_t row = ((int64_t)b * Hq + (int64_t)kvh * G + li_p) * nslots + slot;
+        float *po = att_o + row * 128 + 32 * lg_p;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             *reinterpret_cast<f32x4 *>(po + 8 * r) = f32x4{acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
             *reinterpret_cast<f32x4 *>(po + 8 * r + 4) = f32x4{acc[4][r], acc[5][r], acc[6][r], acc[7][r]};
         }
-        if (lg == 0) {
+        if (lg_p == 0) {
             att_ml[2 * row] = m;
             att_ml[2 * row + 1] = z;
-            sm_m[wave][li] = m;
-            sm_z[wave][li] = z;
+            sm_m[wave][li_p] = m;
+            sm_z[wave][li_p] = z;
         }
     }
     __syncthreads();
@@ -364,18 +381,18 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
         leave();
         return;
     }
-    // every head's log-sum-exp from the ranges' statistics: wave w merges ranges w, w+8, ..; lane = head
+    // every head's log-sum-exp from the ranges' statistics: wave w merges ranges w, w+8, ..; lane_p = head
     {
         float M = kMinusHuge, Z = 0.f;
-        if (lane < Hq) {
-            const unsigned long long *pp = reinterpret_cast<const unsigned long long *>(part_ml) + (int64_t)b * nranges * Hq + lane;
+        if (lane_p < Hq) {
+            const unsigned long long *pp = reinterpret_cast<const unsigned long long *>(part_ml) + (int64_t)b * nranges * Hq + lane_p;
             for (int rr = wave; rr < nranges; rr += kResWaves) {
                 const unsigned long long mz = __hip_atomic_load(pp + (int64_t)rr * Hq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 softmax_merge(M, Z, __uint_as_float((uint32_t)mz), __uint_as_float((uint32_t)(mz >> 32)));
             }
         }
-        sm_pm[wave][lane] = M;
-        sm_pz[wave][lane] = Z;
+        sm_pm[wave][lane_p] = M;
+        sm_pz[wave][lane_p] = Z;
     }
     __syncthreads();
     if ((int)threadIdx.x < Hq) {
@@ -390,10 +407,10 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
     __syncthreads();
 
     // ---- probabilities of the parked logits, summed over the heads of each token ---------------
-    const float lh = hcol < G ? sm_lse[kvh * G + hcol] : INFINITY;
+    const float lh = hcol_p < G ? sm_lse[kvh * G + hcol_p] : INFINITY;
     float *red = reinterpret_cast<float *>(&smem[0][0][0]);          // [Hkv][R], at most 32 KB
     for (int J = 0; J < nimg; ++J) {
-        // this lane's 4 tokens of tile J, one head each on 8 neighbouring lanes
+        // this lane_p's 4 tokens of tile J, one head each on 8 neighbouring lanes
         f32x4 v = f32x4{park0[J], park1[J], park2[J], park3[J]};
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -403,7 +420,7 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
             x += dpp_move<kDppHalfMirror>(x);
             v[r] = x;
         }
-        if ((li & 7) == 0) *reinterpret_cast<f32x4 *>(&red[kvh * R + img_first(J) - r0 + tt0]) = v;
+        if ((li_p & 7) == 0) *reinterpret_cast<f32x4 *>(&red[kvh * R + img_first(J) - r0 + tt0_p]) = v;
     }
     __syncthreads();
     float local = 0.f;
@@ -417,7 +434,7 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
     }
     if (mass_part) {
         local = wave_sum(local);
-        if (lane == 0) sm_red[wave] = local;
+        if (lane_p == 0) sm_red[wave] = local;
         __syncthreads();
         if (threadIdx.x == 0) {
             float t = 0.f;
