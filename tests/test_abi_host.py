@@ -91,6 +91,32 @@ def _dense(lib, kv, bv, Hq=28, q=FAKE, out=FAKE, ws=FAKE, ws_bytes=1 << 40, scal
                                          ws_bytes, None)
 
 
+def _focal_layer(lib, kv, bv, Hq=28, q=FAKE, out=FAKE, scores=FAKE, ws=FAKE, ws_bytes=1 << 40, scale=0.088):
+    return lib.fastocr_focal_attn_score(ctypes.byref(kv) if kv else None, ctypes.byref(bv) if bv else None, q, Hq,
+                                        scale, out, scores, None, None, ws, ws_bytes, None)
+
+
+def test_focal_layer_call_validation_and_workspace(lib):
+    kv, bv = _kv(), _bv()
+    assert _focal_layer(lib, None, bv) == fb.EINVAL
+    assert _focal_layer(lib, kv, bv, out=None) == fb.EINVAL
+    assert _focal_layer(lib, kv, bv, scores=None) == fb.EINVAL
+    assert _focal_layer(lib, kv, bv, q=FAKE + 2) == fb.EINVAL
+    assert _focal_layer(lib, kv, bv, Hq=30) == fb.EINVAL
+    assert _focal_layer(lib, kv, bv, scale=float("inf")) == fb.EINVAL
+    assert _focal_layer(lib, _kv(dtype=7), bv) == fb.EUNSUPPORTED
+    assert _focal_layer(lib, kv, bv, ws=None) == fb.EWORKSPACE
+    assert _focal_layer(lib, kv, bv, ws_bytes=1024) == fb.EWORKSPACE
+    assert _focal_layer(lib, kv, _bv(B=0)) == fb.OK
+    # the call may fall back to the two separate calls in the same buffer: it covers both of theirs
+    w = lambda op: lib.fastocr_workspace_bytes(op, ctypes.byref(kv), ctypes.byref(bv), 28, 0)
+    assert w(fb.OP_FOCAL_ATTN_SCORE) >= max(w(fb.OP_FOCAL_SCORE), w(fb.OP_DENSE_DECODE_ATTN))
+    assert w(fb.OP_FOCAL_ATTN_SCORE) % 256 == 0
+    for key in (b"focal_fused", b"score_resident"):
+        assert lib.fastocr_set_tuning(key, 3) == fb.EINVAL and lib.fastocr_set_tuning(key, -1) == fb.EINVAL
+        assert lib.fastocr_set_tuning(key, 2) == fb.OK and lib.fastocr_set_tuning(key, 1) == fb.OK
+
+
 def test_argument_validation_happens_before_any_gpu_work(lib):
     kv, bv = _kv(), _bv()
     assert _score(lib, None, bv) == fb.EINVAL
