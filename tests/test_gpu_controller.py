@@ -10,6 +10,7 @@ import fastocr_synth as fs
 import oracle
 from oracle.controller import plan_step
 import paper_2605_17447_amd as fo
+from paper_2605_17447_amd import binding as fb
 
 pytestmark = pytest.mark.gpu
 
@@ -124,11 +125,23 @@ def test_focal_layers_are_chosen_from_the_warm_up_ratios():
     assert [tuple(a) for a in plan_step(t, L, want, warmup, False).actions] == trace
 
 
-def test_a_captured_decode_step_replays_like_the_eager_one():
-    """The four calls allocate nothing and never synchronise, so a whole decode step of the
+@pytest.mark.parametrize("form", [1, 2])
+def test_a_captured_decode_step_replays_like_the_eager_one(form):
+    """The calls allocate nothing and never synchronise, so a whole decode step of the
     controller can be captured in a HIP graph (launch-bound small shapes).  Every replay, with
     fresh queries and a longer sequence, must match the eager controller bit for bit; eager work
-    and synchronisations sit between the replays."""
+    and synchronisations sit between the replays.  form 2 forces the register-resident kernels
+    (a captured launch keeps its barrier slot, which every replay must find clean again)."""
+    fb.set_tuning("score_resident", form)
+    fb.set_tuning("focal_fused", form)
+    try:
+        _captured_step_replays()
+    finally:
+        fb.set_tuning("score_resident", 1)
+        fb.set_tuning("focal_fused", 1)
+
+
+def _captured_step_replays():
     L, focal, tau, steps = 5, (1, 3), 0.1, 10
     wl = fs.config(3, batch=2, n_layers=L, focal_layers=focal, steps=steps, warmup=0, n_visual=(1024, 1024),
                    grid_w=(32, 32), text_prefix=(30, 30))
