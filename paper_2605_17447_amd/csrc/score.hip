@@ -278,15 +278,22 @@ __global__ __launch_bounds__(kFinThreads) void score_finalize_kernel(
     __shared__ float red[kFinThreads / 64];
     const int b = blockIdx.y;
     const SeqGeom geo = seq_geom(bv, b);
-    for (int h = threadIdx.x; h < Hq; h += kFinThreads) {
-        const float *ml = part_ml + ((int64_t)b * Hq + h) * nsplit * 2;
-        float M = kMinusHuge;
-        for (int s = 0; s < nsplit; ++s) M = fmaxf(M, ml[2 * s]);
-        float Z = 0.f;
-        for (int s = 0; s < nsplit; ++s) Z += fast_exp2(ml[2 * s] - M) * ml[2 * s + 1];
-        const float l2 = Z > 0.f ? M + log2f(Z) : -INFINITY;
-        lse2[h] = l2;
-        if (lse && blockIdx.x == 0) lse[(int64_t)b * Hq + h] = l2 * kLn2;
+    // every head's log-sum-exp from its nsplit range statistics: 8 lanes share a head and walk every
+    // 8th range (a serial walk is bound by load latency once there are dozens of ranges)
+    for (int h0 = 0; h0 < Hq; h0 += kFinThreads / 8) {
+        const int h = h0 + (threadIdx.x >> 3), part = threadIdx.x & 7;
+        float M = kMinusHuge, Z = 0.f;
+        if (h < Hq) {
+            const float *ml = part_ml + ((int64_t)b * Hq + h) * nsplit * 2;
+            for (int s = part; s < nsplit; s += 8) softmax_merge(M, Z, ml[2 * s], ml[2 * s + 1]);
+        }
+#pragma unroll
+        for (int o = 1; o < 8; o <<= 1) softmax_merge(M, Z, __shfl_xor(M, o), __shfl_xor(Z, o));
+        if (h < Hq && part == 0) {
+            const float l2 = Z > 0.f ? M + log2f(Z) : -INFINITY;
+            lse2[h] = l2;
+            if (lse && blockIdx.x == 0) lse[(int64_t)b * Hq + h] = l2 * kLn2;
+        }
     }
     __syncthreads();
     const int G = Hq / n_kv_heads, Gp = park_heads(G);
