@@ -348,14 +348,26 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(
 template <typename T>
 __global__ __launch_bounds__(256) void attn_combine_wide_kernel(
     const float *__restrict__ part_o, const float *__restrict__ part_ml, int nsplit, int d,
-    T *__restrict__ out, float *__restrict__ lse)
+    T *__restrict__ out, float *__restrict__ lse, const int32_t *__restrict__ seq_meta, int wpk)
 {
     __shared__ float sm_max[4];
     __shared__ float sm_z[256];
     __shared__ __align__(16) float sm_o[1024];         // [split lane][d]: SL * d <= 1024 as DL >= d/4
     const int64_t bh = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;    // b*Hq + h
     const int t = threadIdx.x;
+    // partial s of this head: statistics at ml[s * ml_step], accumulator at po[s * o_step]
     const float *ml = part_ml + bh * nsplit * 2;
+    const float *pbase = part_o + bh * nsplit * d;
+    int64_t ml_step = 2, o_step = d;
+    if (seq_meta) {
+        const int Hq = gridDim.x, h = blockIdx.x, b = blockIdx.y;
+        const int64_t first = (int64_t)seq_meta[2 * b] * wpk;
+        nsplit = seq_meta[2 * b + 1] * wpk;
+        ml = part_ml + (first * Hq + h) * 2;
+        pbase = part_o + (first * Hq + h) * d;
+        ml_step = 2 * (int64_t)Hq;
+        o_step = (int64_t)Hq * d;
+    }
     // dim lanes: the power of two covering d/4 (1 .. 64); split lanes: the rest of the 256 threads
     const int nd4 = d / 4;
     int DL = 1;
@@ -364,7 +376,7 @@ __global__ __launch_bounds__(256) void attn_combine_wide_kernel(
     const int dl = t & (DL - 1), sl = t / DL;
 
     float mloc = -INFINITY;
-    for (int s = t; s < nsplit; s += 256) mloc = fmaxf(mloc, ml[2 * s]);
+    for (int s = t; s < nsplit; s += 256) mloc = fmaxf(mloc, ml[s * ml_step]);
     mloc = wave_max(mloc);
     if ((t & 63) == 0) sm_max[t >> 6] = mloc;
     __syncthreads();
@@ -373,12 +385,12 @@ __global__ __launch_bounds__(256) void attn_combine_wide_kernel(
     float Z = 0.f;
     f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
     if (M > -INFINITY && dl < nd4) {
-        const f32x4 *po = reinterpret_cast<const f32x4 *>(part_o + bh * nsplit * d) + dl;
+        const float *po = pbase + 4 * dl;
 #pragma unroll 4
         for (int s = sl; s < nsplit; s += SL) {
-            const float f = fast_exp2(ml[2 * s] - M);
-            Z += f * ml[2 * s + 1];
-            const f32x4 a = po[(int64_t)s * nd4];
+            const float f = fast_exp2(ml[s * ml_step] - M);
+            Z += f * ml[s * ml_step + 1];
+            const f32x4 a = *reinterpret_cast<const f32x4 *>(po + s * o_step);
             o += a * f;
         }
     }
@@ -464,16 +476,17 @@ hipError_t launch_attn(const Shape &s, const void *q, float scale, const int32_t
 }
 
 hipError_t launch_attn_combine(const Shape &s, const float *part_o, const float *part_ml, int nsplit,
-                               void *out, float *lse, hipStream_t stream)
+                               void *out, float *lse, hipStream_t stream, const int32_t *seq_meta, int wpk)
 {
     const int d = s.kv.head_dim;
     dim3 grid(s.n_q_heads, s.batch), block(256);
-    if (d % 4 == 0 && nsplit > 2) {
+    if (seq_meta && d % 4 != 0) return hipErrorInvalidValue;
+    if (d % 4 == 0 && (nsplit > 2 || seq_meta)) {
         // several partials per head: spread them over the workgroup's threads
         if (s.dtype == DT_BF16)
-            FASTOCR_LAUNCH(K_ATTN_COMBINE, attn_combine_wide_kernel<uint16_t>, grid, block, 0, stream, part_o, part_ml, nsplit, d, (uint16_t *)out, lse);
+            FASTOCR_LAUNCH(K_ATTN_COMBINE, attn_combine_wide_kernel<uint16_t>, grid, block, 0, stream, part_o, part_ml, nsplit, d, (uint16_t *)out, lse, seq_meta, wpk);
         else
-            FASTOCR_LAUNCH(K_ATTN_COMBINE, attn_combine_wide_kernel<float>, grid, block, 0, stream, part_o, part_ml, nsplit, d, (float *)out, lse);
+            FASTOCR_LAUNCH(K_ATTN_COMBINE, attn_combine_wide_kernel<float>, grid, block, 0, stream, part_o, part_ml, nsplit, d, (float *)out, lse, seq_meta, wpk);
         return hipGetLastError();
     }
     if (s.dtype == DT_BF16)

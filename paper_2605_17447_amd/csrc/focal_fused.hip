@@ -44,9 +44,9 @@ static_assert(kResTmax == 32, "one f32x32 per logit row holds kResTmax tiles");
 template <bool PAGED>
 __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
     KvDev kv, BatchDev bv, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2,
-    int nranges, int R, float *part_ml, int sync_slot, long long spin_ticks,
+    int batch, int nranges_uniform, int R_uniform, float *part_ml, int sync_slot, long long spin_ticks,
     float *__restrict__ scores, float *__restrict__ lse_out, float *__restrict__ mass_part,
-    float *__restrict__ att_o, float *__restrict__ att_ml)
+    float *__restrict__ att_o, float *__restrict__ att_ml, int32_t *__restrict__ seq_meta)
 {
     __shared__ __align__(16) unsigned char smem[kResWaves][2][8192];      // [wave][K, V]
     __shared__ float sm_m[kResWaves][8], sm_z[kResWaves][8];
@@ -58,13 +58,18 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int li = lane & 15, lg = lane >> 4;
-    const int rng = blockIdx.x, b = blockIdx.y;
     const int Hkv = kv.n_kv_heads;
     const int wpk = kResWaves / Hkv;
     const int kvh = wave % Hkv, sub = wave / Hkv;
 
-    const SeqGeom geo = seq_geom(bv, b);
-    const int S = geo.S, v0 = geo.v0, N = geo.N;
+    // which sequence and which of its ranges (all wave-uniform); ragged batches get ranges in
+    // proportion to their lengths
+    const RangeAlloc ra = resident_alloc(bv, batch, gridDim.x, nranges_uniform, R_uniform, kResTile * wpk, blockIdx.x);
+    if (!ra.active) return;
+    const int rng = ra.rng, b = ra.b, nranges = ra.nr, R = ra.R, wg0 = ra.wg0;
+    const int S = ra.S, v0 = ra.v0, N = ra.N;
+    // where the sequence's partials are, for the merge and image-mass kernels that follow
+    if (rng == 0 && threadIdx.x == 0) { seq_meta[2 * b] = wg0; seq_meta[2 * b + 1] = nranges; }
     const int Tn = S - N;
 
     // image tiles of this wave: tile ti = sub + j*wpk of the range, j = 0 .. nimg-1
@@ -325,7 +330,7 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
         for (int r = 0; r < 4; ++r) acc[t][r] += dpp_move<kDppRor8>(acc[t][r]);
     if (li_p < 8 && li_p < G) {
         // lane_p (head li_p, group lg_p) holds dims 32lg + 8r + t in acc[t][r]
-        const int64_t row = ((int64_t)b * Hq + (int64_t)kvh * G + li_p) * nslots + slot;
+        const int64_t row = ((int64_t)(wg0 + rng) * wpk + sub) * Hq + kvh * G + li_p;      // [workgroup][sub][head]
         float *po = att_o + row * 128 + 32 * lg_p;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -342,7 +347,7 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
     __syncthreads();
 
     // ---- range statistics to the workspace (agent-scope atomics: see score_resident.hip) ---------
-    unsigned long long *my_part = reinterpret_cast<unsigned long long *>(part_ml) + ((int64_t)b * nranges + rng) * Hq;
+    unsigned long long *my_part = reinterpret_cast<unsigned long long *>(part_ml) + (int64_t)(wg0 + rng) * Hq;
     if ((int)threadIdx.x < Hq) {
         const int h = threadIdx.x, g = h / G, x = h - g * G;
         float M = kMinusHuge, Z = 0.f;
@@ -385,7 +390,7 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
     {
         float M = kMinusHuge, Z = 0.f;
         if (lane_p < Hq) {
-            const unsigned long long *pp = reinterpret_cast<const unsigned long long *>(part_ml) + (int64_t)b * nranges * Hq + lane_p;
+            const unsigned long long *pp = reinterpret_cast<const unsigned long long *>(part_ml) + (int64_t)wg0 * Hq + lane_p;
             for (int rr = wave; rr < nranges; rr += kResWaves) {
                 const unsigned long long mz = __hip_atomic_load(pp + (int64_t)rr * Hq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 softmax_merge(M, Z, __uint_as_float((uint32_t)mz), __uint_as_float((uint32_t)(mz >> 32)));
@@ -439,57 +444,63 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
         if (threadIdx.x == 0) {
             float t = 0.f;
             for (int w = 0; w < kResWaves; ++w) t += sm_red[w];
-            mass_part[(int64_t)b * nranges + rng] = t;
+            mass_part[wg0 + rng] = t;
         }
     }
     leave();
 }
 
-__global__ void fused_mass_kernel(const float *__restrict__ mass_part, int nranges, float *__restrict__ img_mass)
+__global__ void fused_mass_kernel(const float *__restrict__ mass_part, const int32_t *__restrict__ seq_meta,
+                                  float *__restrict__ img_mass)
 {
     const int b = blockIdx.x;
+    const int first = seq_meta[2 * b], n = seq_meta[2 * b + 1];
     float t = 0.f;
-    for (int x = threadIdx.x; x < nranges; x += 64) t += mass_part[(int64_t)b * nranges + x];
+    for (int x = threadIdx.x; x < n; x += 64) t += mass_part[first + x];
     t = wave_sum(t);
     if (threadIdx.x == 0) img_mass[b] = t;
 }
 
-// Workspace: attention partials fp32 [B][Hq][nsp][128] and [B][Hq][nsp][2] with
-// nsp = nranges * wpk, range statistics fp32 [B][nranges][Hq][2], image-mass partials [B][nranges].
+// Workspace, with W = nranges * batch workgroups: attention partials fp32 [W][wpk][Hq][128] and
+// [W][wpk][Hq][2], range statistics fp32 [W][Hq][2], image-mass partials [W], and per sequence
+// its first workgroup and range count int32 [B][2].
 size_t focal_fused_workspace_bytes(const Shape &s, const ResidentPlan &p)
 {
-    const size_t nsp = (size_t)p.nranges * p.wpk;
-    size_t bytes = (size_t)s.batch * s.n_q_heads * nsp * (128 + 2) * sizeof(float);
-    bytes += (size_t)s.batch * p.nranges * s.n_q_heads * 2 * sizeof(float);
-    bytes += (size_t)s.batch * p.nranges * sizeof(float);
+    const size_t W = (size_t)p.nranges * s.batch;
+    size_t bytes = W * p.wpk * s.n_q_heads * (128 + 2) * sizeof(float);
+    bytes += W * s.n_q_heads * 2 * sizeof(float);
+    bytes += W * sizeof(float);
+    bytes += (size_t)s.batch * 2 * sizeof(int32_t);
     return bytes;
 }
 
 hipError_t launch_focal_fused(const Shape &s, const ResidentPlan &p, const void *q, float scale, void *out,
                               float *scores, float *lse, float *img_mass, void *ws, hipStream_t stream)
 {
-    const int nsp = p.nranges * p.wpk;
+    const int W = p.nranges * s.batch;
     float *att_o = reinterpret_cast<float *>(ws);
-    float *att_ml = att_o + (size_t)s.batch * s.n_q_heads * nsp * 128;
-    float *part_ml = att_ml + (size_t)s.batch * s.n_q_heads * nsp * 2;
-    float *mass_part = part_ml + (size_t)s.batch * p.nranges * s.n_q_heads * 2;
+    float *att_ml = att_o + (size_t)W * p.wpk * s.n_q_heads * 128;
+    float *part_ml = att_ml + (size_t)W * p.wpk * s.n_q_heads * 2;
+    float *mass_part = part_ml + (size_t)W * s.n_q_heads * 2;
+    int32_t *seq_meta = reinterpret_cast<int32_t *>(mass_part + W);
     static std::atomic<unsigned> call_no{0};
     const int sync_slot = (int)(call_no.fetch_add(1u) % (unsigned)kResSlots);
     const float scale_log2 = scale * kLog2e;
     const int G = s.n_q_heads / s.kv.n_kv_heads;
     const long long spin_ticks = 100000000ll / 4;          // 0.25 s of the 100 MHz wall clock
 
-    dim3 grid(p.nranges, s.batch), block(kResThreads);
+    dim3 grid(W), block(kResThreads);
     if (s.paged)
         FASTOCR_LAUNCH(K_FOCAL_FUSED, focal_fused_kernel<true>, grid, block, 0, stream, s.kv, s.bv,
-                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, p.nranges, p.range_tokens, part_ml, sync_slot,
-                       spin_ticks, scores, lse, img_mass ? mass_part : nullptr, att_o, att_ml);
+                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens, part_ml,
+                       sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, att_o, att_ml, seq_meta);
     else
         FASTOCR_LAUNCH(K_FOCAL_FUSED, focal_fused_kernel<false>, grid, block, 0, stream, s.kv, s.bv,
-                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, p.nranges, p.range_tokens, part_ml, sync_slot,
-                       spin_ticks, scores, lse, img_mass ? mass_part : nullptr, att_o, att_ml);
-    if (img_mass) fused_mass_kernel<<<s.batch, 64, 0, stream>>>(mass_part, p.nranges, img_mass);
-    return launch_attn_combine(s, att_o, att_ml, nsp, out, nullptr, stream);
+                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens, part_ml,
+                       sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, att_o, att_ml, seq_meta);
+    if (img_mass) fused_mass_kernel<<<s.batch, 64, 0, stream>>>(mass_part, seq_meta, img_mass);
+    // every sequence's partials: workgroups seq_meta[b][0] .. + seq_meta[b][1], wpk of them each
+    return launch_attn_combine(s, att_o, att_ml, p.nranges * p.wpk, out, nullptr, stream, seq_meta, p.wpk);
 }
 
 }  // namespace fastocr

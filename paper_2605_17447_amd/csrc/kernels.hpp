@@ -47,9 +47,12 @@ size_t attn_workspace_bytes(const Shape &s, int nsplit);
 hipError_t launch_attn(const Shape &s, const void *q, float scale, const int32_t *sel_idx,
                        const int32_t *sel_cnt, int64_t kmax, void *out, float *lse, void *ws,
                        int nsplit, hipStream_t stream);
-// merge of nsplit partials per (sequence, head) in the layout above into the final output
+// merge of nsplit partials per (sequence, head) in the layout above into the final output.
+// With seq_meta (device int32 [B][2]: first workgroup, workgroup count) the partials are instead
+// those of the fused focal kernel, [workgroup][wpk][Hq][d] / [..][2], wpk per workgroup.
 hipError_t launch_attn_combine(const Shape &s, const float *part_o, const float *part_ml, int nsplit,
-                               void *out, float *lse, hipStream_t stream);
+                               void *out, float *lse, hipStream_t stream, const int32_t *seq_meta = nullptr,
+                               int wpk = 1);
 
 // ---- focal scoring (score.hip) ----------------------------------------------------------
 // Workspace: logits fp32 [B][Hq][pitch], part_ml fp32 [B][Hq][nsplit][2], mass partials.

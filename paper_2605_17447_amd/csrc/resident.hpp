@@ -44,4 +44,113 @@ constexpr int kDppXor2 = 0x4E;          // quad_perm [2,3,0,1]
 constexpr int kDppHalfMirror = 0x141;   // lane i <-> 7 - i within each 8 lanes
 constexpr int kDppRor8 = 0x128;         // lane i <- lane i ^ 8
 
+// ---- which (sequence, image-token range) a workgroup of a register-resident kernel works on ------
+// The grid has W workgroups (at most one per compute unit).  With sequences of equal length every
+// sequence gets W / batch ranges.  In a ragged batch an equal split would leave the chip waiting
+// for the longest sequence's few workgroups, so the ranges are dealt in proportion to the sequences'
+// token counts: the smallest T with  sum_b max(base_b, ceil(S_b / T)) <= W  (found by bisection) gives sequence b
+// nr_b = max(base_b, ceil(S_b / T)) workgroups (base_b = what its image span needs at the most
+// tiles a wave can park).  Every wave computes the same table from the device-side lengths (the
+// host only knows their maxima): lane l looks after sequences 4l .. 4l+3, so batch <= 256.
+struct RangeAlloc {
+    int b, rng, nr, wg0;       // sequence, range within it, its range count, its first workgroup
+    int R;                     // image tokens per range (a multiple of `unit`)
+    int S, v0, N;              // the sequence's geometry
+    bool active;               // false: this workgroup has nothing to do
+};
+
+__device__ __forceinline__ int wave_total(int x) { return __builtin_amdgcn_readlane(wave_scan_incl(x), 63); }
+
+__device__ __forceinline__ RangeAlloc resident_alloc(const BatchDev &bv, int batch, int W, int nr_uniform, int R_uniform,
+                                                     int unit, int w)
+{
+    const int lane = threadIdx.x & 63;
+    const int cap_tokens = kResTmax * unit;
+    int S[4], V0[4], N[4];
+    bool same = true;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int bb = 4 * lane + j;
+        S[j] = 0; V0[j] = 0; N[j] = 0;
+        if (bb < batch) {
+            const SeqGeom g = seq_geom(bv, bb);
+            S[j] = g.S; V0[j] = g.v0; N[j] = g.N;
+        }
+    }
+    const int S0 = __builtin_amdgcn_readlane(S[0], 0), N0 = __builtin_amdgcn_readlane(N[0], 0);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) same = same && (4 * lane + j >= batch || (S[j] == S0 && N[j] == N0));
+    const bool uniform = __builtin_amdgcn_ballot_w64(!same) == 0ull;
+
+    RangeAlloc ra;
+    int start[4], cnt[4];
+    if (uniform) {
+        ra.b = w / nr_uniform;
+        ra.rng = w - ra.b * nr_uniform;
+        ra.nr = nr_uniform;
+        ra.wg0 = ra.b * nr_uniform;
+        ra.R = R_uniform;
+        ra.active = ra.b < batch;
+    } else {
+        int wt[4], base[4], part = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool live = 4 * lane + j < batch;
+            wt[j] = live ? max(S[j], 1) : 0;
+            base[j] = live ? max(1, (N[j] + cap_tokens - 1) / cap_tokens) : 0;
+            part += wt[j];
+        }
+        const int total = wave_total(part);
+        auto need = [&](int T) {
+            int f = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) f += wt[j] > 0 ? max(base[j], (wt[j] + T - 1) / T) : 0;
+            return wave_total(f);
+        };
+        // T = max_seq_len always fits (every sequence then takes base_b workgroups, and the host has
+        // checked that batch * max base <= W); bisect down from there to the smallest T that fits
+        int lo = max(1, (total + W - 1) / W) - 1, hi = max(bv.max_seq_len, 1);
+        if (lo + 1 <= hi && need(lo + 1) <= W) hi = lo + 1;
+        while (hi - lo > 1) {
+            const int mid = lo + (hi - lo) / 2;
+            if (need(mid) <= W) hi = mid; else lo = mid;
+        }
+        const int T = hi;
+        const bool fits = true;
+        int mine = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            cnt[j] = wt[j] > 0 ? (fits ? max(base[j], (wt[j] + T - 1) / T) : base[j]) : 0;
+            start[j] = mine;
+            mine += cnt[j];
+        }
+        const int before = wave_scan_incl(mine) - mine;
+        int fb = 0, fr = 0, fn = 0, f0 = 0;
+        bool found = false;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int s0 = before + start[j];
+            if (cnt[j] > 0 && w >= s0 && w < s0 + cnt[j]) { found = true; fb = 4 * lane + j; fr = w - s0; fn = cnt[j]; f0 = s0; }
+        }
+        const unsigned long long who = __builtin_amdgcn_ballot_w64(found);
+        ra.active = who != 0ull;
+        const int owner = ra.active ? __builtin_amdgcn_readfirstlane(__ffsll((long long)who) - 1) : 0;
+        ra.b = __builtin_amdgcn_readlane(fb, owner);
+        ra.rng = __builtin_amdgcn_readlane(fr, owner);
+        ra.nr = __builtin_amdgcn_readlane(fn, owner);
+        ra.wg0 = __builtin_amdgcn_readlane(f0, owner);
+        ra.R = 0;
+    }
+    // the sequence's geometry from the lane that loaded it
+    const int ol = __builtin_amdgcn_readfirstlane(min(ra.b, 255) >> 2), oj = ra.b & 3;
+    const int ps = oj == 0 ? S[0] : (oj == 1 ? S[1] : (oj == 2 ? S[2] : S[3]));
+    const int pv = oj == 0 ? V0[0] : (oj == 1 ? V0[1] : (oj == 2 ? V0[2] : V0[3]));
+    const int pn = oj == 0 ? N[0] : (oj == 1 ? N[1] : (oj == 2 ? N[2] : N[3]));
+    ra.S = __builtin_amdgcn_readlane(ps, ol);
+    ra.v0 = __builtin_amdgcn_readlane(pv, ol);
+    ra.N = __builtin_amdgcn_readlane(pn, ol);
+    if (!uniform) ra.R = max(unit, ((ra.N + ra.nr - 1) / max(ra.nr, 1) + unit - 1) / unit * unit);
+    return ra;
+}
+
 }  // namespace fastocr

@@ -83,14 +83,16 @@ size_t resident_workspace_bytes(const Shape &s, const ResidentPlan &p)
 {
     size_t bytes = (size_t)s.batch * p.nranges * s.n_q_heads * 2 * sizeof(float);   // range statistics
     bytes += (size_t)s.batch * p.nranges * sizeof(float);                              // image-mass partials
+    bytes += (size_t)s.batch * 2 * sizeof(int32_t);                                    // where each sequence's partials are
     return bytes;
 }
 
 template <bool PAGED>
 __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
     KvDev kv, BatchDev bv, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2,
-    int nranges, int R, float *part_ml, int sync_slot, long long spin_ticks,
-    float *__restrict__ scores, float *__restrict__ lse_out, float *__restrict__ mass_part)
+    int batch, int nranges_uniform, int R_uniform, float *part_ml, int sync_slot, long long spin_ticks,
+    float *__restrict__ scores, float *__restrict__ lse_out, float *__restrict__ mass_part,
+    int32_t *__restrict__ mass_meta)
 {
     __shared__ __align__(16) unsigned char smem[kResWaves][2][8192];
     __shared__ float sm_m[kResWaves][8], sm_z[kResWaves][8];
@@ -104,13 +106,15 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int li = lane & 15, lg = lane >> 4;
-    const int rng = blockIdx.x, b = blockIdx.y;
     const int Hkv = kv.n_kv_heads;
     const int wpk = kResWaves / Hkv;
     const int kvh = wave % Hkv, sub = wave / Hkv;
 
-    const SeqGeom geo = seq_geom(bv, b);
-    const int S = geo.S, v0 = geo.v0, N = geo.N;
+    // which sequence and which of its ranges (all wave-uniform)
+    const RangeAlloc ra = resident_alloc(bv, batch, gridDim.x, nranges_uniform, R_uniform, kResTile * wpk, blockIdx.x);
+    if (!ra.active) return;
+    const int rng = ra.rng, b = ra.b, nranges = ra.nr, R = ra.R, wg0 = ra.wg0;
+    const int S = ra.S, v0 = ra.v0, N = ra.N;
     const int Tn = S - N;
 
     // image tiles of this wave: tile ti = sub + j*wpk of the range, j = 0 .. nimg-1
@@ -307,7 +311,7 @@ img_done:
     // release/acquire fences: a fence writes back or invalidates the XCD's whole L2 and costs
     // microseconds here.  Order: each publishing thread waits until its stores are acknowledged,
     // the workgroup barrier collects them, then thread 0 counts the range in.
-    unsigned long long *my_part = reinterpret_cast<unsigned long long *>(part_ml) + ((int64_t)b * nranges + rng) * Hq;
+    unsigned long long *my_part = reinterpret_cast<unsigned long long *>(part_ml) + (int64_t)(wg0 + rng) * Hq;
     if ((int)threadIdx.x < Hq) {
         const int h = threadIdx.x, g = h / G, x = h - g * G;
         float M = kMinusHuge, Z = 0.f;
@@ -353,7 +357,7 @@ img_done:
     {
         float M = kMinusHuge, Z = 0.f;
         if (lane < Hq) {
-            const unsigned long long *pp = reinterpret_cast<const unsigned long long *>(part_ml) + (int64_t)b * nranges * Hq + lane;
+            const unsigned long long *pp = reinterpret_cast<const unsigned long long *>(part_ml) + (int64_t)wg0 * Hq + lane;
             for (int rr = wave; rr < nranges; rr += kResWaves) {
                 const unsigned long long mz = __hip_atomic_load(pp + (int64_t)rr * Hq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 softmax_merge(M, Z, __uint_as_float((uint32_t)mz), __uint_as_float((uint32_t)(mz >> 32)));
@@ -400,17 +404,21 @@ fin_done:
         if (threadIdx.x == 0) {
             float t = 0.f;
             for (int w = 0; w < kResWaves; ++w) t += sm_red[w];
-            mass_part[(int64_t)b * nranges + rng] = t;
+            mass_part[wg0 + rng] = t;
+            if (rng == 0) { mass_meta[2 * b] = wg0; mass_meta[2 * b + 1] = nranges; }
         }
     }
     leave();
 }
 
-__global__ void resident_mass_kernel(const float *__restrict__ mass_part, int nranges, float *__restrict__ img_mass)
+// image mass of a sequence = the sum of its ranges' partial sums (their place comes from the kernel)
+__global__ void resident_mass_kernel(const float *__restrict__ mass_part, const int32_t *__restrict__ mass_meta,
+                                     float *__restrict__ img_mass)
 {
     const int b = blockIdx.x;
+    const int first = mass_meta[2 * b], n = mass_meta[2 * b + 1];
     float t = 0.f;
-    for (int x = threadIdx.x; x < nranges; x += 64) t += mass_part[(int64_t)b * nranges + x];
+    for (int x = threadIdx.x; x < n; x += 64) t += mass_part[first + x];
     t = wave_sum(t);
     if (threadIdx.x == 0) img_mass[b] = t;
 }
@@ -418,9 +426,11 @@ __global__ void resident_mass_kernel(const float *__restrict__ mass_part, int nr
 hipError_t launch_score_resident(const Shape &s, const ResidentPlan &p, const void *q, float scale, float *scores,
                                  float *lse, float *img_mass, void *ws, hipStream_t stream)
 {
-    const size_t nstat = (size_t)s.batch * p.nranges * s.n_q_heads * 2;
+    const int W = p.nranges * s.batch;                       // workgroups = range statistics slots
+    const size_t nstat = (size_t)W * s.n_q_heads * 2;
     float *part_ml = reinterpret_cast<float *>(ws);
     float *mass_part = part_ml + nstat;
+    int32_t *mass_meta = reinterpret_cast<int32_t *>(mass_part + W);
     static std::atomic<unsigned> call_no{0};
     const int sync_slot = (int)(call_no.fetch_add(1u) % (unsigned)kResSlots);
     const float scale_log2 = scale * kLog2e;
@@ -429,16 +439,16 @@ hipError_t launch_score_resident(const Shape &s, const ResidentPlan &p, const vo
     // finish within microseconds of each other); past it the call's scores are NaN but it ends
     const long long spin_ticks = 100000000ll / 4;          // 0.25 s of the 100 MHz wall clock
 
-    dim3 grid(p.nranges, s.batch), block(kResThreads);
+    dim3 grid(W), block(kResThreads);
     if (s.paged)
         FASTOCR_LAUNCH(K_SCORE_LOGITS, score_resident_kernel<true>, grid, block, 0, stream, s.kv, s.bv,
-                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, p.nranges, p.range_tokens, part_ml, sync_slot,
-                       spin_ticks, scores, lse, img_mass ? mass_part : nullptr);
+                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens, part_ml,
+                       sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, mass_meta);
     else
         FASTOCR_LAUNCH(K_SCORE_LOGITS, score_resident_kernel<false>, grid, block, 0, stream, s.kv, s.bv,
-                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, p.nranges, p.range_tokens, part_ml, sync_slot,
-                       spin_ticks, scores, lse, img_mass ? mass_part : nullptr);
-    if (img_mass) resident_mass_kernel<<<s.batch, 64, 0, stream>>>(mass_part, p.nranges, img_mass);
+                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens, part_ml,
+                       sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, mass_meta);
+    if (img_mass) resident_mass_kernel<<<s.batch, 64, 0, stream>>>(mass_part, mass_meta, img_mass);
     return hipGetLastError();
 }
 

@@ -299,6 +299,41 @@ def test_focal_layer_one_pass_paged_and_long_text():
         fb.set_tuning("focal_fused", 1)
 
 
+def test_ragged_batches_get_ranges_in_proportion_to_their_lengths():
+    """The register-resident kernels deal their workgroups to the sequences by length (computed on
+    the device): one very long sequence among short ones, a batch where every sequence needs its
+    capacity minimum, empty sequences in between."""
+    cases = [
+        dict(B=12, n_vis=[16384] + [300] * 11, pre=[7] * 12, post=[40] + [5 * i for i in range(11)]),
+        dict(B=9, n_vis=[0, 5000, 0, 33, 9000, 1, 2047, 2049, 0], pre=[0, 3, 50, 0, 9, 0, 1, 2, 0],
+             post=[0, 10, 0, 0, 300, 0, 0, 0, 0]),
+        dict(B=64, n_vis=[200 + 61 * (i % 9) for i in range(64)], pre=[i % 5 for i in range(64)],
+             post=[(7 * i) % 40 for i in range(64)]),
+    ]
+    try:
+        fb.set_tuning("score_resident", 2)
+        fb.set_tuning("focal_fused", 2)
+        for ci, c in enumerate(cases):
+            case = TinyCase(seed=400 + ci, Hq=28, Hkv=4, d=128, dtype="bf16", **c)
+            p = problem_from_case(case)
+            oc = p.oracle_args()
+            ref_sc, ref_lse, ref_mass = oracle.focal_score(*oc)
+            ref_dense, _ = oracle.decode_attn(*oc)
+            nz = [b for b in range(p.B) if p.seq_len[b] > 0]
+            sc, lse, mass = p.scores(want_lse=True, want_mass=True)
+            check_scores(sc, ref_sc, p.vis_len, f"ragged case {ci} scores")
+            assert np.allclose(lse.cpu().numpy()[nz], ref_lse[nz], rtol=2e-5, atol=2e-5)
+            assert np.allclose(mass.cpu().numpy(), ref_mass, atol=2e-5)
+            out, sc, lse, mass = p.focal_attn(want_lse=True, want_mass=True)
+            check_out(out, ref_dense, f"ragged case {ci} one-pass output")
+            check_scores(sc, ref_sc, p.vis_len, f"ragged case {ci} one-pass scores")
+            assert np.allclose(lse.cpu().numpy()[nz], ref_lse[nz], rtol=2e-5, atol=2e-5)
+            assert np.allclose(mass.cpu().numpy(), ref_mass, atol=2e-5)
+    finally:
+        fb.set_tuning("score_resident", 1)
+        fb.set_tuning("focal_fused", 1)
+
+
 # ------------------------------------------------------------------ full size, the benchmark's launch configuration
 
 def test_config4_full_size_in_the_benchmark_launch_configuration():
