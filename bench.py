@@ -48,6 +48,8 @@ def parse_args():
                     help="what one timed step is: the metric's three-step path (default), or a focal layer as "
                          "the controller runs it (dense output + scores from one pass over K and V, then top-k); "
                          "the roofline object then describes the fused kernel")
+    ap.add_argument("--paged", action="store_true",
+                    help="keep the configuration's paged KV layout (configuration 5) instead of a contiguous cache")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
                     help="launch-shape override passed to fastocr_set_tuning (measurement sweeps)")
     return ap.parse_args()
@@ -132,7 +134,9 @@ def main():
     n_steps, n_warm = args.steps, args.warmup
     total = n_steps + n_warm
     over = {"batch": args.batch} if args.batch else {}
-    wl = fs.config(args.config, n_layers=1, focal_layers=(0,), paged=False, **over)
+    if not args.paged:
+        over["paged"] = False
+    wl = fs.config(args.config, n_layers=1, focal_layers=(0,), **over)
     t_first = args.start_step or max(1, wl.steps // 2 - total // 2)
     assert t_first + total - 1 <= wl.steps, "not enough decode steps in this configuration"
     tau = args.tau
@@ -150,7 +154,7 @@ def main():
     vis_len = torch.tensor(bt.n_vis, dtype=torch.int32, device=dev)
     max_vis = max(bt.n_vis)
     batches = [fo.SeqBatch(seq_lens[i], vis_start, vis_len, max(bt.seq_len(t_first + i)), max_vis) for i in range(total)]
-    layer_caches = [fo.KvCache(x.k, x.v) for x in bts]
+    layer_caches = [fo.KvCache(x.k, x.v, "bhsd", x.block_table) if wl.paged else fo.KvCache(x.k, x.v) for x in bts]
     caches = [layer_caches[i % L] for i in range(total)]
     cache = layer_caches[0]
     scale = float(np.float32(d ** -0.5))

@@ -123,6 +123,14 @@ size_t fastocr_workspace_bytes(int op, const fastocr_kv_view *kv, const fastocr_
  *   scores   fp32 [batch, max_vis_len]
  *   lse      fp32 [batch, n_q_heads] natural-log sum-exp of each head's logits, or NULL
  *   img_mass fp32 [batch] sum_i scores[b,i] = the image-attention ratio of Eq. 1, or NULL
+ * Concurrency: for large shapes this call (and fastocr_focal_attn_score) runs as ONE kernel whose
+ * workgroups -- at most one per compute unit -- wait for each other at a per-sequence barrier, so
+ * all of them must be on the chip together.  Launched alone on the GPU (any number of calls in
+ * order on one stream, HIP graphs included) that always holds.  If other kernels occupy compute
+ * units from another stream at the same time, the barrier gives up after 0.25 s and the affected
+ * scores (and outputs) are NaN rather than wrong; callers that overlap such work should select
+ * the forms built from separate kernels with fastocr_set_tuning("score_resident", 0) and
+ * ("focal_fused", 0).  At most 32 calls of a kind may be in flight on one GPU.
  */
 int fastocr_focal_score(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
                         int n_q_heads, float scale, float *scores, float *lse, float *img_mass,
