@@ -244,7 +244,9 @@ int fastocr_stream_probe(const void *src, void *dst, size_t bytes, void *sink, v
 /* Launch-shape overrides for measurement sweeps: key "splits_score" | "splits_dense" |
  * "splits_sparse" (0 = automatic), "score_resident" | "focal_fused" (0 = always the separate
  * kernels, 1 = chosen by size (default), 2 = the single-kernel form whenever the shape fits),
- * "attn_waves" (4 | 8).  Returns FASTOCR_EINVAL for an unknown key. */
+ * "attn_waves" (4 | 8), "barrier_spin_us" (how long a workgroup of the single-kernel forms waits for
+ * its sequence's other workgroups; 0 restores the default of 250000; 1 makes waiting workgroups give
+ * up at once, which tests use to exercise the NaN path).  Returns FASTOCR_EINVAL for an unknown key. */
 int fastocr_set_tuning(const char *key, int value);
 
 const char *fastocr_strerror(int status);

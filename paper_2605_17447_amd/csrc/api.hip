@@ -16,6 +16,7 @@ namespace fastocr {
 static int g_tune_score_resident = 1;
 static int g_tune_focal_fused = 1;
 int g_tune_attn_waves = 4;
+int g_tune_barrier_spin_us = 250000;      // bounded wait of the resident kernels' per-sequence barrier
 static int g_tune_splits[4] = {0, 0, 0, 0};     // indexed by fastocr_op
 
 // ---- per-kernel timers ------------------------------------------------------------------
@@ -421,6 +422,7 @@ int fastocr_set_tuning(const char *key, int value)
     else if (!strcmp(key, "splits_sparse")) g_tune_splits[FASTOCR_OP_SPARSE_DECODE_ATTN] = value;
     else if (!strcmp(key, "splits_dense")) g_tune_splits[FASTOCR_OP_DENSE_DECODE_ATTN] = value;
     else if (!strcmp(key, "attn_waves")) g_tune_attn_waves = value;
+    else if (!strcmp(key, "barrier_spin_us") && value >= 0) g_tune_barrier_spin_us = value ? value : 250000;
     else if (!strcmp(key, "score_resident") && value >= 0 && value <= 2) g_tune_score_resident = value;
     else if (!strcmp(key, "focal_fused") && value >= 0 && value <= 2) g_tune_focal_fused = value;
     else return FASTOCR_EINVAL;

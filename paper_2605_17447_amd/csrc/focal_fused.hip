@@ -31,6 +31,8 @@
 
 namespace fastocr {
 
+extern int g_tune_barrier_spin_us;
+
 // {arrived, left} per sequence and a sticky time-out flag per slot; see score_resident.hip
 __device__ uint32_t g_fus_sync[kResSlots][2 * kResMaxBatch + 1];
 
@@ -487,7 +489,7 @@ hipError_t launch_focal_fused(const Shape &s, const ResidentPlan &p, const void 
     const int sync_slot = (int)(call_no.fetch_add(1u) % (unsigned)kResSlots);
     const float scale_log2 = scale * kLog2e;
     const int G = s.n_q_heads / s.kv.n_kv_heads;
-    const long long spin_ticks = 100000000ll / 4;          // 0.25 s of the 100 MHz wall clock
+    const long long spin_ticks = 100ll * g_tune_barrier_spin_us;     // the wall clock runs at 100 MHz; 0.25 s unless overridden
 
     dim3 grid(W), block(kResThreads);
     if (s.paged)

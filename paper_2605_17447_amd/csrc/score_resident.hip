@@ -28,6 +28,8 @@
 
 namespace fastocr {
 
+extern int g_tune_barrier_spin_us;
+
 #define RES_DECLARE(J) f32x4 park_##J;
 // image tile J of the wave: multiply, keep the logits, refill the tile's LDS slot
 #define RES_STREAM_STEP(J)                                                                          \
@@ -437,7 +439,7 @@ hipError_t launch_score_resident(const Shape &s, const ResidentPlan &p, const vo
     const int G = s.n_q_heads / s.kv.n_kv_heads;
     // a range waits at most this long for its sequence's other ranges (they run concurrently and
     // finish within microseconds of each other); past it the call's scores are NaN but it ends
-    const long long spin_ticks = 100000000ll / 4;          // 0.25 s of the 100 MHz wall clock
+    const long long spin_ticks = 100ll * g_tune_barrier_spin_us;     // the wall clock runs at 100 MHz; 0.25 s unless overridden
 
     dim3 grid(W), block(kResThreads);
     if (s.paged)

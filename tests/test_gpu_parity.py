@@ -299,6 +299,43 @@ def test_focal_layer_one_pass_paged_and_long_text():
         fb.set_tuning("focal_fused", 1)
 
 
+def test_a_barrier_that_gives_up_poisons_the_result_and_leaves_the_library_usable():
+    """With a 1-microsecond limit every workgroup that has to wait for its sequence's others gives
+    up: its part of the scores must be NaN (never a number built on missing statistics), every
+    kernel still ends normally, and the next call with the normal limit is correct again (the
+    barrier counters were left clean)."""
+    case = TinyCase(seed=500, B=2, Hq=28, Hkv=4, d=128, n_vis=[9000, 7000], pre=[12, 0], post=[30, 9], dtype="bf16")
+    p = problem_from_case(case)
+    ref_sc, _, _ = oracle.focal_score(*p.oracle_args())
+    ref_dense, _ = oracle.decode_attn(*p.oracle_args())
+    try:
+        fb.set_tuning("score_resident", 2)
+        fb.set_tuning("focal_fused", 2)
+        fb.set_tuning("barrier_spin_us", 1)
+        sc, _, _ = p.scores()
+        out, sc2, _, _ = p.focal_attn()
+        torch.cuda.synchronize()
+        for got in (sc, sc2):
+            g = got.cpu().numpy()
+            for b in range(p.B):
+                row = g[b, : p.vis_len[b]]
+                bad = np.isnan(row)
+                assert bad.any(), "with dozens of ranges per sequence some workgroup must have had to wait"
+                assert np.abs(row[~bad] - ref_sc[b, : p.vis_len[b]][~bad]).max(initial=0.0) <= 1e-6
+        # the attention output does not depend on the barrier (partials are merged by a later kernel)
+        check_out(out, ref_dense, "output of a call whose score barrier gave up")
+        fb.set_tuning("barrier_spin_us", 0)
+        sc, _, _ = p.scores()
+        out, sc2, _, _ = p.focal_attn()
+        check_scores(sc, ref_sc, p.vis_len, "scores after a timed-out call")
+        check_scores(sc2, ref_sc, p.vis_len, "one-pass scores after a timed-out call")
+        check_out(out, ref_dense, "one-pass output after a timed-out call")
+    finally:
+        fb.set_tuning("barrier_spin_us", 0)
+        fb.set_tuning("score_resident", 1)
+        fb.set_tuning("focal_fused", 1)
+
+
 def test_ragged_batches_get_ranges_in_proportion_to_their_lengths():
     """The register-resident kernels deal their workgroups to the sequences by length (computed on
     the device): one very long sequence among short ones, a batch where every sequence needs its
