@@ -93,9 +93,6 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
         if (hcol < G)
             qq[kk] = *reinterpret_cast<const u32x4 *>(q + ((int64_t)b * Hq + (int64_t)kvh * G + hcol) * 128 + 8 * (4 * kk + lg));
     }
-    // the query has arrived before the first tile is requested: the waits further down count
-    // tile loads only
-    asm volatile("" ::"v"(qq[0]), "v"(qq[1]), "v"(qq[2]), "v"(qq[3]));
     const uint16_t *kbase = reinterpret_cast<const uint16_t *>(kv.k);
     const uint16_t *vbase = reinterpret_cast<const uint16_t *>(kv.v);
 
