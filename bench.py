@@ -294,9 +294,10 @@ def main():
             ms = fb.kernel_timer_read(kid)
             kernels_us[nm] = round(float(np.mean(ms)) * 1e3, 2) if ms else None
             fb.kernel_timer_enable(kid, 0)
-        mean_T = mean_S - max_vis
         dense_bytes = B * (mean_S * 2 * R + 2 * Hq * d * e)
-        sparse_bytes = B * ((kmax + mean_T) * 2 * R + 4 * kmax + 2 * Hq * d * e)
+        # per sequence: its own kept count and its own text length (ragged batches differ in both)
+        sparse_bytes = sum((fo.keep_count(n, tau) + float(seq_lens[n_warm:, b].float().mean().item()) - n) * 2 * R
+                           + 4 * fo.keep_count(n, tau) + 2 * Hq * d * e for b, n in enumerate(bt.n_vis))
         focal_separate_ms = ms_per_step - sparse_ms + dense_ms   # dense output, scores and top-k as three calls
         blend = lambda f: f * focal_ms + (1 - f) * sparse_ms
         result["extras"] = {

@@ -62,8 +62,10 @@ hipError_t launch_score(const Shape &s, const void *q, float scale, float *score
                         float *img_mass, void *ws, int nsplit, hipStream_t stream);
 
 // ---- focal scoring with register-resident logits (score_resident.hip) ---------------------
-// Workspace: range statistics fp32 [B][nranges][Hq][2], image-mass partials fp32 [B][nranges],
-// barrier counters uint32 [B] + one status word.
+// The plan gives the grid (nranges * batch workgroups, at most one per compute unit) and the
+// range length used when all sequences are equally long; ragged batches are split on the device.
+// Workspace, W = nranges * batch: range statistics fp32 [W][Hq][2], image-mass partials fp32 [W],
+// per sequence its first workgroup and range count int32 [B][2].
 struct ResidentPlan { int nranges, range_tokens, wpk; };
 bool resident_plan(const Shape &s, int num_cu, ResidentPlan *plan);
 size_t resident_workspace_bytes(const Shape &s, const ResidentPlan &p);

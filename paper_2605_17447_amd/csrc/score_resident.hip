@@ -5,7 +5,8 @@
 // those writes into the K stream costs far more than their bytes on this chip.  This kernel
 // keeps them in registers instead:
 //   - one 512-thread workgroup per (image-token range, sequence), at most one per compute unit,
-//     so the whole grid is resident at once;
+//     so the whole grid is resident at once; a ragged batch's sequences get ranges in proportion
+//     to their lengths (resident_alloc in resident.hpp);
 //   - wave w streams KV head w % Hkv (8/Hkv waves share a head and interleave its tiles), a
 //     32-token tile (8 KB) at a time.  Tiles travel HBM -> LDS directly (global_load_lds, 16 bytes
 //     per lane, two 8 KB slots per wave, no staging registers); the XOR swizzle that makes the

@@ -291,6 +291,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_general_kernel(
 // atomics or index arrays are needed, and the scores are read exactly once.
 constexpr int kTopkPer = 16;
 constexpr int kTopkRegKeys = kTopkThreads * kTopkPer;
+constexpr int kRegCandCap = 8192;          // candidates this kernel selects among (keep ratios up to 1/3 at 16384 tokens)
 
 // exclusive prefix sums of (a, c) over the 1024 threads; totals through *ta, *tc.  All threads call.
 // w_ac: 2 x 16 wave totals, 16-byte aligned.
@@ -325,7 +326,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(
 {
     extern __shared__ uint32_t dyn_keys[];          // all keys, only when the candidate list fails
     __shared__ uint32_t hist[2][256];
-    __shared__ uint32_t cand[kCandCap];
+    __shared__ uint32_t cand[kRegCandCap];
     __shared__ int s_pick[2];
     __shared__ uint32_t s_theta_prev;
     __shared__ int s_bad;
@@ -406,7 +407,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(
     for (int j = 0; j < kTopkPer; ++j) mine += (j < nvalid && key[j] >= theta0) ? 1 : 0;
     int pos, unused_excl, nc, unused_tot;
     block_scan2(mine, 0, w_ac, pos, unused_excl, &nc, &unused_tot);
-    const bool from_cand = nc >= k && nc <= kCandCap;
+    const bool from_cand = nc >= k && nc <= kRegCandCap;
     uint32_t theta;
     int ties;
     if (from_cand) {
