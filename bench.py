@@ -64,6 +64,7 @@ def stack_extras(fs, fo, torch, np, dev, tau, n_time=30):
     L, focal = wl.n_layers, wl.focal_layers
     bts = [fs.make_batch(wl, device=dev, layer=l) for l in range(L)]
     bt = bts[0]
+    progress("caches generated")
     cs = fs.centres(bt, 4)
     B, Hq, d = wl.batch, wl.n_q_heads, wl.head_dim
     scale = float(np.float32(d ** -0.5))
@@ -109,6 +110,12 @@ def stack_extras(fs, fo, torch, np, dev, tau, n_time=30):
             "fastocr_step_us_without_graph": round(eager_us, 1)}
 
 
+def progress(msg):
+    """Stage markers on stderr when FASTOCR_BENCH_PROGRESS is set (long profiler runs)."""
+    if os.environ.get("FASTOCR_BENCH_PROGRESS"):
+        print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -123,6 +130,7 @@ def main():
     import paper_2605_17447_amd as fo
     from paper_2605_17447_amd import binding as fb
 
+    progress("torch imported")
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
@@ -145,10 +153,12 @@ def main():
     L = max(1, args.layers)
     bts = [fs.make_batch(wl, device=dev, layer=l) for l in range(L)]
     bt = bts[0]
+    progress("caches generated")
     cs = fs.centres(bt, t_first + total)
     B, Hq, Hkv, d = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim
     qs = torch.stack([fs.queries_for_step(bts[i % L], t_first + i, [c[t_first + i - 1] for c in cs])
                       for i in range(total)])
+    progress("queries generated")
     seq_lens = torch.tensor([bt.seq_len(t_first + i) for i in range(total)], dtype=torch.int32, device=dev)
     vis_start = torch.tensor(bt.vis_start, dtype=torch.int32, device=dev)
     vis_len = torch.tensor(bt.n_vis, dtype=torch.int32, device=dev)
@@ -190,6 +200,7 @@ def main():
     step_fn = focal_layer_step if focal_mode else three_step
     timed_kernel = fb.KERNEL_FOCAL_FUSED if focal_mode else fb.KERNEL_SCORE_LOGITS
 
+    progress("inputs resident")
     # ---- timed region ------------------------------------------------------------------------
     for i in range(n_warm):
         step_fn(i)
@@ -201,6 +212,7 @@ def main():
         step_fn(i)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    progress("timed region done")
     logits_ms = fb.kernel_timer_read(timed_kernel)
     fb.kernel_timer_enable(timed_kernel, 0)
 
