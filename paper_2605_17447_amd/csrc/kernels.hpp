@@ -64,8 +64,8 @@ hipError_t launch_score(const Shape &s, const void *q, float scale, float *score
 // ---- focal scoring with register-resident logits (score_resident.hip) ---------------------
 // The plan gives the grid (nranges * batch workgroups, at most one per compute unit) and the
 // range length used when all sequences are equally long; ragged batches are split on the device.
-// Workspace, W = nranges * batch: range statistics fp32 [W][Hq][2], image-mass partials fp32 [W],
-// per sequence its first workgroup and range count int32 [B][2].
+// Workspace, W = nranges * batch: image-mass partials fp32 [W], per sequence its first workgroup
+// and range count int32 [B][2] (the ranges' softmax statistics travel through static device memory).
 struct ResidentPlan { int nranges, range_tokens, wpk; };
 bool resident_plan(const Shape &s, int num_cu, ResidentPlan *plan);
 size_t resident_workspace_bytes(const Shape &s, const ResidentPlan &p);

@@ -40,22 +40,34 @@ extern int g_tune_barrier_spin_us;
         park_##J = logits_of(kb, img_first(J) + tok_in_tile < r1);                                  \
         if ((J) + 1 >= nimg) goto img_done;                                                         \
     }
-// tile J after the barrier: probabilities of this lane's 4 heads, summed with the partner lane's 4
+// tile J while the statistics travel: logits -> probabilities relative to the wave's own maximum
+#define RES_PREEXP_STEP(J)                                                                          \
+    {                                                                                               \
+        _Pragma("unroll") for (int r = 0; r < 4; ++r) park_##J[r] = fast_exp2(park_##J[r] - m[r]);  \
+        if ((J) + 1 >= nimg) goto pre_done;                                                         \
+    }
+// tile J after the exchange: rescaled to the sequence's normalisers, this lane's 4 heads summed
+// with the partner lane's 4
 #define RES_FINISH_STEP(J)                                                                          \
     {                                                                                               \
         float v = 0.f;                                                                              \
-        _Pragma("unroll") for (int r = 0; r < 4; ++r) v += fast_exp2(park_##J[r] - lh[r]);          \
+        _Pragma("unroll") for (int r = 0; r < 4; ++r) v += park_##J[r] * cf[r];                     \
         v += __shfl_xor(v, 16);                                                                     \
         if ((lg & 1) == 0) red[kvh * R + img_first(J) - r0 + tok_in_tile] = v;                      \
         if ((J) + 1 >= nimg) goto fin_done;                                                         \
     }
 
-// Barrier state lives in static device memory (zero when the module is loaded) rather than in
-// the caller's workspace, which would have to be cleared by an extra launch before every call:
-// {arrived, left} per sequence.  The last range to leave a barrier resets both counts, so a slot
-// is clean again when its call ends; calls take slots round-robin, so up to kResSlots calls may
-// overlap on one GPU.  The last word of a slot is a sticky "a barrier timed out" flag.
-__device__ uint32_t g_res_sync[kResSlots][2 * kResMaxBatch + 1];
+// Exchange state lives in static device memory (zero when the module is loaded) rather than in
+// the caller's workspace, which would have to be cleared by an extra launch before every call.
+// g_res_stats: one 64-bit word {max, sum-exp} per (workgroup, head); zero means "not published
+// yet" (a published word is never zero: the sum is positive, or the maximum is the finite
+// stand-in for "no logit").  g_res_left: per sequence, how many of its ranges are done reading.
+// The last range to finish zeroes the sequence's words and its count, so a slot is clean again
+// when its call ends; calls take slots round-robin, so up to kResSlots calls may overlap on one
+// GPU.  The last word of g_res_left[slot] is a sticky "an exchange timed out" flag.
+constexpr int kResMaxWg = 256;
+__device__ unsigned long long g_res_stats[kResSlots][kResMaxWg * kResMaxHq];
+__device__ uint32_t g_res_left[kResSlots][kResMaxBatch + 1];
 
 bool resident_plan(const Shape &s, int num_cu, ResidentPlan *plan)
 {
@@ -84,8 +96,7 @@ bool resident_plan(const Shape &s, int num_cu, ResidentPlan *plan)
 
 size_t resident_workspace_bytes(const Shape &s, const ResidentPlan &p)
 {
-    size_t bytes = (size_t)s.batch * p.nranges * s.n_q_heads * 2 * sizeof(float);   // range statistics
-    bytes += (size_t)s.batch * p.nranges * sizeof(float);                              // image-mass partials
+    size_t bytes = (size_t)s.batch * p.nranges * sizeof(float);                        // image-mass partials
     bytes += (size_t)s.batch * 2 * sizeof(int32_t);                                    // where each sequence's partials are
     return bytes;
 }
@@ -93,7 +104,7 @@ size_t resident_workspace_bytes(const Shape &s, const ResidentPlan &p)
 template <bool PAGED>
 __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
     KvDev kv, BatchDev bv, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2,
-    int batch, int nranges_uniform, int R_uniform, float *part_ml, int sync_slot, long long spin_ticks,
+    int batch, int nranges_uniform, int R_uniform, int sync_slot, long long spin_ticks,
     float *__restrict__ scores, float *__restrict__ lse_out, float *__restrict__ mass_part,
     int32_t *__restrict__ mass_meta)
 {
@@ -102,7 +113,7 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
     __shared__ float sm_lse[kResMaxHq];
     __shared__ float sm_pm[kResWaves][64], sm_pz[kResWaves][64];
     __shared__ float sm_red[kResWaves];
-    __shared__ int sm_met;
+    __shared__ int sm_met, sm_last;
 
     // wave-uniform quantities are kept in scalar registers: tile bookkeeping, addresses and loop
     // exits then cost no vector instructions
@@ -312,64 +323,87 @@ img_done:
     // The statistics cross compute units (and XCDs, each with its own L2) through agent-scope
     // atomic stores and loads, which go through to memory, instead of plain stores bracketed by
     // release/acquire fences: a fence writes back or invalidates the XCD's whole L2 and costs
-    // microseconds here.  Order: each publishing thread waits until its stores are acknowledged,
-    // the workgroup barrier collects them, then thread 0 counts the range in.
-    unsigned long long *my_part = reinterpret_cast<unsigned long long *>(part_ml) + (int64_t)(wg0 + rng) * Hq;
+    // microseconds here.  Every word is its own "ready" flag, so nothing has to be ordered: a
+    // reader simply polls until the words it needs are non-zero.
+    unsigned long long *stats = g_res_stats[sync_slot] + (int64_t)wg0 * Hq;
     if ((int)threadIdx.x < Hq) {
         const int h = threadIdx.x, g = h / G, x = h - g * G;
         float M = kMinusHuge, Z = 0.f;
         for (int sb = 0; sb < wpk; ++sb) softmax_merge(M, Z, sm_m[g + sb * Hkv][x], sm_z[g + sb * Hkv][x]);
         const unsigned long long mz = (unsigned long long)__float_as_uint(M) | ((unsigned long long)__float_as_uint(Z) << 32);
-        __hip_atomic_store(&my_part[h], mz, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __hip_atomic_store(&stats[(int64_t)rng * Hq + h], mz, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    // ---- per-sequence barrier: every range of the sequence has published its statistics ---------
+    if (threadIdx.x == 0) sm_met = 1;
+    // while the words travel: the parked logits become probabilities relative to the wave's own
+    // maxima (m[r] is wave-wide after the merge above); the sequence-wide factor follows below
+    if (nimg > 0) {
+        RES_EACH_TILE(RES_PREEXP_STEP)
+    }
+pre_done:
     __syncthreads();
-    uint32_t left_before = 0u;
-    uint32_t *arrived = &g_res_sync[sync_slot][2 * b], *left = arrived + 1;
-    // the last range to leave has seen every other one pass: it clears the counts for the next call
-    auto leave = [&]() {
-        if (threadIdx.x == 0 && left_before == (uint32_t)nranges - 1u) {
-            __hip_atomic_store(left, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    };
-    if (threadIdx.x == 0) {
-        __hip_atomic_fetch_add(arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const long long t_start = wall_clock64();
-        bool ok = true;
-        while (__hip_atomic_load(arrived, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (uint32_t)nranges) {
-            __builtin_amdgcn_s_sleep(1);
-            if (wall_clock64() - t_start > spin_ticks) { ok = false; break; }
-        }
-        if (!ok) __hip_atomic_fetch_or(&g_res_sync[sync_slot][2 * kResMaxBatch], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        sm_met = ok ? 1 : 0;
-        // count this range out; the answer is only looked at when the kernel ends
-        left_before = __hip_atomic_fetch_add(left, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    __syncthreads();
-    if (!sm_met) {
-        // the sequence's other ranges never arrived (the grid was not resident as a whole):
-        // poison this range's scores rather than publish numbers built on missing statistics
-        for (int i = threadIdx.x; i < r1 - r0; i += kResThreads)
-            scores[(int64_t)b * bv.max_vis_len + r0 + i] = __builtin_nanf("");
-        leave();
-        return;
-    }
-    // every head's log-sum-exp from the ranges' statistics: wave w merges ranges w, w+8, ..; lane = head
+
+    // ---- every head's log-sum-exp from the ranges' statistics ------------------------------------
+    // wave w merges ranges w, w+8, ..; lane = head.  A range's first word is polled with one 8-byte
+    // load per round (256 workgroups polling every word would take a tenth of the HBM bandwidth
+    // from the ranges still streaming); once it is there the whole row is read and checked.
     {
         float M = kMinusHuge, Z = 0.f;
-        if (lane < Hq) {
-            const unsigned long long *pp = reinterpret_cast<const unsigned long long *>(part_ml) + (int64_t)wg0 * Hq + lane;
-            for (int rr = wave; rr < nranges; rr += kResWaves) {
-                const unsigned long long mz = __hip_atomic_load(pp + (int64_t)rr * Hq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                softmax_merge(M, Z, __uint_as_float((uint32_t)mz), __uint_as_float((uint32_t)(mz >> 32)));
+        bool ok = true;
+        const long long t_start = wall_clock64();
+        for (int rr = wave; rr < nranges && ok; rr += kResWaves) {
+            unsigned long long mz = 1ull;
+            if (rr == rng) {
+                // the workgroup's own statistics never leave the chip
+                if (lane < Hq) {
+                    const int g = lane / G, x = lane - g * G;
+                    float Mo = kMinusHuge, Zo = 0.f;
+                    for (int sb = 0; sb < wpk; ++sb) softmax_merge(Mo, Zo, sm_m[g + sb * Hkv][x], sm_z[g + sb * Hkv][x]);
+                    softmax_merge(M, Z, Mo, Zo);
+                }
+                continue;
             }
+            const unsigned long long *row = stats + (int64_t)rr * Hq;
+            while (__hip_atomic_load(row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0ull) {
+                __builtin_amdgcn_s_sleep(1);
+                if (wall_clock64() - t_start > spin_ticks) { ok = false; break; }
+            }
+            while (ok) {
+                mz = lane < Hq ? __hip_atomic_load(row + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1ull;
+                if (__builtin_amdgcn_ballot_w64(mz == 0ull) == 0ull) break;
+                __builtin_amdgcn_s_sleep(1);
+                if (wall_clock64() - t_start > spin_ticks) ok = false;
+            }
+            if (ok && lane < Hq) softmax_merge(M, Z, __uint_as_float((uint32_t)mz), __uint_as_float((uint32_t)(mz >> 32)));
+        }
+        if (!ok && lane == 0) {
+            sm_met = 0;
+            __hip_atomic_fetch_or(&g_res_left[sync_slot][kResMaxBatch], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         sm_pm[wave][lane] = M;
         sm_pz[wave][lane] = Z;
     }
     __syncthreads();
+    // This range is done reading: count it out.  The last one of the sequence (it has seen every
+    // other one finish reading) clears the sequence's words and the count when the kernel ends.
+    uint32_t *left = &g_res_left[sync_slot][b];
+    if (threadIdx.x == 0)
+        sm_last = __hip_atomic_fetch_add(left, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)nranges - 1u;
+    auto leave = [&]() {
+        __syncthreads();
+        if (sm_last) {
+            for (int i = threadIdx.x; i < nranges * Hq; i += kResThreads)
+                __hip_atomic_store(&stats[i], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (threadIdx.x == 0) __hip_atomic_store(left, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    };
+    if (!sm_met) {
+        // a range of the sequence never published (the grid was not resident as a whole): poison
+        // this range's scores rather than publish numbers built on missing statistics
+        for (int i = threadIdx.x; i < r1 - r0; i += kResThreads)
+            scores[(int64_t)b * bv.max_vis_len + r0 + i] = __builtin_nanf("");
+        leave();
+        return;
+    }
     if ((int)threadIdx.x < Hq) {
         const int h = threadIdx.x;
         float M = kMinusHuge, Z = 0.f;
@@ -382,9 +416,9 @@ img_done:
     __syncthreads();
 
     // ---- probabilities of the parked logits, summed over the heads of each token ---------------
-    float lh[4];
+    float cf[4];          // from "relative to the wave's maximum" to "relative to the head's normaliser"
 #pragma unroll
-    for (int r = 0; r < 4; ++r) lh[r] = (hbase + r < G) ? sm_lse[kvh * G + hbase + r] : INFINITY;
+    for (int r = 0; r < 4; ++r) cf[r] = (hbase + r < G) ? fast_exp2(m[r] - sm_lse[kvh * G + hbase + r]) : 0.f;
     float *red = reinterpret_cast<float *>(&smem[0][0][0]);          // [Hkv][R], at most 32 KB
     if (nimg > 0) {
         RES_EACH_TILE(RES_FINISH_STEP)
@@ -430,9 +464,7 @@ hipError_t launch_score_resident(const Shape &s, const ResidentPlan &p, const vo
                                  float *lse, float *img_mass, void *ws, hipStream_t stream)
 {
     const int W = p.nranges * s.batch;                       // workgroups = range statistics slots
-    const size_t nstat = (size_t)W * s.n_q_heads * 2;
-    float *part_ml = reinterpret_cast<float *>(ws);
-    float *mass_part = part_ml + nstat;
+    float *mass_part = reinterpret_cast<float *>(ws);
     int32_t *mass_meta = reinterpret_cast<int32_t *>(mass_part + W);
     static std::atomic<unsigned> call_no{0};
     const int sync_slot = (int)(call_no.fetch_add(1u) % (unsigned)kResSlots);
@@ -445,11 +477,11 @@ hipError_t launch_score_resident(const Shape &s, const ResidentPlan &p, const vo
     dim3 grid(W), block(kResThreads);
     if (s.paged)
         FASTOCR_LAUNCH(K_SCORE_LOGITS, score_resident_kernel<true>, grid, block, 0, stream, s.kv, s.bv,
-                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens, part_ml,
+                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens,
                        sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, mass_meta);
     else
         FASTOCR_LAUNCH(K_SCORE_LOGITS, score_resident_kernel<false>, grid, block, 0, stream, s.kv, s.bv,
-                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens, part_ml,
+                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens,
                        sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, mass_meta);
     if (img_mass) resident_mass_kernel<<<s.batch, 64, 0, stream>>>(mass_part, mass_meta, img_mass);
     return hipGetLastError();
