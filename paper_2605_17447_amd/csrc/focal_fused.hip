@@ -33,8 +33,10 @@ namespace fastocr {
 
 extern int g_tune_barrier_spin_us;
 
-// {arrived, left} per sequence and a sticky time-out flag per slot; see score_resident.hip
-__device__ uint32_t g_fus_sync[kResSlots][2 * kResMaxBatch + 1];
+// statistics words per (workgroup, head), per sequence the count of ranges done reading, and a
+// sticky time-out flag per slot: same protocol as score_resident.hip, own arrays
+__device__ unsigned long long g_fus_stats[kResSlots][kResMaxWg * kResMaxHq];
+__device__ uint32_t g_fus_left[kResSlots][kResMaxBatch + 1];
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // One logit per image tile of the wave, indexed by the (wave-uniform) tile number: the compiler
@@ -46,7 +48,7 @@ static_assert(kResTmax == 32, "one f32x32 per logit row holds kResTmax tiles");
 template <bool PAGED>
 __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
     KvDev kv, BatchDev bv, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2,
-    int batch, int nranges_uniform, int R_uniform, float *part_ml, int sync_slot, long long spin_ticks,
+    int batch, int nranges_uniform, int R_uniform, int sync_slot, long long spin_ticks,
     float *__restrict__ scores, float *__restrict__ lse_out, float *__restrict__ mass_part,
     float *__restrict__ att_o, float *__restrict__ att_ml, int32_t *__restrict__ seq_meta)
 {
@@ -55,7 +57,7 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
     __shared__ float sm_lse[kResMaxHq];
     __shared__ float sm_pm[kResWaves][64], sm_pz[kResWaves][64];
     __shared__ float sm_red[kResWaves];
-    __shared__ int sm_met;
+    __shared__ int sm_met, sm_last;
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
@@ -345,60 +347,39 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
     }
     __syncthreads();
 
-    // ---- range statistics to the workspace (agent-scope atomics: see score_resident.hip) ---------
-    unsigned long long *my_part = reinterpret_cast<unsigned long long *>(part_ml) + (int64_t)(wg0 + rng) * Hq;
-    if ((int)threadIdx.x < Hq) {
-        const int h = threadIdx.x, g = h / G, x = h - g * G;
-        float M = kMinusHuge, Z = 0.f;
-        for (int sb = 0; sb < wpk; ++sb) softmax_merge(M, Z, sm_m[g + sb * Hkv][x], sm_z[g + sb * Hkv][x]);
-        const unsigned long long mz = (unsigned long long)__float_as_uint(M) | ((unsigned long long)__float_as_uint(Z) << 32);
-        __hip_atomic_store(&my_part[h], mz, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
-    // ---- per-sequence barrier: every range of the sequence has published its statistics ---------
+    // ---- range statistics: published as self-validating words, gathered by polling (resident.hpp) ----
+    unsigned long long *stats = g_fus_stats[sync_slot] + (int64_t)wg0 * Hq;
+    resident_publish(stats + (int64_t)rng * Hq, sm_m, sm_z, Hq, G, Hkv, wpk);
+    if (threadIdx.x == 0) sm_met = 1;
     __syncthreads();
-    uint32_t left_before = 0u;
-    uint32_t *arrived = &g_fus_sync[sync_slot][2 * b], *left = arrived + 1;
-    auto leave = [&]() {
-        if (threadIdx.x == 0 && left_before == (uint32_t)nranges - 1u) {
-            __hip_atomic_store(left, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    };
-    if (threadIdx.x == 0) {
-        __hip_atomic_fetch_add(arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const long long t_start = wall_clock64();
-        bool ok = true;
-        while (__hip_atomic_load(arrived, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (uint32_t)nranges) {
-            __builtin_amdgcn_s_sleep(1);
-            if (wall_clock64() - t_start > spin_ticks) { ok = false; break; }
-        }
-        if (!ok) __hip_atomic_fetch_or(&g_fus_sync[sync_slot][2 * kResMaxBatch], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        sm_met = ok ? 1 : 0;
-        left_before = __hip_atomic_fetch_add(left, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    __syncthreads();
-    if (!sm_met) {
-        // the sequence's other ranges never arrived: poison this range's scores
-        for (int i = threadIdx.x; i < r1 - r0; i += kResThreads)
-            scores[(int64_t)b * bv.max_vis_len + r0 + i] = __builtin_nanf("");
-        leave();
-        return;
-    }
-    // every head's log-sum-exp from the ranges' statistics: wave w merges ranges w, w+8, ..; lane_p = head
+    // every head's log-sum-exp from the ranges' statistics: wave w merges ranges w, w+8, ..
     {
-        float M = kMinusHuge, Z = 0.f;
-        if (lane_p < Hq) {
-            const unsigned long long *pp = reinterpret_cast<const unsigned long long *>(part_ml) + (int64_t)wg0 * Hq + lane_p;
-            for (int rr = wave; rr < nranges; rr += kResWaves) {
-                const unsigned long long mz = __hip_atomic_load(pp + (int64_t)rr * Hq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                softmax_merge(M, Z, __uint_as_float((uint32_t)mz), __uint_as_float((uint32_t)(mz >> 32)));
-            }
+        float M, Z;
+        const bool ok = resident_gather(stats, rng, nranges, Hq, G, Hkv, wpk, sm_m, sm_z, spin_ticks, M, Z);
+        if (!ok && lane_p == 0) {
+            sm_met = 0;
+            __hip_atomic_fetch_or(&g_fus_left[sync_slot][kResMaxBatch], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         sm_pm[wave][lane_p] = M;
         sm_pz[wave][lane_p] = Z;
     }
     __syncthreads();
+    // This range is done reading: count it out.  The last one of the sequence clears the
+    // sequence's words and the count when the kernel ends.
+    uint32_t *left = &g_fus_left[sync_slot][b];
+    if (threadIdx.x == 0)
+        sm_last = __hip_atomic_fetch_add(left, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)nranges - 1u;
+    auto leave = [&]() {
+        __syncthreads();
+        resident_retire(sm_last != 0, stats, nranges, Hq, left);
+    };
+    if (!sm_met) {
+        // a range of the sequence never published: poison this range's scores
+        for (int i = threadIdx.x; i < r1 - r0; i += kResThreads)
+            scores[(int64_t)b * bv.max_vis_len + r0 + i] = __builtin_nanf("");
+        leave();
+        return;
+    }
     if ((int)threadIdx.x < Hq) {
         const int h = threadIdx.x;
         float M = kMinusHuge, Z = 0.f;
@@ -461,13 +442,12 @@ __global__ void fused_mass_kernel(const float *__restrict__ mass_part, const int
 }
 
 // Workspace, with W = nranges * batch workgroups: attention partials fp32 [W][wpk][Hq][128] and
-// [W][wpk][Hq][2], range statistics fp32 [W][Hq][2], image-mass partials [W], and per sequence
+// [W][wpk][Hq][2], image-mass partials [W], and per sequence
 // its first workgroup and range count int32 [B][2].
 size_t focal_fused_workspace_bytes(const Shape &s, const ResidentPlan &p)
 {
     const size_t W = (size_t)p.nranges * s.batch;
     size_t bytes = W * p.wpk * s.n_q_heads * (128 + 2) * sizeof(float);
-    bytes += W * s.n_q_heads * 2 * sizeof(float);
     bytes += W * sizeof(float);
     bytes += (size_t)s.batch * 2 * sizeof(int32_t);
     return bytes;
@@ -479,8 +459,7 @@ hipError_t launch_focal_fused(const Shape &s, const ResidentPlan &p, const void 
     const int W = p.nranges * s.batch;
     float *att_o = reinterpret_cast<float *>(ws);
     float *att_ml = att_o + (size_t)W * p.wpk * s.n_q_heads * 128;
-    float *part_ml = att_ml + (size_t)W * p.wpk * s.n_q_heads * 2;
-    float *mass_part = part_ml + (size_t)W * s.n_q_heads * 2;
+    float *mass_part = att_ml + (size_t)W * p.wpk * s.n_q_heads * 2;
     int32_t *seq_meta = reinterpret_cast<int32_t *>(mass_part + W);
     static std::atomic<unsigned> call_no{0};
     const int sync_slot = (int)(call_no.fetch_add(1u) % (unsigned)kResSlots);
@@ -491,11 +470,11 @@ hipError_t launch_focal_fused(const Shape &s, const ResidentPlan &p, const void 
     dim3 grid(W), block(kResThreads);
     if (s.paged)
         FASTOCR_LAUNCH(K_FOCAL_FUSED, focal_fused_kernel<true>, grid, block, 0, stream, s.kv, s.bv,
-                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens, part_ml,
+                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens,
                        sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, att_o, att_ml, seq_meta);
     else
         FASTOCR_LAUNCH(K_FOCAL_FUSED, focal_fused_kernel<false>, grid, block, 0, stream, s.kv, s.bv,
-                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens, part_ml,
+                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens,
                        sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, att_o, att_ml, seq_meta);
     if (img_mass) fused_mass_kernel<<<s.batch, 64, 0, stream>>>(mass_part, seq_meta, img_mass);
     // every sequence's partials: workgroups seq_meta[b][0] .. + seq_meta[b][1], wpk of them each

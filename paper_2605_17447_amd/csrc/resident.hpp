@@ -153,4 +153,90 @@ __device__ __forceinline__ RangeAlloc resident_alloc(const BatchDev &bv, int bat
     return ra;
 }
 
+// ---- exchange of the ranges' softmax statistics ----------------------------------------------------
+// One 64-bit word {max, sum-exp} per (workgroup, head) in static device memory; zero means "not
+// published yet" (a published word is never zero: the sum is positive, or the maximum is the finite
+// stand-in for "no logit").  The words cross compute units (and XCDs, each with its own L2) through
+// agent-scope atomic stores and loads, which go through to memory, instead of plain stores bracketed
+// by release/acquire fences: a fence writes back or invalidates the XCD's whole L2 and costs
+// microseconds.  Every word is its own "ready" flag, so nothing has to be ordered: a reader polls
+// until the words it needs are non-zero.  The last range of a sequence to finish reading zeroes the
+// sequence's words again (resident_retire), so a slot is clean when its call ends.
+constexpr int kResMaxWg = 256;
+
+// (max, sum-exp) of head h over this workgroup's waves, from the per-wave values in LDS
+__device__ __forceinline__ void resident_own_stats(const float (*sm_m)[8], const float (*sm_z)[8], int h, int G, int Hkv,
+                                                   int wpk, float &M, float &Z)
+{
+    const int g = h / G, x = h - g * G;
+    M = kMinusHuge;
+    Z = 0.f;
+    for (int sb = 0; sb < wpk; ++sb) softmax_merge(M, Z, sm_m[g + sb * Hkv][x], sm_z[g + sb * Hkv][x]);
+}
+
+// threads 0 .. Hq-1 publish this range's row; no wait, no ordering
+__device__ __forceinline__ void resident_publish(unsigned long long *row, const float (*sm_m)[8], const float (*sm_z)[8],
+                                                 int Hq, int G, int Hkv, int wpk)
+{
+    if ((int)threadIdx.x < Hq) {
+        float M, Z;
+        resident_own_stats(sm_m, sm_z, threadIdx.x, G, Hkv, wpk, M, Z);
+        const unsigned long long mz = (unsigned long long)__float_as_uint(M) | ((unsigned long long)__float_as_uint(Z) << 32);
+        __hip_atomic_store(&row[threadIdx.x], mz, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// Called by every wave: wave w merges ranges w, w+8, .. of the sequence; lane = head.  A range's
+// first word is polled with one 8-byte load per round (256 workgroups polling every word would take
+// a tenth of the HBM bandwidth from the ranges still streaming); once it is there the whole row is
+// read and checked.  The workgroup's own statistics never leave the chip.  Returns false when a
+// word did not appear within spin_ticks of the 100 MHz wall clock.
+__device__ __forceinline__ bool resident_gather(const unsigned long long *stats, int rng, int nranges, int Hq, int G,
+                                                int Hkv, int wpk, const float (*sm_m)[8], const float (*sm_z)[8],
+                                                long long spin_ticks, float &M, float &Z)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    M = kMinusHuge;
+    Z = 0.f;
+    bool ok = true;
+    const long long t_start = wall_clock64();
+    for (int rr = wave; rr < nranges && ok; rr += kResWaves) {
+        if (rr == rng) {
+            if (lane < Hq) {
+                float Mo, Zo;
+                resident_own_stats(sm_m, sm_z, lane, G, Hkv, wpk, Mo, Zo);
+                softmax_merge(M, Z, Mo, Zo);
+            }
+            continue;
+        }
+        const unsigned long long *row = stats + (int64_t)rr * Hq;
+        while (__hip_atomic_load(row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0ull) {
+            __builtin_amdgcn_s_sleep(1);
+            if (wall_clock64() - t_start > spin_ticks) { ok = false; break; }
+        }
+        unsigned long long mz = 1ull;
+        while (ok) {
+            mz = lane < Hq ? __hip_atomic_load(row + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1ull;
+            if (__builtin_amdgcn_ballot_w64(mz == 0ull) == 0ull) break;
+            __builtin_amdgcn_s_sleep(1);
+            if (wall_clock64() - t_start > spin_ticks) ok = false;
+        }
+        if (ok && lane < Hq) softmax_merge(M, Z, __uint_as_float((uint32_t)mz), __uint_as_float((uint32_t)(mz >> 32)));
+    }
+    return ok;
+}
+
+// Called by every thread when the workgroup is done reading (after a __syncthreads): `last` says
+// whether this range was the sequence's last to finish reading; it then clears the sequence's words
+// and the count.
+__device__ __forceinline__ void resident_retire(bool last, unsigned long long *stats, int nranges, int Hq, uint32_t *left)
+{
+    if (last) {
+        for (int i = threadIdx.x; i < nranges * Hq; i += kResThreads)
+            __hip_atomic_store(&stats[i], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (threadIdx.x == 0) __hip_atomic_store(left, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
 }  // namespace fastocr

@@ -65,7 +65,6 @@ extern int g_tune_barrier_spin_us;
 // The last range to finish zeroes the sequence's words and its count, so a slot is clean again
 // when its call ends; calls take slots round-robin, so up to kResSlots calls may overlap on one
 // GPU.  The last word of g_res_left[slot] is a sticky "an exchange timed out" flag.
-constexpr int kResMaxWg = 256;
 __device__ unsigned long long g_res_stats[kResSlots][kResMaxWg * kResMaxHq];
 __device__ uint32_t g_res_left[kResSlots][kResMaxBatch + 1];
 
@@ -320,19 +319,9 @@ img_done:
         for (int r = 0; r < 4; ++r) { sm_m[wave][hbase + r] = m[r]; sm_z[wave][hbase + r] = z[r]; }
     }
     __syncthreads();
-    // The statistics cross compute units (and XCDs, each with its own L2) through agent-scope
-    // atomic stores and loads, which go through to memory, instead of plain stores bracketed by
-    // release/acquire fences: a fence writes back or invalidates the XCD's whole L2 and costs
-    // microseconds here.  Every word is its own "ready" flag, so nothing has to be ordered: a
-    // reader simply polls until the words it needs are non-zero.
+    // publish this range's statistics (resident.hpp: every word is its own "ready" flag)
     unsigned long long *stats = g_res_stats[sync_slot] + (int64_t)wg0 * Hq;
-    if ((int)threadIdx.x < Hq) {
-        const int h = threadIdx.x, g = h / G, x = h - g * G;
-        float M = kMinusHuge, Z = 0.f;
-        for (int sb = 0; sb < wpk; ++sb) softmax_merge(M, Z, sm_m[g + sb * Hkv][x], sm_z[g + sb * Hkv][x]);
-        const unsigned long long mz = (unsigned long long)__float_as_uint(M) | ((unsigned long long)__float_as_uint(Z) << 32);
-        __hip_atomic_store(&stats[(int64_t)rng * Hq + h], mz, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
+    resident_publish(stats + (int64_t)rng * Hq, sm_m, sm_z, Hq, G, Hkv, wpk);
     if (threadIdx.x == 0) sm_met = 1;
     // while the words travel: the parked logits become probabilities relative to the wave's own
     // maxima (m[r] is wave-wide after the merge above); the sequence-wide factor follows below
@@ -342,39 +331,10 @@ img_done:
 pre_done:
     __syncthreads();
 
-    // ---- every head's log-sum-exp from the ranges' statistics ------------------------------------
-    // wave w merges ranges w, w+8, ..; lane = head.  A range's first word is polled with one 8-byte
-    // load per round (256 workgroups polling every word would take a tenth of the HBM bandwidth
-    // from the ranges still streaming); once it is there the whole row is read and checked.
+    // ---- every head's log-sum-exp from the ranges' statistics: wave w merges ranges w, w+8, .. ------
     {
-        float M = kMinusHuge, Z = 0.f;
-        bool ok = true;
-        const long long t_start = wall_clock64();
-        for (int rr = wave; rr < nranges && ok; rr += kResWaves) {
-            unsigned long long mz = 1ull;
-            if (rr == rng) {
-                // the workgroup's own statistics never leave the chip
-                if (lane < Hq) {
-                    const int g = lane / G, x = lane - g * G;
-                    float Mo = kMinusHuge, Zo = 0.f;
-                    for (int sb = 0; sb < wpk; ++sb) softmax_merge(Mo, Zo, sm_m[g + sb * Hkv][x], sm_z[g + sb * Hkv][x]);
-                    softmax_merge(M, Z, Mo, Zo);
-                }
-                continue;
-            }
-            const unsigned long long *row = stats + (int64_t)rr * Hq;
-            while (__hip_atomic_load(row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0ull) {
-                __builtin_amdgcn_s_sleep(1);
-                if (wall_clock64() - t_start > spin_ticks) { ok = false; break; }
-            }
-            while (ok) {
-                mz = lane < Hq ? __hip_atomic_load(row + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1ull;
-                if (__builtin_amdgcn_ballot_w64(mz == 0ull) == 0ull) break;
-                __builtin_amdgcn_s_sleep(1);
-                if (wall_clock64() - t_start > spin_ticks) ok = false;
-            }
-            if (ok && lane < Hq) softmax_merge(M, Z, __uint_as_float((uint32_t)mz), __uint_as_float((uint32_t)(mz >> 32)));
-        }
+        float M, Z;
+        const bool ok = resident_gather(stats, rng, nranges, Hq, G, Hkv, wpk, sm_m, sm_z, spin_ticks, M, Z);
         if (!ok && lane == 0) {
             sm_met = 0;
             __hip_atomic_fetch_or(&g_res_left[sync_slot][kResMaxBatch], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -390,11 +350,7 @@ pre_done:
         sm_last = __hip_atomic_fetch_add(left, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)nranges - 1u;
     auto leave = [&]() {
         __syncthreads();
-        if (sm_last) {
-            for (int i = threadIdx.x; i < nranges * Hq; i += kResThreads)
-                __hip_atomic_store(&stats[i], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (threadIdx.x == 0) __hip_atomic_store(left, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+        resident_retire(sm_last != 0, stats, nranges, Hq, left);
     };
     if (!sm_met) {
         // a range of the sequence never published (the grid was not resident as a whole): poison
