@@ -16,6 +16,7 @@ namespace fastocr {
 static int g_tune_score_resident = 1;
 static int g_tune_focal_fused = 1;
 int g_tune_attn_waves = 4;
+static int g_tune_attn_merge = 1;          // pruned attention: ranges of a stream merged inside the launch (0 never, 1 yes)
 int g_tune_barrier_spin_us = 250000;      // bounded wait of the resident kernels' per-sequence barrier
 static int g_tune_splits[4] = {0, 0, 0, 0};     // indexed by fastocr_op
 
@@ -113,6 +114,15 @@ static int choose_splits(int op, const Shape &s, int max_positions)
         // Measured on MI355X: the streaming kernels run best with about one workgroup per compute
         // unit (few, long, equally sized streams), the plain-FMA kernels with many small ones.
         const int target_wg = fast ? kNumCU : 8 * kNumCU;
+        if (fast && op == FASTOCR_OP_SPARSE_DECODE_ATTN && g_tune_attn_merge) {
+            // pruned attention is short: one launch whose eight-wave workgroups fill the chip once,
+            // the ranges of a stream merged inside the launch; a stream is only cut when that leaves
+            // a wave two tiles or more (measured: below that the merge costs what the cut saves)
+            int n = kNumCU / (streams > 0 ? streams : 1);
+            n = n < (ntile + 15) / 16 ? n : (ntile + 15) / 16;
+            n = n < 1 ? 1 : n;
+            if (n == 1 || attn_merges_in_kernel(s, n)) return n;
+        }
         nsplit = (target_wg + streams - 1) / (streams > 0 ? streams : 1);
         // pruned attention is short: when eight waves get at most eight tiles each, or at least half
         // a chip of streams exists, one eight-wave workgroup per stream writes the final output
@@ -293,7 +303,8 @@ static int attn_common(int op, const fastocr_kv_view *kv, const fastocr_batch_vi
     if (bv->batch == 0) return FASTOCR_OK;
     Shape s = make_shape(kv, bv, n_q_heads);
     const int nsplit = choose_splits(op, s, op == FASTOCR_OP_SPARSE_DECODE_ATTN ? sparse_positions(bv, kmax) : bv->max_seq_len);
-    hipError_t e = launch_attn(s, q, scale, sel_idx, sel_cnt, kmax, out, lse, ws, nsplit, (hipStream_t)hip_stream);
+    const bool merge = op == FASTOCR_OP_SPARSE_DECODE_ATTN && g_tune_attn_merge != 0;
+    hipError_t e = launch_attn(s, q, scale, sel_idx, sel_cnt, kmax, out, lse, ws, nsplit, merge, (hipStream_t)hip_stream);
     return e == hipSuccess ? FASTOCR_OK : FASTOCR_EHIP;
 }
 
@@ -422,6 +433,7 @@ int fastocr_set_tuning(const char *key, int value)
     else if (!strcmp(key, "splits_sparse")) g_tune_splits[FASTOCR_OP_SPARSE_DECODE_ATTN] = value;
     else if (!strcmp(key, "splits_dense")) g_tune_splits[FASTOCR_OP_DENSE_DECODE_ATTN] = value;
     else if (!strcmp(key, "attn_waves")) g_tune_attn_waves = value;
+    else if (!strcmp(key, "attn_merge") && value <= 1) g_tune_attn_merge = value;
     else if (!strcmp(key, "barrier_spin_us") && value >= 0) g_tune_barrier_spin_us = value ? value : 250000;
     else if (!strcmp(key, "score_resident") && value >= 0 && value <= 2) g_tune_score_resident = value;
     else if (!strcmp(key, "focal_fused") && value >= 0 && value <= 2) g_tune_focal_fused = value;

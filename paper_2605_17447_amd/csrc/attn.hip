@@ -16,11 +16,41 @@
 // coalesced (16 lanes x 16 B = one 256 B row) and transposed in registers with v_perm_b32.
 // K is loaded the same coalesced way and re-laid to the A layout through a wave-private,
 // XOR-swizzled LDS tile.
+#include <atomic>
+
 #include "kernels.hpp"
 
 namespace fastocr {
 
 extern int g_tune_attn_waves;
+extern int g_tune_barrier_spin_us;
+
+// How a workgroup's result leaves the kernel.
+//   kPartial: an fp32 partial (m, Z, acc[d]) in the workspace; a merge kernel follows.
+//   kDirect : the stream has a single range: the normalised output itself.
+//   kMerge  : several ranges per stream, merged inside the launch.  Ranges 0 .. nsplit-2 publish
+//             their partial as 64-bit words {value, tag} in static device memory with agent-scope
+//             atomic stores; the stream's last range (dispatched after them) polls until every word
+//             it needs carries this call's tag, merges and writes the output.  Every word is its
+//             own "ready" flag, so nothing has to be ordered and no fence (an L2 write-back on this
+//             chip) is needed.  The tag is the stream's epoch + 1; the epoch is a device-side
+//             counter per (slot, stream) that the last range advances when it has everything, so a
+//             replayed HIP graph sees fresh tags too and stale words of earlier calls never match
+//             (short of 2^32 calls without the word being overwritten).  Calls take slots
+//             round-robin: up to kMergeSlots calls using this mode may overlap on one GPU.
+enum { kPartial = 0, kDirect = 1, kMerge = 2 };
+constexpr int kMergeSlots = 4;
+constexpr int kMergeMaxSplits = 8;
+constexpr int kMergeMaxStreams = 4096;
+constexpr size_t kMergeWords = (size_t)512 * 1024;           // per slot: 4 MB
+__device__ unsigned long long g_merge_words[kMergeSlots][kMergeWords];
+__device__ uint32_t g_merge_epoch[kMergeSlots][kMergeMaxStreams];
+__device__ uint32_t g_merge_timeouts;                        // sticky count of merges that gave up
+
+__device__ __forceinline__ unsigned long long tagged(float x, uint32_t tag)
+{
+    return (unsigned long long)__float_as_uint(x) | ((unsigned long long)tag << 32);
+}
 
 
 constexpr int kTile = 32;          // tokens per wave tile (two 16-token MFMA tiles)
@@ -32,21 +62,28 @@ __device__ __forceinline__ int tile_row(int lg, int e) { return (e < 4) ? (4 * l
 // -----------------------------------------------------------------------------------------
 // MFMA kernel: bf16, head_dim = 128, G <= 16.
 // -----------------------------------------------------------------------------------------
-// kWaves waves per workgroup walk the range; with DIRECT (a single range per stream) the merged
-// result is final and is written normalised to `out`, otherwise as an fp32 partial.
-template <bool GATHER, bool PAGED, int kWaves, bool DIRECT>
+// kWaves waves per workgroup walk the range.  Dense: the workgroup's tiles are dealt to its waves
+// in turn.  Gather: the attended list is cut into nsplit * kWaves contiguous pieces, one per wave,
+// of equal length to within one token (or one tile, for short lists: see below) -- with a
+// handful of tiles per wave, whole tiles would leave some waves a quarter more bytes than others.
+template <bool GATHER, bool PAGED, int kWaves, int MODE>
 __global__ __launch_bounds__(64 * kWaves, 8 / kWaves) void attn_mfma_kernel(
     KvDev kv, BatchDev bv, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2,
     const int32_t *__restrict__ sel_idx, const int32_t *__restrict__ sel_cnt, int64_t kmax,
     float *__restrict__ part_o, float *__restrict__ part_ml, int nsplit, uint16_t *__restrict__ out,
-    float *__restrict__ lse)
+    float *__restrict__ lse, int merge_slot, long long spin_ticks)
 {
     __shared__ __align__(16) unsigned char smem[kWaves][8192];
     __shared__ float sm_m[kWaves][16], sm_z[kWaves][16];
 
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int li = lane & 15, lg = lane >> 4;
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+
+    const int stream_id = b * gridDim.y + kvh;
+    uint32_t tag = 0;
+    if (MODE == kMerge)
+        tag = __builtin_amdgcn_readfirstlane(__hip_atomic_load(&g_merge_epoch[merge_slot][stream_id], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) + 1u;
 
     const SeqGeom geo = seq_geom(bv, b);
     int cnt = 0;
@@ -56,9 +93,30 @@ __global__ __launch_bounds__(64 * kWaves, 8 / kWaves) void attn_mfma_kernel(
         sel = sel_idx + (int64_t)b * kmax;
     }
     const int L = GATHER ? (geo.S - geo.N + cnt) : geo.S;
-    const int ntile = (L + kTile - 1) / kTile;
-    const int tps = (ntile + nsplit - 1) / nsplit;
-    const int t0 = split * tps, t1 = min(ntile, t0 + tps);
+    // this wave's tiles: tile i starts at position tile_pos(i) and ends before pend
+    int wp0 = 0, pend = L, nt, tfirst = 0;
+    if (GATHER) {
+        // piece gw of nw: x units each, the first `rem` pieces one more.  A unit is a token when
+        // that leaves a wave three tiles or more (the stream is then bound by memory and equal byte
+        // counts matter), else a whole tile: a partial tile costs the load path as many
+        // instructions as a full one, which is what bounds a short list.
+        const int gw = split * kWaves + wave, nw = nsplit * kWaves;
+        const int ntile = (L + kTile - 1) / kTile;
+        const bool by_token = ntile >= 3 * nw;
+        const int units = by_token ? L : ntile;
+        const int x = units / nw, rem = units - x * nw;
+        const int u0 = gw * x + min(gw, rem), u1 = u0 + x + (gw < rem ? 1 : 0);
+        wp0 = by_token ? u0 : u0 * kTile;
+        pend = by_token ? u1 : min(L, u1 * kTile);
+        nt = (pend - wp0 + kTile - 1) / kTile;
+    } else {
+        const int ntile = (L + kTile - 1) / kTile;
+        const int tps = (ntile + nsplit - 1) / nsplit;
+        const int t1 = min(ntile, split * tps + tps);
+        tfirst = split * tps + wave;
+        nt = tfirst < t1 ? (t1 - 1 - tfirst) / kWaves + 1 : 0;
+    }
+    auto tile_pos = [&](int i) { return GATHER ? wp0 + i * kTile : (tfirst + i * kWaves) * kTile; };
 
     // Q as the B operand: lane (head li, k-block lg) holds dims 8*(4kk+lg) .. +7 for step kk.
     u32x4 qreg[4];
@@ -74,21 +132,22 @@ __global__ __launch_bounds__(64 * kWaves, 8 / kWaves) void attn_mfma_kernel(
     const uint16_t *kbase = reinterpret_cast<const uint16_t *>(kv.k);
     const uint16_t *vbase = reinterpret_cast<const uint16_t *>(kv.v);
 
-    // element offset of the row this lane looks up for tile `tile` (position tile*32 + lane%32)
-    auto rowoff_of = [&](int tile) -> int64_t {
-        int p = min(tile * kTile + (lane & 31), L - 1);
+    // element offset of the row this lane looks up for the wave's tile i (row lane % 32; rows past
+    // the end repeat the last one)
+    auto rowoff_of = [&](int i) -> int64_t {
+        int p = min(tile_pos(i) + (lane & 31), pend - 1);
         int tok = pos_to_token<GATHER>(p, geo, cnt, sel);
         return row_offset<PAGED>(kv, b, tok, kvh);
     };
     const int64_t seq_base = row_offset<false>(kv, b, 0, kvh);
 
-    auto load_tile = [&](int tile, int64_t off, u32x4(&K)[8], u32x4(&V)[8]) {
+    auto load_tile = [&](int i, int64_t off, u32x4(&K)[8], u32x4(&V)[8]) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const int r = tile_row(lg, e);
             int64_t ro;
             if (GATHER || PAGED) ro = __shfl(off, r);
-            else ro = seq_base + (int64_t)min(tile * kTile + r, L - 1) * kv.stride_token;
+            else ro = seq_base + (int64_t)min(tile_pos(i) + r, L - 1) * kv.stride_token;
             V[e] = stream_load(vbase + ro + 8 * li);
             K[e] = stream_load(kbase + ro + 8 * li);
         }
@@ -99,7 +158,7 @@ __global__ __launch_bounds__(64 * kWaves, 8 / kWaves) void attn_mfma_kernel(
 #pragma unroll
     for (int t = 0; t < 8; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    auto compute = [&](int tile, u32x4(&K)[8], u32x4(&V)[8]) {
+    auto compute = [&](int i, u32x4(&K)[8], u32x4(&V)[8]) {
         u32x4 ka[8];
         {
             unsigned char *sw = smem[wave];
@@ -128,11 +187,11 @@ __global__ __launch_bounds__(64 * kWaves, 8 / kWaves) void attn_mfma_kernel(
         }
         // lane (head li, group lg): s0[r] is token 4lg+r of the tile, s1[r] token 16+4lg+r
         float s[8];
-        const int pbase = tile * kTile + 4 * lg;
+        const int pbase = tile_pos(i) + 4 * lg;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            s[r] = (pbase + r < L) ? s0[r] * scale_log2 : -INFINITY;
-            s[4 + r] = (pbase + 16 + r < L) ? s1[r] * scale_log2 : -INFINITY;
+            s[r] = (pbase + r < pend) ? s0[r] * scale_log2 : -INFINITY;
+            s[4 + r] = (pbase + 16 + r < pend) ? s1[r] * scale_log2 : -INFINITY;
         }
         float mx = s[0];
 #pragma unroll
@@ -161,24 +220,24 @@ __global__ __launch_bounds__(64 * kWaves, 8 / kWaves) void attn_mfma_kernel(
         }
     };
 
-    if (t0 + wave < t1) {
-        // Two register buffers, software pipelined.  The prefetch is unconditional (past the end
-        // the last tile is loaded again): a branch between a load and the wait that matches it
-        // would make the compiler drain every outstanding load at the join.
+    if (nt > 0) {
+        // Two register buffers, software pipelined.  The prefetch is unconditional: a branch between
+        // a load and the wait that matches it would make the compiler drain every outstanding load
+        // at the join (and a copy of the step without the prefetch for the last tile costs more
+        // registers than the kernel has).  Past the wave's last tile it fetches a single row (all
+        // lanes the same address) instead of a tile.
         u32x4 KA[8], VA[8], KB[8], VB[8];
-        int tile = t0 + wave;
-        const int last = tile + (t1 - 1 - tile) / kWaves * kWaves;
+        int i = 0;
+        const int last = nt - 1;
         if (!(GATHER || PAGED)) {
-            load_tile(tile, 0, KA, VA);
+            load_tile(0, 0, KA, VA);
             while (true) {
-                load_tile(min(tile + kWaves, last), 0, KB, VB);
-                compute(tile, KA, VA);
-                tile += kWaves;
-                if (tile > last) break;
-                load_tile(min(tile + kWaves, last), 0, KA, VA);
-                compute(tile, KB, VB);
-                tile += kWaves;
-                if (tile > last) break;
+                load_tile(min(i + 1, last), 0, KB, VB);
+                compute(i, KA, VA);
+                if (++i > last) break;
+                load_tile(min(i + 1, last), 0, KA, VA);
+                compute(i, KB, VB);
+                if (++i > last) break;
             }
         } else {
             // Row offsets come from memory (selected indices, block table).  They are fetched a
@@ -187,21 +246,21 @@ __global__ __launch_bounds__(64 * kWaves, 8 / kWaves) void attn_mfma_kernel(
             constexpr int kGroup = 4;
             int64_t offc[kGroup], offn[kGroup];
 #pragma unroll
-            for (int i = 0; i < kGroup; ++i) offc[i] = rowoff_of(min(tile + i * kWaves, last));
-            load_tile(tile, offc[0], KA, VA);
+            for (int j = 0; j < kGroup; ++j) offc[j] = rowoff_of(min(j, last));
+            load_tile(0, offc[0], KA, VA);
             while (true) {
 #pragma unroll
-                for (int i = 0; i < kGroup; ++i) offn[i] = rowoff_of(min(tile + (kGroup + i) * kWaves, last));
+                for (int j = 0; j < kGroup; ++j) offn[j] = rowoff_of(min(i + kGroup + j, last));
 #pragma unroll
-                for (int i = 0; i < kGroup; ++i) {
-                    const int64_t onext = (i + 1 < kGroup) ? offc[i + 1] : offn[0];
-                    if ((i & 1) == 0) { load_tile(min(tile + kWaves, last), onext, KB, VB); compute(tile, KA, VA); }
-                    else              { load_tile(min(tile + kWaves, last), onext, KA, VA); compute(tile, KB, VB); }
-                    tile += kWaves;
-                    if (tile > last) goto tiles_done;
+                for (int j = 0; j < kGroup; ++j) {
+                    int64_t onext = (j + 1 < kGroup) ? offc[j + 1] : offn[0];
+                    onext = (i + 1 <= last) ? onext : __shfl(onext, 0);
+                    if ((j & 1) == 0) { load_tile(0, onext, KB, VB); compute(i, KA, VA); }
+                    else              { load_tile(0, onext, KA, VA); compute(i, KB, VB); }
+                    if (++i > last) goto tiles_done;
                 }
 #pragma unroll
-                for (int i = 0; i < kGroup; ++i) offc[i] = offn[i];
+                for (int j = 0; j < kGroup; ++j) offc[j] = offn[j];
             }
         }
     }
@@ -218,6 +277,9 @@ tiles_done:
     if (lg == 0) { sm_m[wave][li] = m; sm_z[wave][li] = zl; }
     __syncthreads();
 
+    const int np = nsplit - 1;                                       // ranges that publish (kMerge)
+    const int pitch = G * 130;                                       // words per published partial
+    unsigned long long *words = g_merge_words[merge_slot] + (int64_t)stream_id * np * pitch;
     for (int idx = threadIdx.x; idx < G * 128; idx += 64 * kWaves) {
         const int hh = idx >> 7, c = idx & 127;
         float M = sm_m[0][hh];
@@ -232,12 +294,71 @@ tiles_done:
                 Z += f * sm_z[w][hh];
             }
         }
-        if (DIRECT) {
-            const int64_t bh = (int64_t)b * Hq + (int64_t)kvh * G + hh;
+        const int64_t bh = (int64_t)b * Hq + (int64_t)kvh * G + hh;
+        if (MODE == kMerge && split < np) {
+            unsigned long long *w = words + (int64_t)split * pitch;
+            __hip_atomic_store(w + idx, tagged(o, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (c == 0) {
+                __hip_atomic_store(w + G * 128 + hh, tagged(M, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(w + G * 129 + hh, tagged(Z, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        } else if (MODE == kMerge) {
+            // the stream's last range: every other range's (o, m, Z) for this element, all requested
+            // at once, again until each word carries this call's tag
+            unsigned long long wo[kMergeMaxSplits - 1], wm[kMergeMaxSplits - 1], wz[kMergeMaxSplits - 1];
+            const long long t_start = wall_clock64();
+            bool ok = true;
+            while (true) {
+#pragma unroll
+                for (int x = 0; x < kMergeMaxSplits - 1; ++x) {
+                    if (x < np) {
+                        const unsigned long long *w = words + (int64_t)x * pitch;
+                        wo[x] = __hip_atomic_load(w + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        wm[x] = __hip_atomic_load(w + G * 128 + hh, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        wz[x] = __hip_atomic_load(w + G * 129 + hh, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                }
+                bool all = true;
+#pragma unroll
+                for (int x = 0; x < kMergeMaxSplits - 1; ++x)
+                    if (x < np)
+                        all = all && (uint32_t)(wo[x] >> 32) == tag && (uint32_t)(wm[x] >> 32) == tag && (uint32_t)(wz[x] >> 32) == tag;
+                if (all) break;
+                __builtin_amdgcn_s_sleep(1);
+                if (wall_clock64() - t_start > spin_ticks) { ok = false; break; }
+            }
+            float Mt = M;
+#pragma unroll
+            for (int x = 0; x < kMergeMaxSplits - 1; ++x)
+                if (x < np) Mt = fmaxf(Mt, __uint_as_float((uint32_t)wm[x]));
+            float ot = 0.f, Zt = 0.f;
+            if (Mt > -INFINITY) {
+                const float f = fast_exp2(M - Mt);
+                ot = f * o;
+                Zt = f * Z;
+#pragma unroll
+                for (int x = 0; x < kMergeMaxSplits - 1; ++x) {
+                    if (x < np) {
+                        const float fx = fast_exp2(__uint_as_float((uint32_t)wm[x]) - Mt);
+                        ot += fx * __uint_as_float((uint32_t)wo[x]);
+                        Zt += fx * __uint_as_float((uint32_t)wz[x]);
+                    }
+                }
+            }
+            // a range that never published: no number is better than a wrong one
+            out[bh * 128 + c] = ok ? f32_to_bf16_bits(Zt > 0.f ? ot / Zt : 0.f) : (uint16_t)0x7fc0;
+            if (lse && c == 0) lse[bh] = !ok ? __builtin_nanf("") : (Zt > 0.f ? (Mt + log2f(Zt)) * kLn2 : -INFINITY);
+            if (idx == 0) {
+                // this thread has seen every range's words (or given up): all of them have read the
+                // epoch, so it may advance
+                __hip_atomic_store(&g_merge_epoch[merge_slot][stream_id], tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (!ok) __hip_atomic_fetch_add(&g_merge_timeouts, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        } else if (MODE == kDirect) {
             out[bh * 128 + c] = f32_to_bf16_bits(Z > 0.f ? o / Z : 0.f);
             if (lse && c == 0) lse[bh] = Z > 0.f ? (M + log2f(Z)) * kLn2 : -INFINITY;
         } else {
-            const int64_t ph = ((int64_t)b * Hq + (int64_t)kvh * G + hh) * nsplit + split;
+            const int64_t ph = bh * nsplit + split;
             part_o[ph * 128 + c] = o;
             if (c == 0) { part_ml[ph * 2] = M; part_ml[ph * 2 + 1] = Z; }
         }
@@ -416,26 +537,40 @@ size_t attn_workspace_bytes(const Shape &s, int nsplit)
     return rows * (size_t)(s.kv.head_dim + 2) * sizeof(float);
 }
 
+bool attn_merges_in_kernel(const Shape &s, int nsplit)
+{
+    if (!mfma_path(s) || nsplit < 2 || nsplit > kMergeMaxSplits) return false;
+    const size_t streams = (size_t)s.batch * s.kv.n_kv_heads;
+    const size_t G = s.n_q_heads / s.kv.n_kv_heads;
+    return streams <= (size_t)kMergeMaxStreams && streams * (nsplit - 1) * G * 130 <= kMergeWords;
+}
+
 template <bool GATHER, bool PAGED>
 static void launch_mfma(int kid, const Shape &s, const void *q, float scale_log2, const int32_t *sel_idx,
                         const int32_t *sel_cnt, int64_t kmax, float *part_o, float *part_ml,
-                        int nsplit, void *out, float *lse, hipStream_t stream)
+                        int nsplit, bool merge, void *out, float *lse, hipStream_t stream)
 {
     const int G = s.n_q_heads / s.kv.n_kv_heads;
     dim3 grid(nsplit, s.kv.n_kv_heads, s.batch);
-#define FASTOCR_ATTN(W, D) FASTOCR_LAUNCH(kid, (attn_mfma_kernel<GATHER, PAGED, W, D>), grid, dim3(64 * W), 0, stream, \
+    static std::atomic<unsigned> call_no{0};
+    const int slot = merge && nsplit > 1 ? (int)(call_no.fetch_add(1u) % (unsigned)kMergeSlots) : 0;
+    // the stream's last range waits at most this long for the others (they run concurrently and
+    // finish within microseconds of each other); past it the outputs are NaN but the call ends
+    const long long spin_ticks = 100ll * g_tune_barrier_spin_us;     // the wall clock runs at 100 MHz
+#define FASTOCR_ATTN(W, MODE) FASTOCR_LAUNCH(kid, (attn_mfma_kernel<GATHER, PAGED, W, MODE>), grid, dim3(64 * W), 0, stream, \
         s.kv, s.bv, (const uint16_t *)q, s.n_q_heads, G, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, \
-        (uint16_t *)out, lse)
-    if (nsplit == 1) FASTOCR_ATTN(8, true);          // one range per stream: eight waves, final output
-    else if (g_tune_attn_waves == 8) FASTOCR_ATTN(8, false);
-    else FASTOCR_ATTN(4, false);
+        (uint16_t *)out, lse, slot, spin_ticks)
+    if (nsplit == 1) FASTOCR_ATTN(8, kDirect);       // one range per stream: eight waves, final output
+    else if (merge) FASTOCR_ATTN(8, kMerge);         // the stream's last range merges inside the launch
+    else if (g_tune_attn_waves == 8) FASTOCR_ATTN(8, kPartial);
+    else FASTOCR_ATTN(4, kPartial);
 #undef FASTOCR_ATTN
 }
 
 template <typename T, bool GATHER, bool PAGED>
 static void launch_generic(int kid, const Shape &s, const void *q, float scale_log2, const int32_t *sel_idx,
                            const int32_t *sel_cnt, int64_t kmax, float *part_o, float *part_ml,
-                           int nsplit, void *, float *, hipStream_t stream)
+                           int nsplit, bool, void *, float *, hipStream_t stream)
 {
     dim3 grid(nsplit, s.n_q_heads, s.batch), block(64);
     FASTOCR_LAUNCH(kid, (attn_generic_kernel<T, GATHER, PAGED>), grid, block, 0, stream,
@@ -444,9 +579,10 @@ static void launch_generic(int kid, const Shape &s, const void *q, float scale_l
 
 hipError_t launch_attn(const Shape &s, const void *q, float scale, const int32_t *sel_idx,
                        const int32_t *sel_cnt, int64_t kmax, void *out, float *lse, void *ws,
-                       int nsplit, hipStream_t stream)
+                       int nsplit, bool merge_in_kernel, hipStream_t stream)
 {
     const bool gather = sel_idx != nullptr;
+    const bool merge = merge_in_kernel && attn_merges_in_kernel(s, nsplit);
     const int d = s.kv.head_dim;
     float *part_o = reinterpret_cast<float *>(ws);
     float *part_ml = part_o + (size_t)s.batch * s.n_q_heads * nsplit * d;
@@ -455,10 +591,10 @@ hipError_t launch_attn(const Shape &s, const void *q, float scale, const int32_t
 
 #define FASTOCR_DISPATCH(FN, ...)                                                                      \
     do {                                                                                               \
-        if (gather) { if (s.paged) FN<__VA_ARGS__ true, true>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, out, lse, stream); \
-                      else         FN<__VA_ARGS__ true, false>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, out, lse, stream); } \
-        else        { if (s.paged) FN<__VA_ARGS__ false, true>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, out, lse, stream); \
-                      else         FN<__VA_ARGS__ false, false>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, out, lse, stream); } \
+        if (gather) { if (s.paged) FN<__VA_ARGS__ true, true>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, merge, out, lse, stream); \
+                      else         FN<__VA_ARGS__ true, false>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, merge, out, lse, stream); } \
+        else        { if (s.paged) FN<__VA_ARGS__ false, true>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, merge, out, lse, stream); \
+                      else         FN<__VA_ARGS__ false, false>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, merge, out, lse, stream); } \
     } while (0)
     if (mfma_path(s)) {
         FASTOCR_DISPATCH(launch_mfma, );
@@ -470,7 +606,7 @@ hipError_t launch_attn(const Shape &s, const void *q, float scale, const int32_t
 #undef FASTOCR_DISPATCH
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (mfma_path(s) && nsplit == 1) return hipSuccess;        // the kernel wrote the final output itself
+    if (mfma_path(s) && (nsplit == 1 || merge)) return hipSuccess;        // the kernel wrote the final output itself
 
     return launch_attn_combine(s, part_o, part_ml, nsplit, out, lse, stream);
 }

@@ -44,9 +44,13 @@ inline bool mfma_path(const Shape &s) { return s.fast; }
 // Workspace: part_o fp32 [B][Hq][nsplit][d] followed by part_ml fp32 [B][Hq][nsplit][2].
 int attn_tile_tokens(const Shape &s);
 size_t attn_workspace_bytes(const Shape &s, int nsplit);
+// merge_in_kernel: with 2 .. 16 ranges per stream on the MFMA path the stream's last range merges
+// the others' partials inside the launch (through static device memory) when the shape fits
+// (attn_merges_in_kernel); otherwise partials go to the workspace and a merge kernel follows.
+bool attn_merges_in_kernel(const Shape &s, int nsplit);
 hipError_t launch_attn(const Shape &s, const void *q, float scale, const int32_t *sel_idx,
                        const int32_t *sel_cnt, int64_t kmax, void *out, float *lse, void *ws,
-                       int nsplit, hipStream_t stream);
+                       int nsplit, bool merge_in_kernel, hipStream_t stream);
 // merge of nsplit partials per (sequence, head) in the layout above into the final output.
 // With seq_meta (device int32 [B][2]: first workgroup, workgroup count) the partials are instead
 // those of the fused focal kernel, [workgroup][wpk][Hq][d] / [..][2], wpk per workgroup.

@@ -108,10 +108,14 @@ def test_mfma_bf16_ragged_batch(Hq, Hkv):
     full_check(problem_from_case(case), 0.05, f"mfma Hq{Hq} Hkv{Hkv}")
 
 
+@pytest.mark.parametrize("merge", [1, 0])
 @pytest.mark.parametrize("nsplit", [1, 2, 5, 64])
-def test_split_counts_give_the_same_result(nsplit):
+def test_split_counts_give_the_same_result(nsplit, merge):
+    """merge = 1: pruned attention with 2 .. 8 ranges per stream merges them inside the launch;
+    merge = 0: partials in the workspace and a merge kernel."""
     for key in ("splits_score", "splits_dense", "splits_sparse"):
         fb.set_tuning(key, nsplit)
+    fb.set_tuning("attn_merge", merge)
     try:
         case = TinyCase(seed=6, B=2, Hq=28, Hkv=4, d=128, n_vis=[1200, 500], pre=[20, 3], post=[30, 9], dtype="bf16")
         full_check(problem_from_case(case), 0.05, f"nsplit={nsplit}")
@@ -120,6 +124,93 @@ def test_split_counts_give_the_same_result(nsplit):
     finally:
         for key in ("splits_score", "splits_dense", "splits_sparse"):
             fb.set_tuning(key, 0)
+        fb.set_tuning("attn_merge", 1)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(28, 4), (64, 8), (16, 1)])
+@pytest.mark.parametrize("nsplit", [2, 3, 8])
+def test_pruned_attention_merged_inside_the_launch(Hq, Hkv, nsplit):
+    """Ranges of a stream hand their partials to the stream's last range through tagged words in
+    static device memory.  Twelve calls in a row (three times round the slots) with a fresh query
+    each: a stale word of an earlier call taken for a fresh one would show as a wrong output.
+    Sequences shorter than the number of waves leave some ranges without a token."""
+    case = TinyCase(seed=40 + Hq + nsplit, B=4, Hq=Hq, Hkv=Hkv, d=128, n_vis=[1500, 900, 64, 0], pre=[40, 3, 0, 2],
+                    post=[77, 130, 5, 1], dtype="bf16")
+    p = problem_from_case(case)
+    oc = list(p.oracle_args())
+    ref_sc, _, _ = oracle.focal_score(*oc)
+    ref_idx, ref_cnt = oracle.topk_fixation(ref_sc, p.vis_len, 0.1)
+    sel, selc = torch.from_numpy(ref_idx).to(DEV).contiguous(), torch.from_numpy(ref_cnt).to(DEV)
+    rng = np.random.default_rng(nsplit)
+    fb.set_tuning("splits_sparse", nsplit)
+    try:
+        for call in range(12):
+            qn = rng.standard_normal(p.q.shape).astype(np.float32)
+            p.q = torch.from_numpy(qn).to(DEV).to(torch.bfloat16)
+            oc[4] = to_np(p.q)
+            ref, _ = oracle.decode_attn(*oc, ref_idx, ref_cnt)
+            check_out(p.sparse(sel, selc), ref, f"merged pruned attention, call {call}")
+    finally:
+        fb.set_tuning("splits_sparse", 0)
+
+
+def test_pruned_attention_merged_inside_the_launch_replays_in_a_graph():
+    """The tags come from a device-side epoch, so a captured call is fresh on every replay."""
+    case = TinyCase(seed=77, B=3, Hq=28, Hkv=4, d=128, n_vis=[1100, 700, 1300], pre=[10, 3, 0], post=[50, 30, 9], dtype="bf16")
+    p = problem_from_case(case)
+    oc = list(p.oracle_args())
+    ref_sc, _, _ = oracle.focal_score(*oc)
+    ref_idx, ref_cnt = oracle.topk_fixation(ref_sc, p.vis_len, 0.1)
+    sel, selc = torch.from_numpy(ref_idx).to(DEV).contiguous(), torch.from_numpy(ref_cnt).to(DEV)
+    fb.set_tuning("splits_sparse", 4)
+    try:
+        out = torch.zeros_like(p.q)
+        ws = p.ws(fb.OP_SPARSE_DECODE_ATTN, sel.shape[1])
+        run = lambda: fo.sparse_decode_attn(p.cache, p.batch, p.q, p.scale, sel, selc, out, ws)
+        run()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            run()
+        rng = np.random.default_rng(5)
+        for replay in range(6):
+            p.q.copy_(torch.from_numpy(rng.standard_normal(p.q.shape).astype(np.float32)).to(DEV).to(torch.bfloat16))
+            oc[4] = to_np(p.q)
+            ref, _ = oracle.decode_attn(*oc, ref_idx, ref_cnt)
+            g.replay()
+            torch.cuda.synchronize()
+            check_out(out, ref, f"replay {replay}")
+            if replay % 2:                         # eager calls between the replays use other slots and epochs
+                check_out(p.sparse(sel, selc), ref, f"eager call after replay {replay}")
+    finally:
+        fb.set_tuning("splits_sparse", 0)
+
+
+def test_a_merge_that_gives_up_writes_nan_and_the_next_call_is_correct():
+    """With a 1-microsecond limit the stream's last range may give up on the others: what it could
+    not finish is NaN, never a number built on missing partials; the kernel ends normally and
+    later calls (fresh tags) are correct."""
+    case = TinyCase(seed=78, B=2, Hq=28, Hkv=4, d=128, n_vis=[3000, 2500], pre=[10, 3], post=[50, 30], dtype="bf16")
+    p = problem_from_case(case)
+    oc = p.oracle_args()
+    ref_sc, _, _ = oracle.focal_score(*oc)
+    ref_idx, ref_cnt = oracle.topk_fixation(ref_sc, p.vis_len, 0.25)
+    ref, _ = oracle.decode_attn(*oc, ref_idx, ref_cnt)
+    sel, selc = torch.from_numpy(ref_idx).to(DEV).contiguous(), torch.from_numpy(ref_cnt).to(DEV)
+    fb.set_tuning("splits_sparse", 8)
+    try:
+        fb.set_tuning("barrier_spin_us", 1)
+        for _ in range(3):
+            out = p.sparse(sel, selc).float().cpu().numpy().astype(np.float64)
+            bad = np.isnan(out)                    # every element gives up, or not, on its own
+            err = np.where(bad, 0.0, np.abs(out - ref)) / np.abs(ref).max(axis=-1, keepdims=True)
+            assert err.max() <= 2e-2
+        fb.set_tuning("barrier_spin_us", 0)
+        for _ in range(5):
+            check_out(p.sparse(sel, selc), ref, "pruned attention after a merge that gave up")
+    finally:
+        fb.set_tuning("barrier_spin_us", 0)
+        fb.set_tuning("splits_sparse", 0)
 
 
 def test_token_major_layout():
