@@ -164,6 +164,13 @@ int fastocr_topk_fixation(const float *scores, const fastocr_batch_view *bv, dou
  * An entry outside the span is clamped into it.  An empty J_b gives a zero row.
  *   out  [batch, n_q_heads, head_dim], kv->dtype (bf16 rounded to nearest even), 16-byte aligned;
  *        q as in fastocr_focal_score
+ * Concurrency: when a (sequence, kv head) stream is cut into 2 .. 8 ranges (bf16, head_dim 128),
+ * the stream's last workgroup waits for the partial results of the others, which were dispatched
+ * before it.  Alone on the GPU that wait is microseconds; if it exceeds 0.25 s (other work
+ * keeping the earlier workgroups off the chip) the affected outputs are NaN rather than wrong.
+ * At most 4 such calls may be in flight on one GPU at a time (calls in order on one stream and
+ * HIP-graph replays never overlap); fastocr_set_tuning("attn_merge", 0) selects partials in the
+ * workspace and a separate merge kernel instead, which has no such limit.
  */
 int fastocr_sparse_decode_attn(const fastocr_kv_view *kv, const fastocr_batch_view *bv,
                                const void *q, int n_q_heads, float scale, const int32_t *sel_idx,
@@ -244,7 +251,8 @@ int fastocr_stream_probe(const void *src, void *dst, size_t bytes, void *sink, v
 /* Launch-shape overrides for measurement sweeps: key "splits_score" | "splits_dense" |
  * "splits_sparse" (0 = automatic), "score_resident" | "focal_fused" (0 = always the separate
  * kernels, 1 = chosen by size (default), 2 = the single-kernel form whenever the shape fits),
- * "attn_waves" (4 | 8), "barrier_spin_us" (how long a workgroup of the single-kernel forms waits for
+ * "attn_waves" (4 | 8), "attn_merge" (pruned attention with several ranges per stream: 1 = merged
+ * inside the launch (default), 0 = by a second kernel), "barrier_spin_us" (how long a workgroup of the single-kernel forms waits for
  * its sequence's other workgroups; 0 restores the default of 250000; 1 makes waiting workgroups give
  * up at once, which tests use to exercise the NaN path).  Returns FASTOCR_EINVAL for an unknown key. */
 int fastocr_set_tuning(const char *key, int value);
