@@ -186,11 +186,13 @@ __device__ __forceinline__ void resident_publish(unsigned long long *row, const 
     }
 }
 
-// Called by every wave: wave w merges ranges w, w+8, .. of the sequence; lane = head.  A range's
-// first word is polled with one 8-byte load per round (256 workgroups polling every word would take
-// a tenth of the HBM bandwidth from the ranges still streaming); once it is there the whole row is
-// read and checked.  The workgroup's own statistics never leave the chip.  Returns false when a
-// word did not appear within spin_ticks of the 100 MHz wall clock.
+// Called by every wave: wave w merges ranges w, w+8, .. of the sequence; lane = head.  First the
+// ranges' first words are polled, one lane per range and one 8-byte load per lane and round (256
+// workgroups polling every word would take a tenth of the HBM bandwidth from the ranges still
+// streaming); once they are all there the rows are requested together, read and checked.  Two
+// memory round trips however many ranges the wave looks after.  The workgroup's own statistics
+// never leave the chip.  Returns false when a word did not appear within spin_ticks of the
+// 100 MHz wall clock.
 __device__ __forceinline__ bool resident_gather(const unsigned long long *stats, int rng, int nranges, int Hq, int G,
                                                 int Hkv, int wpk, const float (*sm_m)[8], const float (*sm_z)[8],
                                                 long long spin_ticks, float &M, float &Z)
@@ -201,28 +203,49 @@ __device__ __forceinline__ bool resident_gather(const unsigned long long *stats,
     Z = 0.f;
     bool ok = true;
     const long long t_start = wall_clock64();
-    for (int rr = wave; rr < nranges && ok; rr += kResWaves) {
-        if (rr == rng) {
-            if (lane < Hq) {
-                float Mo, Zo;
-                resident_own_stats(sm_m, sm_z, lane, G, Hkv, wpk, Mo, Zo);
-                softmax_merge(M, Z, Mo, Zo);
-            }
-            continue;
-        }
-        const unsigned long long *row = stats + (int64_t)rr * Hq;
-        while (__hip_atomic_load(row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0ull) {
+    // ranges of this wave: wave + 8 x, x = 0 .. nmine-1 (nmine <= 32 as nranges <= 256)
+    const int nmine = nranges > wave ? (nranges - wave + kResWaves - 1) / kResWaves : 0;
+    {
+        const int rr = wave + kResWaves * lane;
+        const bool polls = lane < nmine && rr != rng;
+        const unsigned long long *first = stats + (int64_t)(polls ? rr : 0) * Hq;
+        while (true) {
+            const unsigned long long w = polls ? __hip_atomic_load(first, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1ull;
+            if (__builtin_amdgcn_ballot_w64(w == 0ull) == 0ull) break;
             __builtin_amdgcn_s_sleep(1);
             if (wall_clock64() - t_start > spin_ticks) { ok = false; break; }
         }
-        unsigned long long mz = 1ull;
-        while (ok) {
-            mz = lane < Hq ? __hip_atomic_load(row + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1ull;
-            if (__builtin_amdgcn_ballot_w64(mz == 0ull) == 0ull) break;
+    }
+    for (int x0 = 0; x0 < nmine && ok; x0 += 4) {
+        unsigned long long mz[4];
+        while (true) {
+            bool missing = false;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int rr = wave + kResWaves * (x0 + j);
+                mz[j] = 1ull;
+                if (x0 + j < nmine && rr != rng && lane < Hq)
+                    mz[j] = __hip_atomic_load(stats + (int64_t)rr * Hq + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) missing = missing || mz[j] == 0ull;
+            if (__builtin_amdgcn_ballot_w64(missing) == 0ull) break;
             __builtin_amdgcn_s_sleep(1);
-            if (wall_clock64() - t_start > spin_ticks) ok = false;
+            if (wall_clock64() - t_start > spin_ticks) { ok = false; break; }
         }
-        if (ok && lane < Hq) softmax_merge(M, Z, __uint_as_float((uint32_t)mz), __uint_as_float((uint32_t)(mz >> 32)));
+        if (!ok) break;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int rr = wave + kResWaves * (x0 + j);
+            if (x0 + j >= nmine || lane >= Hq) continue;
+            if (rr == rng) {
+                float Mo, Zo;
+                resident_own_stats(sm_m, sm_z, lane, G, Hkv, wpk, Mo, Zo);
+                softmax_merge(M, Z, Mo, Zo);
+            } else {
+                softmax_merge(M, Z, __uint_as_float((uint32_t)mz[j]), __uint_as_float((uint32_t)(mz[j] >> 32)));
+            }
+        }
     }
     return ok;
 }

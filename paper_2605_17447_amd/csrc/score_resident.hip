@@ -346,9 +346,11 @@ pre_done:
     // This range is done reading: count it out.  The last one of the sequence (it has seen every
     // other one finish reading) clears the sequence's words and the count when the kernel ends.
     uint32_t *left = &g_res_left[sync_slot][b];
-    if (threadIdx.x == 0)
-        sm_last = __hip_atomic_fetch_add(left, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)nranges - 1u;
+    // (the count's old value is only looked at when the kernel ends: nobody waits for the atomic)
+    uint32_t left_before = 0u;
+    if (threadIdx.x == 0) left_before = __hip_atomic_fetch_add(left, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     auto leave = [&]() {
+        if (threadIdx.x == 0) sm_last = left_before == (uint32_t)nranges - 1u;
         __syncthreads();
         resident_retire(sm_last != 0, stats, nranges, Hq, left);
     };
