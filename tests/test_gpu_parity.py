@@ -502,3 +502,19 @@ def test_config4_full_size_in_the_benchmark_launch_configuration():
     check_scores(sc1, ref_sc, p.vis_len, "config4 focal-layer scores")
     assert np.allclose(lse1.cpu().numpy(), ref_lse, rtol=2e-5, atol=2e-5)
     assert np.allclose(mass1.cpu().numpy(), ref_mass, atol=2e-5)
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 5])
+def test_other_configurations_at_full_size_with_automatic_launch_shapes(cfg):
+    """Configurations 2 (batch 1), 3 (batch 8, one layer of the stack) and 5 (batch 32, ragged image
+    spans from 2048 to 16384 tokens in one paged pool) at their full shapes, mid-run, with the launch
+    shapes the library picks by itself: every call against the oracle."""
+    wl = fs.config(cfg, n_layers=1, focal_layers=(0,))
+    bt = fs.make_batch(wl, device=DEV)
+    t = 40
+    q = fs.queries_for_step(bt, t, [x[t - 1] for x in fs.centres(bt, t)])
+    p = GpuProblem(bt.k, bt.v, q, bt.seq_len(t), bt.vis_start, bt.n_vis, wl.head_dim ** -0.5,
+                   block_table=bt.block_table if wl.paged else None)
+    full_check(p, 0.05, f"config {cfg} full size", exact_topk=True)
+    if cfg == 3:
+        full_check(p, 0.10, "config 3 full size, tau 0.10", exact_topk=True)
