@@ -123,7 +123,8 @@ size_t fastocr_workspace_bytes(int op, const fastocr_kv_view *kv, const fastocr_
  *   scores   fp32 [batch, max_vis_len]
  *   lse      fp32 [batch, n_q_heads] natural-log sum-exp of each head's logits, or NULL
  *   img_mass fp32 [batch] sum_i scores[b,i] = the image-attention ratio of Eq. 1, or NULL
- * Concurrency: for large shapes this call (and fastocr_focal_attn_score) runs as ONE kernel whose
+ * Concurrency: when the shape fits (bf16, head_dim 128, 1/2/4/8 kv heads with at most 8 query heads
+ * each, batch <= 256 and <= the compute-unit count) this call (and fastocr_focal_attn_score) runs as ONE kernel whose
  * workgroups -- at most one per compute unit -- wait for each other at a per-sequence barrier, so
  * all of them must be on the chip together.  Launched alone on the GPU (any number of calls in
  * order on one stream, HIP graphs included) that always holds.  If other kernels occupy compute
@@ -250,7 +251,8 @@ int fastocr_stream_probe(const void *src, void *dst, size_t bytes, void *sink, v
 
 /* Launch-shape overrides for measurement sweeps: key "splits_score" | "splits_dense" |
  * "splits_sparse" (0 = automatic), "score_resident" | "focal_fused" (0 = always the separate
- * kernels, 1 = chosen by size (default), 2 = the single-kernel form whenever the shape fits),
+ * kernels, 1 = chosen by the library (default; currently whenever the shape fits), 2 = the
+ * single-kernel form whenever the shape fits),
  * "attn_waves" (4 | 8), "attn_merge" (pruned attention with several ranges per stream: 1 = merged
  * inside the launch (default), 0 = by a second kernel), "barrier_spin_us" (how long a workgroup of the single-kernel forms waits for
  * its sequence's other workgroups; 0 restores the default of 250000; 1 makes waiting workgroups give

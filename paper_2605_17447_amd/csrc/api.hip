@@ -223,15 +223,16 @@ static int check_qo(const fastocr_kv_view *kv, const void *q, const void *out, f
     return FASTOCR_OK;
 }
 
-// The register-resident kernels (scoring alone, or fused with the dense output) pay a fixed price
-// of 10-15 microseconds for their grid-wide exchange (statistics written through to memory, a
-// per-sequence barrier, partials read back); the paths built from separate kernels pay a second
-// read of K or a round trip of the logits through memory instead.  Measured crossovers on MI355X,
-// in image tiles per wave: scoring about 3, the fused focal layer about 12 (it saves one K read
-// but adds the merge of its attention partials).  mode 0 = never, 1 = by that rule, 2 = whenever
-// the shape fits.
-constexpr int kResidentMinTiles = 3;
-constexpr int kFusedMinTiles = 12;
+// The register-resident kernels (scoring alone, or fused with the dense output) pay a few
+// microseconds for their grid-wide exchange (statistics through memory, polled); the paths built
+// from separate kernels pay a second read of K or a round trip of the logits through memory, and
+// one or two more launches.  Measured on MI355X down to one image tile per wave (batch 1, N = 4096)
+// the single-kernel forms are never slower: scoring 13 us against 5 + 6 us in two launches, the
+// focal layer 16 + 5 us against 6 + 4 + 11 us, at batch 8 25 + 4 against 16 + 4 + 18 us.  So the
+// size rule (mode 1) takes them whenever the shape fits, like mode 2; mode 0 = never.  The
+// thresholds stay as the place to change that.
+constexpr int kResidentMinTiles = 1;
+constexpr int kFusedMinTiles = 1;
 
 static bool use_resident(int mode, const Shape &s, ResidentPlan *rp, int min_tiles)
 {
