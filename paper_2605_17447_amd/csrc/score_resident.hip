@@ -46,14 +46,14 @@ extern int g_tune_barrier_spin_us;
         _Pragma("unroll") for (int r = 0; r < 4; ++r) park_##J[r] = fast_exp2(park_##J[r] - m[r]);  \
         if ((J) + 1 >= nimg) goto pre_done;                                                         \
     }
-// tile J after the exchange: rescaled to the sequence's normalisers, this lane's 4 heads summed
-// with the partner lane's 4
+// tile J after the exchange: rescaled to the sequence's normalisers, this lane's 4 heads summed;
+// the partner lane's 4 heads of the same token go to a row of their own (a cross-lane move per
+// tile would cost more than the second row does in the final sum)
 #define RES_FINISH_STEP(J)                                                                          \
     {                                                                                               \
         float v = 0.f;                                                                              \
         _Pragma("unroll") for (int r = 0; r < 4; ++r) v += park_##J[r] * cf[r];                     \
-        v += __shfl_xor(v, 16);                                                                     \
-        if ((lg & 1) == 0) red[kvh * R + img_first(J) - r0 + tok_in_tile] = v;                      \
+        red[(2 * kvh + (lg & 1)) * R + img_first(J) - r0 + tok_in_tile] = v;                        \
         if ((J) + 1 >= nimg) goto fin_done;                                                         \
     }
 
@@ -377,7 +377,7 @@ pre_done:
     float cf[4];          // from "relative to the wave's maximum" to "relative to the head's normaliser"
 #pragma unroll
     for (int r = 0; r < 4; ++r) cf[r] = (hbase + r < G) ? fast_exp2(m[r] - sm_lse[kvh * G + hbase + r]) : 0.f;
-    float *red = reinterpret_cast<float *>(&smem[0][0][0]);          // [Hkv][R], at most 32 KB
+    float *red = reinterpret_cast<float *>(&smem[0][0][0]);          // [2 Hkv][R], at most 64 KB
     if (nimg > 0) {
         RES_EACH_TILE(RES_FINISH_STEP)
     }
@@ -387,7 +387,7 @@ fin_done:
     const float inv = 1.0f / (float)Hq;
     for (int i = threadIdx.x; i < r1 - r0; i += kResThreads) {
         float a = 0.f;
-        for (int g = 0; g < Hkv; ++g) a += red[g * R + i];
+        for (int g = 0; g < 2 * Hkv; ++g) a += red[g * R + i];
         a *= inv;
         scores[(int64_t)b * bv.max_vis_len + r0 + i] = a;
         local += a;
