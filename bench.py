@@ -251,6 +251,8 @@ def main():
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "algorithmic_bytes": int(score_bytes), "avg_launch_us": round(k_ms * 1e3, 2),
+                "launch_us_p10_p50_p90": [round(float(np.percentile(logits_ms, p)) * 1e3, 2) for p in (10, 50, 90)]
+                if logits_ms else None,
                 "launches": len(logits_ms)}
 
     result = {
@@ -307,6 +309,18 @@ def main():
             kernels_us[nm] = round(float(np.mean(ms)) * 1e3, 2) if ms else None
             fb.kernel_timer_enable(kid, 0)
         dense_bytes = B * (mean_S * 2 * R + 2 * Hq * d * e)
+        # what a plain read-only stream reaches on this machine (2 GiB, a trivial kernel of the library)
+        probe_src = torch.empty(1 << 31, dtype=torch.uint8, device=dev).fill_(1)
+        sink = torch.zeros(4, dtype=torch.int32, device=dev)
+        fb.stream_probe(probe_src, None, sink)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for _ in range(5):
+            fb.stream_probe(probe_src, None, sink)
+        ev1.record()
+        torch.cuda.synchronize()
+        read_ceiling = 5 * float(1 << 31) / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+        del probe_src
         # per sequence: its own kept count and its own text length (ragged batches differ in both)
         sparse_bytes = sum((fo.keep_count(n, tau) + float(seq_lens[n_warm:, b].float().mean().item()) - n) * 2 * R
                            + 4 * fo.keep_count(n, tau) + 2 * Hq * d * e for b, n in enumerate(bt.n_vis))
@@ -323,6 +337,7 @@ def main():
             "speedup_sparse_vs_dense": round(dense_ms / sparse_ms, 3),
             "blended_speedup_vs_dense": {"focal_fraction_0.1": round(dense_ms / blend(0.1), 3),
                                          "focal_fraction_2_of_28": round(dense_ms / blend(2 / 28), 3)},
+            "measured_read_stream_ceiling_GBs": round(read_ceiling, 1),
             "dense_achieved_GBs": round(dense_bytes / (dense_ms * 1e-3) / 1e9, 1),
             "sparse_achieved_GBs": round(sparse_bytes / (sparse_ms * 1e-3) / 1e9, 1),
             "kernels_us": kernels_us,

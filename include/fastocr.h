@@ -254,7 +254,8 @@ int fastocr_stream_probe(const void *src, void *dst, size_t bytes, void *sink, v
  * kernels, 1 = chosen by the library (default; currently whenever the shape fits), 2 = the
  * single-kernel form whenever the shape fits),
  * "attn_waves" (4 | 8), "attn_merge" (pruned attention with several ranges per stream: 1 = merged
- * inside the launch (default), 0 = by a second kernel), "barrier_spin_us" (how long a workgroup of the single-kernel forms waits for
+ * inside the launch (default), 0 = by a second kernel, 2 = dense attention merges inside the launch
+ * too -- measured slower, kept for comparison), "barrier_spin_us" (how long a workgroup of the single-kernel forms waits for
  * its sequence's other workgroups; 0 restores the default of 250000; 1 makes waiting workgroups give
  * up at once, which tests use to exercise the NaN path).  Returns FASTOCR_EINVAL for an unknown key. */
 int fastocr_set_tuning(const char *key, int value);

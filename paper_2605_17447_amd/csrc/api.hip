@@ -304,7 +304,7 @@ static int attn_common(int op, const fastocr_kv_view *kv, const fastocr_batch_vi
     if (bv->batch == 0) return FASTOCR_OK;
     Shape s = make_shape(kv, bv, n_q_heads);
     const int nsplit = choose_splits(op, s, op == FASTOCR_OP_SPARSE_DECODE_ATTN ? sparse_positions(bv, kmax) : bv->max_seq_len);
-    const bool merge = op == FASTOCR_OP_SPARSE_DECODE_ATTN && g_tune_attn_merge != 0;
+    const bool merge = (op == FASTOCR_OP_SPARSE_DECODE_ATTN && g_tune_attn_merge != 0) || g_tune_attn_merge == 2;
     hipError_t e = launch_attn(s, q, scale, sel_idx, sel_cnt, kmax, out, lse, ws, nsplit, merge, (hipStream_t)hip_stream);
     return e == hipSuccess ? FASTOCR_OK : FASTOCR_EHIP;
 }
@@ -434,7 +434,7 @@ int fastocr_set_tuning(const char *key, int value)
     else if (!strcmp(key, "splits_sparse")) g_tune_splits[FASTOCR_OP_SPARSE_DECODE_ATTN] = value;
     else if (!strcmp(key, "splits_dense")) g_tune_splits[FASTOCR_OP_DENSE_DECODE_ATTN] = value;
     else if (!strcmp(key, "attn_waves")) g_tune_attn_waves = value;
-    else if (!strcmp(key, "attn_merge") && value <= 1) g_tune_attn_merge = value;
+    else if (!strcmp(key, "attn_merge") && value <= 2) g_tune_attn_merge = value;
     else if (!strcmp(key, "barrier_spin_us") && value >= 0) g_tune_barrier_spin_us = value ? value : 250000;
     else if (!strcmp(key, "score_resident") && value >= 0 && value <= 2) g_tune_score_resident = value;
     else if (!strcmp(key, "focal_fused") && value >= 0 && value <= 2) g_tune_focal_fused = value;

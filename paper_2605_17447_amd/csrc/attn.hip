@@ -82,8 +82,10 @@ __global__ __launch_bounds__(64 * kWaves, 8 / kWaves) void attn_mfma_kernel(
 
     const int stream_id = b * gridDim.y + kvh;
     uint32_t tag = 0;
-    if (MODE == kMerge)
+    if (MODE == kMerge) {
         tag = __builtin_amdgcn_readfirstlane(__hip_atomic_load(&g_merge_epoch[merge_slot][stream_id], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) + 1u;
+        if (tag == 0u) tag = 1u;             // zero is what never-written words hold
+    }
 
     const SeqGeom geo = seq_geom(bv, b);
     int cnt = 0;

@@ -11,24 +11,37 @@ __global__ __launch_bounds__(256) void stream_probe_kernel(const u32x4 *__restri
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     u32x4 acc = u32x4{0u, 0u, 0u, 0u};
-    for (; i + 3 * stride < n16; i += 4 * stride) {
-        const u32x4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-        if (dst) { dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d; }
-        else acc ^= a ^ b ^ c ^ d;
+    if (dst) {
+        for (; i + 3 * stride < n16; i += 4 * stride) {
+            const u32x4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+            dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d;
+        }
+        for (; i < n16; i += stride) dst[i] = src[i];
+        return;
     }
-    for (; i < n16; i += stride) {
-        const u32x4 a = src[i];
-        if (dst) dst[i] = a;
-        else acc ^= a;
+    // read only, the way the attention kernels stream K and V: every wave owns a contiguous chunk
+    // and walks it in pieces of 8 x 1 KB with non-temporal loads, eight in flight per lane
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const size_t nw = (size_t)gridDim.x * 4, w = (size_t)blockIdx.x * 4 + wave;
+    const size_t per = (n16 / nw) / 512 * 512;                  // 16-byte units per wave, whole pieces
+    const u32x4 *p = src + w * per + lane;
+    for (size_t k = 0; k < per; k += 512) {
+        u32x4 v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(p + k + 64 * j);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc ^= v[j];
     }
-    // keeps the read-only variant's loads alive; the value is never expected to match
-    if (!dst && (acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u && sink) sink[0] = acc[0];
+    // what the chunks leave over
+    for (i += nw * per; i < n16; i += stride) acc ^= __builtin_nontemporal_load(src + i);
+    // keeps the loads alive; the value is never expected to match
+    if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u && sink) sink[0] = acc[0];
 }
 
 hipError_t launch_stream_probe(const void *src, void *dst, size_t bytes, void *sink, hipStream_t stream)
 {
     const size_t n16 = bytes / 16;
-    stream_probe_kernel<<<256 * 8, 256, 0, stream>>>(reinterpret_cast<const u32x4 *>(src),
+    stream_probe_kernel<<<256 * 12, 256, 0, stream>>>(reinterpret_cast<const u32x4 *>(src),
                                                      reinterpret_cast<u32x4 *>(dst), n16,
                                                      reinterpret_cast<uint32_t *>(sink));
     return hipGetLastError();
