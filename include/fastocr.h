@@ -260,6 +260,15 @@ int fastocr_stream_probe(const void *src, void *dst, size_t bytes, void *sink, v
  * up at once, which tests use to exercise the NaN path).  Returns FASTOCR_EINVAL for an unknown key. */
 int fastocr_set_tuning(const char *key, int value);
 
+/*
+ * For the callers of the single-launch forms (see the Concurrency notes above): how many waves
+ * have given up waiting for another workgroup of their own launch since the library was loaded
+ * (each such wave left NaN in what it could not finish).  0 in any run where those launches had
+ * the GPU to themselves.  Copies three counters from the device: synchronises with it, so not
+ * for use under stream capture.  count: host pointer.
+ */
+int fastocr_exchange_timeouts(uint64_t *count);
+
 const char *fastocr_strerror(int status);
 const char *fastocr_version(void);
 

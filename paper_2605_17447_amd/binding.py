@@ -25,7 +25,7 @@ OP_FOCAL_SCORE, OP_TOPK_FIXATION, OP_SPARSE_DECODE_ATTN, OP_DENSE_DECODE_ATTN, O
 EXPORTS = (
     "fastocr_keep_count", "fastocr_workspace_bytes", "fastocr_focal_score", "fastocr_topk_fixation",
     "fastocr_sparse_decode_attn", "fastocr_dense_decode_attn", "fastocr_focal_attn_score", "fastocr_kernel_timer_enable",
-    "fastocr_kernel_timer_read", "fastocr_select_focal_layers", "fastocr_stream_probe", "fastocr_set_tuning", "fastocr_strerror", "fastocr_version",
+    "fastocr_kernel_timer_read", "fastocr_select_focal_layers", "fastocr_stream_probe", "fastocr_set_tuning", "fastocr_exchange_timeouts", "fastocr_strerror", "fastocr_version",
 )
 
 
@@ -87,6 +87,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.fastocr_select_focal_layers.argtypes = [P, I, I, I, ctypes.c_double, I, P, P]
     lib.fastocr_stream_probe.restype, lib.fastocr_stream_probe.argtypes = I, [P, P, SZ, P, P]
     lib.fastocr_set_tuning.restype, lib.fastocr_set_tuning.argtypes = I, [ctypes.c_char_p, I]
+    lib.fastocr_exchange_timeouts.restype, lib.fastocr_exchange_timeouts.argtypes = I, [ctypes.POINTER(ctypes.c_uint64)]
     lib.fastocr_strerror.restype, lib.fastocr_strerror.argtypes = ctypes.c_char_p, [I]
     lib.fastocr_version.restype, lib.fastocr_version.argtypes = ctypes.c_char_p, []
     _lib = lib
@@ -298,6 +299,13 @@ def stream_probe(src: torch.Tensor, dst: Optional[torch.Tensor], sink: torch.Ten
     nbytes = src.numel() * src.element_size()
     _check(load_library().fastocr_stream_probe(_ptr(src), _ptr(dst), nbytes, _ptr(sink), _stream_handle(stream)),
            "fastocr_stream_probe")
+
+
+def exchange_timeouts() -> int:
+    """fastocr_exchange_timeouts: waves that gave up waiting inside a single-launch form since load."""
+    n = ctypes.c_uint64(0)
+    _check(load_library().fastocr_exchange_timeouts(ctypes.byref(n)), "fastocr_exchange_timeouts")
+    return int(n.value)
 
 
 def kernel_timer_enable(kernel: int, capacity: int) -> None:

@@ -427,6 +427,17 @@ int fastocr_stream_probe(const void *src, void *dst, size_t bytes, void *sink, v
     return e == hipSuccess ? FASTOCR_OK : FASTOCR_EHIP;
 }
 
+int fastocr_exchange_timeouts(uint64_t *count)
+{
+    if (!count) return FASTOCR_EINVAL;
+    uint32_t a = 0, b = 0, c = 0;
+    if (score_resident_timeouts(&a) != hipSuccess || focal_fused_timeouts(&b) != hipSuccess ||
+        attn_merge_timeouts(&c) != hipSuccess)
+        return FASTOCR_EHIP;
+    *count = (uint64_t)a + b + c;
+    return FASTOCR_OK;
+}
+
 int fastocr_set_tuning(const char *key, int value)
 {
     if (!key || value < 0) return FASTOCR_EINVAL;

@@ -579,6 +579,8 @@ static void launch_generic(int kid, const Shape &s, const void *q, float scale_l
         s.kv, s.bv, (const T *)q, s.n_q_heads, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit);
 }
 
+hipError_t attn_merge_timeouts(uint32_t *n) { return hipMemcpyFromSymbol(n, HIP_SYMBOL(g_merge_timeouts), sizeof(uint32_t)); }
+
 hipError_t launch_attn(const Shape &s, const void *q, float scale, const int32_t *sel_idx,
                        const int32_t *sel_cnt, int64_t kmax, void *out, float *lse, void *ws,
                        int nsplit, bool merge_in_kernel, hipStream_t stream)

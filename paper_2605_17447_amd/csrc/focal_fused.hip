@@ -34,9 +34,10 @@ namespace fastocr {
 extern int g_tune_barrier_spin_us;
 
 // statistics words per (workgroup, head), per sequence the count of ranges done reading, and a
-// sticky time-out flag per slot: same protocol as score_resident.hip, own arrays
+// count of the waves that gave up waiting: same protocol as score_resident.hip, own arrays
 __device__ unsigned long long g_fus_stats[kResSlots][kResMaxWg * kResMaxHq];
-__device__ uint32_t g_fus_left[kResSlots][kResMaxBatch + 1];
+__device__ uint32_t g_fus_left[kResSlots][kResMaxBatch];
+__device__ uint32_t g_fus_timeouts;
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // One logit per image tile of the wave, indexed by the (wave-uniform) tile number: the compiler
@@ -358,7 +359,7 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
         const bool ok = resident_gather(stats, rng, nranges, Hq, G, Hkv, wpk, sm_m, sm_z, spin_ticks, M, Z);
         if (!ok && lane_p == 0) {
             sm_met = 0;
-            __hip_atomic_fetch_or(&g_fus_left[sync_slot][kResMaxBatch], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_fetch_add(&g_fus_timeouts, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         sm_pm[wave][lane_p] = M;
         sm_pz[wave][lane_p] = Z;
@@ -454,6 +455,8 @@ size_t focal_fused_workspace_bytes(const Shape &s, const ResidentPlan &p)
     bytes += (size_t)s.batch * 2 * sizeof(int32_t);
     return bytes;
 }
+
+hipError_t focal_fused_timeouts(uint32_t *n) { return hipMemcpyFromSymbol(n, HIP_SYMBOL(g_fus_timeouts), sizeof(uint32_t)); }
 
 hipError_t launch_focal_fused(const Shape &s, const ResidentPlan &p, const void *q, float scale, void *out,
                               float *scores, float *lse, float *img_mass, void *ws, hipStream_t stream)

@@ -82,6 +82,12 @@ size_t focal_fused_workspace_bytes(const Shape &s, const ResidentPlan &p);
 hipError_t launch_focal_fused(const Shape &s, const ResidentPlan &p, const void *q, float scale, void *out,
                               float *scores, float *lse, float *img_mass, void *ws, hipStream_t stream);
 
+// ---- how often a workgroup gave up waiting for another one of its launch (each file's own count;
+// the copies synchronise with the device) ----------------------------------------------------
+hipError_t score_resident_timeouts(uint32_t *n);
+hipError_t focal_fused_timeouts(uint32_t *n);
+hipError_t attn_merge_timeouts(uint32_t *n);
+
 // ---- top-k (topk.hip) -------------------------------------------------------------------
 size_t topk_workspace_bytes(int batch, int max_vis_len);
 hipError_t launch_topk(const float *scores, const BatchDev &bv, int batch, double tau,

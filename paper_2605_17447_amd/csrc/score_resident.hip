@@ -64,9 +64,10 @@ extern int g_tune_barrier_spin_us;
 // stand-in for "no logit").  g_res_left: per sequence, how many of its ranges are done reading.
 // The last range to finish zeroes the sequence's words and its count, so a slot is clean again
 // when its call ends; calls take slots round-robin, so up to kResSlots calls may overlap on one
-// GPU.  The last word of g_res_left[slot] is a sticky "an exchange timed out" flag.
+// GPU.  g_res_timeouts counts the waves that gave up waiting (fastocr_exchange_timeouts).
 __device__ unsigned long long g_res_stats[kResSlots][kResMaxWg * kResMaxHq];
-__device__ uint32_t g_res_left[kResSlots][kResMaxBatch + 1];
+__device__ uint32_t g_res_left[kResSlots][kResMaxBatch];
+__device__ uint32_t g_res_timeouts;          // waves that gave up waiting, since the module was loaded
 
 bool resident_plan(const Shape &s, int num_cu, ResidentPlan *plan)
 {
@@ -337,7 +338,7 @@ pre_done:
         const bool ok = resident_gather(stats, rng, nranges, Hq, G, Hkv, wpk, sm_m, sm_z, spin_ticks, M, Z);
         if (!ok && lane == 0) {
             sm_met = 0;
-            __hip_atomic_fetch_or(&g_res_left[sync_slot][kResMaxBatch], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_fetch_add(&g_res_timeouts, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         sm_pm[wave][lane] = M;
         sm_pz[wave][lane] = Z;
@@ -417,6 +418,8 @@ __global__ void resident_mass_kernel(const float *__restrict__ mass_part, const 
     t = wave_sum(t);
     if (threadIdx.x == 0) img_mass[b] = t;
 }
+
+hipError_t score_resident_timeouts(uint32_t *n) { return hipMemcpyFromSymbol(n, HIP_SYMBOL(g_res_timeouts), sizeof(uint32_t)); }
 
 hipError_t launch_score_resident(const Shape &s, const ResidentPlan &p, const void *q, float scale, float *scores,
                                  float *lse, float *img_mass, void *ws, hipStream_t stream)

@@ -165,6 +165,12 @@ def test_topk_and_sparse_validation(lib):
     assert sp(ws_bytes=64) == fb.EWORKSPACE
 
 
+def test_exchange_timeouts_rejects_a_null_pointer(lib):
+    lib.fastocr_exchange_timeouts.restype = ctypes.c_int
+    lib.fastocr_exchange_timeouts.argtypes = [ctypes.c_void_p]
+    assert lib.fastocr_exchange_timeouts(None) == -1          # FASTOCR_EINVAL, before any GPU call
+
+
 def test_tuning_keys(lib):
     assert lib.fastocr_set_tuning(b"splits_dense", 3) == fb.OK
     kv, bv = _kv(), _bv()

@@ -206,8 +206,10 @@ def test_a_merge_that_gives_up_writes_nan_and_the_next_call_is_correct():
             err = np.where(bad, 0.0, np.abs(out - ref)) / np.abs(ref).max(axis=-1, keepdims=True)
             assert err.max() <= 2e-2
         fb.set_tuning("barrier_spin_us", 0)
+        gave_up_before = fb.exchange_timeouts()
         for _ in range(5):
             check_out(p.sparse(sel, selc), ref, "pruned attention after a merge that gave up")
+        assert fb.exchange_timeouts() == gave_up_before
     finally:
         fb.set_tuning("barrier_spin_us", 0)
         fb.set_tuning("splits_sparse", 0)
@@ -403,9 +405,11 @@ def test_a_barrier_that_gives_up_poisons_the_result_and_leaves_the_library_usabl
         fb.set_tuning("score_resident", 2)
         fb.set_tuning("focal_fused", 2)
         fb.set_tuning("barrier_spin_us", 1)
+        gave_up_before = fb.exchange_timeouts()
         sc, _, _ = p.scores()
         out, sc2, _, _ = p.focal_attn()
         torch.cuda.synchronize()
+        assert fb.exchange_timeouts() > gave_up_before, "the library counts the waves that gave up"
         for got in (sc, sc2):
             g = got.cpu().numpy()
             for b in range(p.B):
@@ -416,8 +420,10 @@ def test_a_barrier_that_gives_up_poisons_the_result_and_leaves_the_library_usabl
         # the attention output does not depend on the barrier (partials are merged by a later kernel)
         check_out(out, ref_dense, "output of a call whose score barrier gave up")
         fb.set_tuning("barrier_spin_us", 0)
+        gave_up_before = fb.exchange_timeouts()
         sc, _, _ = p.scores()
         out, sc2, _, _ = p.focal_attn()
+        assert fb.exchange_timeouts() == gave_up_before, "no wave gives up with the normal limit"
         check_scores(sc, ref_sc, p.vis_len, "scores after a timed-out call")
         check_scores(sc2, ref_sc, p.vis_len, "one-pass scores after a timed-out call")
         check_out(out, ref_dense, "one-pass output after a timed-out call")
