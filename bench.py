@@ -369,8 +369,19 @@ def main():
                     break
             n_steps_cpu += 1
             i -= 1
+        # the same oracle on one thread, one sequence-step (context for the all-core figure)
+        src = bts[(total - 1) % L]
+        ok1 = oracle.Cache.from_bhsd(fs.to_oracle_array(src.k[0:1]), fs.to_oracle_array(src.v[0:1]))
+        q1 = fs.to_oracle_array(qs[total - 1][0:1])
+        geo = ([bt.seq_len(t_first + total - 1)[0]], [bt.vis_start[0]], [bt.n_vis[0]])
+        t0 = time.perf_counter()
+        sc, _, _ = oracle.focal_score(ok1, *geo, q1, scale, n_threads=1)
+        sel, c = oracle.topk_fixation(sc, geo[2], tau)
+        oracle.decode_attn(ok1, *geo, q1, scale, sel, c, n_threads=1)
+        one_thread_s = time.perf_counter() - t0
         result["cpu_baseline"] = {
             "value": round(n_seq / (B * cpu_s), 5), "unit": "layer-steps/s", "cores": threads, "kind": "oracle",
+            "single_thread_value": round(1.0 / (B * one_thread_s), 5),
             "sample": "%d sequence-steps (batch %d, decode steps %d..%d backwards) of the whole three-step path, "
                       "%.1f s of CPU time; rate scaled to the full batch"
                       % (n_seq, B, t_first + total - 1, t_first + total - n_steps_cpu, cpu_s)}
