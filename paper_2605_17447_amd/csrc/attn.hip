@@ -371,11 +371,40 @@ tiles_done:
 // Generic kernel: any dtype / head_dim <= 256 / group size.  One wave per (range, query
 // head, sequence); lanes over tokens for q.k, lanes over dims for p.V.  Plain fp32 FMAs.
 // -----------------------------------------------------------------------------------------
+// acc[x] += sum_j p_j V[j][lane + 64 x] over the nv tokens of a tile; lane j holds token j's
+// probability pj and row offset off.  Eight tokens' rows are requested before any is used (a row's
+// address comes from another lane, so the compiler does not overlap the rows by itself); every load is
+// unconditional -- components past d read the row's last component and are never stored, tokens
+// past the tile's end repeat its last row with probability zero.
+template <typename T, int NX>
+__device__ __forceinline__ void pv_rows(const T *__restrict__ vbase, int64_t off, float pj, int nv, int d, int lane,
+                                        float (&acc)[4])
+{
+    int cc[NX];
+#pragma unroll
+    for (int x = 0; x < NX; ++x) cc[x] = min(lane + 64 * x, d - 1);
+    for (int j0 = 0; j0 < nv; j0 += 8) {
+        float pb[8], vv[8][NX];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int jj = min(j0 + u, nv - 1);
+            pb[u] = j0 + u < nv ? __shfl(pj, jj) : 0.f;
+            const int64_t oj = __shfl(off, jj);
+#pragma unroll
+            for (int x = 0; x < NX; ++x) vv[u][x] = load_elem<T>(vbase + oj + cc[x]);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int x = 0; x < NX; ++x) acc[x] = fmaf(pb[u], vv[u][x], acc[x]);
+    }
+}
+
 template <typename T, bool GATHER, bool PAGED>
 __global__ __launch_bounds__(64) void attn_generic_kernel(
     KvDev kv, BatchDev bv, const T *__restrict__ q, int Hq, float scale_log2,
     const int32_t *__restrict__ sel_idx, const int32_t *__restrict__ sel_cnt, int64_t kmax,
-    float *__restrict__ part_o, float *__restrict__ part_ml, int nsplit)
+    float *__restrict__ part_o, float *__restrict__ part_ml, int nsplit, bool vec16)
 {
     __shared__ float qs[256];
     const int lane = threadIdx.x;
@@ -409,8 +438,7 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(
         const bool valid = p < L;
         const int tok = pos_to_token<GATHER>(min(p, L - 1), geo, cnt, sel);
         const int64_t off = row_offset<PAGED>(kv, b, tok, g);
-        float s = 0.f;
-        for (int c = 0; c < d; ++c) s = fmaf(qs[c], load_elem<T>(kbase + off + c), s);
+        float s = dot_row<T>(qs, kbase + off, d, vec16);
         s = valid ? s * scale_log2 : -INFINITY;
         const float m_new = fmaxf(m, wave_max(s));
         const float alpha = fast_exp2(m - m_new);
@@ -420,15 +448,9 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(
 #pragma unroll
         for (int x = 0; x < 4; ++x) acc[x] *= alpha;
         const int nv = min(64, L - tile * 64);
-        for (int jj = 0; jj < nv; ++jj) {
-            const float pb = __shfl(pj, jj);
-            const int64_t oj = __shfl(off, jj);
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int c = lane + 64 * x;
-                if (c < d) acc[x] = fmaf(pb, load_elem<T>(vbase + oj + c), acc[x]);
-            }
-        }
+        if (d <= 64) pv_rows<T, 1>(vbase, off, pj, nv, d, lane, acc);
+        else if (d <= 128) pv_rows<T, 2>(vbase, off, pj, nv, d, lane, acc);
+        else pv_rows<T, 4>(vbase, off, pj, nv, d, lane, acc);
     }
     const int64_t ph = ((int64_t)b * Hq + h) * nsplit + split;
 #pragma unroll
@@ -576,7 +598,7 @@ static void launch_generic(int kid, const Shape &s, const void *q, float scale_l
 {
     dim3 grid(nsplit, s.n_q_heads, s.batch), block(64);
     FASTOCR_LAUNCH(kid, (attn_generic_kernel<T, GATHER, PAGED>), grid, block, 0, stream,
-        s.kv, s.bv, (const T *)q, s.n_q_heads, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit);
+        s.kv, s.bv, (const T *)q, s.n_q_heads, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, s.vec16);
 }
 
 hipError_t attn_merge_timeouts(uint32_t *n) { return hipMemcpyFromSymbol(n, HIP_SYMBOL(g_merge_timeouts), sizeof(uint32_t)); }

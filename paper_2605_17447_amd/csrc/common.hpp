@@ -126,6 +126,33 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// <q, row> over d components in ascending order (one fp32 FMA chain, the same result whichever way
+// the row is fetched).  vec16: the row starts 16-byte aligned and d covers whole 16-byte pieces, so
+// it is fetched 16 bytes per load instead of one element per load.
+template <typename T>
+__device__ __forceinline__ float dot_row(const float *__restrict__ qs, const T *__restrict__ row, int d, bool vec16)
+{
+    float s = 0.f;
+    if (vec16) {
+        constexpr int E = 16 / (int)sizeof(T);
+        for (int c = 0; c < d; c += E) {
+            const u32x4 w = *reinterpret_cast<const u32x4 *>(row + c);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (sizeof(T) == 2) {
+                    s = fmaf(qs[c + 2 * e], __uint_as_float(w[e] << 16), s);
+                    s = fmaf(qs[c + 2 * e + 1], __uint_as_float(w[e] & 0xffff0000u), s);
+                } else {
+                    s = fmaf(qs[c + e], __uint_as_float(w[e]), s);
+                }
+            }
+        }
+    } else {
+        for (int c = 0; c < d; ++c) s = fmaf(qs[c], load_elem<T>(row + c), s);
+    }
+    return s;
+}
+
 // LDS traffic of one wave executes in order; this only stops the compiler from moving the reads
 // of other lanes' data above the writes that produce it.
 __device__ __forceinline__ void wave_lds_fence()

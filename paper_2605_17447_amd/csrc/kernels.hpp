@@ -34,6 +34,7 @@ struct Shape {
     int n_q_heads;
     int dtype;
     bool paged;
+    bool vec16;     // every cache row starts 16-byte aligned and head_dim covers whole 16-byte pieces
     bool fast;      // the MFMA kernels cover this shape: bf16, head_dim 128, group size <= 16,
                     // 16-byte aligned rows (decided once from the views by the C-ABI layer)
 };

@@ -223,7 +223,7 @@ stream_done:
 template <typename T, bool PAGED>
 __global__ __launch_bounds__(64) void score_generic_kernel(
     KvDev kv, BatchDev bv, const T *__restrict__ q, int Hq, float scale_log2,
-    float *__restrict__ logits, int64_t pitch, float *__restrict__ part_ml, int nsplit)
+    float *__restrict__ logits, int64_t pitch, float *__restrict__ part_ml, int nsplit, bool vec16)
 {
     __shared__ float qs[256];
     const int lane = threadIdx.x;
@@ -246,8 +246,7 @@ __global__ __launch_bounds__(64) void score_generic_kernel(
         const int p = tile * 64 + lane;
         const bool valid = p < L;
         const int64_t off = row_offset<PAGED>(kv, b, min(p, L - 1), g);
-        float s = 0.f;
-        for (int c = 0; c < d; ++c) s = fmaf(qs[c], load_elem<T>(kbase + off + c), s);
+        float s = dot_row<T>(qs, kbase + off, d, vec16);
         s = valid ? s * scale_log2 : -INFINITY;
         lrow[(int64_t)p * Gp] = s;                       // p < pitch: pitch is a multiple of 64
         const float m_new = fmaxf(m, wave_max(s));
@@ -387,7 +386,7 @@ hipError_t launch_score(const Shape &s, const void *q, float scale, float *score
     } else {
         dim3 grid(nsplit, s.n_q_heads, s.batch), block(64);
 #define FASTOCR_SCORE(T, P) FASTOCR_LAUNCH(K_SCORE_LOGITS, (score_generic_kernel<T, P>), grid, block, 0, stream, \
-        s.kv, s.bv, (const T *)q, s.n_q_heads, scale_log2, logits, pitch, part_ml, nsplit)
+        s.kv, s.bv, (const T *)q, s.n_q_heads, scale_log2, logits, pitch, part_ml, nsplit, s.vec16)
         if (s.dtype == DT_BF16) { if (s.paged) FASTOCR_SCORE(uint16_t, true); else FASTOCR_SCORE(uint16_t, false); }
         else                    { if (s.paged) FASTOCR_SCORE(float, true); else FASTOCR_SCORE(float, false); }
 #undef FASTOCR_SCORE
