@@ -154,6 +154,28 @@ def test_pruned_attention_merged_inside_the_launch(Hq, Hkv, nsplit):
         fb.set_tuning("splits_sparse", 0)
 
 
+@pytest.mark.parametrize("nsplit", [2, 7])
+def test_pruned_attention_merged_inside_the_launch_paged(nsplit):
+    """The same hand-over with a paged, ragged cache (rows found through the block table)."""
+    wl = fs.config(5, batch=6, steps=8, n_visual=(200, 2500), grid_w=(16, 50), text_prefix=(3, 300), page_tokens=64)
+    bt = fs.make_batch(wl, device=DEV)
+    c = fs.centres(bt)
+    fb.set_tuning("splits_sparse", nsplit)
+    try:
+        for t in (1, 5, 8):
+            q = fs.queries_for_step(bt, t, [x[t - 1] for x in c])
+            p = GpuProblem(bt.k, bt.v, q, bt.seq_len(t), bt.vis_start, bt.n_vis, wl.head_dim ** -0.5,
+                           block_table=bt.block_table)
+            oc = p.oracle_args()
+            ref_sc, _, _ = oracle.focal_score(*oc)
+            ref_idx, ref_cnt = oracle.topk_fixation(ref_sc, p.vis_len, 0.1)
+            ref, _ = oracle.decode_attn(*oc, ref_idx, ref_cnt)
+            sel, selc = torch.from_numpy(ref_idx).to(DEV).contiguous(), torch.from_numpy(ref_cnt).to(DEV)
+            check_out(p.sparse(sel, selc), ref, f"paged merged pruned attention, step {t}")
+    finally:
+        fb.set_tuning("splits_sparse", 0)
+
+
 def test_pruned_attention_merged_inside_the_launch_replays_in_a_graph():
     """The tags come from a device-side epoch, so a captured call is fresh on every replay."""
     case = TinyCase(seed=77, B=3, Hq=28, Hkv=4, d=128, n_vis=[1100, 700, 1300], pre=[10, 3, 0], post=[50, 30, 9], dtype="bf16")
