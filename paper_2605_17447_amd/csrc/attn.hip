@@ -34,15 +34,20 @@ extern int g_tune_barrier_spin_us;
 //             it needs carries this call's tag, merges and writes the output.  Every word is its
 //             own "ready" flag, so nothing has to be ordered and no fence (an L2 write-back on this
 //             chip) is needed.  The tag is the stream's epoch + 1; the epoch is a device-side
-//             counter per (slot, stream) that the last range advances when it has everything, so a
-//             replayed HIP graph sees fresh tags too and stale words of earlier calls never match
-//             (short of 2^32 calls without the word being overwritten).  Calls take slots
-//             round-robin: up to kMergeSlots calls using this mode may overlap on one GPU.
+//             counter per (slot, stream number) that the last range advances when it has
+//             everything, so a replayed HIP graph sees fresh tags too.  A word's place depends on
+//             (stream number, range, element) only -- never on the call's shape -- so whatever a
+//             word still holds was written under an older epoch of the same counter and cannot be
+//             taken for this call's (short of 2^32 calls).  Calls take slots round-robin: up to
+//             kMergeSlots calls using this mode may overlap on one GPU.
 enum { kPartial = 0, kDirect = 1, kMerge = 2 };
 constexpr int kMergeSlots = 4;
-constexpr int kMergeMaxSplits = 8;
-constexpr int kMergeMaxStreams = 4096;
-constexpr size_t kMergeWords = (size_t)512 * 1024;           // per slot: 4 MB
+constexpr int kMergeMaxSplits = 4;
+constexpr int kMergeMaxStreams = 128;
+constexpr int kMergeMaxG = 8;
+constexpr int kMergeStatsAt = kMergeMaxG * 128;                 // a partial: o[G][128], then m[G], then Z[G]
+constexpr int kMergePitch = kMergeMaxG * 130;                   // words per published partial, whatever G is
+constexpr size_t kMergeWords = (size_t)kMergeMaxStreams * (kMergeMaxSplits - 1) * kMergePitch;   // per slot: 3.2 MB
 __device__ unsigned long long g_merge_words[kMergeSlots][kMergeWords];
 __device__ uint32_t g_merge_epoch[kMergeSlots][kMergeMaxStreams];
 __device__ uint32_t g_merge_timeouts;                        // sticky count of merges that gave up
@@ -280,8 +285,8 @@ tiles_done:
     __syncthreads();
 
     const int np = nsplit - 1;                                       // ranges that publish (kMerge)
-    const int pitch = G * 130;                                       // words per published partial
-    unsigned long long *words = g_merge_words[merge_slot] + (int64_t)stream_id * np * pitch;
+    // the stream's published partials: kMergeMaxSplits - 1 fixed places of kMergePitch words
+    unsigned long long *words = MODE == kMerge ? g_merge_words[merge_slot] + (int64_t)stream_id * (kMergeMaxSplits - 1) * kMergePitch : nullptr;
     for (int idx = threadIdx.x; idx < G * 128; idx += 64 * kWaves) {
         const int hh = idx >> 7, c = idx & 127;
         float M = sm_m[0][hh];
@@ -298,11 +303,11 @@ tiles_done:
         }
         const int64_t bh = (int64_t)b * Hq + (int64_t)kvh * G + hh;
         if (MODE == kMerge && split < np) {
-            unsigned long long *w = words + (int64_t)split * pitch;
+            unsigned long long *w = words + (int64_t)split * kMergePitch;
             __hip_atomic_store(w + idx, tagged(o, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (c == 0) {
-                __hip_atomic_store(w + G * 128 + hh, tagged(M, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(w + G * 129 + hh, tagged(Z, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(w + kMergeStatsAt + hh, tagged(M, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(w + kMergeStatsAt + kMergeMaxG + hh, tagged(Z, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         } else if (MODE == kMerge) {
             // the stream's last range: every other range's (o, m, Z) for this element, all requested
@@ -314,10 +319,10 @@ tiles_done:
 #pragma unroll
                 for (int x = 0; x < kMergeMaxSplits - 1; ++x) {
                     if (x < np) {
-                        const unsigned long long *w = words + (int64_t)x * pitch;
+                        const unsigned long long *w = words + (int64_t)x * kMergePitch;
                         wo[x] = __hip_atomic_load(w + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        wm[x] = __hip_atomic_load(w + G * 128 + hh, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        wz[x] = __hip_atomic_load(w + G * 129 + hh, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        wm[x] = __hip_atomic_load(w + kMergeStatsAt + hh, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        wz[x] = __hip_atomic_load(w + kMergeStatsAt + kMergeMaxG + hh, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
                 }
                 bool all = true;
@@ -566,7 +571,7 @@ bool attn_merges_in_kernel(const Shape &s, int nsplit)
     if (!mfma_path(s) || nsplit < 2 || nsplit > kMergeMaxSplits) return false;
     const size_t streams = (size_t)s.batch * s.kv.n_kv_heads;
     const size_t G = s.n_q_heads / s.kv.n_kv_heads;
-    return streams <= (size_t)kMergeMaxStreams && streams * (nsplit - 1) * G * 130 <= kMergeWords;
+    return streams <= (size_t)kMergeMaxStreams && G <= (size_t)kMergeMaxG;
 }
 
 template <bool GATHER, bool PAGED>

@@ -45,7 +45,7 @@ inline bool mfma_path(const Shape &s) { return s.fast; }
 // Workspace: part_o fp32 [B][Hq][nsplit][d] followed by part_ml fp32 [B][Hq][nsplit][2].
 int attn_tile_tokens(const Shape &s);
 size_t attn_workspace_bytes(const Shape &s, int nsplit);
-// merge_in_kernel: with 2 .. 16 ranges per stream on the MFMA path the stream's last range merges
+// merge_in_kernel: with 2 .. 4 ranges per stream on the MFMA path the stream's last range merges
 // the others' partials inside the launch (through static device memory) when the shape fits
 // (attn_merges_in_kernel); otherwise partials go to the workspace and a merge kernel follows.
 bool attn_merges_in_kernel(const Shape &s, int nsplit);

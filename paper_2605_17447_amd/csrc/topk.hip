@@ -334,12 +334,30 @@ __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int b = blockIdx.x;
+    int32_t *out = sel_idx + (int64_t)b * kmax;
+    const float *srow = scores + (int64_t)b * bv.max_vis_len;
+
+    // The thread's 16 scores and its first two entries of the previous set are requested before
+    // the sequence's geometry is known (the rows are max_vis_len and kmax entries long whatever the
+    // sequence's own counts are): one memory round trip instead of two before the keys exist.
+    const int base = tid * kTopkPer;
+    const bool whole = base + kTopkPer <= bv.max_vis_len && (reinterpret_cast<uintptr_t>(srow + base) & 15u) == 0;
+    f32x4 raw[kTopkPer / 4];
+#pragma unroll
+    for (int v = 0; v < kTopkPer / 4; ++v) raw[v] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (whole) {
+#pragma unroll
+        for (int v = 0; v < kTopkPer / 4; ++v) raw[v] = *reinterpret_cast<const f32x4 *>(srow + base + 4 * v);
+    }
+    const int32_t *prev = prev_idx ? prev_idx + (int64_t)b * kmax : nullptr;
+    int prev0 = 0, prev1 = 0;
+    if (prev && tid < kmax) prev0 = prev[tid];
+    if (prev && tid + 1 < kmax) prev1 = prev[tid + 1];
+
     const SeqGeom geo = seq_geom(bv, b);
     const int N = geo.N;
     const int k = (int)min((int64_t)keep_count_dev(N, tau), kmax);
     const int pcnt = prev_cnt ? prev_cnt[b] : -1;
-    int32_t *out = sel_idx + (int64_t)b * kmax;
-    const float *srow = scores + (int64_t)b * bv.max_vis_len;
 
     if (k <= 0 || k >= N) {
         if (k >= N && k > 0)
@@ -350,16 +368,13 @@ __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(
     if (tid == 0) { s_theta_prev = 0xffffffffu; s_bad = 0; }
 
     // ---- the thread's 16 keys; tokens past N get key 0 and are never counted ----------------------
-    const int base = tid * kTopkPer;
     const int nvalid = min(max(N - base, 0), kTopkPer);
     uint32_t key[kTopkPer];
-    if (nvalid == kTopkPer && (reinterpret_cast<uintptr_t>(srow + base) & 15u) == 0) {
+    if (whole) {
 #pragma unroll
-        for (int v = 0; v < kTopkPer / 4; ++v) {
-            const f32x4 x = *reinterpret_cast<const f32x4 *>(srow + base + 4 * v);
+        for (int v = 0; v < kTopkPer / 4; ++v)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) key[4 * v + e] = order_key(x[e]);
-        }
+            for (int e = 0; e < 4; ++e) key[4 * v + e] = 4 * v + e < nvalid ? order_key(raw[v][e]) : 0u;
     } else {
 #pragma unroll
         for (int j = 0; j < kTopkPer; ++j) key[j] = j < nvalid ? order_key(srow[base + j]) : 0u;
@@ -369,10 +384,9 @@ __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(
     uint32_t lo = 0xffffffffu;
     int bad = 0;
     if (have_prev) {
-        const int32_t *prev = prev_idx + (int64_t)b * kmax;
         for (int r = tid; r < k; r += kTopkThreads) {
-            const int i = prev[r];
-            const int nx = (r + 1 < k) ? prev[r + 1] : 0x7fffffff;
+            const int i = r == tid ? prev0 : prev[r];
+            const int nx = (r + 1 < k) ? (r == tid ? prev1 : prev[r + 1]) : 0x7fffffff;
             if (i < 0 || i >= N || i >= nx) bad = 1;
             else lo = min(lo, order_key(srow[i]));
         }
