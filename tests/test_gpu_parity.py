@@ -202,6 +202,39 @@ def test_merged_pruned_attention_with_alternating_shapes():
         fb.set_tuning("splits_sparse", 0)
 
 
+def test_merged_pruned_attention_calls_on_three_streams_at_once():
+    """Up to four calls of this mode may be in flight on one GPU (they take different exchange
+    slots): three problems on three streams, enqueued without waiting for each other."""
+    probs = []
+    for i, (B, Hq, Hkv) in enumerate([(3, 28, 4), (2, 64, 8), (4, 16, 2)]):
+        case = TinyCase(seed=950 + i, B=B, Hq=Hq, Hkv=Hkv, d=128, n_vis=[1200 + 90 * j for j in range(B)],
+                        pre=[5 * j for j in range(B)], post=[60 + j for j in range(B)], dtype="bf16")
+        p = problem_from_case(case)
+        oc = p.oracle_args()
+        ref_sc, _, _ = oracle.focal_score(*oc)
+        ref_idx, ref_cnt = oracle.topk_fixation(ref_sc, p.vis_len, 0.1)
+        ref, _ = oracle.decode_attn(*oc, ref_idx, ref_cnt)
+        sel, selc = torch.from_numpy(ref_idx).to(DEV).contiguous(), torch.from_numpy(ref_cnt).to(DEV)
+        probs.append([p, sel, selc, ref, torch.zeros_like(p.q), None, torch.cuda.Stream()])
+    fb.set_tuning("splits_sparse", 3)
+    try:
+        for pr in probs:                               # the workspace size follows the range count
+            pr[5] = torch.empty(fo.workspace_bytes(fb.OP_SPARSE_DECODE_ATTN, pr[0].cache, pr[0].batch, pr[0].Hq, pr[1].shape[1]),
+                                dtype=torch.uint8, device=DEV)
+        torch.cuda.synchronize()
+        for rnd in range(6):
+            for p, sel, selc, ref, out, ws, st in probs:
+                out.zero_()
+            torch.cuda.synchronize()
+            for p, sel, selc, ref, out, ws, st in probs:
+                fo.sparse_decode_attn(p.cache, p.batch, p.q, p.scale, sel, selc, out, ws, stream=st)
+            torch.cuda.synchronize()
+            for i, (p, sel, selc, ref, out, ws, st) in enumerate(probs):
+                check_out(out, ref, f"round {rnd}, stream {i}")
+    finally:
+        fb.set_tuning("splits_sparse", 0)
+
+
 def test_pruned_attention_merged_inside_the_launch_replays_in_a_graph():
     """The tags come from a device-side epoch, so a captured call is fresh on every replay."""
     case = TinyCase(seed=77, B=3, Hq=28, Hkv=4, d=128, n_vis=[1100, 700, 1300], pre=[10, 3, 0], post=[50, 30, 9], dtype="bf16")
