@@ -3,9 +3,12 @@
 // One launch covers both branches of Eq. 2: the focal branch attends all cached tokens
 // (dense), the non-focal branch attends the kept set T u F (gather: text before the image
 // span, the selected image tokens, text after the span).  The attended list is cut into
-// `nsplit` position ranges; a workgroup owns one (sequence, kv head, range), its four waves
-// walk interleaved 32-token tiles with a private online softmax each, merge through LDS and
-// write one fp32 partial (m, Z, acc[d]); a second small kernel merges the partials.
+// `nsplit` position ranges; a workgroup owns one (sequence, kv head, range), its four or
+// eight waves walk 32-token tiles with a private online softmax each and merge through LDS.
+// What leaves the workgroup depends on the mode (see kPartial / kDirect / kMerge below): an fp32
+// partial (m, Z, acc[d]) that a second small kernel merges, the final output when the stream has
+// one range, or -- pruned attention with a few ranges per stream -- a partial handed to the
+// stream's last workgroup inside the same launch.
 //
 // bf16, head_dim 128 path: the G = Hq/Hkv query heads that share a kv head form the 16-wide
 // side of v_mfma_f32_16x16x32_bf16 (rows beyond G are zero), tokens the other side.
