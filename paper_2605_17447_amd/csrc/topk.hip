@@ -9,7 +9,7 @@
 // a sample of the scores; the writing is spread over several 1024-thread workgroups per
 // sequence; see topk_kernel.  The result never depends on either bound.
 
-#include "kernels.hpp"
+#include "topk_dev.hpp"
 
 namespace fastocr {
 
@@ -17,93 +17,6 @@ constexpr int kTopkThreads = 1024;
 constexpr int kTopkWaves = kTopkThreads / 64;
 constexpr int kCandCap = 4096;
 constexpr int kLdsKeyCap = 24576;
-
-__device__ __forceinline__ uint32_t order_key(float x)
-{
-    uint32_t u = __float_as_uint(x);
-    if ((u << 1) == 0u) u = 0u;                 // -0.0 compares equal to +0.0
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-__device__ __forceinline__ int keep_count_dev(int n, double tau)
-{
-#pragma clang fp contract(off)
-    if (n <= 0 || !(tau > 0.0)) return 0;
-    double x = ceil(tau * (double)n - 1e-9);
-    if (x < 0.0) x = 0.0;
-    if (x > (double)n) x = (double)n;
-    return (int)x;
-}
-
-// k-th largest (1-based rank `k`) of keys[0..n): returns the threshold key and, through
-// *ties_needed, how many keys equal to it belong to the top k.  All threads must call.
-// With stop_shift > 0 only the bits at and above it are resolved: the result is the k-th largest
-// key with its low bits cleared, a lower bound of it (and *ties_needed is meaningless).
-// Two histograms alternate between the passes (the idle one is cleared while the other is being
-// filled), which leaves two workgroup barriers per 8-bit pass.
-__device__ uint32_t radix_select(const uint32_t *keys, int n, int k, uint32_t (*hist)[256], int *s_pick,
-                                 int *ties_needed, int stop_shift = 0)
-{
-    const int tid = threadIdx.x, lane = tid & 63;
-    uint32_t prefix = 0u, mask = 0u;
-    int kk = k, cur = 0;
-    if (tid < 256) hist[0][tid] = 0u;
-    __syncthreads();
-    for (int shift = 24; shift >= stop_shift; shift -= 8) {
-        uint32_t *h = hist[cur];
-        if (tid < 256) hist[cur ^ 1][tid] = 0u;
-        for (int i0 = 0; i0 < n; i0 += kTopkThreads) {
-            const int i = i0 + tid;
-            const bool in = i < n;
-            const uint32_t key = in ? keys[i] : 0u;
-            const bool live = in && ((key & mask) == prefix);
-            const uint32_t dgt = (key >> shift) & 255u;
-            // a whole wave on one digit (the usual case for the exponent byte) adds once
-            const uint64_t live_mask = __ballot(live);
-            if (live_mask) {
-                const int first = __builtin_amdgcn_readfirstlane(__ffsll((long long)live_mask) - 1);
-                const uint32_t d0 = (uint32_t)__builtin_amdgcn_readlane((int)dgt, first);
-                const uint64_t same = __ballot(live && dgt == d0);
-                if (same == live_mask) {
-                    if (lane == first) atomicAdd(&h[d0], (uint32_t)__popcll(live_mask));
-                } else if (live) {
-                    atomicAdd(&h[dgt], 1u);
-                }
-            }
-        }
-        __syncthreads();
-        if (tid < 64) {
-            // lane owns digits 255-4*lane .. 252-4*lane (descending)
-            uint32_t c[4], tot = 0u;
-#pragma unroll
-            for (int x = 0; x < 4; ++x) { c[x] = h[255 - (4 * lane + x)]; tot += c[x]; }
-            const uint32_t incl = (uint32_t)wave_scan_incl((int)tot);
-            const uint32_t above = incl - tot;           // keys in strictly larger digits
-            if (above < (uint32_t)kk && incl >= (uint32_t)kk) {
-                // the k-th key falls into one of this lane's four digits
-                uint32_t run = above;
-                for (int x = 0; x < 4; ++x) {
-                    if (run + c[x] >= (uint32_t)kk) {
-                        s_pick[0] = 255 - (4 * lane + x);
-                        s_pick[1] = kk - (int)run;
-                        break;
-                    }
-                    run += c[x];
-                }
-            }
-        }
-        __syncthreads();
-        // the next pass writes s_pick only after its own first barrier, which every thread
-        // reaches after this read
-        prefix |= ((uint32_t)s_pick[0]) << shift;
-        mask |= 255u << shift;
-        kk = s_pick[1];
-        cur ^= 1;
-    }
-    __syncthreads();          // callers may reuse keys, hist and s_pick right away
-    *ties_needed = kk;
-    return prefix;
-}
 
 // General form, for image spans beyond the register-resident kernel below.
 // Grid (parts, batch).  The workgroups of a sequence do not talk to each other: each one loads ALL
@@ -198,7 +111,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_general_kernel(
             if (r < ns) {
                 int unused;
                 // the upper 16 bits are enough for a bound (fp32: sign, exponent, 7 mantissa bits)
-                const uint32_t ths = radix_select(cand, ns, r, hist, s_pick, &unused, 16);
+                const uint32_t ths = radix_select<kTopkThreads>(cand, ns, r, hist, s_pick, &unused, 16);
                 theta0 = max(theta0, ths);
             }
             __syncthreads();
@@ -221,8 +134,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_general_kernel(
         nc = s_ncand;
         from_cand = nc >= k && nc <= kCandCap;
     }
-    if (from_cand) theta = radix_select(cand, nc, k, hist, s_pick, &ties);
-    else theta = radix_select(keys, N, k, hist, s_pick, &ties);
+    if (from_cand) theta = radix_select<kTopkThreads>(cand, nc, k, hist, s_pick, &ties);
+    else theta = radix_select<kTopkThreads>(keys, N, k, hist, s_pick, &ties);
 
     // ---- this workgroup's segment of the token range, and how much of the result precedes it ------
     const int seg = ((N + nparts - 1) / nparts + 63) / 64 * 64;
@@ -285,45 +198,14 @@ __global__ __launch_bounds__(kTopkThreads) void topk_general_kernel(
     if (part == 0 && tid == 0) sel_cnt[b] = k;
 }
 
-// Image spans of up to kTopkRegKeys tokens: one workgroup per sequence, thread t keeps the keys of
-// tokens 16t .. 16t+15 in registers.  The candidate list (keys at or above the bound theta0, see
-// above) and the result are both written in index order through block-wide prefix sums, so no
-// atomics or index arrays are needed, and the scores are read exactly once.
 constexpr int kTopkPer = 16;
 constexpr int kTopkRegKeys = kTopkThreads * kTopkPer;
-constexpr int kRegCandCap = 8192;          // candidates this kernel selects among (keep ratios up to 1/3 at 16384 tokens)
-
-// exclusive prefix sums of (a, c) over the 1024 threads; totals through *ta, *tc.  All threads call.
-// w_ac: 2 x 16 wave totals, 16-byte aligned.
-typedef int i32x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ void block_scan2(int a, int c, int *w_ac, int &a_excl, int &c_excl, int *ta, int *tc)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int ai = wave_scan_incl(a), ci = wave_scan_incl(c);
-    if (lane == 63) { w_ac[wave] = ai; w_ac[kTopkWaves + wave] = ci; }
-    __syncthreads();
-    int ab = 0, cb = 0, at = 0, ct = 0;
-#pragma unroll
-    for (int v = 0; v < kTopkWaves / 4; ++v) {
-        const i32x4 x = reinterpret_cast<const i32x4 *>(w_ac)[v], y = reinterpret_cast<const i32x4 *>(w_ac)[kTopkWaves / 4 + v];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if (4 * v + e < wave) { ab += x[e]; cb += y[e]; }
-            at += x[e];
-            ct += y[e];
-        }
-    }
-    a_excl = ab + ai - a;
-    c_excl = cb + ci - c;
-    *ta = at;
-    *tc = ct;
-    __syncthreads();
-}
 
 __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(
     const float *__restrict__ scores, BatchDev bv, double tau, const int32_t *prev_idx,
     const int32_t *prev_cnt, int32_t *sel_idx, int32_t *sel_cnt, int64_t kmax)
 {
+
     extern __shared__ uint32_t dyn_keys[];          // all keys, only when the candidate list fails
     __shared__ uint32_t hist[2][256];
     __shared__ uint32_t cand[kRegCandCap];
@@ -332,134 +214,11 @@ __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(
     __shared__ int s_bad;
     __shared__ __align__(16) int w_ac[2 * kTopkWaves];
 
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int b = blockIdx.x;
-    int32_t *out = sel_idx + (int64_t)b * kmax;
-    const float *srow = scores + (int64_t)b * bv.max_vis_len;
-
-    // The thread's 16 scores and its first two entries of the previous set are requested before
-    // the sequence's geometry is known (the rows are max_vis_len and kmax entries long whatever the
-    // sequence's own counts are): one memory round trip instead of two before the keys exist.
-    const int base = tid * kTopkPer;
-    const bool whole = base + kTopkPer <= bv.max_vis_len && (reinterpret_cast<uintptr_t>(srow + base) & 15u) == 0;
-    f32x4 raw[kTopkPer / 4];
-#pragma unroll
-    for (int v = 0; v < kTopkPer / 4; ++v) raw[v] = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (whole) {
-#pragma unroll
-        for (int v = 0; v < kTopkPer / 4; ++v) raw[v] = *reinterpret_cast<const f32x4 *>(srow + base + 4 * v);
-    }
-    const int32_t *prev = prev_idx ? prev_idx + (int64_t)b * kmax : nullptr;
-    int prev0 = 0, prev1 = 0;
-    if (prev && tid < kmax) prev0 = prev[tid];
-    if (prev && tid + 1 < kmax) prev1 = prev[tid + 1];
-
-    const SeqGeom geo = seq_geom(bv, b);
-    const int N = geo.N;
-    const int k = (int)min((int64_t)keep_count_dev(N, tau), kmax);
-    const int pcnt = prev_cnt ? prev_cnt[b] : -1;
-
-    if (k <= 0 || k >= N) {
-        if (k >= N && k > 0)
-            for (int i = tid; i < N; i += kTopkThreads) out[i] = i;
-        if (tid == 0) sel_cnt[b] = k <= 0 ? 0 : N;
-        return;
-    }
-    if (tid == 0) { s_theta_prev = 0xffffffffu; s_bad = 0; }
-
-    // ---- the thread's 16 keys; tokens past N get key 0 and are never counted ----------------------
-    const int nvalid = min(max(N - base, 0), kTopkPer);
-    uint32_t key[kTopkPer];
-    if (whole) {
-#pragma unroll
-        for (int v = 0; v < kTopkPer / 4; ++v)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) key[4 * v + e] = 4 * v + e < nvalid ? order_key(raw[v][e]) : 0u;
-    } else {
-#pragma unroll
-        for (int j = 0; j < kTopkPer; ++j) key[j] = j < nvalid ? order_key(srow[base + j]) : 0u;
-    }
-    // ---- bound from the previous set: k distinct valid tokens (strictly ascending) or ignored ----
-    const bool have_prev = prev_idx && pcnt == k;
-    uint32_t lo = 0xffffffffu;
-    int bad = 0;
-    if (have_prev) {
-        for (int r = tid; r < k; r += kTopkThreads) {
-            const int i = r == tid ? prev0 : prev[r];
-            const int nx = (r + 1 < k) ? (r == tid ? prev1 : prev[r + 1]) : 0x7fffffff;
-            if (i < 0 || i >= N || i >= nx) bad = 1;
-            else lo = min(lo, order_key(srow[i]));
-        }
-    }
-    // ---- bound from a sample: the first key of every thread (every 16th token) ---------------------
-    const int ns = (N + kTopkPer - 1) / kTopkPer;
-    if (tid < ns) cand[tid] = key[0];
-    __syncthreads();
-    uint32_t theta0 = 0u;
-    if (have_prev) {
-        if (bad) s_bad = 1;
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) lo = min(lo, (uint32_t)__shfl_xor((int)lo, o));
-        if (lane == 0) atomicMin(&s_theta_prev, lo);
-        __syncthreads();
-        if (!s_bad) theta0 = s_theta_prev;
-    }
-    {
-        // about 1.5 k of the N tokens should reach the bound: rank 1.5 k ns / N in the sample, plus slack
-        const int r = (int)(((int64_t)3 * k * ns) / ((int64_t)2 * N)) + 24;
-        if (r < ns) {
-            int unused;
-            // the upper 16 bits are enough for a bound (fp32: sign, exponent, 7 mantissa bits)
-            const uint32_t ths = radix_select(cand, ns, r, hist, s_pick, &unused, 16);
-            theta0 = max(theta0, ths);
-        }
-        __syncthreads();
-    }
-    // ---- candidates, compacted in index order --------------------------------------------------------
-    int mine = 0;
-#pragma unroll
-    for (int j = 0; j < kTopkPer; ++j) mine += (j < nvalid && key[j] >= theta0) ? 1 : 0;
-    int pos, unused_excl, nc, unused_tot;
-    block_scan2(mine, 0, w_ac, pos, unused_excl, &nc, &unused_tot);
-    const bool from_cand = nc >= k && nc <= kRegCandCap;
-    uint32_t theta;
-    int ties;
-    if (from_cand) {
-#pragma unroll
-        for (int j = 0; j < kTopkPer; ++j)
-            if (j < nvalid && key[j] >= theta0) cand[pos++] = key[j];
-        __syncthreads();
-        theta = radix_select(cand, nc, k, hist, s_pick, &ties);
-    } else {
-#pragma unroll
-        for (int j = 0; j < kTopkPer; ++j)
-            if (j < nvalid) dyn_keys[base + j] = key[j];
-        __syncthreads();
-        theta = radix_select(dyn_keys, N, k, hist, s_pick, &ties);
-    }
-    // ---- the result in ascending index order; ties go to the lowest indices ------------------------
-    // bit j of the masks: key j of this thread lies above / on the threshold
-    uint32_t m_gt = 0u, m_eq = 0u;
-#pragma unroll
-    for (int j = 0; j < kTopkPer; ++j) {
-        m_gt |= (j < nvalid && key[j] > theta) ? (1u << j) : 0u;
-        m_eq |= (j < nvalid && key[j] == theta) ? (1u << j) : 0u;
-    }
-    int gt_excl, eq_excl, gt_tot, eq_tot;
-    block_scan2(__popc(m_gt), __popc(m_eq), w_ac, gt_excl, eq_excl, &gt_tot, &eq_tot);
-    // of this thread's keys on the threshold, the first (ties - eq_excl) are still wanted
-    uint32_t take = m_gt;
-    {
-        int want = min(max(ties - eq_excl, 0), __popc(m_eq));
-        uint32_t rest = m_eq;
-        while (want > 0) { const uint32_t low = rest & (0u - rest); take |= low; rest ^= low; --want; }
-    }
-    int opos = gt_excl + min(ties, eq_excl);
-    while (take) {
-        out[opos++] = base + __ffs((int)take) - 1;
-        take &= take - 1u;
-    }
-    if (tid == 0) sel_cnt[b] = k;
+    TopkRegShared sh;
+    sh.hist = hist; sh.cand = cand; sh.all_keys = dyn_keys; sh.pick = s_pick;
+    sh.theta_prev = &s_theta_prev; sh.bad = &s_bad; sh.w_ac = w_ac;
+    topk_reg_body<kTopkThreads, kTopkPer>(scores, bv, blockIdx.x, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax, sh,
+                                          [](int, int) {});
 }
 
 // Workgroups per sequence: one per 1024 image tokens, as long as the grid still fits the chip in
