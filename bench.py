@@ -268,6 +268,7 @@ def main():
                                % (wl.config_id, wl.name, B, Hq, Hkv, d, max_vis, bt.prefix[0], t_first + n_warm,
                                   t_first + total - 1, tau, L)},
         "roofline": roofline,
+        "sequence_layer_steps_per_s": round(value * B, 1),
     }
 
     # ---- extras: comparator and per-kernel breakdown (outside the timed region) ---------------
