@@ -569,7 +569,8 @@ def test_config4_full_size_in_the_benchmark_launch_configuration():
     assert np.allclose(mass.cpu().numpy(), ref_mass, atol=2e-5)
     # the default keep ratio, the paper's sweep towards 2 %, its 25 % setting and the very sparse
     # regime of its qualitative study (66 tokens of 16384)
-    for tau in (0.05, 0.02, 0.25, 0.004):
+    # ... and tau = 1, the configuration's dense comparator through the pruned path (every image token kept)
+    for tau in (0.05, 0.02, 0.25, 0.004, 1.0):
         ref_idx, ref_cnt = oracle.topk_fixation(ref_sc, p.vis_len, tau)
         idx, cnt = p.topk(sc, tau)
         idx_h, cnt_h, sc_h = idx.cpu().numpy(), cnt.cpu().numpy(), sc.cpu().numpy()
@@ -605,3 +606,13 @@ def test_other_configurations_at_full_size_with_automatic_launch_shapes(cfg):
     full_check(p, 0.05, f"config {cfg} full size", exact_topk=True)
     if cfg == 3:
         full_check(p, 0.10, "config 3 full size, tau 0.10", exact_topk=True)
+
+
+def test_more_sequences_than_compute_units():
+    """Batch 300 of short sequences: beyond the single-kernel forms (one workgroup per sequence and
+    compute unit at least) and beyond the in-launch merge of pruned attention; every call takes its
+    general form."""
+    B = 300
+    case = TinyCase(seed=1234, B=B, Hq=8, Hkv=2, d=128, n_vis=[64 + (7 * i) % 90 for i in range(B)],
+                    pre=[i % 6 for i in range(B)], post=[1 + i % 9 for i in range(B)], dtype="bf16")
+    full_check(problem_from_case(case), 0.1, "batch 300")
