@@ -183,12 +183,16 @@ __device__ __forceinline__ void topk_reg_body(
 
     // ---- the thread's 16 keys; tokens past N get key 0 and are never counted ----------------------
     const int nvalid = min(max(N - base, 0), PER);
+    // which of the thread's keys are real, as a bit mask in a vector register (PER lane masks kept in
+    // scalar registers, as `j < nvalid` would have it, take most of the scalar file)
+    const uint32_t vmask = nvalid >= 32 ? 0xffffffffu : ((1u << nvalid) - 1u);
+    auto real = [&](int j) { return ((vmask >> j) & 1u) != 0u; };
     uint32_t key[PER];
     if (whole) {
 #pragma unroll
         for (int v = 0; v < PER / 4; ++v)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) key[4 * v + e] = 4 * v + e < nvalid ? order_key(raw[v][e]) : 0u;
+            for (int e = 0; e < 4; ++e) key[4 * v + e] = real(4 * v + e) ? order_key(raw[v][e]) : 0u;
     } else {
 #pragma unroll
         for (int j = 0; j < PER; ++j) key[j] = j < nvalid ? order_key(srow[base + j]) : 0u;
@@ -232,7 +236,7 @@ __device__ __forceinline__ void topk_reg_body(
     // ---- candidates, compacted in index order --------------------------------------------------------
     int mine = 0;
 #pragma unroll
-    for (int j = 0; j < PER; ++j) mine += (j < nvalid && key[j] >= theta0) ? 1 : 0;
+    for (int j = 0; j < PER; ++j) mine += (real(j) && key[j] >= theta0) ? 1 : 0;
     int pos, unused_excl, nc, unused_tot;
     block_scan2<THREADS>(mine, 0, sh.w_ac, pos, unused_excl, &nc, &unused_tot);
     const bool from_cand = nc >= k && nc <= kRegCandCap;
@@ -241,13 +245,13 @@ __device__ __forceinline__ void topk_reg_body(
     if (from_cand) {
 #pragma unroll
         for (int j = 0; j < PER; ++j)
-            if (j < nvalid && key[j] >= theta0) sh.cand[pos++] = key[j];
+            if (real(j) && key[j] >= theta0) sh.cand[pos++] = key[j];
         __syncthreads();
         theta = radix_select<THREADS>(sh.cand, nc, k, sh.hist, sh.pick, &ties);
     } else {
 #pragma unroll
         for (int j = 0; j < PER; ++j)
-            if (j < nvalid) sh.all_keys[base + j] = key[j];
+            if (real(j)) sh.all_keys[base + j] = key[j];
         __syncthreads();
         theta = radix_select<THREADS>(sh.all_keys, N, k, sh.hist, sh.pick, &ties);
     }
@@ -256,8 +260,8 @@ __device__ __forceinline__ void topk_reg_body(
     uint32_t m_gt = 0u, m_eq = 0u;
 #pragma unroll
     for (int j = 0; j < PER; ++j) {
-        m_gt |= (j < nvalid && key[j] > theta) ? (1u << j) : 0u;
-        m_eq |= (j < nvalid && key[j] == theta) ? (1u << j) : 0u;
+        m_gt |= (real(j) && key[j] > theta) ? (1u << j) : 0u;
+        m_eq |= (real(j) && key[j] == theta) ? (1u << j) : 0u;
     }
     int gt_excl, eq_excl, gt_tot, eq_tot;
     block_scan2<THREADS>(__popc(m_gt), __popc(m_eq), sh.w_ac, gt_excl, eq_excl, &gt_tot, &eq_tot);
