@@ -113,7 +113,8 @@ def set_tuning(key: str, value: int) -> None:
 
 
 def _ptr(t: Optional[torch.Tensor]):
-    return None if t is None else ctypes.c_void_p(t.data_ptr())
+    # the entry points' argtypes are declared, so a plain address converts (None is NULL)
+    return None if t is None else t.data_ptr()
 
 
 def _dtype_code(t: torch.Tensor) -> int:
@@ -137,6 +138,19 @@ class KvCache:
     block_table: Optional[torch.Tensor] = None
 
     def view(self) -> KvView:
+        """The C view of the cache.  Built once and kept while the tensors stay what they were
+        (same addresses, shapes and strides): building it costs more host time than a small launch."""
+        k, v, bt = self.k, self.v, self.block_table
+        key = (k.data_ptr(), v.data_ptr(), k.shape, k.stride(), self.layout,
+               None if bt is None else (bt.data_ptr(), bt.shape))
+        cached = self.__dict__.get("_view")
+        if cached is not None and cached[0] == key:
+            return cached[1]
+        view = self._build_view()
+        self.__dict__["_view"] = (key, view)
+        return view
+
+    def _build_view(self) -> KvView:
         k, v = self.k, self.v
         assert k.shape == v.shape and k.dtype == v.dtype and k.stride() == v.stride()
         assert k.stride(-1) == 1
@@ -173,15 +187,22 @@ class SeqBatch:
                         max(vis_len) if len(vis_len) else 0)
 
     def view(self) -> BatchView:
-        for t in (self.seq_len, self.vis_start, self.vis_len):
-            assert t.dtype == torch.int32 and t.is_contiguous()
-        return BatchView(self.seq_len.shape[0], self.seq_len.data_ptr(), self.vis_start.data_ptr(),
-                         self.vis_len.data_ptr(), int(self.max_seq_len), int(self.max_vis_len))
+        """The C view of the batch; kept while the arrays and the maxima stay what they were."""
+        a, b, c = self.seq_len, self.vis_start, self.vis_len
+        key = (a.data_ptr(), b.data_ptr(), c.data_ptr(), a.shape, self.max_seq_len, self.max_vis_len)
+        cached = self.__dict__.get("_view")
+        if cached is not None and cached[0] == key:
+            return cached[1]
+        for t in (a, b, c):
+            assert t.dtype == torch.int32 and t.is_contiguous() and t.shape == a.shape
+        view = BatchView(a.shape[0], a.data_ptr(), b.data_ptr(), c.data_ptr(), int(self.max_seq_len), int(self.max_vis_len))
+        self.__dict__["_view"] = (key, view)
+        return view
 
 
 def _stream_handle(stream: Optional[torch.cuda.Stream]):
     s = stream if stream is not None else torch.cuda.current_stream()
-    return ctypes.c_void_p(s.cuda_stream)
+    return s.cuda_stream or None          # the default stream's handle is 0 = NULL
 
 
 def workspace_bytes(op: int, cache: Optional[KvCache], batch: SeqBatch, n_q_heads: int, kmax: int = 0) -> int:

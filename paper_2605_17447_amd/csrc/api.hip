@@ -19,11 +19,13 @@ int g_tune_attn_waves = 4;
 static int g_tune_attn_merge = 1;          // pruned attention: ranges of a stream merged inside the launch (0 never, 1 yes)
 int g_tune_barrier_spin_us = 250000;      // bounded wait of the resident kernels' per-sequence barrier
 static int g_tune_splits[4] = {0, 0, 0, 0};     // indexed by fastocr_op
+static int g_tune_timer_every = 1;          // per-kernel timers: which launches record events (every n-th)
 
 // ---- per-kernel timers ------------------------------------------------------------------
 struct KernelTimer {
     int capacity = 0;
     int count = 0;
+    unsigned seen = 0;      // launches of the kernel since the timer was enabled
     hipEvent_t *start = nullptr;
     hipEvent_t *stop = nullptr;
 };
@@ -33,6 +35,8 @@ TimerEvents timer_events(int kernel)
 {
     KernelTimer &t = g_timers[kernel];
     if (t.count >= t.capacity) return TimerEvents{nullptr, nullptr};
+    // an event pair costs the stream a few microseconds: only every g_tune_timer_every-th launch carries one
+    if (t.seen++ % (unsigned)g_tune_timer_every != 0u) return TimerEvents{nullptr, nullptr};
     const int i = t.count++;
     return TimerEvents{t.start[i], t.stop[i]};
 }
@@ -449,6 +453,7 @@ int fastocr_set_tuning(const char *key, int value)
     else if (!strcmp(key, "splits_sparse")) g_tune_splits[FASTOCR_OP_SPARSE_DECODE_ATTN] = value;
     else if (!strcmp(key, "splits_dense")) g_tune_splits[FASTOCR_OP_DENSE_DECODE_ATTN] = value;
     else if (!strcmp(key, "attn_waves")) g_tune_attn_waves = value;
+    else if (!strcmp(key, "timer_every") && value >= 1) g_tune_timer_every = value;
     else if (!strcmp(key, "attn_merge") && value <= 2) g_tune_attn_merge = value;
     else if (!strcmp(key, "barrier_spin_us") && value >= 0) g_tune_barrier_spin_us = value ? value : 250000;
     else if (!strcmp(key, "score_resident") && value >= 0 && value <= 2) g_tune_score_resident = value;
