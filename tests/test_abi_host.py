@@ -183,3 +183,44 @@ def test_tuning_keys(lib):
     assert lib.fastocr_set_tuning(None, 1) == fb.EINVAL
     assert lib.fastocr_kernel_timer_enable(99, 4) == fb.EINVAL
     assert lib.fastocr_kernel_timer_read(0, None, 0) == 0
+    assert lib.fastocr_set_tuning(b"timer_every", 0) == fb.EINVAL
+    assert lib.fastocr_set_tuning(b"timer_every", 4) == fb.OK
+    assert lib.fastocr_set_tuning(b"timer_every", 1) == fb.OK
+
+
+def test_binding_views_follow_their_tensors():
+    """The binding keeps the C views of a cache and a batch; a changed tensor, shape or maximum must
+    give a new view, an unchanged one the same view."""
+    import torch
+    import paper_2605_17447_amd as fo
+    k = torch.zeros(2, 4, 40, 128, dtype=torch.bfloat16)
+    v = torch.zeros_like(k)
+    cache = fo.KvCache(k, v)
+    a = cache.view()
+    assert cache.view() is a
+    assert (a.k, a.v, a.n_kv_heads, a.head_dim, a.stride_token, a.stride_head, a.stride_seq) == \
+           (k.data_ptr(), v.data_ptr(), 4, 128, 128, 40 * 128, 4 * 40 * 128)
+    cache.k, cache.v = k[:, :2], v[:, :2]                     # same addresses, fewer heads
+    b = cache.view()
+    assert b is not a and b.n_kv_heads == 2 and b.stride_seq == 4 * 40 * 128
+    k2 = torch.zeros_like(k)
+    cache.k, cache.v = k2, v
+    assert cache.view().k == k2.data_ptr()
+    cache = fo.KvCache(k.permute(0, 2, 1, 3).contiguous(), v.permute(0, 2, 1, 3).contiguous(), layout="bshd")
+    c = cache.view()
+    assert (c.stride_token, c.stride_head) == (4 * 128, 128)
+    table = torch.zeros(2, 3, dtype=torch.int32)
+    paged = fo.KvCache(torch.zeros(6, 4, 16, 128), torch.zeros(6, 4, 16, 128), block_table=table)
+    p = paged.view()
+    assert (p.page_tokens, p.stride_page, p.max_pages_per_seq, p.block_table) == (16, 4 * 16 * 128, 3, table.data_ptr())
+    paged.block_table = torch.zeros(2, 5, dtype=torch.int32)
+    assert paged.view().max_pages_per_seq == 5
+
+    batch = fo.SeqBatch.from_lists([30, 40], [2, 3], [20, 25], "cpu")
+    x = batch.view()
+    assert batch.view() is x and (x.batch, x.max_seq_len, x.max_vis_len) == (2, 40, 25)
+    batch.max_seq_len = 41
+    y = batch.view()
+    assert y is not x and y.max_seq_len == 41
+    batch.seq_len = torch.tensor([31, 41], dtype=torch.int32)
+    assert batch.view().seq_len == batch.seq_len.data_ptr()

@@ -616,3 +616,33 @@ def test_more_sequences_than_compute_units():
     case = TinyCase(seed=1234, B=B, Hq=8, Hkv=2, d=128, n_vis=[64 + (7 * i) % 90 for i in range(B)],
                     pre=[i % 6 for i in range(B)], post=[1 + i % 9 for i in range(B)], dtype="bf16")
     full_check(problem_from_case(case), 0.1, "batch 300")
+
+
+def test_kernel_timer_records_every_nth_launch():
+    """The per-kernel event timer: every launch by default, every n-th with "timer_every" n (counted
+    from the enable call), never more than the capacity; the timed launches' results are unchanged."""
+    case = TinyCase(seed=21, B=2, Hq=28, Hkv=4, d=128, n_vis=[900, 400], pre=[10, 3], post=[30, 9], dtype="bf16")
+    p = problem_from_case(case)
+    ref, _, _ = p.scores()
+    ref = ref.clone()
+    kid = fb.KERNEL_SCORE_LOGITS
+    try:
+        fb.kernel_timer_enable(kid, 16)
+        for _ in range(5):
+            sc, _, _ = p.scores()
+        ms = fb.kernel_timer_read(kid)
+        assert len(ms) == 5 and all(0.0 < x < 5.0 for x in ms)
+        fb.set_tuning("timer_every", 3)
+        fb.kernel_timer_enable(kid, 16)
+        for _ in range(8):
+            sc, _, _ = p.scores()
+        assert torch.equal(sc, ref)
+        ms = fb.kernel_timer_read(kid)
+        assert len(ms) == 3 and all(0.0 < x < 5.0 for x in ms)          # launches 0, 3 and 6
+        fb.kernel_timer_enable(kid, 2)
+        for _ in range(10):
+            p.scores()
+        assert len(fb.kernel_timer_read(kid)) == 2
+    finally:
+        fb.set_tuning("timer_every", 1)
+        fb.kernel_timer_enable(kid, 0)
