@@ -245,7 +245,11 @@ hipError_t launch_topk(const float *scores, const BatchDev &bv, int batch, doubl
 {
     const int lds_keys = bv.max_vis_len <= kLdsKeyCap ? bv.max_vis_len : 0;
     const size_t dyn = (size_t)lds_keys * sizeof(uint32_t);
-    static bool attr_set = false;
+    // once per device: the opt-in belongs to the device's copy of the code
+    static bool attr_set_on[64] = {false};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    bool &attr_set = attr_set_on[dev];
     if (!attr_set) {
         // gfx950 has 160 KB of LDS per workgroup; the keys of up to 24576 tokens take 96 KB next to
         // the static candidate arrays.  If the runtime refuses the opt-in, a launch that needs it
