@@ -124,10 +124,13 @@ static int choose_splits(int op, const Shape &s, int max_positions)
         const int target_wg = fast ? kNumCU : 8 * kNumCU;
         if (fast && op == FASTOCR_OP_SPARSE_DECODE_ATTN && g_tune_attn_merge) {
             // pruned attention is short: one launch whose eight-wave workgroups fill the chip once,
-            // the ranges of a stream merged inside the launch; a stream is only cut when that leaves
-            // a wave two tiles or more (measured: below that the merge costs what the cut saves)
+            // the ranges of a stream merged inside the launch.  Up to 16 tiles one workgroup has the
+            // whole list in flight at once (two tiles per wave) and a cut only adds the merge; beyond
+            // that a range per 12 tiles measured best (25 tiles, 4 or 32 streams: 15.4 / 13.2 / 11.5 /
+            // 11.7 us with 1 / 2 / 3 / 4 ranges; 40 tiles: 18.6 / 16.0 / 13.7 / 13.9 us)
             int n = kNumCU / (streams > 0 ? streams : 1);
-            n = n < (ntile + 15) / 16 ? n : (ntile + 15) / 16;
+            const int by_len = ntile <= 16 ? 1 : (ntile + 11) / 12;
+            n = n < by_len ? n : by_len;
             n = n < 1 ? 1 : n;
             if (n == 1 || attn_merges_in_kernel(s, n)) return n;
         }

@@ -66,6 +66,7 @@ def _draw(rng):
 def test_random_small_problems(seed):
     rng = np.random.default_rng(1000 + seed)
     done = 0
+    timeouts_before = fb.exchange_timeouts()          # counted since the library was loaded
     for n in range(40):
         c = _draw(rng)
         what = f"random seed {seed} case {n}: " + ", ".join(f"{k}={v}" for k, v in c.items())
@@ -97,4 +98,4 @@ def test_random_small_problems(seed):
             fb.set_tuning("attn_merge", 1)
             fb.set_tuning("attn_waves", 4)
     assert done >= 30
-    assert fb.exchange_timeouts() == 0
+    assert fb.exchange_timeouts() == timeouts_before
