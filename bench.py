@@ -240,9 +240,10 @@ def main():
     e = 2 if wl.dtype == "bf16" else 4
     R = Hkv * d * e
     mean_S = float(seq_lens[n_warm:].float().mean().item())
-    score_bytes = B * (mean_S * R + Hq * d * e)                 # K rows of every cached token + the queries
+    scores_out = 4 * float(sum(bt.n_vis))                       # the fp32 scores written
+    score_bytes = B * (mean_S * R + Hq * d * e) + scores_out    # K rows of every cached token + the queries + the scores
     if focal_mode:
-        score_bytes = B * (mean_S * 2 * R + 2 * Hq * d * e)     # K and V rows, queries in, outputs out
+        score_bytes = B * (mean_S * 2 * R + 2 * Hq * d * e) + scores_out     # K and V rows, queries in, outputs and scores out
     k_ms = float(np.mean(logits_ms)) if logits_ms else float("nan")
     achieved = score_bytes / (k_ms * 1e-3) / 1e9
     traffic = None
