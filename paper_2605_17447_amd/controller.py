@@ -58,11 +58,23 @@ class FixationController:
         self.kept_from: Optional[object] = None     # None: no set yet; "F_last"; or a layer index
         self._ws = None
         self._ws_bytes = 0
+        # workspace sizes are asked for once per layer, for the longest sequences the run will see
+        # (a size never shrinks as sequences grow), not at every step
+        self._bound_seq, self._bound_vis = int(max_seq_len), int(max_vis_len)
+        self._need = {}
 
     def _workspace(self, cache, batch):
-        need = 0
-        for op in (_b.OP_FOCAL_ATTN_SCORE, _b.OP_TOPK_FIXATION, _b.OP_SPARSE_DECODE_ATTN, _b.OP_DENSE_DECODE_ATTN):
-            need = max(need, self.ops.workspace_bytes(op, cache, batch, self.n_q_heads, self.kmax))
+        if batch.max_seq_len > self._bound_seq or batch.max_vis_len > self._bound_vis:
+            self._bound_seq = max(self._bound_seq, int(batch.max_seq_len))
+            self._bound_vis = max(self._bound_vis, int(batch.max_vis_len))
+            self._need.clear()
+        need = self._need.get(id(cache))
+        if need is None:
+            bound = _b.SeqBatch(batch.seq_len, batch.vis_start, batch.vis_len, self._bound_seq, self._bound_vis)
+            need = 0
+            for op in (_b.OP_FOCAL_ATTN_SCORE, _b.OP_TOPK_FIXATION, _b.OP_SPARSE_DECODE_ATTN, _b.OP_DENSE_DECODE_ATTN):
+                need = max(need, self.ops.workspace_bytes(op, cache, bound, self.n_q_heads, self.kmax))
+            self._need[id(cache)] = need
         if self._ws is None or self._ws_bytes < need:
             self._ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
             self._ws_bytes = need

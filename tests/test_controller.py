@@ -4,7 +4,11 @@ import pytest
 import torch
 
 from oracle.controller import plan_step
+from paper_2605_17447_amd.binding import SeqBatch
 from paper_2605_17447_amd.controller import FixationController
+
+# geometry of one sequence; the recorder never looks inside, the controller reads its maxima
+_BATCH = SeqBatch.from_lists([300], [10], [256], "cpu")
 
 
 class Recorder:
@@ -39,7 +43,7 @@ def _run(n_layers, focal, warmup, steps):
     have_last = False
     for t in range(1, steps + 1):
         rec.calls.clear()
-        trace = ctl.step(t, None, q, q)
+        trace = ctl.step(t, _BATCH, q, q)
         plan = plan_step(t, n_layers, focal, warmup, have_last)
         assert [tuple(a) for a in plan.actions] == trace, (t, trace)
         # the calls behind each mode
@@ -64,11 +68,11 @@ def test_hand_traced_four_layer_example():
     rec = Recorder()
     ctl = FixationController([0, 1, 2, 3], 4, 0.125, [1, 3], 0.05, 2, 300, 256, 1, "cpu", ops=rec)
     q = [torch.zeros(1)] * 4
-    assert ctl.step(1, None, q, q) == [(0, "full", None), (1, "full", None), (2, "full", None), (3, "full", None)]
-    ctl.step(2, None, q, q)
-    assert ctl.step(3, None, q, q) == [(0, "full+select", None), (1, "full+select", None), (2, "pruned", 1),
+    assert ctl.step(1, _BATCH, q, q) == [(0, "full", None), (1, "full", None), (2, "full", None), (3, "full", None)]
+    ctl.step(2, _BATCH, q, q)
+    assert ctl.step(3, _BATCH, q, q) == [(0, "full+select", None), (1, "full+select", None), (2, "pruned", 1),
                                        (3, "full+select", None)]
-    assert ctl.step(4, None, q, q) == [(0, "pruned", "F_last"), (1, "full+select", None), (2, "pruned", 1),
+    assert ctl.step(4, _BATCH, q, q) == [(0, "pruned", "F_last"), (1, "full+select", None), (2, "pruned", 1),
                                        (3, "full+select", None)]
     assert ctl.kept_from == 3
 
@@ -84,10 +88,10 @@ def test_first_topk_is_cold_and_later_ones_are_warm_started():
     rec = Recorder()
     ctl = FixationController([0, 1, 2], 4, 0.125, [1], 0.05, 0, 300, 256, 1, "cpu", ops=rec)
     q = [torch.zeros(1)] * 3
-    ctl.step(1, None, q, q)
+    ctl.step(1, _BATCH, q, q)
     assert [c for c in rec.calls if c[0] == "topk"] == [("topk", False), ("topk", True)]
     rec.calls.clear()
-    ctl.step(2, None, q, q)
+    ctl.step(2, _BATCH, q, q)
     assert [c for c in rec.calls if c[0] == "topk"] == [("topk", True)]
 
 

@@ -11,7 +11,11 @@ import torch
 from oracle.controller import select_focal_layers
 import paper_2605_17447_amd as fo
 from paper_2605_17447_amd import binding as fb
+from paper_2605_17447_amd.binding import SeqBatch
 from paper_2605_17447_amd.controller import FixationController
+
+# geometry of three sequences; the recorder never looks inside, the controller reads its maxima
+_BATCH = SeqBatch.from_lists([300, 280, 260], [10, 10, 10], [256, 256, 200], "cpu")
 
 
 def test_hand_worked_cases():
@@ -120,14 +124,14 @@ def test_controller_profiles_during_warm_up_and_then_uses_the_chosen_set():
                              focal_ratio=0.5)
     q = [torch.zeros(1)] * 4
     with pytest.raises(RuntimeError):
-        ctl.step(3, None, q, q)                       # selection has not happened yet
-    ctl.step(1, None, q, q)
+        ctl.step(3, _BATCH, q, q)                       # selection has not happened yet
+    ctl.step(1, _BATCH, q, q)
     assert rec.calls == [("dense+score", True)] * 4 and ctl.focal is None
     rec.calls.clear()
-    ctl.step(2, None, q, q)
+    ctl.step(2, _BATCH, q, q)
     assert rec.calls[-1] == ("select", (2, 4, 3), 0.5, 1) and ctl.focal == [1, 3]
     rec.calls.clear()
-    trace = ctl.step(3, None, q, q)
+    trace = ctl.step(3, _BATCH, q, q)
     assert [m for _, m, _ in trace] == ["full+select", "full+select", "pruned", "full+select"]
     with pytest.raises(ValueError):
         FixationController([0, 1], 4, 0.1, None, 0.05, 0, 300, 256, 1, "cpu", ops=rec)     # no warm-up to profile
