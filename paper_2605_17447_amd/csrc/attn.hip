@@ -377,7 +377,12 @@ tiles_done:
 
 // -----------------------------------------------------------------------------------------
 // Generic kernel: any dtype / head_dim <= 256 / group size.  One wave per (range, query
-// head, sequence); lanes over tokens for q.k, lanes over dims for p.V.  Plain fp32 FMAs.
+// head, sequence); lanes over tokens for q.k, lanes over dims for p.V.  Plain FMAs.
+// The fp32 cache's outputs are held to 1e-5 of their row maximum whatever the logits' size, so
+// everything a long chain of roundings could spoil runs in fp64: the q.k sums (dot_row), the
+// difference between a logit and the running maximum (exact in double; only the small difference
+// is rounded to fp32 for the exponential), the sum of the weights and the p.V accumulators.  The
+// kernel is off the hot path (none of the paper's models takes it) and stays latency-bound.
 // -----------------------------------------------------------------------------------------
 // acc[x] += sum_j p_j V[j][lane + 64 x] over the nv tokens of a tile; lane j holds token j's
 // probability pj and row offset off.  Eight tokens' rows are requested before any is used (a row's
@@ -386,7 +391,7 @@ tiles_done:
 // past the tile's end repeat its last row with probability zero.
 template <typename T, int NX>
 __device__ __forceinline__ void pv_rows(const T *__restrict__ vbase, int64_t off, float pj, int nv, int d, int lane,
-                                        float (&acc)[4])
+                                        double (&acc)[4])
 {
     int cc[NX];
 #pragma unroll
@@ -404,13 +409,13 @@ __device__ __forceinline__ void pv_rows(const T *__restrict__ vbase, int64_t off
 #pragma unroll
         for (int u = 0; u < 8; ++u)
 #pragma unroll
-            for (int x = 0; x < NX; ++x) acc[x] = fmaf(pb[u], vv[u][x], acc[x]);
+            for (int x = 0; x < NX; ++x) acc[x] = fma((double)pb[u], (double)vv[u][x], acc[x]);
     }
 }
 
 template <typename T, bool GATHER, bool PAGED>
 __global__ __launch_bounds__(64) void attn_generic_kernel(
-    KvDev kv, BatchDev bv, const T *__restrict__ q, int Hq, float scale_log2,
+    KvDev kv, BatchDev bv, const T *__restrict__ q, int Hq, double scale_log2,
     const int32_t *__restrict__ sel_idx, const int32_t *__restrict__ sel_cnt, int64_t kmax,
     float *__restrict__ part_o, float *__restrict__ part_ml, int nsplit, bool vec16)
 {
@@ -438,23 +443,26 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(
 
     const T *kbase = reinterpret_cast<const T *>(kv.k);
     const T *vbase = reinterpret_cast<const T *>(kv.v);
-    float m = -INFINITY, z = 0.f;
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    float m = -INFINITY;                 // running maximum: an fp32 value, exact as a double
+    double z = 0.0;
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
 
     for (int tile = t0; tile < t1; ++tile) {
         const int p = tile * 64 + lane;
         const bool valid = p < L;
         const int tok = pos_to_token<GATHER>(min(p, L - 1), geo, cnt, sel);
         const int64_t off = row_offset<PAGED>(kv, b, tok, g);
-        float s = dot_row<T>(qs, kbase + off, d, vec16);
-        s = valid ? s * scale_log2 : -INFINITY;
-        const float m_new = fmaxf(m, wave_max(s));
+        const double sd = dot_row<T>(qs, kbase + off, d, vec16) * scale_log2;
+        const float s = valid ? (float)sd : -INFINITY;
+        const float m_new = fmaxf(m, wave_max(s));          // finite: every tile holds a valid position
         const float alpha = fast_exp2(m - m_new);
-        const float pj = fast_exp2(s - m_new);
-        z = z * alpha + wave_sum(pj);
+        // the weight from the exact difference: rounding it to fp32 costs 2^-24 of a number that is
+        // small wherever the weight matters
+        const float pj = valid ? fast_exp2((float)(sd - (double)m_new)) : 0.f;
+        z = z * (double)alpha + (double)wave_sum(pj);
         m = m_new;
 #pragma unroll
-        for (int x = 0; x < 4; ++x) acc[x] *= alpha;
+        for (int x = 0; x < 4; ++x) acc[x] *= (double)alpha;
         const int nv = min(64, L - tile * 64);
         if (d <= 64) pv_rows<T, 1>(vbase, off, pj, nv, d, lane, acc);
         else if (d <= 128) pv_rows<T, 2>(vbase, off, pj, nv, d, lane, acc);
@@ -464,9 +472,9 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
         const int c = lane + 64 * x;
-        if (c < d) part_o[ph * d + c] = acc[x];
+        if (c < d) part_o[ph * d + c] = (float)acc[x];
     }
-    if (lane == 0) { part_ml[ph * 2] = m; part_ml[ph * 2 + 1] = z; }
+    if (lane == 0) { part_ml[ph * 2] = m; part_ml[ph * 2 + 1] = (float)z; }
 }
 
 // -----------------------------------------------------------------------------------------
@@ -600,7 +608,7 @@ static void launch_mfma(int kid, const Shape &s, const void *q, float scale_log2
 }
 
 template <typename T, bool GATHER, bool PAGED>
-static void launch_generic(int kid, const Shape &s, const void *q, float scale_log2, const int32_t *sel_idx,
+static void launch_generic(int kid, const Shape &s, const void *q, double scale_log2, const int32_t *sel_idx,
                            const int32_t *sel_cnt, int64_t kmax, float *part_o, float *part_ml,
                            int nsplit, bool, void *, float *, hipStream_t stream)
 {
@@ -620,10 +628,11 @@ hipError_t launch_attn(const Shape &s, const void *q, float scale, const int32_t
     const int d = s.kv.head_dim;
     float *part_o = reinterpret_cast<float *>(ws);
     float *part_ml = part_o + (size_t)s.batch * s.n_q_heads * nsplit * d;
-    const float scale_log2 = scale * kLog2e;
+    const float scale_log2f = scale * kLog2e;
+    const double scale_log2d = (double)scale * 1.4426950408889634074;     // the fp64 kernels take the scale unrounded
     const int kid = gather ? K_SPARSE_ATTN : K_DENSE_ATTN;
 
-#define FASTOCR_DISPATCH(FN, ...)                                                                      \
+#define FASTOCR_DISPATCH(FN, scale_log2, ...)                                                                      \
     do {                                                                                               \
         if (gather) { if (s.paged) FN<__VA_ARGS__ true, true>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, merge, out, lse, stream); \
                       else         FN<__VA_ARGS__ true, false>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, merge, out, lse, stream); } \
@@ -631,11 +640,11 @@ hipError_t launch_attn(const Shape &s, const void *q, float scale, const int32_t
                       else         FN<__VA_ARGS__ false, false>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, merge, out, lse, stream); } \
     } while (0)
     if (mfma_path(s)) {
-        FASTOCR_DISPATCH(launch_mfma, );
+        FASTOCR_DISPATCH(launch_mfma, scale_log2f, );
     } else if (s.dtype == DT_BF16) {
-        FASTOCR_DISPATCH(launch_generic, uint16_t, );
+        FASTOCR_DISPATCH(launch_generic, scale_log2d, uint16_t, );
     } else {
-        FASTOCR_DISPATCH(launch_generic, float, );
+        FASTOCR_DISPATCH(launch_generic, scale_log2d, float, );
     }
 #undef FASTOCR_DISPATCH
     hipError_t e = hipGetLastError();

@@ -126,13 +126,16 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// <q, row> over d components in ascending order (one fp32 FMA chain, the same result whichever way
-// the row is fetched).  vec16: the row starts 16-byte aligned and d covers whole 16-byte pieces, so
-// it is fetched 16 bytes per load instead of one element per load.
+// <q, row> over d components, accumulated in fp64: a product of two fp32 (or bf16) values is exact in
+// double and the sum of up to 256 of them carries a relative error near 2^-53, so the logit is
+// the exactly rounded one whichever way the row is fetched.  (A single fp32 chain over d left the
+// logit off by about sqrt(d) 2^-24 of the largest partial sum, which is the relative error of the
+// token's weight: 1.2e-5 on logits near 30.)  vec16: the row starts 16-byte aligned and d covers
+// whole 16-byte pieces, so it is fetched 16 bytes per load instead of one element per load.
 template <typename T>
-__device__ __forceinline__ float dot_row(const float *__restrict__ qs, const T *__restrict__ row, int d, bool vec16)
+__device__ __forceinline__ double dot_row(const float *__restrict__ qs, const T *__restrict__ row, int d, bool vec16)
 {
-    float s = 0.f;
+    double s = 0.0;
     if (vec16) {
         constexpr int E = 16 / (int)sizeof(T);
         for (int c = 0; c < d; c += E) {
@@ -140,15 +143,15 @@ __device__ __forceinline__ float dot_row(const float *__restrict__ qs, const T *
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 if (sizeof(T) == 2) {
-                    s = fmaf(qs[c + 2 * e], __uint_as_float(w[e] << 16), s);
-                    s = fmaf(qs[c + 2 * e + 1], __uint_as_float(w[e] & 0xffff0000u), s);
+                    s = fma((double)qs[c + 2 * e], (double)__uint_as_float(w[e] << 16), s);
+                    s = fma((double)qs[c + 2 * e + 1], (double)__uint_as_float(w[e] & 0xffff0000u), s);
                 } else {
-                    s = fmaf(qs[c + e], __uint_as_float(w[e]), s);
+                    s = fma((double)qs[c + e], (double)__uint_as_float(w[e]), s);
                 }
             }
         }
     } else {
-        for (int c = 0; c < d; ++c) s = fmaf(qs[c], load_elem<T>(row + c), s);
+        for (int c = 0; c < d; ++c) s = fma((double)qs[c], (double)load_elem<T>(row + c), s);
     }
     return s;
 }

@@ -219,10 +219,11 @@ stream_done:
     }
 }
 
-// Generic: one wave per (range, query head, sequence), lanes over tokens.  Plain fp32 FMAs.
+// Generic: one wave per (range, query head, sequence), lanes over tokens.  The q.k sums run in
+// fp64 (dot_row) and are scaled there; the logit is rounded to fp32 once, when it is parked.
 template <typename T, bool PAGED>
 __global__ __launch_bounds__(64) void score_generic_kernel(
-    KvDev kv, BatchDev bv, const T *__restrict__ q, int Hq, float scale_log2,
+    KvDev kv, BatchDev bv, const T *__restrict__ q, int Hq, double scale_log2,
     float *__restrict__ logits, int64_t pitch, float *__restrict__ part_ml, int nsplit, bool vec16)
 {
     __shared__ float qs[256];
@@ -246,8 +247,7 @@ __global__ __launch_bounds__(64) void score_generic_kernel(
         const int p = tile * 64 + lane;
         const bool valid = p < L;
         const int64_t off = row_offset<PAGED>(kv, b, min(p, L - 1), g);
-        float s = dot_row<T>(qs, kbase + off, d, vec16);
-        s = valid ? s * scale_log2 : -INFINITY;
+        const float s = valid ? (float)(dot_row<T>(qs, kbase + off, d, vec16) * scale_log2) : -INFINITY;
         lrow[(int64_t)p * Gp] = s;                       // p < pitch: pitch is a multiple of 64
         const float m_new = fmaxf(m, wave_max(s));
         z = z * fast_exp2(m - m_new) + wave_sum(fast_exp2(s - m_new));
@@ -386,7 +386,7 @@ hipError_t launch_score(const Shape &s, const void *q, float scale, float *score
     } else {
         dim3 grid(nsplit, s.n_q_heads, s.batch), block(64);
 #define FASTOCR_SCORE(T, P) FASTOCR_LAUNCH(K_SCORE_LOGITS, (score_generic_kernel<T, P>), grid, block, 0, stream, \
-        s.kv, s.bv, (const T *)q, s.n_q_heads, scale_log2, logits, pitch, part_ml, nsplit, s.vec16)
+        s.kv, s.bv, (const T *)q, s.n_q_heads, (double)scale * 1.4426950408889634074, logits, pitch, part_ml, nsplit, s.vec16)
         if (s.dtype == DT_BF16) { if (s.paged) FASTOCR_SCORE(uint16_t, true); else FASTOCR_SCORE(uint16_t, false); }
         else                    { if (s.paged) FASTOCR_SCORE(float, true); else FASTOCR_SCORE(float, false); }
 #undef FASTOCR_SCORE

@@ -56,9 +56,8 @@ def _draw(rng):
     return dict(mfma=mfma, Hq=Hq, Hkv=Hkv, d=d, dtype=dtype, B=B, n_vis=n_vis, pre=pre, post=post,
                 tau=float(TAUS[rng.integers(len(TAUS))]), tune=tune,
                 layout="bshd" if rng.random() < 0.3 else "bhsd", paged=mfma and rng.random() < 0.25,
-                # keys and queries up to three times the workload's spread for bf16 caches; fp32 caches stay
-                # within the range of logits their 1e-5 bar is derived for (|logit| of the workload's size)
-                spread=float([1.0, 1.0, 3.0 if dtype == "bf16" else 1.5, 0.3][rng.integers(4)]),
+                # keys and queries up to three times the workload's spread, for every dtype (logits near 30)
+                spread=float([1.0, 1.0, 3.0, 0.3][rng.integers(4)]),
                 seed=int(rng.integers(1 << 30)))
 
 

@@ -13,7 +13,7 @@ import pytest
 import torch
 
 import oracle
-from util import (TinyCase, as_f64, brute_attn, brute_scores, brute_topk, store)
+from util import (TinyCase, as_f64, brute_attn, brute_logits, brute_scores, brute_topk, store)
 
 HEAD_COMBOS = [(1, 1), (2, 1), (4, 1), (4, 2), (6, 3), (8, 8), (7, 1), (12, 4)]
 
@@ -40,6 +40,13 @@ def test_scores_match_pure_python_brute_force(Hq, Hkv, dtype):
         n = int(case.vis_len[b])
         assert np.allclose(sc[b, :n], ref, rtol=1e-12, atol=1e-15)
         assert abs(mass[b] - math.fsum(ref)) < 1e-12
+        # the per-head log-sum-exp the call also returns: ln sum_j exp(logit_j) over ALL cached tokens
+        # (image and text), from the pure-Python logits
+        for h in range(Hq):
+            lg = brute_logits(case, b, h)
+            mx = max(lg)
+            want = mx + math.log(math.fsum(math.exp(x - mx) for x in lg))
+            assert abs(lse[b, h] - want) <= 1e-12 * max(1.0, abs(want))
 
 
 @pytest.mark.parametrize("Hq,Hkv", HEAD_COMBOS)
