@@ -6,6 +6,8 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
+#include <mutex>
 #include <vector>
 
 #include "fastocr.h"
@@ -13,13 +15,23 @@
 
 namespace fastocr {
 
-static int g_tune_score_resident = 1;
-static int g_tune_focal_fused = 1;
-int g_tune_attn_waves = 4;
-static int g_tune_attn_merge = 1;          // pruned attention: ranges of a stream merged inside the launch (0 never, 1 yes)
-int g_tune_barrier_spin_us = 250000;      // bounded wait of the resident kernels' per-sequence barrier
-static int g_tune_splits[4] = {0, 0, 0, 0};     // indexed by fastocr_op
-static int g_tune_timer_every = 1;          // per-kernel timers: which launches record events (every n-th)
+// ---- launch-shape overrides (fastocr_set_tuning) --------------------------------------------
+// Plain values read on every call and written rarely, possibly from another thread: atomics.
+static std::atomic<int> g_tune_score_resident{1};
+static std::atomic<int> g_tune_focal_fused{1};
+static std::atomic<int> g_tune_attn_waves{4};
+static std::atomic<int> g_tune_attn_merge{1};          // pruned attention: ranges of a stream merged inside the launch (0 never, 1 yes)
+static std::atomic<int> g_tune_barrier_spin_us{250000};      // bounded wait of the single-launch forms
+static std::atomic<int> g_tune_splits[4];              // indexed by fastocr_op; 0 = automatic
+static std::atomic<int> g_tune_timer_every{1};         // per-kernel timers: which launches record events (every n-th)
+static std::atomic<int> g_exchange_distrusted{0};      // "exchange_fallback" 1
+
+int tune_attn_waves() { return g_tune_attn_waves.load(std::memory_order_relaxed); }
+long long tune_spin_ticks() { return 100ll * g_tune_barrier_spin_us.load(std::memory_order_relaxed); }   // the wall clock runs at 100 MHz
+
+// Everything below that is more than one word (timers, slot registry, per-device tables) is
+// guarded by one mutex; it is held for a few table look-ups per call.
+static std::mutex g_mu;
 
 // ---- per-kernel timers ------------------------------------------------------------------
 struct KernelTimer {
@@ -33,17 +45,96 @@ static KernelTimer g_timers[K_COUNT];
 
 TimerEvents timer_events(int kernel)
 {
+    std::lock_guard<std::mutex> lock(g_mu);
     KernelTimer &t = g_timers[kernel];
     if (t.count >= t.capacity) return TimerEvents{nullptr, nullptr};
-    // an event pair costs the stream a few microseconds: only every g_tune_timer_every-th launch carries one
-    if (t.seen++ % (unsigned)g_tune_timer_every != 0u) return TimerEvents{nullptr, nullptr};
+    // an event pair costs the stream a few microseconds: only every timer_every-th launch carries one
+    if (t.seen++ % (unsigned)g_tune_timer_every.load(std::memory_order_relaxed) != 0u) return TimerEvents{nullptr, nullptr};
     const int i = t.count++;
     return TimerEvents{t.start[i], t.stop[i]};
 }
 
-// ---- shapes -----------------------------------------------------------------------------
-constexpr int kNumCU = 256;       // MI355X
+// ---- the device the call runs on ----------------------------------------------------------------
+constexpr int kMaxDevices = 64;
 
+static int current_device()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return -1; }
+    return dev >= 0 && dev < kMaxDevices ? dev : -1;
+}
+
+int plan_cu_count()
+{
+    static int cached[kMaxDevices] = {0};          // 0 = not asked yet; guarded by g_mu
+    const int dev = current_device();
+    if (dev < 0) return 256;
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) { (void)hipGetLastError(); n = 0; }
+        cached[dev] = n > 0 ? n : 256;
+    }
+    return cached[dev];
+}
+
+// ---- exchange slots (see kernels.hpp) --------------------------------------------------------------
+struct SlotOwner { hipStream_t stream; unsigned long long capture; };
+struct SlotTable { std::vector<SlotOwner> eager, graph; };
+static SlotTable g_slots[EX_KINDS][kMaxDevices];
+
+static uint32_t *g_gave_up[kMaxDevices];       // pinned host memory, one word per device, never freed
+
+int exchange_slot(int kind, hipStream_t stream, uint32_t **gave_up_flag)
+{
+    *gave_up_flag = nullptr;
+    const int total = kind == EX_MERGE ? kMergeSlots : kResSlots;
+    const int n_eager = total / 2;
+    const int dev = current_device();
+    if (dev < 0) return -1;
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    unsigned long long cap = 0;
+    if (hipStreamGetCaptureInfo(stream, &st, &cap) != hipSuccess) {
+        // e.g. the legacy default stream while another stream of the device is capturing
+        (void)hipGetLastError();
+        return -1;
+    }
+    if (st == hipStreamCaptureStatusInvalidated) return -1;
+    const bool capturing = st == hipStreamCaptureStatusActive;
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (!g_gave_up[dev] && !capturing) {
+        // one word of pinned host memory per device, allocated on the first eager call that reaches
+        // this point (an allocation is not a capturable call) and kept until the process ends
+        void *p = nullptr;
+        if (hipHostMalloc(&p, 64, hipHostMallocMapped) == hipSuccess && p) {
+            memset(p, 0, 64);
+            g_gave_up[dev] = static_cast<uint32_t *>(p);
+        } else {
+            (void)hipGetLastError();
+        }
+    }
+    *gave_up_flag = g_gave_up[dev];
+    SlotTable &t = g_slots[kind][dev];
+    std::vector<SlotOwner> &pool = capturing ? t.graph : t.eager;
+    const int cap_n = capturing ? total - n_eager : n_eager;
+    for (size_t i = 0; i < pool.size(); ++i)
+        if (pool[i].stream == stream && (!capturing || pool[i].capture == cap)) return (capturing ? n_eager : 0) + (int)i;
+    if ((int)pool.size() >= cap_n) return -1;
+    pool.push_back(SlotOwner{stream, capturing ? cap : 0ull});
+    return (capturing ? n_eager : 0) + (int)pool.size() - 1;
+}
+
+bool exchange_trusted()
+{
+    if (g_exchange_distrusted.load(std::memory_order_relaxed)) return false;
+    const int dev = current_device();
+    if (dev < 0) return true;
+    std::lock_guard<std::mutex> lock(g_mu);
+    const uint32_t *f = g_gave_up[dev];
+    return !f || __atomic_load_n(f, __ATOMIC_RELAXED) == 0u;
+}
+
+// ---- shapes -----------------------------------------------------------------------------
 static int check_views(const fastocr_kv_view *kv, const fastocr_batch_view *bv, int n_q_heads)
 {
     if (!kv || !bv) return FASTOCR_EINVAL;
@@ -109,7 +200,8 @@ static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 static int choose_splits(int op, const Shape &s, int max_positions)
 {
     const bool fast = s.fast;
-    int forced = g_tune_splits[op];
+    const int kNumCU = plan_cu_count();
+    const int forced = g_tune_splits[op].load(std::memory_order_relaxed);
     const int tile = fast ? 32 : 64;
     const int waves_per_wg = fast ? 4 : 1;
     const int ntile = (max_positions + tile - 1) / tile;
@@ -122,7 +214,7 @@ static int choose_splits(int op, const Shape &s, int max_positions)
         // Measured on MI355X: the streaming kernels run best with about one workgroup per compute
         // unit (few, long, equally sized streams), the plain-FMA kernels with many small ones.
         const int target_wg = fast ? kNumCU : 8 * kNumCU;
-        if (fast && op == FASTOCR_OP_SPARSE_DECODE_ATTN && g_tune_attn_merge) {
+        if (fast && op == FASTOCR_OP_SPARSE_DECODE_ATTN && g_tune_attn_merge.load(std::memory_order_relaxed)) {
             // pruned attention is short: one launch whose eight-wave workgroups fill the chip once,
             // the ranges of a stream merged inside the launch.  Up to 16 tiles one workgroup has the
             // whole list in flight at once (two tiles per wave) and a cut only adds the merge; beyond
@@ -152,20 +244,6 @@ static int sparse_positions(const fastocr_batch_view *bv, int64_t kmax)
 {
     if (kmax <= 0 || kmax >= bv->max_vis_len) return bv->max_seq_len;
     return bv->max_seq_len - bv->max_vis_len + (int)kmax;
-}
-
-// Compute units of the current device (queried once per device).
-static int device_cu_count()
-{
-    static int cached[64] = {0};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
-    if (cached[dev] == 0) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 0;
-        cached[dev] = n > 0 ? n : -1;
-    }
-    return cached[dev] > 0 ? cached[dev] : 0;
 }
 
 static size_t round256(size_t x) { return (x + 255) / 256 * 256; }
@@ -201,7 +279,7 @@ size_t fastocr_workspace_bytes(int op, const fastocr_kv_view *kv, const fastocr_
         const size_t dense = fastocr_workspace_bytes(FASTOCR_OP_DENSE_DECODE_ATTN, kv, bv, n_q_heads, 0);
         need = need > dense ? need : dense;
         ResidentPlan rp;
-        if (resident_plan(s, kNumCU, &rp)) {
+        if (resident_plan(s, plan_cu_count(), &rp)) {
             const size_t fused = round256(focal_fused_workspace_bytes(s, rp) + 256);
             need = need > fused ? need : fused;
         }
@@ -213,7 +291,7 @@ size_t fastocr_workspace_bytes(int op, const fastocr_kv_view *kv, const fastocr_
         // sized for either scoring path, so that the choice can be made at launch
         size_t need = score_workspace_bytes(s, nsplit);
         ResidentPlan rp;
-        if (resident_plan(s, kNumCU, &rp)) need = need > resident_workspace_bytes(s, rp) ? need : resident_workspace_bytes(s, rp);
+        if (resident_plan(s, plan_cu_count(), &rp)) need = need > resident_workspace_bytes(s, rp) ? need : resident_workspace_bytes(s, rp);
         return round256(need + 256);
     }
     return round256(attn_workspace_bytes(s, nsplit) + 256);
@@ -245,11 +323,19 @@ static int check_qo(const fastocr_kv_view *kv, const void *q, const void *out, f
 constexpr int kResidentMinTiles = 1;
 constexpr int kFusedMinTiles = 1;
 
-static bool use_resident(int mode, const Shape &s, ResidentPlan *rp, int min_tiles)
+// mode: the tuning value (0 never, 1 the library's choice, 2 whenever the shape fits).  The
+// library's own choice also requires that no wave of a single-launch form has ever given up
+// waiting in this process: a launch that cannot have the chip to itself is not tried twice.
+// On success *slot is the call's exchange slot.
+static bool use_resident(int kind, int mode, const Shape &s, ResidentPlan *rp, int min_tiles, hipStream_t stream, int *slot,
+                         uint32_t **flag)
 {
-    if (mode == 0 || !resident_plan(s, kNumCU, rp)) return false;
-    if (rp->nranges * s.batch > device_cu_count()) return false;
-    return mode == 2 || rp->range_tokens / (32 * rp->wpk) >= min_tiles;
+    const int cus = plan_cu_count();
+    if (mode == 0 || !resident_plan(s, cus, rp)) return false;
+    if (rp->nranges * s.batch > cus) return false;
+    if (mode != 2 && (rp->range_tokens / (32 * rp->wpk) < min_tiles || !exchange_trusted())) return false;
+    *slot = exchange_slot(kind, stream, flag);
+    return *slot >= 0;
 }
 
 int fastocr_focal_score(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
@@ -269,8 +355,10 @@ int fastocr_focal_score(const fastocr_kv_view *kv, const fastocr_batch_view *bv,
     const int nsplit = choose_splits(FASTOCR_OP_FOCAL_SCORE, s, bv->max_seq_len);
     ResidentPlan rp;
     hipError_t e;
-    if (use_resident(g_tune_score_resident, s, &rp, kResidentMinTiles))
-        e = launch_score_resident(s, rp, q, scale, scores, lse, img_mass, ws, (hipStream_t)hip_stream);
+    int slot = -1;
+    uint32_t *flag = nullptr;
+    if (use_resident(EX_SCORE, g_tune_score_resident.load(std::memory_order_relaxed), s, &rp, kResidentMinTiles, (hipStream_t)hip_stream, &slot, &flag))
+        e = launch_score_resident(s, rp, slot, flag, q, scale, scores, lse, img_mass, ws, (hipStream_t)hip_stream);
     else
         e = launch_score(s, q, scale, scores, lse, img_mass, ws, nsplit, (hipStream_t)hip_stream);
     return e == hipSuccess ? FASTOCR_OK : FASTOCR_EHIP;
@@ -315,8 +403,16 @@ static int attn_common(int op, const fastocr_kv_view *kv, const fastocr_batch_vi
     if (bv->batch == 0) return FASTOCR_OK;
     Shape s = make_shape(kv, bv, n_q_heads);
     const int nsplit = choose_splits(op, s, op == FASTOCR_OP_SPARSE_DECODE_ATTN ? sparse_positions(bv, kmax) : bv->max_seq_len);
-    const bool merge = (op == FASTOCR_OP_SPARSE_DECODE_ATTN && g_tune_attn_merge != 0) || g_tune_attn_merge == 2;
-    hipError_t e = launch_attn(s, q, scale, sel_idx, sel_cnt, kmax, out, lse, ws, nsplit, merge, (hipStream_t)hip_stream);
+    // the ranges of a stream merged inside the launch: when asked for, the shape fits, the stream has
+    // an exchange slot and no such wait has ever been given up in this process (the range count
+    // does not depend on the last two, so the workspace the caller sized always covers the
+    // separate merge kernel)
+    const int mode = g_tune_attn_merge.load(std::memory_order_relaxed);
+    int merge_slot = -1;
+    uint32_t *flag = nullptr;
+    if (((op == FASTOCR_OP_SPARSE_DECODE_ATTN && mode != 0) || mode == 2) && attn_merges_in_kernel(s, nsplit) && exchange_trusted())
+        merge_slot = exchange_slot(EX_MERGE, (hipStream_t)hip_stream, &flag);
+    hipError_t e = launch_attn(s, q, scale, sel_idx, sel_cnt, kmax, out, lse, ws, nsplit, merge_slot, flag, (hipStream_t)hip_stream);
     return e == hipSuccess ? FASTOCR_OK : FASTOCR_EHIP;
 }
 
@@ -352,8 +448,10 @@ int fastocr_focal_attn_score(const fastocr_kv_view *kv, const fastocr_batch_view
     if (bv->batch == 0) return FASTOCR_OK;
     Shape s = make_shape(kv, bv, n_q_heads);
     ResidentPlan rp;
-    if (use_resident(g_tune_focal_fused, s, &rp, kFusedMinTiles)) {
-        hipError_t e = launch_focal_fused(s, rp, q, scale, out, scores, lse, img_mass, ws, (hipStream_t)hip_stream);
+    int slot = -1;
+    uint32_t *flag = nullptr;
+    if (use_resident(EX_FUSED, g_tune_focal_fused.load(std::memory_order_relaxed), s, &rp, kFusedMinTiles, (hipStream_t)hip_stream, &slot, &flag)) {
+        hipError_t e = launch_focal_fused(s, rp, slot, flag, q, scale, out, scores, lse, img_mass, ws, (hipStream_t)hip_stream);
         return e == hipSuccess ? FASTOCR_OK : FASTOCR_EHIP;
     }
     rc = fastocr_dense_decode_attn(kv, bv, q, n_q_heads, scale, out, nullptr, ws, ws_bytes, hip_stream);
@@ -395,6 +493,7 @@ int fastocr_select_focal_layers(const float *ratio, int steps, int layers, int b
 int fastocr_kernel_timer_enable(int kernel, int capacity)
 {
     if (kernel < 0 || kernel >= K_COUNT || capacity < 0) return FASTOCR_EINVAL;
+    std::lock_guard<std::mutex> lock(g_mu);
     KernelTimer &t = g_timers[kernel];
     for (int i = 0; i < t.capacity; ++i) {
         (void)hipEventDestroy(t.start[i]);
@@ -419,6 +518,7 @@ int fastocr_kernel_timer_enable(int kernel, int capacity)
 int fastocr_kernel_timer_read(int kernel, float *ms_out, int max_out)
 {
     if (kernel < 0 || kernel >= K_COUNT || (max_out > 0 && !ms_out)) return FASTOCR_EINVAL;
+    std::lock_guard<std::mutex> lock(g_mu);
     KernelTimer &t = g_timers[kernel];
     const int n = t.count;
     for (int i = 0; i < n && i < max_out; ++i) {
@@ -455,12 +555,21 @@ int fastocr_set_tuning(const char *key, int value)
     if (!strcmp(key, "splits_score")) g_tune_splits[FASTOCR_OP_FOCAL_SCORE] = value;
     else if (!strcmp(key, "splits_sparse")) g_tune_splits[FASTOCR_OP_SPARSE_DECODE_ATTN] = value;
     else if (!strcmp(key, "splits_dense")) g_tune_splits[FASTOCR_OP_DENSE_DECODE_ATTN] = value;
-    else if (!strcmp(key, "attn_waves")) g_tune_attn_waves = value;
+    else if (!strcmp(key, "attn_waves") && (value == 4 || value == 8)) g_tune_attn_waves = value;
     else if (!strcmp(key, "timer_every") && value >= 1) g_tune_timer_every = value;
     else if (!strcmp(key, "attn_merge") && value <= 2) g_tune_attn_merge = value;
-    else if (!strcmp(key, "barrier_spin_us") && value >= 0) g_tune_barrier_spin_us = value ? value : 250000;
-    else if (!strcmp(key, "score_resident") && value >= 0 && value <= 2) g_tune_score_resident = value;
-    else if (!strcmp(key, "focal_fused") && value >= 0 && value <= 2) g_tune_focal_fused = value;
+    else if (!strcmp(key, "barrier_spin_us")) g_tune_barrier_spin_us = value ? value : 250000;
+    else if (!strcmp(key, "score_resident") && value <= 2) g_tune_score_resident = value;
+    else if (!strcmp(key, "focal_fused") && value <= 2) g_tune_focal_fused = value;
+    else if (!strcmp(key, "exchange_fallback") && value <= 1) {
+        g_exchange_distrusted = value;
+        if (value == 0) {
+            // re-arm: forget that waves have given up (the caller has taken the other work off the GPU)
+            std::lock_guard<std::mutex> lock(g_mu);
+            for (int d = 0; d < kMaxDevices; ++d)
+                if (g_gave_up[d]) __atomic_store_n(g_gave_up[d], 0u, __ATOMIC_RELAXED);
+        }
+    }
     else return FASTOCR_EINVAL;
     return FASTOCR_OK;
 }

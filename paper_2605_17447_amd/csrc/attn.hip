@@ -19,14 +19,9 @@
 // coalesced (16 lanes x 16 B = one 256 B row) and transposed in registers with v_perm_b32.
 // K is loaded the same coalesced way and re-laid to the A layout through a wave-private,
 // XOR-swizzled LDS tile.
-#include <atomic>
-
 #include "kernels.hpp"
 
 namespace fastocr {
-
-extern int g_tune_attn_waves;
-extern int g_tune_barrier_spin_us;
 
 // How a workgroup's result leaves the kernel.
 //   kPartial: an fp32 partial (m, Z, acc[d]) in the workspace; a merge kernel follows.
@@ -36,23 +31,27 @@ extern int g_tune_barrier_spin_us;
 //             atomic stores; the stream's last range (dispatched after them) polls until every word
 //             it needs carries this call's tag, merges and writes the output.  Every word is its
 //             own "ready" flag, so nothing has to be ordered and no fence (an L2 write-back on this
-//             chip) is needed.  The tag is the stream's epoch + 1; the epoch is a device-side
-//             counter per (slot, stream number) that the last range advances when it has
-//             everything, so a replayed HIP graph sees fresh tags too.  A word's place depends on
-//             (stream number, range, element) only -- never on the call's shape -- so whatever a
-//             word still holds was written under an older epoch of the same counter and cannot be
-//             taken for this call's (short of 2^32 calls).  Calls take slots round-robin: up to
-//             kMergeSlots calls using this mode may overlap on one GPU.
+//             chip) is needed.  The tag is the call's number on its (slot, stream number): every
+//             workgroup of the call draws a ticket from a device-side counter by adding
+//             kTicketUnit / nsplit to it, so one call adds kTicketUnit whatever its range count and
+//             ticket / kTicketUnit is the same for all its workgroups, however late one of them
+//             starts.  Calls that share a slot are enqueued on one stream (api.hip hands slots to
+//             streams), so a call's last workgroup has drawn its ticket before the next call's first
+//             one does: two calls never see the same number, a replayed HIP graph gets fresh tags
+//             too, and a workgroup that publishes after its call's last range has given up waiting
+//             still publishes under its own call's tag, which no later call accepts.  A word's place
+//             depends on (stream number, range, element) only -- never on the call's shape -- so
+//             whatever a word still holds was written under an older number of the same counter.
 enum { kPartial = 0, kDirect = 1, kMerge = 2 };
-constexpr int kMergeSlots = 4;
 constexpr int kMergeMaxSplits = 4;
+constexpr unsigned long long kTicketUnit = 12;                  // divisible by every range count 2 .. kMergeMaxSplits
 constexpr int kMergeMaxStreams = 128;
 constexpr int kMergeMaxG = 8;
 constexpr int kMergeStatsAt = kMergeMaxG * 128;                 // a partial: o[G][128], then m[G], then Z[G]
 constexpr int kMergePitch = kMergeMaxG * 130;                   // words per published partial, whatever G is
 constexpr size_t kMergeWords = (size_t)kMergeMaxStreams * (kMergeMaxSplits - 1) * kMergePitch;   // per slot: 3.2 MB
 __device__ unsigned long long g_merge_words[kMergeSlots][kMergeWords];
-__device__ uint32_t g_merge_epoch[kMergeSlots][kMergeMaxStreams];
+__device__ unsigned long long g_merge_ticket[kMergeSlots][kMergeMaxStreams];
 __device__ uint32_t g_merge_timeouts;                        // sticky count of merges that gave up
 
 __device__ __forceinline__ unsigned long long tagged(float x, uint32_t tag)
@@ -79,21 +78,23 @@ __global__ __launch_bounds__(64 * kWaves, 8 / kWaves) void attn_mfma_kernel(
     KvDev kv, BatchDev bv, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2,
     const int32_t *__restrict__ sel_idx, const int32_t *__restrict__ sel_cnt, int64_t kmax,
     float *__restrict__ part_o, float *__restrict__ part_ml, int nsplit, uint16_t *__restrict__ out,
-    float *__restrict__ lse, int merge_slot, long long spin_ticks)
+    float *__restrict__ lse, int merge_slot, long long spin_ticks, uint32_t *__restrict__ gave_up_flag)
 {
     __shared__ __align__(16) unsigned char smem[kWaves][8192];
     __shared__ float sm_m[kWaves][16], sm_z[kWaves][16];
+    __shared__ uint32_t sm_tag;
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int li = lane & 15, lg = lane >> 4;
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
 
     const int stream_id = b * gridDim.y + kvh;
-    uint32_t tag = 0;
-    if (MODE == kMerge) {
-        tag = __builtin_amdgcn_readfirstlane(__hip_atomic_load(&g_merge_epoch[merge_slot][stream_id], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) + 1u;
-        if (tag == 0u) tag = 1u;             // zero is what never-written words hold
-    }
+    // this workgroup's ticket (see kMerge above), requested before anything else; the tag is only
+    // needed after the tile loop and is put into LDS once the geometry (requested after it) is there
+    unsigned long long ticket = 0;
+    if (MODE == kMerge && threadIdx.x == 0)
+        ticket = __hip_atomic_fetch_add(&g_merge_ticket[merge_slot][stream_id], kTicketUnit / (unsigned long long)nsplit,
+                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
     const SeqGeom geo = seq_geom(bv, b);
     int cnt = 0;
@@ -103,6 +104,10 @@ __global__ __launch_bounds__(64 * kWaves, 8 / kWaves) void attn_mfma_kernel(
         sel = sel_idx + (int64_t)b * kmax;
     }
     const int L = GATHER ? (geo.S - geo.N + cnt) : geo.S;
+    if (MODE == kMerge && threadIdx.x == 0) {
+        const uint32_t t = (uint32_t)(ticket / kTicketUnit) + 1u;
+        sm_tag = t ? t : 1u;                  // zero is what never-written words hold
+    }
     // this wave's tiles: tile i starts at position tile_pos(i) and ends before pend
     int wp0 = 0, pend = L, nt, tfirst = 0;
     if (GATHER) {
@@ -286,6 +291,7 @@ tiles_done:
         for (int r = 0; r < 4; ++r) buf[li * 128 + 32 * lg + 8 * r + t] = acc[t][r];
     if (lg == 0) { sm_m[wave][li] = m; sm_z[wave][li] = zl; }
     __syncthreads();
+    const uint32_t tag = MODE == kMerge ? sm_tag : 0u;
 
     const int np = nsplit - 1;                                       // ranges that publish (kMerge)
     // the stream's published partials: kMergeMaxSplits - 1 fixed places of kMergePitch words
@@ -358,11 +364,9 @@ tiles_done:
             // a range that never published: no number is better than a wrong one
             out[bh * 128 + c] = ok ? f32_to_bf16_bits(Zt > 0.f ? ot / Zt : 0.f) : (uint16_t)0x7fc0;
             if (lse && c == 0) lse[bh] = !ok ? __builtin_nanf("") : (Zt > 0.f ? (Mt + log2f(Zt)) * kLn2 : -INFINITY);
-            if (idx == 0) {
-                // this thread has seen every range's words (or given up): all of them have read the
-                // epoch, so it may advance
-                __hip_atomic_store(&g_merge_epoch[merge_slot][stream_id], tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (!ok) __hip_atomic_fetch_add(&g_merge_timeouts, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (idx == 0 && !ok) {
+                __hip_atomic_fetch_add(&g_merge_timeouts, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (gave_up_flag) __hip_atomic_store(gave_up_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
             }
         } else if (MODE == kDirect) {
             out[bh * 128 + c] = f32_to_bf16_bits(Z > 0.f ? o / Z : 0.f);
@@ -588,21 +592,21 @@ bool attn_merges_in_kernel(const Shape &s, int nsplit)
 template <bool GATHER, bool PAGED>
 static void launch_mfma(int kid, const Shape &s, const void *q, float scale_log2, const int32_t *sel_idx,
                         const int32_t *sel_cnt, int64_t kmax, float *part_o, float *part_ml,
-                        int nsplit, bool merge, void *out, float *lse, hipStream_t stream)
+                        int nsplit, int merge_slot, uint32_t *flag, void *out, float *lse, hipStream_t stream)
 {
     const int G = s.n_q_heads / s.kv.n_kv_heads;
     dim3 grid(nsplit, s.kv.n_kv_heads, s.batch);
-    static std::atomic<unsigned> call_no{0};
-    const int slot = merge && nsplit > 1 ? (int)(call_no.fetch_add(1u) % (unsigned)kMergeSlots) : 0;
+    const bool merge = merge_slot >= 0 && nsplit > 1;
+    const int slot = merge ? merge_slot : 0;
     // the stream's last range waits at most this long for the others (they run concurrently and
     // finish within microseconds of each other); past it the outputs are NaN but the call ends
-    const long long spin_ticks = 100ll * g_tune_barrier_spin_us;     // the wall clock runs at 100 MHz
+    const long long spin_ticks = tune_spin_ticks();
 #define FASTOCR_ATTN(W, MODE) FASTOCR_LAUNCH(kid, (attn_mfma_kernel<GATHER, PAGED, W, MODE>), grid, dim3(64 * W), 0, stream, \
         s.kv, s.bv, (const uint16_t *)q, s.n_q_heads, G, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, \
-        (uint16_t *)out, lse, slot, spin_ticks)
+        (uint16_t *)out, lse, slot, spin_ticks, flag)
     if (nsplit == 1) FASTOCR_ATTN(8, kDirect);       // one range per stream: eight waves, final output
     else if (merge) FASTOCR_ATTN(8, kMerge);         // the stream's last range merges inside the launch
-    else if (g_tune_attn_waves == 8) FASTOCR_ATTN(8, kPartial);
+    else if (tune_attn_waves() == 8) FASTOCR_ATTN(8, kPartial);
     else FASTOCR_ATTN(4, kPartial);
 #undef FASTOCR_ATTN
 }
@@ -610,7 +614,7 @@ static void launch_mfma(int kid, const Shape &s, const void *q, float scale_log2
 template <typename T, bool GATHER, bool PAGED>
 static void launch_generic(int kid, const Shape &s, const void *q, double scale_log2, const int32_t *sel_idx,
                            const int32_t *sel_cnt, int64_t kmax, float *part_o, float *part_ml,
-                           int nsplit, bool, void *, float *, hipStream_t stream)
+                           int nsplit, int, uint32_t *, void *, float *, hipStream_t stream)
 {
     dim3 grid(nsplit, s.n_q_heads, s.batch), block(64);
     FASTOCR_LAUNCH(kid, (attn_generic_kernel<T, GATHER, PAGED>), grid, block, 0, stream,
@@ -621,10 +625,11 @@ hipError_t attn_merge_timeouts(uint32_t *n) { return hipMemcpyFromSymbol(n, HIP_
 
 hipError_t launch_attn(const Shape &s, const void *q, float scale, const int32_t *sel_idx,
                        const int32_t *sel_cnt, int64_t kmax, void *out, float *lse, void *ws,
-                       int nsplit, bool merge_in_kernel, hipStream_t stream)
+                       int nsplit, int merge_slot, uint32_t *gave_up_flag, hipStream_t stream)
 {
     const bool gather = sel_idx != nullptr;
-    const bool merge = merge_in_kernel && attn_merges_in_kernel(s, nsplit);
+    const bool merge = merge_slot >= 0 && attn_merges_in_kernel(s, nsplit);
+    if (!merge) merge_slot = -1;
     const int d = s.kv.head_dim;
     float *part_o = reinterpret_cast<float *>(ws);
     float *part_ml = part_o + (size_t)s.batch * s.n_q_heads * nsplit * d;
@@ -634,10 +639,10 @@ hipError_t launch_attn(const Shape &s, const void *q, float scale, const int32_t
 
 #define FASTOCR_DISPATCH(FN, scale_log2, ...)                                                                      \
     do {                                                                                               \
-        if (gather) { if (s.paged) FN<__VA_ARGS__ true, true>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, merge, out, lse, stream); \
-                      else         FN<__VA_ARGS__ true, false>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, merge, out, lse, stream); } \
-        else        { if (s.paged) FN<__VA_ARGS__ false, true>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, merge, out, lse, stream); \
-                      else         FN<__VA_ARGS__ false, false>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, merge, out, lse, stream); } \
+        if (gather) { if (s.paged) FN<__VA_ARGS__ true, true>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, merge_slot, gave_up_flag, out, lse, stream); \
+                      else         FN<__VA_ARGS__ true, false>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, merge_slot, gave_up_flag, out, lse, stream); } \
+        else        { if (s.paged) FN<__VA_ARGS__ false, true>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, merge_slot, gave_up_flag, out, lse, stream); \
+                      else         FN<__VA_ARGS__ false, false>(kid, s, q, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, merge_slot, gave_up_flag, out, lse, stream); } \
     } while (0)
     if (mfma_path(s)) {
         FASTOCR_DISPATCH(launch_mfma, scale_log2f, );

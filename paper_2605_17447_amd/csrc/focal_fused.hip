@@ -24,14 +24,10 @@
 //     split-merge kernel of attn.hip; the ranges then exchange their softmax statistics, meet at
 //     the per-sequence barrier and turn the parked logits into scores exactly as the
 //     scoring-only kernel does.
-#include <atomic>
-
 #include "kernels.hpp"
 #include "resident.hpp"
 
 namespace fastocr {
-
-extern int g_tune_barrier_spin_us;
 
 // statistics words per (workgroup, head), per sequence the count of ranges done reading, and a
 // count of the waves that gave up waiting: same protocol as score_resident.hip, own arrays
@@ -51,7 +47,8 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
     KvDev kv, BatchDev bv, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2,
     int batch, int nranges_uniform, int R_uniform, int sync_slot, long long spin_ticks,
     float *__restrict__ scores, float *__restrict__ lse_out, float *__restrict__ mass_part,
-    float *__restrict__ att_o, float *__restrict__ att_ml, int32_t *__restrict__ seq_meta)
+    float *__restrict__ att_o, float *__restrict__ att_ml, int32_t *__restrict__ seq_meta,
+    uint32_t *__restrict__ gave_up_flag)
 {
     __shared__ __align__(16) unsigned char smem[kResWaves][2][8192];      // [wave][K, V]
     __shared__ float sm_m[kResWaves][8], sm_z[kResWaves][8];
@@ -360,6 +357,7 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
         if (!ok && lane_p == 0) {
             sm_met = 0;
             __hip_atomic_fetch_add(&g_fus_timeouts, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (gave_up_flag) __hip_atomic_store(gave_up_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
         sm_pm[wave][lane_p] = M;
         sm_pz[wave][lane_p] = Z;
@@ -458,29 +456,28 @@ size_t focal_fused_workspace_bytes(const Shape &s, const ResidentPlan &p)
 
 hipError_t focal_fused_timeouts(uint32_t *n) { return hipMemcpyFromSymbol(n, HIP_SYMBOL(g_fus_timeouts), sizeof(uint32_t)); }
 
-hipError_t launch_focal_fused(const Shape &s, const ResidentPlan &p, const void *q, float scale, void *out,
-                              float *scores, float *lse, float *img_mass, void *ws, hipStream_t stream)
+hipError_t launch_focal_fused(const Shape &s, const ResidentPlan &p, int sync_slot, uint32_t *flag, const void *q, float scale,
+                              void *out, float *scores, float *lse, float *img_mass, void *ws, hipStream_t stream)
 {
+    if (sync_slot < 0 || sync_slot >= kResSlots) return hipErrorInvalidValue;
     const int W = p.nranges * s.batch;
     float *att_o = reinterpret_cast<float *>(ws);
     float *att_ml = att_o + (size_t)W * p.wpk * s.n_q_heads * 128;
     float *mass_part = att_ml + (size_t)W * p.wpk * s.n_q_heads * 2;
     int32_t *seq_meta = reinterpret_cast<int32_t *>(mass_part + W);
-    static std::atomic<unsigned> call_no{0};
-    const int sync_slot = (int)(call_no.fetch_add(1u) % (unsigned)kResSlots);
     const float scale_log2 = scale * kLog2e;
     const int G = s.n_q_heads / s.kv.n_kv_heads;
-    const long long spin_ticks = 100ll * g_tune_barrier_spin_us;     // the wall clock runs at 100 MHz; 0.25 s unless overridden
+    const long long spin_ticks = tune_spin_ticks();                  // 0.25 s unless overridden
 
     dim3 grid(W), block(kResThreads);
     if (s.paged)
         FASTOCR_LAUNCH(K_FOCAL_FUSED, focal_fused_kernel<true>, grid, block, 0, stream, s.kv, s.bv,
                        (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens,
-                       sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, att_o, att_ml, seq_meta);
+                       sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, att_o, att_ml, seq_meta, flag);
     else
         FASTOCR_LAUNCH(K_FOCAL_FUSED, focal_fused_kernel<false>, grid, block, 0, stream, s.kv, s.bv,
                        (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens,
-                       sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, att_o, att_ml, seq_meta);
+                       sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, att_o, att_ml, seq_meta, flag);
     if (img_mass) fused_mass_kernel<<<s.batch, 64, 0, stream>>>(mass_part, seq_meta, img_mass);
     // every sequence's partials: workgroups seq_meta[b][0] .. + seq_meta[b][1], wpk of them each
     return launch_attn_combine(s, att_o, att_ml, p.nranges * p.wpk, out, nullptr, stream, seq_meta, p.wpk);

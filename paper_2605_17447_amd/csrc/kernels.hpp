@@ -41,17 +41,47 @@ struct Shape {
 
 inline bool mfma_path(const Shape &s) { return s.fast; }
 
+// ---- host-side state shared by the launchers (api.hip) --------------------------------------
+// Launch-shape overrides (fastocr_set_tuning); atomics, so that callers on several threads may
+// read them while another thread sets one.
+int tune_attn_waves();                 // 4 or 8
+long long tune_spin_ticks();           // bounded wait of the single-launch forms, in 100 MHz wall-clock ticks
+// Compute units the launch shapes are planned for: the current device's, or 256 (MI355X) when no
+// device can be asked.
+int plan_cu_count();
+
+// Exchange slots of the single-launch forms.  Workgroups of such a launch hand each other data
+// through static device memory, one slot per call in flight.  Two calls may share a slot only if
+// the second cannot start before the first has ended, i.e. if they are enqueued on the same
+// stream; so a slot belongs to a stream: the first kEagerSlots streams of a device that ask for
+// one keep it for the life of the process.  A call that is being captured into a HIP graph gets a
+// slot of a separate pool that belongs to (capture, stream) and is never handed out again -- the
+// graph may be replayed on any stream next to eager calls.  Returns the slot, or -1 when none is
+// left (or the stream's capture state cannot be read): the caller then takes the form built from
+// separate kernels, which shares nothing.
+enum ExchangeKind { EX_SCORE = 0, EX_FUSED = 1, EX_MERGE = 2, EX_KINDS = 3 };
+constexpr int kResSlots = 32;          // slots of each register-resident kernel (scoring, fused focal layer)
+constexpr int kMergeSlots = 8;         // slots of pruned attention's in-launch merge (3.2 MB of static memory each)
+// *gave_up_flag: a device-visible word in pinned host memory that a wave sets when it gives up
+// waiting inside a single-launch form (null if it could not be allocated yet: the first call on a
+// device happened inside a capture); once it is set the library's own choice (tuning mode 1) is
+// the separate-kernel forms for the rest of the process ("exchange_fallback" 0 re-arms it).
+int exchange_slot(int kind, hipStream_t stream, uint32_t **gave_up_flag);
+bool exchange_trusted();               // false once a wave has given up (or "exchange_fallback" 1)
+
 // ---- attention (attn.hip) ---------------------------------------------------------------
 // Workspace: part_o fp32 [B][Hq][nsplit][d] followed by part_ml fp32 [B][Hq][nsplit][2].
 int attn_tile_tokens(const Shape &s);
 size_t attn_workspace_bytes(const Shape &s, int nsplit);
-// merge_in_kernel: with 2 .. 4 ranges per stream on the MFMA path the stream's last range merges
-// the others' partials inside the launch (through static device memory) when the shape fits
-// (attn_merges_in_kernel); otherwise partials go to the workspace and a merge kernel follows.
+// With 2 .. 4 ranges per stream on the MFMA path the stream's last range can merge the others'
+// partials inside the launch (through static device memory) when the shape fits
+// (attn_merges_in_kernel) and an exchange slot is given; otherwise partials go to the workspace
+// and a merge kernel follows.
 bool attn_merges_in_kernel(const Shape &s, int nsplit);
+// merge_slot: exchange slot for the in-launch merge (EX_MERGE), or -1 = partials + merge kernel.
 hipError_t launch_attn(const Shape &s, const void *q, float scale, const int32_t *sel_idx,
                        const int32_t *sel_cnt, int64_t kmax, void *out, float *lse, void *ws,
-                       int nsplit, bool merge_in_kernel, hipStream_t stream);
+                       int nsplit, int merge_slot, uint32_t *gave_up_flag, hipStream_t stream);
 // merge of nsplit partials per (sequence, head) in the layout above into the final output.
 // With seq_meta (device int32 [B][2]: first workgroup, workgroup count) the partials are instead
 // those of the fused focal kernel, [workgroup][wpk][Hq][d] / [..][2], wpk per workgroup.
@@ -74,14 +104,14 @@ hipError_t launch_score(const Shape &s, const void *q, float scale, float *score
 struct ResidentPlan { int nranges, range_tokens, wpk; };
 bool resident_plan(const Shape &s, int num_cu, ResidentPlan *plan);
 size_t resident_workspace_bytes(const Shape &s, const ResidentPlan &p);
-hipError_t launch_score_resident(const Shape &s, const ResidentPlan &p, const void *q, float scale, float *scores,
-                                 float *lse, float *img_mass, void *ws, hipStream_t stream);
+hipError_t launch_score_resident(const Shape &s, const ResidentPlan &p, int sync_slot, uint32_t *gave_up_flag, const void *q, float scale,
+                                 float *scores, float *lse, float *img_mass, void *ws, hipStream_t stream);
 
 // ---- focal layer in one pass: dense attention output + scores (focal_fused.hip) -----------
 // Uses the same plan as the register-resident scoring kernel.
 size_t focal_fused_workspace_bytes(const Shape &s, const ResidentPlan &p);
-hipError_t launch_focal_fused(const Shape &s, const ResidentPlan &p, const void *q, float scale, void *out,
-                              float *scores, float *lse, float *img_mass, void *ws, hipStream_t stream);
+hipError_t launch_focal_fused(const Shape &s, const ResidentPlan &p, int sync_slot, uint32_t *gave_up_flag, const void *q, float scale,
+                              void *out, float *scores, float *lse, float *img_mass, void *ws, hipStream_t stream);
 
 // ---- how often a workgroup gave up waiting for another one of its launch (each file's own count;
 // the copies synchronise with the device) ----------------------------------------------------

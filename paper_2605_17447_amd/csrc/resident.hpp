@@ -11,7 +11,6 @@ constexpr int kResThreads = 64 * kResWaves;
 constexpr int kResTmax = 32;          // image tiles per wave held in registers
 constexpr int kResTile = 32;
 constexpr int kResMaxHq = 64;
-constexpr int kResSlots = 32;         // barrier slots: calls that may overlap on one GPU
 constexpr int kResMaxBatch = 256;
 
 #define RES_EACH_TILE(M)                                                                            \

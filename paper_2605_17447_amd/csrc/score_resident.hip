@@ -15,21 +15,17 @@
 //   - C[head][token] = Q * K^T with v_mfma_f32_16x16x32_bf16 leaves 4 heads x 1 token per lane; those
 //     4 logits stay in 4 VGPRs named for the tile -- the image-tile loop is fully unrolled for
 //     that (up to 32 tiles = 128 VGPRs per lane); text tokens only feed the softmax statistics;
-//   - the ranges of one sequence exchange their per-head (max, sum-exp) through the workspace
-//     (agent-scope atomic stores and loads) and meet at a per-sequence barrier (atomic counter,
-//     bounded spin);
+//   - the ranges of one sequence exchange their per-head (max, sum-exp) through static device
+//     memory: each range publishes one self-validating 64-bit word per head (agent-scope atomic
+//     store; zero = not there yet) and polls for the others' (bounded spin, no counter, no fence);
 //   - every wave then turns its parked logits into probabilities, the heads of a token are
 //     summed through LDS and the finished scores are written -- the only HBM writes.
 // Shapes that do not fit (group size > 8, Hkv not dividing 8, more sequences than compute
 // units, more than 32 tiles per wave, pages shorter than a tile) take the two-kernel path.
-#include <atomic>
-
 #include "kernels.hpp"
 #include "resident.hpp"
 
 namespace fastocr {
-
-extern int g_tune_barrier_spin_us;
 
 #define RES_DECLARE(J) f32x4 park_##J;
 // image tile J of the wave: multiply, keep the logits, refill the tile's LDS slot
@@ -63,8 +59,9 @@ extern int g_tune_barrier_spin_us;
 // yet" (a published word is never zero: the sum is positive, or the maximum is the finite
 // stand-in for "no logit").  g_res_left: per sequence, how many of its ranges are done reading.
 // The last range to finish zeroes the sequence's words and its count, so a slot is clean again
-// when its call ends; calls take slots round-robin, so up to kResSlots calls may overlap on one
-// GPU.  g_res_timeouts counts the waves that gave up waiting (fastocr_exchange_timeouts).
+// when its call ends.  A slot belongs to a stream (or to a stream of a graph capture): calls that
+// share one are ordered by their stream, so the next call starts on a clean slot.
+// g_res_timeouts counts the waves that gave up waiting (fastocr_exchange_timeouts).
 __device__ unsigned long long g_res_stats[kResSlots][kResMaxWg * kResMaxHq];
 __device__ uint32_t g_res_left[kResSlots][kResMaxBatch];
 __device__ uint32_t g_res_timeouts;          // waves that gave up waiting, since the module was loaded
@@ -106,7 +103,7 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
     KvDev kv, BatchDev bv, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2,
     int batch, int nranges_uniform, int R_uniform, int sync_slot, long long spin_ticks,
     float *__restrict__ scores, float *__restrict__ lse_out, float *__restrict__ mass_part,
-    int32_t *__restrict__ mass_meta)
+    int32_t *__restrict__ mass_meta, uint32_t *__restrict__ gave_up_flag)
 {
     __shared__ __align__(16) unsigned char smem[kResWaves][2][8192];
     __shared__ float sm_m[kResWaves][8], sm_z[kResWaves][8];
@@ -339,6 +336,7 @@ pre_done:
         if (!ok && lane == 0) {
             sm_met = 0;
             __hip_atomic_fetch_add(&g_res_timeouts, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (gave_up_flag) __hip_atomic_store(gave_up_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
         sm_pm[wave][lane] = M;
         sm_pz[wave][lane] = Z;
@@ -421,29 +419,28 @@ __global__ void resident_mass_kernel(const float *__restrict__ mass_part, const 
 
 hipError_t score_resident_timeouts(uint32_t *n) { return hipMemcpyFromSymbol(n, HIP_SYMBOL(g_res_timeouts), sizeof(uint32_t)); }
 
-hipError_t launch_score_resident(const Shape &s, const ResidentPlan &p, const void *q, float scale, float *scores,
-                                 float *lse, float *img_mass, void *ws, hipStream_t stream)
+hipError_t launch_score_resident(const Shape &s, const ResidentPlan &p, int sync_slot, uint32_t *flag, const void *q, float scale,
+                                 float *scores, float *lse, float *img_mass, void *ws, hipStream_t stream)
 {
+    if (sync_slot < 0 || sync_slot >= kResSlots) return hipErrorInvalidValue;
     const int W = p.nranges * s.batch;                       // workgroups = range statistics slots
     float *mass_part = reinterpret_cast<float *>(ws);
     int32_t *mass_meta = reinterpret_cast<int32_t *>(mass_part + W);
-    static std::atomic<unsigned> call_no{0};
-    const int sync_slot = (int)(call_no.fetch_add(1u) % (unsigned)kResSlots);
     const float scale_log2 = scale * kLog2e;
     const int G = s.n_q_heads / s.kv.n_kv_heads;
     // a range waits at most this long for its sequence's other ranges (they run concurrently and
     // finish within microseconds of each other); past it the call's scores are NaN but it ends
-    const long long spin_ticks = 100ll * g_tune_barrier_spin_us;     // the wall clock runs at 100 MHz; 0.25 s unless overridden
+    const long long spin_ticks = tune_spin_ticks();                  // 0.25 s unless overridden
 
     dim3 grid(W), block(kResThreads);
     if (s.paged)
         FASTOCR_LAUNCH(K_SCORE_LOGITS, score_resident_kernel<true>, grid, block, 0, stream, s.kv, s.bv,
                        (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens,
-                       sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, mass_meta);
+                       sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, mass_meta, flag);
     else
         FASTOCR_LAUNCH(K_SCORE_LOGITS, score_resident_kernel<false>, grid, block, 0, stream, s.kv, s.bv,
                        (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens,
-                       sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, mass_meta);
+                       sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, mass_meta, flag);
     if (img_mass) resident_mass_kernel<<<s.batch, 64, 0, stream>>>(mass_part, mass_meta, img_mass);
     return hipGetLastError();
 }

@@ -1,5 +1,5 @@
-// Device code of the exact top-k select, shared by the stand-alone kernels (topk.hip) and the
-// kernel that selects and attends in one launch (select_attn.hip).
+// Device code of the exact top-k select as templates (workgroup size and keys per thread are
+// parameters, a hook is called for every selected entry); topk.hip instantiates it.
 #pragma once
 #include "kernels.hpp"
 

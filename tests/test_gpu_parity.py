@@ -288,12 +288,25 @@ def test_a_merge_that_gives_up_writes_nan_and_the_next_call_is_correct():
             assert err.max() <= 2e-2
         fb.set_tuning("barrier_spin_us", 0)
         gave_up_before = fb.exchange_timeouts()
+        if gave_up_before > 0:
+            # a wave has given up in this process: the library now merges with a second kernel by itself
+            fb.kernel_timer_enable(fb.KERNEL_ATTN_COMBINE, 4)
+            check_out(p.sparse(sel, selc), ref, "pruned attention once the library distrusts the in-launch merge")
+            assert len(fb.kernel_timer_read(fb.KERNEL_ATTN_COMBINE)) == 1
+            fb.kernel_timer_enable(fb.KERNEL_ATTN_COMBINE, 0)
+        # re-armed, the in-launch merge runs again and is correct (late words of the calls that gave
+        # up carry those calls' own tags)
+        fb.set_tuning("exchange_fallback", 0)
+        fb.kernel_timer_enable(fb.KERNEL_ATTN_COMBINE, 8)
         for _ in range(5):
             check_out(p.sparse(sel, selc), ref, "pruned attention after a merge that gave up")
+        assert len(fb.kernel_timer_read(fb.KERNEL_ATTN_COMBINE)) == 0
         assert fb.exchange_timeouts() == gave_up_before
     finally:
+        fb.kernel_timer_enable(fb.KERNEL_ATTN_COMBINE, 0)
         fb.set_tuning("barrier_spin_us", 0)
         fb.set_tuning("splits_sparse", 0)
+        fb.set_tuning("exchange_fallback", 0)
 
 
 def test_token_major_layout():
@@ -508,10 +521,23 @@ def test_a_barrier_that_gives_up_poisons_the_result_and_leaves_the_library_usabl
         check_scores(sc, ref_sc, p.vis_len, "scores after a timed-out call")
         check_scores(sc2, ref_sc, p.vis_len, "one-pass scores after a timed-out call")
         check_out(out, ref_dense, "one-pass output after a timed-out call")
+        # left to itself (mode 1) the library no longer takes the single-kernel forms in this process:
+        # scoring runs as its two kernels (the finalize kernel is launched) until it is re-armed
+        fb.set_tuning("score_resident", 1)
+        fb.kernel_timer_enable(fb.KERNEL_SCORE_FINALIZE, 4)
+        sc, _, _ = p.scores()
+        check_scores(sc, ref_sc, p.vis_len, "scores by the separate kernels after a timed-out call")
+        assert len(fb.kernel_timer_read(fb.KERNEL_SCORE_FINALIZE)) == 1
+        fb.set_tuning("exchange_fallback", 0)
+        sc, _, _ = p.scores()
+        check_scores(sc, ref_sc, p.vis_len, "scores after re-arming")
+        assert len(fb.kernel_timer_read(fb.KERNEL_SCORE_FINALIZE)) == 0
     finally:
+        fb.kernel_timer_enable(fb.KERNEL_SCORE_FINALIZE, 0)
         fb.set_tuning("barrier_spin_us", 0)
         fb.set_tuning("score_resident", 1)
         fb.set_tuning("focal_fused", 1)
+        fb.set_tuning("exchange_fallback", 0)
 
 
 def test_ragged_batches_get_ranges_in_proportion_to_their_lengths():
