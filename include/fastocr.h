@@ -23,10 +23,19 @@
  *     reported here.
  *   - `ws` is caller-provided device scratch of at least fastocr_workspace_bytes(...)
  *     bytes, 256-byte aligned, private to the call until the stream reaches its end.
- *   - fastocr_focal_score and fastocr_topk_fixation keep a few synchronisation counters in
- *     static device memory (cleared by the kernels themselves when they end); calls take one
- *     of 32 slots in turn, so at most 32 calls of each kind may be in flight on one GPU at a
- *     time (more would share a slot and corrupt each other's results).
+ *   - Single-launch forms.  fastocr_focal_score, fastocr_focal_attn_score and
+ *     fastocr_sparse_decode_attn each have a form in which the workgroups of ONE launch hand each
+ *     other data through static device memory (see the Concurrency notes at each call), one
+ *     "exchange slot" per call in flight.  A slot belongs to a stream: the first 16 streams of a
+ *     GPU that use scoring (16 for the focal layer, 4 for pruned attention) keep a slot for the
+ *     life of the process, and calls in order on one stream share it safely.  A call that is being
+ *     captured into a HIP graph gets a slot of a separate pool (48 / 48 / 12) that belongs to that
+ *     capture and stream, so a replay may run next to eager calls on any stream; instantiate a
+ *     captured graph once (two instances replayed at the same time would share its slots).  A
+ *     stream or capture beyond these counts gets the forms built from separate kernels, which
+ *     share nothing.  The library is thread-safe in the sense that calls on different streams may
+ *     come from different threads; fastocr_set_tuning and the timers may be called from any thread.
+ *     fastocr_topk_fixation keeps no state between or across workgroups at all.
  *   - Sequences are independent.  Sequence b holds seq_len[b] tokens; its image tokens
  *     are the contiguous span [vis_start[b], vis_start[b] + vis_len[b]); every other
  *     position (text before, text after, generated tokens, the current token) is text.
@@ -125,13 +134,15 @@ size_t fastocr_workspace_bytes(int op, const fastocr_kv_view *kv, const fastocr_
  *   img_mass fp32 [batch] sum_i scores[b,i] = the image-attention ratio of Eq. 1, or NULL
  * Concurrency: when the shape fits (bf16, head_dim 128, 1/2/4/8 kv heads with at most 8 query heads
  * each, batch <= 256 and <= the compute-unit count) this call (and fastocr_focal_attn_score) runs as ONE kernel whose
- * workgroups -- at most one per compute unit -- wait for each other at a per-sequence barrier, so
+ * workgroups -- at most one per compute unit -- wait for each other's softmax statistics, so
  * all of them must be on the chip together.  Launched alone on the GPU (any number of calls in
  * order on one stream, HIP graphs included) that always holds.  If other kernels occupy compute
- * units from another stream at the same time, the barrier gives up after 0.25 s and the affected
- * scores (and outputs) are NaN rather than wrong; callers that overlap such work should select
- * the forms built from separate kernels with fastocr_set_tuning("score_resident", 0) and
- * ("focal_fused", 0).  At most 32 calls of a kind may be in flight on one GPU.
+ * units at the same time, a workgroup gives up after 0.25 s and the affected scores are NaN rather
+ * than wrong; the give-up is recorded (fastocr_exchange_timeouts) and from then on the library
+ * itself takes the forms built from separate kernels for the rest of the process
+ * (fastocr_set_tuning("exchange_fallback", 0) re-arms the single-launch forms).  Callers that
+ * overlap other GPU work by design should select the separate kernels up front with
+ * fastocr_set_tuning("score_resident", 0) and ("focal_fused", 0).
  */
 int fastocr_focal_score(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
                         int n_q_heads, float scale, float *scores, float *lse, float *img_mass,
@@ -166,13 +177,14 @@ int fastocr_topk_fixation(const float *scores, const fastocr_batch_view *bv, dou
  *   out  [batch, n_q_heads, head_dim], kv->dtype (bf16 rounded to nearest even), 16-byte aligned;
  *        q as in fastocr_focal_score
  * Concurrency: when a (sequence, kv head) stream is cut into 2 .. 4 ranges (bf16, head_dim 128, at
- * most 8 query heads per kv head, at most 128 streams),
+ * most 8 query heads per kv head, at most 128 streams) and the call's stream owns an exchange slot,
  * the stream's last workgroup waits for the partial results of the others, which were dispatched
- * before it.  Alone on the GPU that wait is microseconds; if it exceeds 0.25 s (other work
- * keeping the earlier workgroups off the chip) the affected outputs are NaN rather than wrong.
- * At most 4 such calls may be in flight on one GPU at a time (calls in order on one stream and
- * HIP-graph replays never overlap); fastocr_set_tuning("attn_merge", 0) selects partials in the
- * workspace and a separate merge kernel instead, which has no such limit.
+ * before it and wait for nobody.  That wait is microseconds; if it exceeds 0.25 s the affected
+ * outputs are NaN rather than wrong, the give-up is recorded and the library takes the separate
+ * merge kernel from then on (as for fastocr_focal_score).  A partial published late -- after its
+ * call gave up -- carries that call's own number and is never accepted by a later call.
+ * fastocr_set_tuning("attn_merge", 0) always selects partials in the workspace and a separate merge
+ * kernel.
  */
 int fastocr_sparse_decode_attn(const fastocr_kv_view *kv, const fastocr_batch_view *bv,
                                const void *q, int n_q_heads, float scale, const int32_t *sel_idx,
@@ -253,15 +265,24 @@ int fastocr_kernel_timer_read(int kernel, float *ms_out, int max_out);
  */
 int fastocr_stream_probe(const void *src, void *dst, size_t bytes, void *sink, void *hip_stream);
 
-/* Launch-shape overrides for measurement sweeps: key "splits_score" | "splits_dense" |
- * "splits_sparse" (0 = automatic), "score_resident" | "focal_fused" (0 = always the separate
- * kernels, 1 = chosen by the library (default; currently whenever the shape fits), 2 = the
- * single-kernel form whenever the shape fits),
- * "attn_waves" (4 | 8), "attn_merge" (pruned attention with several ranges per stream: 1 = merged
- * inside the launch (default), 0 = by a second kernel, 2 = dense attention merges inside the launch
- * too -- measured slower, kept for comparison), "timer_every" (n >= 1: see the kernel timers above), "barrier_spin_us" (how long a workgroup of the single-kernel forms waits for
- * its sequence's other workgroups; 0 restores the default of 250000; 1 makes waiting workgroups give
- * up at once, which tests use to exercise the NaN path).  Returns FASTOCR_EINVAL for an unknown key. */
+/* Launch-shape overrides for measurement sweeps and deployment choices (value >= 0):
+ *   "splits_score" | "splits_dense" | "splits_sparse"   ranges per stream; 0 = automatic
+ *   "score_resident" | "focal_fused"   0 = always the separate kernels; 1 = chosen by the library
+ *       (default: the single-kernel form whenever the shape fits, the stream has an exchange slot
+ *       and no wave of such a form has ever given up waiting in this process); 2 = the
+ *       single-kernel form whenever the shape fits and the stream has a slot
+ *   "attn_waves"      4 | 8: waves per workgroup of attention launches that leave partials
+ *   "attn_merge"      pruned attention with several ranges per stream: 1 = merged inside the launch
+ *       (default, under the same conditions as above), 0 = by a second kernel, 2 = dense attention
+ *       merges inside the launch too (measured slower, kept for comparison)
+ *   "timer_every"     n >= 1: see the kernel timers above
+ *   "barrier_spin_us" how long a workgroup of a single-launch form waits for the others; 0 restores
+ *       the default of 250000; 1 makes waiting workgroups give up at once (tests use it to exercise
+ *       the NaN path; every kernel still ends normally)
+ *   "exchange_fallback"  1 = treat the single-launch forms as distrusted (as after a give-up);
+ *       0 = forget every recorded give-up and trust them again
+ * Returns FASTOCR_EINVAL for an unknown key or a value outside the key's range.  Values are read
+ * by later calls; workspace sizes must be asked for after the split and merge keys are set. */
 int fastocr_set_tuning(const char *key, int value);
 
 /*

@@ -89,7 +89,7 @@ int exchange_slot(int kind, hipStream_t stream, uint32_t **gave_up_flag)
 {
     *gave_up_flag = nullptr;
     const int total = kind == EX_MERGE ? kMergeSlots : kResSlots;
-    const int n_eager = total / 2;
+    const int n_eager = kind == EX_MERGE ? kMergeEagerSlots : kResEagerSlots;
     const int dev = current_device();
     if (dev < 0) return -1;
     hipStreamCaptureStatus st = hipStreamCaptureStatusNone;

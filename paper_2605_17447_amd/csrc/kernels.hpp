@@ -53,15 +53,17 @@ int plan_cu_count();
 // Exchange slots of the single-launch forms.  Workgroups of such a launch hand each other data
 // through static device memory, one slot per call in flight.  Two calls may share a slot only if
 // the second cannot start before the first has ended, i.e. if they are enqueued on the same
-// stream; so a slot belongs to a stream: the first kEagerSlots streams of a device that ask for
+// stream; so a slot belongs to a stream: the first k*EagerSlots streams of a device that ask for
 // one keep it for the life of the process.  A call that is being captured into a HIP graph gets a
 // slot of a separate pool that belongs to (capture, stream) and is never handed out again -- the
 // graph may be replayed on any stream next to eager calls.  Returns the slot, or -1 when none is
 // left (or the stream's capture state cannot be read): the caller then takes the form built from
 // separate kernels, which shares nothing.
 enum ExchangeKind { EX_SCORE = 0, EX_FUSED = 1, EX_MERGE = 2, EX_KINDS = 3 };
-constexpr int kResSlots = 32;          // slots of each register-resident kernel (scoring, fused focal layer)
-constexpr int kMergeSlots = 8;         // slots of pruned attention's in-launch merge (3.2 MB of static memory each)
+constexpr int kResSlots = 64;          // slots of each register-resident kernel (scoring, fused focal layer), 128 KB of static memory each
+constexpr int kResEagerSlots = 16;     //   of which for streams; the rest for graph captures
+constexpr int kMergeSlots = 16;        // slots of pruned attention's in-launch merge, 3.2 MB of static memory each
+constexpr int kMergeEagerSlots = 4;
 // *gave_up_flag: a device-visible word in pinned host memory that a wave sets when it gives up
 // waiting inside a single-launch form (null if it could not be allocated yet: the first call on a
 // device happened inside a capture); once it is set the library's own choice (tuning mode 1) is
