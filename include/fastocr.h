@@ -57,7 +57,9 @@ typedef enum {
     FASTOCR_EINVAL = -1,        /* null pointer, negative size, tau outside [0,1], ...   */
     FASTOCR_EUNSUPPORTED = -2,  /* dtype / head_dim / group size the kernels do not cover */
     FASTOCR_EWORKSPACE = -3,    /* ws NULL, misaligned or smaller than required           */
-    FASTOCR_EHIP = -4           /* a HIP runtime call (launch, event) failed              */
+    FASTOCR_EHIP = -4,          /* a HIP runtime call (launch, event) failed              */
+    FASTOCR_ETOOLARGE = -5      /* fastocr_dense_decode_attn_static: the shape needs more scratch
+                                   than FASTOCR_STATIC_SCRATCH_BYTES                       */
 } fastocr_status;
 
 typedef enum { FASTOCR_F32 = 0, FASTOCR_BF16 = 1 } fastocr_dtype;
@@ -198,6 +200,27 @@ int fastocr_sparse_decode_attn(const fastocr_kv_view *kv, const fastocr_batch_vi
 int fastocr_dense_decode_attn(const fastocr_kv_view *kv, const fastocr_batch_view *bv,
                               const void *q, int n_q_heads, float scale, void *out, float *lse,
                               void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * fastocr_dense_decode_attn for callers that cannot provide (or allocate) a workspace: code under
+ * HIP-graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and bit-identical results, but the split partials live in a buffer of
+ * FASTOCR_STATIC_SCRATCH_BYTES (8 MiB) of static device memory inside the library (each GPU the
+ * library runs on holds one such buffer until the process ends).  The call allocates nothing: no
+ * hipMalloc / hipFree, no allocating library routine, and the in-launch merge of
+ * fastocr_set_tuning("attn_merge", 2) is never taken here.
+ *   - Shapes whose partials need more than the buffer (fastocr_workspace_bytes(
+ *     FASTOCR_OP_DENSE_DECODE_ATTN, ...) > FASTOCR_STATIC_SCRATCH_BYTES) are refused with
+ *     FASTOCR_ETOOLARGE before anything is enqueued; every configuration of the paper's models
+ *     needs about 1 MiB.
+ *   - All calls on one GPU share that GPU's buffer: calls in order on one stream are safe (every
+ *     partial a call reads it has written first, so nothing needs clearing), calls that overlap
+ *     on one GPU (different streams, concurrent graph replays) race on it and give wrong outputs.
+ */
+#define FASTOCR_STATIC_SCRATCH_BYTES (8u << 20)
+int fastocr_dense_decode_attn_static(const fastocr_kv_view *kv, const fastocr_batch_view *bv,
+                                     const void *q, int n_q_heads, float scale, void *out, float *lse,
+                                     void *hip_stream);
 
 /*
  * A focal layer in one call (Alg. 1, focal branch; Eq. 1 and Eq. 2 with the full cache): the

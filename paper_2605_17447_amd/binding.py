@@ -16,7 +16,8 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfastocr.so")
 
-OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP, ETOOLARGE = 0, -1, -2, -3, -4, -5
+STATIC_SCRATCH_BYTES = 8 << 20
 F32, BF16 = 0, 1
 OP_FOCAL_SCORE, OP_TOPK_FIXATION, OP_SPARSE_DECODE_ATTN, OP_DENSE_DECODE_ATTN, OP_FOCAL_ATTN_SCORE = 0, 1, 2, 3, 4
 (KERNEL_SCORE_LOGITS, KERNEL_SCORE_FINALIZE, KERNEL_TOPK, KERNEL_SPARSE_ATTN, KERNEL_DENSE_ATTN,
@@ -24,7 +25,7 @@ OP_FOCAL_SCORE, OP_TOPK_FIXATION, OP_SPARSE_DECODE_ATTN, OP_DENSE_DECODE_ATTN, O
 
 EXPORTS = (
     "fastocr_keep_count", "fastocr_workspace_bytes", "fastocr_focal_score", "fastocr_topk_fixation",
-    "fastocr_sparse_decode_attn", "fastocr_dense_decode_attn", "fastocr_focal_attn_score", "fastocr_kernel_timer_enable",
+    "fastocr_sparse_decode_attn", "fastocr_dense_decode_attn", "fastocr_dense_decode_attn_static", "fastocr_focal_attn_score", "fastocr_kernel_timer_enable",
     "fastocr_kernel_timer_read", "fastocr_select_focal_layers", "fastocr_stream_probe", "fastocr_set_tuning", "fastocr_exchange_timeouts", "fastocr_strerror", "fastocr_version",
 )
 
@@ -79,6 +80,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.fastocr_sparse_decode_attn.argtypes = [KV, BV, P, I, F, P, P, I64, P, P, SZ, P]
     lib.fastocr_dense_decode_attn.restype = I
     lib.fastocr_dense_decode_attn.argtypes = [KV, BV, P, I, F, P, P, P, SZ, P]
+    lib.fastocr_dense_decode_attn_static.restype = I
+    lib.fastocr_dense_decode_attn_static.argtypes = [KV, BV, P, I, F, P, P, P]
     lib.fastocr_focal_attn_score.restype = I
     lib.fastocr_focal_attn_score.argtypes = [KV, BV, P, I, F, P, P, P, P, P, SZ, P]
     lib.fastocr_kernel_timer_enable.restype, lib.fastocr_kernel_timer_enable.argtypes = I, [I, I]
@@ -285,6 +288,17 @@ def dense_decode_attn(cache: KvCache, batch: SeqBatch, q: torch.Tensor, scale: f
     _check(lib.fastocr_dense_decode_attn(ctypes.byref(kv), ctypes.byref(bv), _ptr(q), q.shape[1],
                                          float(scale), _ptr(out), _ptr(lse), _ptr(ws), ws.numel(),
                                          _stream_handle(stream)), "fastocr_dense_decode_attn")
+
+
+def dense_decode_attn_static(cache: KvCache, batch: SeqBatch, q: torch.Tensor, scale: float, out: torch.Tensor,
+                             lse: Optional[torch.Tensor] = None, stream=None) -> None:
+    """fastocr_dense_decode_attn_static: as dense_decode_attn, scratch in the library's static device buffer."""
+    lib = load_library()
+    kv, bv = cache.view(), batch.view()
+    assert q.is_contiguous() and out.is_contiguous() and out.shape == q.shape and out.dtype == q.dtype
+    _check(lib.fastocr_dense_decode_attn_static(ctypes.byref(kv), ctypes.byref(bv), _ptr(q), q.shape[1],
+                                                float(scale), _ptr(out), _ptr(lse), _stream_handle(stream)),
+           "fastocr_dense_decode_attn_static")
 
 
 def focal_attn_score(cache: KvCache, batch: SeqBatch, q: torch.Tensor, scale: float, out: torch.Tensor,

@@ -134,6 +134,26 @@ bool exchange_trusted()
     return !f || __atomic_load_n(f, __ATOMIC_RELAXED) == 0u;
 }
 
+// ---- workspace in static device memory, for fastocr_dense_decode_attn_static -------------------------
+// The array's name is a host-side handle, not a device address: what kernels and copies get is the
+// address hipGetSymbolAddress returns for the device that is current, asked for once per device
+// (every GPU holds its own copy of the array at its own address).
+static __device__ __align__(256) unsigned char scratch[FASTOCR_STATIC_SCRATCH_BYTES];
+static void *g_scratch_ptr[kMaxDevices];       // guarded by g_mu
+
+static void *static_scratch_ptr()
+{
+    const int dev = current_device();
+    if (dev < 0) return nullptr;
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return nullptr; }
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+
 // ---- shapes -----------------------------------------------------------------------------
 static int check_views(const fastocr_kv_view *kv, const fastocr_batch_view *bv, int n_q_heads)
 {
@@ -389,7 +409,8 @@ int fastocr_topk_fixation(const float *scores, const fastocr_batch_view *bv, dou
 
 static int attn_common(int op, const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
                        int n_q_heads, float scale, const int32_t *sel_idx, const int32_t *sel_cnt,
-                       int64_t kmax, void *out, float *lse, void *ws, size_t ws_bytes, void *hip_stream)
+                       int64_t kmax, void *out, float *lse, void *ws, size_t ws_bytes, void *hip_stream,
+                       bool static_ws = false)
 {
     int rc = check_views(kv, bv, n_q_heads);
     if (rc != FASTOCR_OK) return rc;
@@ -398,6 +419,14 @@ static int attn_common(int op, const fastocr_kv_view *kv, const fastocr_batch_vi
     if (rc != FASTOCR_OK) return rc;
     if (op == FASTOCR_OP_SPARSE_DECODE_ATTN && (!sel_idx || !sel_cnt || kmax < 1)) return FASTOCR_EINVAL;
     const size_t need = fastocr_workspace_bytes(op, kv, bv, n_q_heads, kmax);
+    if (static_ws) {
+        // the library's own buffer: a shape that needs more than it holds is refused before any GPU call
+        if (need > (size_t)FASTOCR_STATIC_SCRATCH_BYTES) return FASTOCR_ETOOLARGE;
+        if (bv->batch == 0) return FASTOCR_OK;
+        ws = static_scratch_ptr();
+        ws_bytes = FASTOCR_STATIC_SCRATCH_BYTES;
+        if (!ws) return FASTOCR_EHIP;
+    }
     rc = check_ws(ws, ws_bytes, need);
     if (rc != FASTOCR_OK) return rc;
     if (bv->batch == 0) return FASTOCR_OK;
@@ -410,7 +439,9 @@ static int attn_common(int op, const fastocr_kv_view *kv, const fastocr_batch_vi
     const int mode = g_tune_attn_merge.load(std::memory_order_relaxed);
     int merge_slot = -1;
     uint32_t *flag = nullptr;
-    if (((op == FASTOCR_OP_SPARSE_DECODE_ATTN && mode != 0) || mode == 2) && attn_merges_in_kernel(s, nsplit) && exchange_trusted())
+    // (never for the static-workspace entry point: the first in-launch merge on a device allocates
+    // the pinned "gave up" word)
+    if (!static_ws && ((op == FASTOCR_OP_SPARSE_DECODE_ATTN && mode != 0) || mode == 2) && attn_merges_in_kernel(s, nsplit) && exchange_trusted())
         merge_slot = exchange_slot(EX_MERGE, (hipStream_t)hip_stream, &flag);
     hipError_t e = launch_attn(s, q, scale, sel_idx, sel_cnt, kmax, out, lse, ws, nsplit, merge_slot, flag, (hipStream_t)hip_stream);
     return e == hipSuccess ? FASTOCR_OK : FASTOCR_EHIP;
@@ -430,6 +461,13 @@ int fastocr_dense_decode_attn(const fastocr_kv_view *kv, const fastocr_batch_vie
 {
     return attn_common(FASTOCR_OP_DENSE_DECODE_ATTN, kv, bv, q, n_q_heads, scale, nullptr, nullptr, 0,
                        out, lse, ws, ws_bytes, hip_stream);
+}
+
+int fastocr_dense_decode_attn_static(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
+                                     int n_q_heads, float scale, void *out, float *lse, void *hip_stream)
+{
+    return attn_common(FASTOCR_OP_DENSE_DECODE_ATTN, kv, bv, q, n_q_heads, scale, nullptr, nullptr, 0,
+                       out, lse, nullptr, 0, hip_stream, /*static_ws=*/true);
 }
 
 int fastocr_focal_attn_score(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
@@ -582,6 +620,7 @@ const char *fastocr_strerror(int status)
     case FASTOCR_EUNSUPPORTED: return "unsupported dtype, head_dim or head count";
     case FASTOCR_EWORKSPACE: return "workspace missing, misaligned or too small";
     case FASTOCR_EHIP: return "HIP runtime error";
+    case FASTOCR_ETOOLARGE: return "shape needs more scratch than the library's static buffer holds (FASTOCR_STATIC_SCRATCH_BYTES)";
     default: return "unknown status";
     }
 }
