@@ -369,11 +369,13 @@ def test_repeat_runs_are_bit_identical():
     case = TinyCase(seed=12, B=2, Hq=64, Hkv=8, d=128, n_vis=[2000, 1300], pre=[9, 3], post=[6, 40], dtype="bf16")
     p = problem_from_case(case)
     first = None
-    for _ in range(5):
+    for _ in range(100):
         sc, _, _ = p.scores()
         idx, cnt = p.topk(sc, 0.05)
         out = p.sparse(idx, cnt)
-        cur = (sc.clone(), idx.clone(), cnt.clone(), out.clone())
+        dense, _ = p.dense()
+        fout, fsc, _, _ = p.focal_attn()
+        cur = (sc.clone(), idx.clone(), cnt.clone(), out.clone(), dense.clone(), fout.clone(), fsc.clone())
         if first is None:
             first = cur
         else:
