@@ -25,15 +25,25 @@ _LIB = os.path.join(_HERE, "libfastocr_oracle.so")
 F32, BF16 = 0, 1
 
 
+# FASTOCR_ORACLE_SANITIZE=1 (set by tests/test_host_sanitizers.py for a child process) builds and
+# loads the same source under AddressSanitizer and UndefinedBehaviorSanitizer instead.
+_SANITIZE = os.environ.get("FASTOCR_ORACLE_SANITIZE") == "1"
+_LIB_SAN = os.path.join(_HERE, "libfastocr_oracle_san.so")
+
+
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2, OpenMP for the outer head loop only)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        tmp = _LIB + f".tmp{os.getpid()}"
+    lib = _LIB_SAN if _SANITIZE else _LIB
+    if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(_SRC):
+        tmp = lib + f".tmp{os.getpid()}"
+        flags = ["-O2"]
+        if _SANITIZE:
+            flags = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer"]
         subprocess.check_call(
-            ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-o", tmp, _SRC, "-lm"]
+            ["gcc", *flags, "-std=c99", "-fPIC", "-shared", "-fopenmp", "-o", tmp, _SRC, "-lm"]
         )
-        os.replace(tmp, _LIB)
-    return _LIB
+        os.replace(tmp, lib)
+    return lib
 
 
 class _KV(ctypes.Structure):

@@ -18,14 +18,23 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
          "-Wno-unused-command-line-argument", "-I", INCLUDE, "-I", CSRC]
 
 
-def build(verbose: bool = False) -> str:
+# Host code only under AddressSanitizer and UndefinedBehaviorSanitizer (the device code is built as
+# always): a checking build for the CPU-only tests of the argument validation, never the product.
+HOST_SANITIZE = ["-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                 "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
+LIB_HOSTSAN = os.path.join(HERE, "libfastocr_hostsan.so")
+
+
+def build(verbose: bool = False, host_sanitize: bool = False) -> str:
     """Compile every source and link the shared library; returns its path."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
     procs = []
+    flags = FLAGS + (HOST_SANITIZE if host_sanitize else [])
+    lib = LIB_HOSTSAN if host_sanitize else LIB
     for src in SOURCES:
-        obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        obj = os.path.join(CSRC, src.replace(".hip", ".san.o" if host_sanitize else ".o"))
+        cmd = [hipcc, *flags, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
@@ -41,10 +50,13 @@ def build(verbose: bool = False) -> str:
             print(out)
     if failed:
         raise RuntimeError("hipcc failed")
-    tmp = LIB + f".tmp{os.getpid()}"
-    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])
-    os.replace(tmp, LIB)
-    return LIB
+    tmp = lib + f".tmp{os.getpid()}"
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs]
+    if host_sanitize:
+        link += ["-fsanitize=address", "-fsanitize=undefined", "-shared-libsan"]
+    subprocess.check_call(link)
+    os.replace(tmp, lib)
+    return lib
 
 
 if __name__ == "__main__":

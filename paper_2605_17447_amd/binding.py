@@ -14,7 +14,8 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libfastocr.so")
+# FASTOCR_LIB names another build of the same library (the host-sanitized one of the CPU tests)
+LIB_PATH = os.environ.get("FASTOCR_LIB") or os.path.join(_HERE, "libfastocr.so")
 
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP, ETOOLARGE = 0, -1, -2, -3, -4, -5
 STATIC_SCRATCH_BYTES = 8 << 20
