@@ -42,6 +42,9 @@ def parse_args():
                     help="launches of the dominant kernel between two that carry HIP events (an event pair costs the "
                          "stream about 4.5 us; 1 = every launch)")
     ap.add_argument("--no-extras", action="store_true", help="skip the comparator / breakdown passes")
+    ap.add_argument("--stacks", default="3,5,4", help="28-layer stacks measured in the extras, by configuration shape "
+                                                        "(3: batch 8, N 4096; 5: ragged paged batch 32, 18 GB; 4: the metric "
+                                                        "workload's shape, 33 GB); empty = none")
     ap.add_argument("--cpu-budget-s", type=float, default=12.0)
     ap.add_argument("--layers", type=int, default=2, help="distinct caches the steps rotate over")
     ap.add_argument("--calibrate", action="store_true",
@@ -58,26 +61,40 @@ def parse_args():
     return ap.parse_args()
 
 
-def stack_extras(fs, fo, torch, np, dev, tau, n_time=30):
-    """Measured (not modelled) blend of focal and pruned layers: the 28-layer attention-only stack of
-    configuration 3 (batch 8, N = 4096, focal layers 2 and 14) driven by the step controller, one
-    decode step captured in a HIP graph and replayed, against 28 dense attention layers captured the
-    same way.  Shapes this small are launch-bound when every call is enqueued from Python."""
-    wl = fs.config(3, steps=n_time + 8, warmup=0)
+def kernel_sources_sha256(names):
+    """Digest of the source files a kernel is built from (the profile summaries under profiles/ record the
+    digest they were taken with, so that a stale traffic figure is not reported for a changed kernel)."""
+    import hashlib
+    h = hashlib.sha256()
+    for n in names:
+        with open(os.path.join(ROOT, "paper_2605_17447_amd", "csrc", n), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def stack_extras(fs, fo, torch, np, dev, tau, cfg, n_time=30, **over):
+    """Measured (not modelled) blend of focal and pruned layers: a 28-layer attention-only stack with
+    focal layers {2, 14} driven by the step controller, one decode step captured in a HIP graph and
+    replayed (the sequences grow by one token per replay), against 28 dense attention layers captured
+    the same way.  cfg 3: batch 8, N = 4096 (launch-bound shapes); cfg 5: batch 32, ragged image spans
+    up to 16384 tokens, paged; cfg 4 with n_layers=28: the metric workload's shape as a stack.  Every
+    layer has its own generated cache."""
+    t_start = fs.config(cfg).steps // 2                   # mid-run, like the single-layer measurement
+    wl = fs.config(cfg, steps=t_start + n_time + 16, warmup=0, **over)
     L, focal = wl.n_layers, wl.focal_layers
     bts = [fs.make_batch(wl, device=dev, layer=l) for l in range(L)]
     bt = bts[0]
-    progress("caches generated")
-    cs = fs.centres(bt, 4)
+    progress("stack config %d: %d caches generated" % (cfg, L))
+    cs = fs.centres(bt, t_start + 4)
     B, Hq, d = wl.batch, wl.n_q_heads, wl.head_dim
     scale = float(np.float32(d ** -0.5))
-    caches = [fo.KvCache(x.k, x.v) for x in bts]
+    caches = [fo.KvCache(x.k, x.v, "bhsd", x.block_table) for x in bts]
     max_seq, max_vis = max(bt.seq_len(wl.steps)), max(bt.n_vis)
     ctl = fo.FixationController(caches, Hq, scale, focal, tau, 0, max_seq, max_vis, B, dev, focal_gap=wl.focal_gap)
-    seq_len = torch.tensor(bt.seq_len(1), dtype=torch.int32, device=dev)
+    seq_len = torch.tensor(bt.seq_len(t_start), dtype=torch.int32, device=dev)
     batch = fo.SeqBatch(seq_len, torch.tensor(bt.vis_start, dtype=torch.int32, device=dev),
                         torch.tensor(bt.n_vis, dtype=torch.int32, device=dev), max_seq, max_vis)
-    qs = [fs.queries_for_step(bts[l], 3, [c[2] for c in cs]) for l in range(L)]
+    qs = [fs.queries_for_step(bts[l], t_start + 2, [c[t_start + 1] for c in cs]) for l in range(L)]
     outs = [torch.zeros_like(q) for q in qs]
     for t in (1, 2):                                   # fallback step, then the steady-state schedule
         ctl.step(t, batch, qs, outs)
@@ -96,8 +113,9 @@ def stack_extras(fs, fo, torch, np, dev, tau, n_time=30):
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
         ctl.step(3, batch, qs, outs)
+    timed(lambda: (g.replay(), seq_len.add_(1)), 3)
     graph_us = timed(lambda: (g.replay(), seq_len.add_(1)), n_time)
-    seq_len.copy_(torch.tensor(bt.seq_len(3), dtype=torch.int32))
+    seq_len.copy_(torch.tensor(bt.seq_len(t_start + 2), dtype=torch.int32))
     ws = torch.empty(max(fo.workspace_bytes(3, c, batch, Hq, 0) for c in caches[:1]), dtype=torch.uint8, device=dev)
     dense = lambda: [fo.dense_decode_attn(caches[l], batch, qs[l], scale, outs[l], ws) for l in range(L)]
     dense()
@@ -105,12 +123,28 @@ def stack_extras(fs, fo, torch, np, dev, tau, n_time=30):
     gd = torch.cuda.CUDAGraph()
     with torch.cuda.graph(gd):
         dense()
+    timed(lambda: (gd.replay(), seq_len.add_(1)), 3)
     dense_us = timed(lambda: (gd.replay(), seq_len.add_(1)), n_time)
-    return {"workload": "config3 %s: %d attention layers, batch %d, Hq %d, Hkv %d, N %d, focal layers %s, tau %g, "
-                        "one decode step per HIP-graph replay" % (wl.name, L, B, Hq, wl.n_kv_heads, max_vis, list(focal), tau),
+    e = 2 if wl.dtype == "bf16" else 4
+    R = wl.n_kv_heads * d * e
+    kv_gb = sum(x.k.numel() + x.v.numel() for x in bts) * e / 1e9
+    # bytes the method must move per decode step: focal layers read all of K and V once, the others text + kept rows
+    s_mid = [n + bt.prefix[b] + t_start + 2 + (11 + n_time) // 2 for b, n in enumerate(bt.n_vis)]
+    dense_b = sum(s * 2 * R for s in s_mid)
+    sparse_b = sum((fo.keep_count(n, tau) + s - n) * 2 * R for s, n in zip(s_mid, bt.n_vis))
+    step_bytes = len(focal) * dense_b + (L - len(focal)) * sparse_b
+    progress("stack config %d measured" % cfg)
+    return {"workload": "config%d shape %s: %d attention layers (%.1f GB of K and V, a generated cache per layer), batch %d, Hq %d, "
+                        "Hkv %d, N %s, %s, focal layers %s, tau %g, decode steps from %d on (mid-run text length), one decode step per HIP-graph replay"
+                        % (cfg, wl.name, L, kv_gb, B, Hq, wl.n_kv_heads,
+                           max_vis if min(bt.n_vis) == max_vis else "%d..%d" % (min(bt.n_vis), max_vis),
+                           "paged" if wl.paged else "contiguous", list(focal), tau, t_start + 2),
             "fastocr_step_us": round(graph_us, 1), "dense_step_us": round(dense_us, 1),
             "measured_speedup_vs_dense": round(dense_us / graph_us, 3),
-            "fastocr_step_us_without_graph": round(eager_us, 1)}
+            "fastocr_step_us_without_graph": round(eager_us, 1),
+            "fastocr_step_algorithmic_GBs": round(step_bytes / graph_us / 1e3, 1),
+            "fastocr_step_frac_of_peak": round(step_bytes / graph_us / 1e3 / HBM_PEAK_GBS, 4),
+            "dense_step_GBs": round(L * dense_b / dense_us / 1e3, 1)}
 
 
 def progress(msg):
@@ -246,17 +280,33 @@ def main():
         score_bytes = B * (mean_S * 2 * R + 2 * Hq * d * e) + scores_out     # K and V rows, queries in, outputs and scores out
     k_ms = float(np.mean(logits_ms)) if logits_ms else float("nan")
     achieved = score_bytes / (k_ms * 1e-3) / 1e9
-    traffic = None
+    traffic, traffic_source = None, None
     prof = os.path.join(ROOT, "profiles", "focal_layer_config4_tau0.05.md" if focal_mode else "three_step_config4_tau0.05.md")
+    kernel_files = (["focal_fused.hip"] if focal_mode else ["score_resident.hip"]) + ["resident.hpp", "common.hpp", "kernels.hpp"]
     if wl.config_id == 4 and abs(tau - 0.05) < 1e-12 and not args.batch and os.path.exists(prof):
-        # HBM bytes per launch of this kernel from the committed rocprofv3 --pmc summary of this command
+        # HBM bytes per launch of this kernel from the committed rocprofv3 --pmc summary of this command; only
+        # reported while the kernel's sources are the ones the summary was taken with
         for line in open(prof):
             if line.startswith("machine-readable:"):
-                traffic = json.loads(line.split(":", 1)[1])["traffic_bytes_per_launch"]
+                rec = json.loads(line.split(":", 1)[1])
+                same = rec.get("kernel_sources_sha256") == kernel_sources_sha256(kernel_files)
+                traffic = rec["traffic_bytes_per_launch"] if same else None
+                traffic_source = {"file": os.path.relpath(prof, ROOT), "kernel_sources_sha256": rec.get("kernel_sources_sha256"),
+                                  "kernel_sources_unchanged": same}
+    # the whole path against the same peak: the bytes the three steps must move per step (K once, the kept
+    # K and V rows, scores out and in, sets, queries, outputs) over the step time
+    keep = [fo.keep_count(n, tau) for n in bt.n_vis]
+    tn = [float(seq_lens[n_warm:, b].float().mean().item()) - n for b, n in enumerate(bt.n_vis)]
+    path_bytes = sum((n + t_) * R + (k_ + t_) * 2 * R + 8 * n + 12 * k_ + 3 * Hq * d * e for n, t_, k_ in zip(bt.n_vis, tn, keep))
+    if focal_mode:
+        path_bytes = sum((n + t_) * 2 * R + 8 * n + 8 * k_ + 2 * Hq * d * e for n, t_, k_ in zip(bt.n_vis, tn, keep))
+    path_gbs = path_bytes / (ms_per_step * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "focal_fused_kernel (focal layer: K and V stream, dense output and scores)" if focal_mode
                 else "score_resident_kernel (focal scoring: K stream, logits kept in registers)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_source,
+                "path_frac": round(path_gbs / HBM_PEAK_GBS, 4), "path_achieved": round(path_gbs, 1),
+                "path_algorithmic_bytes": int(path_bytes),
                 "algorithmic_bytes": int(score_bytes), "avg_launch_us": round(k_ms * 1e3, 2),
                 "launch_us_p10_p50_p90": [round(float(np.percentile(logits_ms, p)) * 1e3, 2) for p in (10, 50, 90)]
                 if logits_ms else None,
@@ -343,16 +393,33 @@ def main():
             "dense_layer_steps_per_s": round(1e3 / dense_ms, 2),
             "speedup_three_step_vs_dense": round(dense_ms / ms_per_step, 3),
             "speedup_sparse_vs_dense": round(dense_ms / sparse_ms, 3),
-            "blended_speedup_vs_dense": {"focal_fraction_0.1": round(dense_ms / blend(0.1), 3),
-                                         "focal_fraction_2_of_28": round(dense_ms / blend(2 / 28), 3)},
+            "modelled_blended_speedup_vs_dense": {"focal_fraction_0.1": round(dense_ms / blend(0.1), 3),
+                                                  "focal_fraction_2_of_28": round(dense_ms / blend(2 / 28), 3),
+                                                  "how": "a formula over the separately timed calls above; the measured stacks are below"},
             "measured_read_stream_ceiling_GBs": round(read_ceiling, 1),
             "dense_achieved_GBs": round(dense_bytes / (dense_ms * 1e-3) / 1e9, 1),
             "sparse_achieved_GBs": round(sparse_bytes / (sparse_ms * 1e-3) / 1e9, 1),
             "kernels_us": kernels_us,
-            "stack": stack_extras(fs, fo, torch, np, dev, tau),
             "paper_context": "paper reports 3.0x lower attention latency (26.00 -> 8.69 ms/step, whole model, "
                              "Qwen2.5-VL 3B, batch 12, Nvidia H800): other hardware, not a target",
         }
+
+        # measured stacks: free this run's caches first (the largest stack holds 33 GB by itself)
+        stacks = [int(x) for x in args.stacks.split(",") if x.strip()]
+        result["extras"]["measured_stacks"] = {}
+        if stacks:
+            keep_for_cpu = None if args.no_cpu_baseline else [(x.k.cpu(), x.v.cpu()) for x in bts]
+            for x in bts:
+                x.k = x.v = None
+            del caches, layer_caches, cache
+            torch.cuda.empty_cache()
+            for c in stacks:
+                over = dict(n_layers=28, focal_layers=(2, 14), focal_gap=8) if c == 4 else {}
+                result["extras"]["measured_stacks"]["config%d_shape" % c] = stack_extras(fs, fo, torch, np, dev, tau, c, **over)
+                torch.cuda.empty_cache()
+            if keep_for_cpu is not None:
+                for x, (k_, v_) in zip(bts, keep_for_cpu):
+                    x.k, x.v = k_, v_
 
     # ---- the oracle timed on this machine's host cores (a baseline, not a target) -----------------
     if not args.no_cpu_baseline and not focal_mode:
@@ -360,7 +427,7 @@ def main():
         threads = oracle.max_threads()
         n_seq, cpu_s, n_steps_cpu = 0, 0.0, 0
         i = total - 1
-        while cpu_s < args.cpu_budget_s and i >= 0:
+        while cpu_s < args.cpu_budget_s:
             t_dec = t_first + i
             src = bts[i % L]
             for b in range(B):
@@ -376,7 +443,7 @@ def main():
                 if cpu_s >= args.cpu_budget_s:
                     break
             n_steps_cpu += 1
-            i -= 1
+            i = (i - 1) % total            # a short run's steps are taken again until the time budget is spent
         # the same oracle on one thread, one sequence-step (context for the all-core figure)
         src = bts[(total - 1) % L]
         ok1 = oracle.Cache.from_bhsd(fs.to_oracle_array(src.k[0:1]), fs.to_oracle_array(src.v[0:1]))
@@ -390,9 +457,10 @@ def main():
         result["cpu_baseline"] = {
             "value": round(n_seq / (B * cpu_s), 5), "unit": "layer-steps/s", "cores": threads, "kind": "oracle",
             "single_thread_value": round(1.0 / (B * one_thread_s), 5),
-            "sample": "%d sequence-steps (batch %d, decode steps %d..%d backwards) of the whole three-step path, "
-                      "%.1f s of CPU time; rate scaled to the full batch"
-                      % (n_seq, B, t_first + total - 1, t_first + total - n_steps_cpu, cpu_s)}
+            "sample": "%d sequence-steps (batch %d, decode steps %d backwards, %d step(s) of the %d-step run, taken again in "
+                      "turn until the %.0f s time budget was spent) of the whole three-step path, %.1f s of CPU time; "
+                      "rate scaled to the full batch"
+                      % (n_seq, B, t_first + total - 1, min(n_steps_cpu, total), total, args.cpu_budget_s, cpu_s)}
 
     print(json.dumps(result))
 
