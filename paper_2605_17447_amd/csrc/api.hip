@@ -204,7 +204,7 @@ static Shape make_shape(const fastocr_kv_view *kv, const fastocr_batch_view *bv,
     auto a16 = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
     const bool aligned = a16(kv->k) && a16(kv->v) && kv->stride_token % 8 == 0 &&
                          kv->stride_head % 8 == 0 && kv->stride_seq % 8 == 0 && kv->stride_page % 8 == 0;
-    s.fast = kv->dtype == FASTOCR_BF16 && kv->head_dim == 128 && n_q_heads / kv->n_kv_heads <= 16 && aligned;
+    s.fast = kv->dtype == FASTOCR_BF16 && (kv->head_dim == 128 || kv->head_dim == 64) && n_q_heads / kv->n_kv_heads <= 16 && aligned;
     const int64_t esz = kv->dtype == FASTOCR_BF16 ? 2 : 4;
     auto m16 = [&](int64_t elems) { return (elems * esz) % 16 == 0; };
     s.vec16 = a16(kv->k) && a16(kv->v) && m16(kv->stride_token) && m16(kv->stride_head) && m16(kv->stride_seq) &&

@@ -67,13 +67,20 @@ constexpr int kTile = 32;          // tokens per wave tile (two 16-token MFMA ti
 __device__ __forceinline__ int tile_row(int lg, int e) { return (e < 4) ? (4 * lg + e) : (16 + 4 * lg + (e - 4)); }
 
 // -----------------------------------------------------------------------------------------
-// MFMA kernel: bf16, head_dim = 128, G <= 16.
+// MFMA kernel: bf16, head_dim D = 128 or 64, G <= 16.
+// D = 64: rows are 128 bytes (8 chunks of 16), a 1 KB load instruction brings 8 rows, the logits take
+// two k-steps and the output four 16-dim blocks.  K goes through the LDS tile as for D = 128 (pitch
+// 128 bytes, chunk ^ ((row >> 1) & 7)).  V: P*V's A operand wants, in lane (li, lg), the 8 tokens of
+// k-block lg for ONE dim -- rows i and i + 8 of the operand share a 16-byte chunk (chunk i & 7) and
+// take its even / odd elements: row i is dim 8 (i & 7) + 2 t + (i >> 3) of block t.  Lanes li < 8
+// load the k-block's first four tokens, lanes li >= 8 its last four, and the halves swap through
+// a data-parallel-primitive move (lane ^ 8), so every V byte is still fetched once.
 // -----------------------------------------------------------------------------------------
 // kWaves waves per workgroup walk the range.  Dense: the workgroup's tiles are dealt to its waves
 // in turn.  Gather: the attended list is cut into nsplit * kWaves contiguous pieces, one per wave,
 // of equal length to within one token (or one tile, for short lists: see below) -- with a
 // handful of tiles per wave, whole tiles would leave some waves a quarter more bytes than others.
-template <bool GATHER, bool PAGED, int kWaves, int MODE>
+template <int D, bool GATHER, bool PAGED, int kWaves, int MODE>
 __global__ __launch_bounds__(64 * kWaves, 8 / kWaves) void attn_mfma_kernel(
     KvDev kv, BatchDev bv, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2,
     const int32_t *__restrict__ sel_idx, const int32_t *__restrict__ sel_cnt, int64_t kmax,
@@ -84,6 +91,11 @@ __global__ __launch_bounds__(64 * kWaves, 8 / kWaves) void attn_mfma_kernel(
     __shared__ float sm_m[kWaves][16], sm_z[kWaves][16];
     __shared__ uint32_t sm_tag;
 
+    static_assert(D == 128 || D == 64, "head_dim 128 or 64");
+    static_assert(D == 128 || MODE != kMerge, "the in-launch merge's word layout is for head_dim 128");
+    constexpr int KS = D / 32;            // k-steps of the logits
+    constexpr int NACC = D / 16;          // 16-dim blocks of the output
+    constexpr int NL = D / 16;            // 1 KB load instructions per 32-token K (or V) tile
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int li = lane & 15, lg = lane >> 4;
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
@@ -134,12 +146,12 @@ __global__ __launch_bounds__(64 * kWaves, 8 / kWaves) void attn_mfma_kernel(
     auto tile_pos = [&](int i) { return GATHER ? wp0 + i * kTile : (tfirst + i * kWaves) * kTile; };
 
     // Q as the B operand: lane (head li, k-block lg) holds dims 8*(4kk+lg) .. +7 for step kk.
-    u32x4 qreg[4];
+    u32x4 qreg[KS];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
+    for (int kk = 0; kk < KS; ++kk) {
         qreg[kk] = u32x4{0u, 0u, 0u, 0u};
         if (li < G) {
-            const uint16_t *qp = q + ((int64_t)b * Hq + (int64_t)kvh * G + li) * 128 + 8 * (4 * kk + lg);
+            const uint16_t *qp = q + ((int64_t)b * Hq + (int64_t)kvh * G + li) * D + 8 * (4 * kk + lg);
             qreg[kk] = *reinterpret_cast<const u32x4 *>(qp);
         }
     }
@@ -156,48 +168,69 @@ __global__ __launch_bounds__(64 * kWaves, 8 / kWaves) void attn_mfma_kernel(
     };
     const int64_t seq_base = row_offset<false>(kv, b, 0, kvh);
 
-    auto load_tile = [&](int i, int64_t off, u32x4(&K)[8], u32x4(&V)[8]) {
+    // D = 64: which of the k-block's halves this lane loads of V, and its chunk of a row
+    const int vh = li >> 3, lc = lane & 7;
+    auto load_tile = [&](int i, int64_t off, u32x4(&K)[NL], u32x4(&V)[NL]) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int r = tile_row(lg, e);
-            int64_t ro;
-            if (GATHER || PAGED) ro = __shfl(off, r);
-            else ro = seq_base + (int64_t)min(tile_pos(i) + r, L - 1) * kv.stride_token;
-            V[e] = stream_load(vbase + ro + 8 * li);
-            K[e] = stream_load(kbase + ro + 8 * li);
+        for (int e = 0; e < NL; ++e) {
+            if constexpr (D == 128) {
+                const int r = tile_row(lg, e);
+                int64_t ro;
+                if (GATHER || PAGED) ro = __shfl(off, r);
+                else ro = seq_base + (int64_t)min(tile_pos(i) + r, L - 1) * kv.stride_token;
+                V[e] = stream_load(vbase + ro + 8 * li);
+                K[e] = stream_load(kbase + ro + 8 * li);
+            } else {
+                // V: row 16 vh + 4 lg + e (the k-block's tokens); K: rows 8e .. 8e+7, one per 8 lanes
+                const int rv = 16 * vh + 4 * lg + e, rk = 8 * e + (lane >> 3);
+                int64_t rov, rok;
+                if (GATHER || PAGED) { rov = __shfl(off, rv); rok = __shfl(off, rk); }
+                else {
+                    rov = seq_base + (int64_t)min(tile_pos(i) + rv, L - 1) * kv.stride_token;
+                    rok = seq_base + (int64_t)min(tile_pos(i) + rk, L - 1) * kv.stride_token;
+                }
+                V[e] = stream_load(vbase + rov + 8 * lc);
+                K[e] = stream_load(kbase + rok + 8 * lc);
+            }
         }
     };
 
     float m = -INFINITY, zl = 0.f;
-    f32x4 acc[8];
+    f32x4 acc[NACC];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < NACC; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    auto compute = [&](int i, u32x4(&K)[8], u32x4(&V)[8]) {
-        u32x4 ka[8];
+    auto compute = [&](int i, u32x4(&K)[NL], u32x4(&V)[NL]) {
+        u32x4 ka[2 * KS];
         {
             unsigned char *sw = smem[wave];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int r = tile_row(lg, e);
-                *reinterpret_cast<u32x4 *>(sw + r * 256 + ((li ^ (r & 15)) << 4)) = K[e];
+            for (int e = 0; e < NL; ++e) {
+                if constexpr (D == 128) {
+                    const int r = tile_row(lg, e);
+                    *reinterpret_cast<u32x4 *>(sw + r * 256 + ((li ^ (r & 15)) << 4)) = K[e];
+                } else {
+                    const int r = 8 * e + (lane >> 3);
+                    *reinterpret_cast<u32x4 *>(sw + r * 128 + ((lc ^ ((r >> 1) & 7)) << 4)) = K[e];
+                }
             }
             wave_lds_fence();
 #pragma unroll
             for (int T = 0; T < 2; ++T)
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    const int c = 4 * kk + lg;
-                    ka[4 * T + kk] = *reinterpret_cast<const u32x4 *>(sw + (16 * T + li) * 256 + (((c ^ li) & 15) << 4));
+                for (int kk = 0; kk < KS; ++kk) {
+                    const int c = 4 * kk + lg, r = 16 * T + li;
+                    if constexpr (D == 128) ka[KS * T + kk] = *reinterpret_cast<const u32x4 *>(sw + r * 256 + (((c ^ li) & 15) << 4));
+                    else ka[KS * T + kk] = *reinterpret_cast<const u32x4 *>(sw + r * 128 + ((c ^ ((r >> 1) & 7)) << 4));
                 }
             wave_lds_fence();
         }
         f32x4 s0 = f32x4{0.f, 0.f, 0.f, 0.f}, s1 = s0;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
+        for (int kk = 0; kk < KS; ++kk) {
             s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[kk]),
                                                          __builtin_bit_cast(bf16x8, qreg[kk]), s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[4 + kk]),
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[KS + kk]),
                                                          __builtin_bit_cast(bf16x8, qreg[kk]), s1, 0, 0, 0);
         }
         // lane (head li, group lg): s0[r] is token 4lg+r of the tile, s1[r] token 16+4lg+r
@@ -223,15 +256,41 @@ __global__ __launch_bounds__(64 * kWaves, 8 / kWaves) void attn_mfma_kernel(
         bf16x8 pb;
 #pragma unroll
         for (int e = 0; e < 8; ++e) pb[e] = (__bf16)p[e];
+        if constexpr (D == 128) {
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            acc[t] *= alpha;
-            const int w = t >> 1;
-            const uint32_t selb = (t & 1) ? 0x07060302u : 0x05040100u;
-            u32x4 a;
+            for (int t = 0; t < NACC; ++t) {
+                acc[t] *= alpha;
+                const int w = t >> 1;
+                const uint32_t selb = (t & 1) ? 0x07060302u : 0x05040100u;
+                u32x4 a;
 #pragma unroll
-            for (int pp = 0; pp < 4; ++pp) a[pp] = __builtin_amdgcn_perm(V[2 * pp + 1][w], V[2 * pp][w], selb);
-            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), pb, acc[t], 0, 0, 0);
+                for (int pp = 0; pp < 4; ++pp) a[pp] = __builtin_amdgcn_perm(V[2 * pp + 1][w], V[2 * pp][w], selb);
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), pb, acc[t], 0, 0, 0);
+            }
+        } else {
+            // fa[e]: this lane's chunk of token 4lg + e, sb[e]: of token 16 + 4lg + e -- one half loaded by
+            // this lane, the other by lane ^ 8
+            u32x4 fa[4], sb[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const uint32_t own = V[e][w];
+                    const uint32_t other = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)own, 0x128, 0xf, 0xf, false);   // row_ror:8 = lane ^ 8
+                    fa[e][w] = vh ? other : own;
+                    sb[e][w] = vh ? own : other;
+                }
+            const uint32_t selb = vh ? 0x07060302u : 0x05040100u;      // rows 8 .. 15 of the operand take the odd elements
+#pragma unroll
+            for (int t = 0; t < NACC; ++t) {
+                acc[t] *= alpha;
+                u32x4 a;
+                a[0] = __builtin_amdgcn_perm(fa[1][t], fa[0][t], selb);
+                a[1] = __builtin_amdgcn_perm(fa[3][t], fa[2][t], selb);
+                a[2] = __builtin_amdgcn_perm(sb[1][t], sb[0][t], selb);
+                a[3] = __builtin_amdgcn_perm(sb[3][t], sb[2][t], selb);
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), pb, acc[t], 0, 0, 0);
+            }
         }
     };
 
@@ -241,7 +300,7 @@ __global__ __launch_bounds__(64 * kWaves, 8 / kWaves) void attn_mfma_kernel(
         // at the join (and a copy of the step without the prefetch for the last tile costs more
         // registers than the kernel has).  Past the wave's last tile it fetches a single row (all
         // lanes the same address) instead of a tile.
-        u32x4 KA[8], VA[8], KB[8], VB[8];
+        u32x4 KA[NL], VA[NL], KB[NL], VB[NL];
         int i = 0;
         const int last = nt - 1;
         if (!(GATHER || PAGED)) {
@@ -284,11 +343,16 @@ tiles_done:
     // ---- cross-wave merge through LDS -----------------------------------------------------
     zl += __shfl_xor(zl, 16);
     zl += __shfl_xor(zl, 32);
-    float *buf = reinterpret_cast<float *>(smem[wave]);        // [16 heads][128 dims]
+    float *buf = reinterpret_cast<float *>(smem[wave]);        // [16 heads][D dims]
 #pragma unroll
-    for (int t = 0; t < 8; ++t)
+    for (int t = 0; t < NACC; ++t)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) buf[li * 128 + 32 * lg + 8 * r + t] = acc[t][r];
+        for (int r = 0; r < 4; ++r) {
+            // the operand row 4lg + r of block t: dim 8 row + t (D = 128), dim 8 (row & 7) + 2 t + (row >> 3) (D = 64)
+            const int row = 4 * lg + r;
+            const int dim = D == 128 ? 8 * row + t : 8 * (row & 7) + 2 * t + (row >> 3);
+            buf[li * D + dim] = acc[t][r];
+        }
     if (lg == 0) { sm_m[wave][li] = m; sm_z[wave][li] = zl; }
     __syncthreads();
     const uint32_t tag = MODE == kMerge ? sm_tag : 0u;
@@ -296,8 +360,8 @@ tiles_done:
     const int np = nsplit - 1;                                       // ranges that publish (kMerge)
     // the stream's published partials: kMergeMaxSplits - 1 fixed places of kMergePitch words
     unsigned long long *words = MODE == kMerge ? g_merge_words[merge_slot] + (int64_t)stream_id * (kMergeMaxSplits - 1) * kMergePitch : nullptr;
-    for (int idx = threadIdx.x; idx < G * 128; idx += 64 * kWaves) {
-        const int hh = idx >> 7, c = idx & 127;
+    for (int idx = threadIdx.x; idx < G * D; idx += 64 * kWaves) {
+        const int hh = idx / D, c = idx % D;
         float M = sm_m[0][hh];
 #pragma unroll
         for (int w = 1; w < kWaves; ++w) M = fmaxf(M, sm_m[w][hh]);
@@ -306,7 +370,7 @@ tiles_done:
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) {
                 const float f = fast_exp2(sm_m[w][hh] - M);
-                o += f * reinterpret_cast<const float *>(smem[w])[hh * 128 + c];
+                o += f * reinterpret_cast<const float *>(smem[w])[hh * D + c];
                 Z += f * sm_z[w][hh];
             }
         }
@@ -362,18 +426,18 @@ tiles_done:
                 }
             }
             // a range that never published: no number is better than a wrong one
-            out[bh * 128 + c] = ok ? f32_to_bf16_bits(Zt > 0.f ? ot / Zt : 0.f) : (uint16_t)0x7fc0;
+            out[bh * D + c] = ok ? f32_to_bf16_bits(Zt > 0.f ? ot / Zt : 0.f) : (uint16_t)0x7fc0;
             if (lse && c == 0) lse[bh] = !ok ? __builtin_nanf("") : (Zt > 0.f ? (Mt + log2f(Zt)) * kLn2 : -INFINITY);
             if (idx == 0 && !ok) {
                 __hip_atomic_fetch_add(&g_merge_timeouts, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (gave_up_flag) __hip_atomic_store(gave_up_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
             }
         } else if (MODE == kDirect) {
-            out[bh * 128 + c] = f32_to_bf16_bits(Z > 0.f ? o / Z : 0.f);
+            out[bh * D + c] = f32_to_bf16_bits(Z > 0.f ? o / Z : 0.f);
             if (lse && c == 0) lse[bh] = Z > 0.f ? (M + log2f(Z)) * kLn2 : -INFINITY;
         } else {
             const int64_t ph = bh * nsplit + split;
-            part_o[ph * 128 + c] = o;
+            part_o[ph * D + c] = o;
             if (c == 0) { part_ml[ph * 2] = M; part_ml[ph * 2 + 1] = Z; }
         }
     }
@@ -583,7 +647,7 @@ size_t attn_workspace_bytes(const Shape &s, int nsplit)
 
 bool attn_merges_in_kernel(const Shape &s, int nsplit)
 {
-    if (!mfma_path(s) || nsplit < 2 || nsplit > kMergeMaxSplits) return false;
+    if (!mfma_path(s) || s.kv.head_dim != 128 || nsplit < 2 || nsplit > kMergeMaxSplits) return false;
     const size_t streams = (size_t)s.batch * s.kv.n_kv_heads;
     const size_t G = s.n_q_heads / s.kv.n_kv_heads;
     return streams <= (size_t)kMergeMaxStreams && G <= (size_t)kMergeMaxG;
@@ -601,13 +665,18 @@ static void launch_mfma(int kid, const Shape &s, const void *q, float scale_log2
     // the stream's last range waits at most this long for the others (they run concurrently and
     // finish within microseconds of each other); past it the outputs are NaN but the call ends
     const long long spin_ticks = tune_spin_ticks();
-#define FASTOCR_ATTN(W, MODE) FASTOCR_LAUNCH(kid, (attn_mfma_kernel<GATHER, PAGED, W, MODE>), grid, dim3(64 * W), 0, stream, \
+#define FASTOCR_ATTN(DD, W, MODE) FASTOCR_LAUNCH(kid, (attn_mfma_kernel<DD, GATHER, PAGED, W, MODE>), grid, dim3(64 * W), 0, stream, \
         s.kv, s.bv, (const uint16_t *)q, s.n_q_heads, G, scale_log2, sel_idx, sel_cnt, kmax, part_o, part_ml, nsplit, \
         (uint16_t *)out, lse, slot, spin_ticks, flag)
-    if (nsplit == 1) FASTOCR_ATTN(8, kDirect);       // one range per stream: eight waves, final output
-    else if (merge) FASTOCR_ATTN(8, kMerge);         // the stream's last range merges inside the launch
-    else if (tune_attn_waves() == 8) FASTOCR_ATTN(8, kPartial);
-    else FASTOCR_ATTN(4, kPartial);
+    if (s.kv.head_dim == 64) {
+        if (nsplit == 1) FASTOCR_ATTN(64, 8, kDirect);
+        else if (tune_attn_waves() == 8) FASTOCR_ATTN(64, 8, kPartial);
+        else FASTOCR_ATTN(64, 4, kPartial);
+    }
+    else if (nsplit == 1) FASTOCR_ATTN(128, 8, kDirect);       // one range per stream: eight waves, final output
+    else if (merge) FASTOCR_ATTN(128, 8, kMerge);         // the stream's last range merges inside the launch
+    else if (tune_attn_waves() == 8) FASTOCR_ATTN(128, 8, kPartial);
+    else FASTOCR_ATTN(128, 4, kPartial);
 #undef FASTOCR_ATTN
 }
 

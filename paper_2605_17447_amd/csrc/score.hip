@@ -31,7 +31,9 @@ __host__ __device__ inline int park_heads(int G) { return (G + 3) / 4 * 4; }
 //   GR = 16: heads fill all 16 rows; two accumulators per tile.
 // Each lane keeps a running (max, sum-exp) for its 4 heads; lanes, waves and ranges are merged
 // at the end.
-template <bool PAGED, int GR, int kWaves, int NBUF>
+// D = 64 (rows of 128 bytes): a load instruction brings 8 rows, the LDS tile has a pitch of 128
+// bytes with chunk ^ ((row >> 1) & 7), and the product takes two k-steps per 16-token half.
+template <int D, bool PAGED, int GR, int kWaves, int NBUF>
 __global__ __launch_bounds__(64 * kWaves) void score_mfma_kernel(
     KvDev kv, BatchDev bv, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2,
     float *__restrict__ logits, int64_t pitch, float *__restrict__ part_ml, int nsplit)
@@ -39,6 +41,9 @@ __global__ __launch_bounds__(64 * kWaves) void score_mfma_kernel(
     __shared__ __align__(16) unsigned char smem[kWaves][8192];
     __shared__ float sm_m[kWaves][16], sm_z[kWaves][16];
 
+    static_assert(D == 128 || D == 64, "head_dim 128 or 64");
+    constexpr int KS = D / 32;            // k-steps per product
+    constexpr int NL = D / 16;            // 1 KB load instructions per 32-token tile
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int li = lane & 15, lg = lane >> 4;
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
@@ -51,18 +56,18 @@ __global__ __launch_bounds__(64 * kWaves) void score_mfma_kernel(
     const int t0 = split * tps, t1 = min(ntile, t0 + tps);
 
     // Q as the A operand: lane (row li, k-block lg) holds dims 32*kk + 8*lg .. +7 of step kk.
-    u32x4 qlo[4], qhi[4];
+    u32x4 qlo[KS], qhi[KS];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
+    for (int kk = 0; kk < KS; ++kk) {
         qlo[kk] = u32x4{0u, 0u, 0u, 0u};
         qhi[kk] = u32x4{0u, 0u, 0u, 0u};
         const int hl = li, hh = li - 8;
         if (hl < G && (GR == 16 || hl < 8)) {
-            const uint16_t *qp = q + ((int64_t)b * Hq + (int64_t)kvh * G + hl) * 128 + 8 * (4 * kk + lg);
+            const uint16_t *qp = q + ((int64_t)b * Hq + (int64_t)kvh * G + hl) * D + 8 * (4 * kk + lg);
             qlo[kk] = *reinterpret_cast<const u32x4 *>(qp);
         }
         if (GR == 8 && hh >= 0 && hh < G) {
-            const uint16_t *qp = q + ((int64_t)b * Hq + (int64_t)kvh * G + hh) * 128 + 8 * (4 * kk + lg);
+            const uint16_t *qp = q + ((int64_t)b * Hq + (int64_t)kvh * G + hh) * D + 8 * (4 * kk + lg);
             qhi[kk] = *reinterpret_cast<const u32x4 *>(qp);
         }
     }
@@ -74,17 +79,22 @@ __global__ __launch_bounds__(64 * kWaves) void score_mfma_kernel(
         return row_offset<PAGED>(kv, b, p, kvh);
     };
 
-    // load e covers rows 4e .. 4e+3 of the tile: lane group lg takes row 4e+lg, lane li its 16-byte chunk
-    auto load_tile = [&](int tile, int64_t off, u32x4(&K)[8]) {
+    // load e covers rows 4e .. 4e+3 of the tile (D = 128: lane group lg takes row 4e+lg, lane li its 16-byte
+    // chunk) or rows 8e .. 8e+7 (D = 64: one row per 8 lanes)
+    constexpr int CH = D / 8;                      // 16-byte chunks per row
+    const int lrow = lane / CH, lchunk = lane % CH;
+    auto load_tile = [&](int tile, int64_t off, u32x4(&K)[NL]) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int r = 4 * e + lg;
+        for (int e = 0; e < NL; ++e) {
+            const int r = (64 / CH) * e + lrow;
             int64_t ro;
             if (PAGED) ro = __shfl(off, r);
             else ro = seq_base + (int64_t)min(tile * kTile + r, L - 1) * kv.stride_token;
-            K[e] = stream_load(kbase + ro + 8 * li);
+            K[e] = stream_load(kbase + ro + 8 * lchunk);
         }
     };
+    // byte offset of chunk c of row r in the wave's LDS tile
+    auto lds_at = [&](int r, int c) { return D == 128 ? r * 256 + (((c ^ r) & 15) << 4) : r * 128 + ((c ^ ((r >> 1) & 7)) << 4); };
 
     // heads of this lane: hbase .. hbase+3 ; token of the tile: li (+16 in the upper lane groups for GR = 8)
     const int hbase = (GR == 8) ? 4 * (lg & 1) : 4 * lg;
@@ -95,34 +105,32 @@ __global__ __launch_bounds__(64 * kWaves) void score_mfma_kernel(
     for (int r = 0; r < 4; ++r) { m[r] = kMinusHuge; z[r] = 0.f; }
     float *lpark = logits + ((int64_t)b * kv.n_kv_heads + kvh) * pitch * Gp + hbase;
 
-    auto compute = [&](int tile, u32x4(&K)[8]) {
+    auto compute = [&](int tile, u32x4(&K)[NL]) {
         unsigned char *sw = smem[wave];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int r = 4 * e + lg;
-            *reinterpret_cast<u32x4 *>(sw + r * 256 + ((li ^ (r & 15)) << 4)) = K[e];
+        for (int e = 0; e < NL; ++e) {
+            const int r = (64 / CH) * e + lrow;
+            *reinterpret_cast<u32x4 *>(sw + lds_at(r, lchunk)) = K[e];
         }
         wave_lds_fence();
-        u32x4 kb[8];
+        u32x4 kb[2 * KS];
 #pragma unroll
         for (int T = 0; T < 2; ++T)
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const int c = 4 * kk + lg;
-                kb[4 * T + kk] = *reinterpret_cast<const u32x4 *>(sw + (16 * T + li) * 256 + (((c ^ li) & 15) << 4));
-            }
+            for (int kk = 0; kk < KS; ++kk)
+                kb[KS * T + kk] = *reinterpret_cast<const u32x4 *>(sw + lds_at(16 * T + li, 4 * kk + lg));
         wave_lds_fence();
         const int p0 = tile * kTile;
         if (GR == 8) {
             f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
+            for (int kk = 0; kk < KS; ++kk)
                 s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qlo[kk]),
                                                             __builtin_bit_cast(bf16x8, kb[kk]), s, 0, 0, 0);
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
+            for (int kk = 0; kk < KS; ++kk)
                 s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qhi[kk]),
-                                                            __builtin_bit_cast(bf16x8, kb[4 + kk]), s, 0, 0, 0);
+                                                            __builtin_bit_cast(bf16x8, kb[KS + kk]), s, 0, 0, 0);
             const int p = p0 + tok_in_tile;
             const bool valid = p < L;
 #pragma unroll
@@ -137,11 +145,11 @@ __global__ __launch_bounds__(64 * kWaves) void score_mfma_kernel(
         } else {
             f32x4 s0 = f32x4{0.f, 0.f, 0.f, 0.f}, s1 = s0;
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
+            for (int kk = 0; kk < KS; ++kk) {
                 s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qlo[kk]),
                                                              __builtin_bit_cast(bf16x8, kb[kk]), s0, 0, 0, 0);
                 s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qlo[kk]),
-                                                             __builtin_bit_cast(bf16x8, kb[4 + kk]), s1, 0, 0, 0);
+                                                             __builtin_bit_cast(bf16x8, kb[KS + kk]), s1, 0, 0, 0);
             }
             const int p = p0 + li;
             const bool v0 = p < L, v1 = p + 16 < L;
@@ -169,7 +177,7 @@ __global__ __launch_bounds__(64 * kWaves) void score_mfma_kernel(
         // The refills are unconditional (past the end the last tile is loaded again) so that no
         // branch separates a load from the wait that matches it -- a conditional prefetch makes the
         // compiler drain every outstanding load at the join.
-        u32x4 KB[NBUF][8];
+        u32x4 KB[NBUF][NL];
         int64_t off[NBUF];
         int tile = t0 + wave;
         const int last = tile + (t1 - 1 - tile) / kWaves * kWaves;
@@ -378,10 +386,14 @@ hipError_t launch_score(const Shape &s, const void *q, float scale, float *score
 
     if (mfma_path(s)) {
         dim3 grid(nsplit, s.kv.n_kv_heads, s.batch);
-#define FASTOCR_SCORE(P, GR) FASTOCR_LAUNCH(K_SCORE_LOGITS, (score_mfma_kernel<P, GR, 4, 2>), grid, dim3(256), 0, stream, \
+#define FASTOCR_SCORE(DD, P, GR) FASTOCR_LAUNCH(K_SCORE_LOGITS, (score_mfma_kernel<DD, P, GR, 4, 2>), grid, dim3(256), 0, stream, \
         s.kv, s.bv, (const uint16_t *)q, s.n_q_heads, G, scale_log2, logits, pitch, part_ml, nsplit)
-        if (s.paged) { if (G <= 8) FASTOCR_SCORE(true, 8); else FASTOCR_SCORE(true, 16); }
-        else         { if (G <= 8) FASTOCR_SCORE(false, 8); else FASTOCR_SCORE(false, 16); }
+        if (s.kv.head_dim == 64) {
+            if (s.paged) { if (G <= 8) FASTOCR_SCORE(64, true, 8); else FASTOCR_SCORE(64, true, 16); }
+            else         { if (G <= 8) FASTOCR_SCORE(64, false, 8); else FASTOCR_SCORE(64, false, 16); }
+        }
+        else if (s.paged) { if (G <= 8) FASTOCR_SCORE(128, true, 8); else FASTOCR_SCORE(128, true, 16); }
+        else              { if (G <= 8) FASTOCR_SCORE(128, false, 8); else FASTOCR_SCORE(128, false, 16); }
 #undef FASTOCR_SCORE
     } else {
         dim3 grid(nsplit, s.n_q_heads, s.batch), block(64);

@@ -69,7 +69,7 @@ __device__ uint32_t g_res_timeouts;          // waves that gave up waiting, sinc
 bool resident_plan(const Shape &s, int num_cu, ResidentPlan *plan)
 {
     const int Hkv = s.kv.n_kv_heads;
-    if (!s.fast || Hkv < 1 || s.n_q_heads % Hkv != 0) return false;
+    if (!s.fast || s.kv.head_dim != 128 || Hkv < 1 || s.n_q_heads % Hkv != 0) return false;
     const int G = s.n_q_heads / Hkv;
     if (G > 8 || s.n_q_heads > kResMaxHq) return false;
     if (Hkv != 1 && Hkv != 2 && Hkv != 4 && Hkv != 8) return false;

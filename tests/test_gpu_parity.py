@@ -108,6 +108,53 @@ def test_mfma_bf16_ragged_batch(Hq, Hkv):
     full_check(problem_from_case(case), 0.05, f"mfma Hq{Hq} Hkv{Hkv}")
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(16, 2), (4, 1), (32, 2), (6, 6), (12, 4)])
+def test_mfma_bf16_head_dim_64(Hq, Hkv):
+    """head_dim 64 on the matrix-core kernels (two k-steps per product, 128-byte rows, the value tile's
+    halves swapped between lanes): ragged batch, both contiguous layouts, forced split counts."""
+    case = TinyCase(seed=640 + Hq, B=4, Hq=Hq, Hkv=Hkv, d=64, n_vis=[1000, 777, 1500, 31], pre=[32, 5, 0, 2],
+                    post=[41, 130, 7, 0], dtype="bf16")
+    full_check(problem_from_case(case), 0.05, f"mfma d64 Hq{Hq} Hkv{Hkv}")
+    full_check(problem_from_case(case, layout="bshd"), 0.25, f"mfma d64 bshd Hq{Hq} Hkv{Hkv}")
+    try:
+        for nsplit in (1, 3):
+            for key in ("splits_score", "splits_dense", "splits_sparse"):
+                fb.set_tuning(key, nsplit)
+            for waves in (4, 8):
+                fb.set_tuning("attn_waves", waves)
+                full_check(problem_from_case(case), 0.1, f"mfma d64 Hq{Hq} Hkv{Hkv} nsplit {nsplit} waves {waves}")
+    finally:
+        for key in ("splits_score", "splits_dense", "splits_sparse"):
+            fb.set_tuning(key, 0)
+        fb.set_tuning("attn_waves", 4)
+
+
+def test_mfma_bf16_head_dim_64_paged():
+    wl = fs.config(5, batch=5, steps=8, n_visual=(300, 2500), grid_w=(16, 50), text_prefix=(3, 200), page_tokens=64,
+                   head_dim=64, n_q_heads=16, n_kv_heads=2)
+    bt = fs.make_batch(wl, device=DEV)
+    c = fs.centres(bt)
+    for t in (1, 8):
+        q = fs.queries_for_step(bt, t, [x[t - 1] for x in c])
+        p = GpuProblem(bt.k, bt.v, q, bt.seq_len(t), bt.vis_start, bt.n_vis, wl.head_dim ** -0.5,
+                       block_table=bt.block_table)
+        full_check(p, 0.05, f"paged d64 step {t}")
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 28, 4, 128), ("bf16", 16, 2, 64)])
+def test_other_model_classes_at_large_size(dtype, Hq, Hkv, d):
+    """Shapes beside the paper's two model classes at a large image span: an fp32 cache (batch 4,
+    N = 16384, the plain-FMA kernels with fp64 accumulation, outputs to 1e-5) and bf16 with
+    head_dim 64 (batch 8, N = 16384, the matrix-core kernels), automatic launch shapes."""
+    B = 4 if dtype == "f32" else 8
+    wl = fs.config(4, batch=B, steps=16, dtype=dtype, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d)
+    bt = fs.make_batch(wl, device=DEV)
+    t = 16
+    q = fs.queries_for_step(bt, t, [x[t - 1] for x in fs.centres(bt)])
+    p = GpuProblem(bt.k, bt.v, q, bt.seq_len(t), bt.vis_start, bt.n_vis, wl.head_dim ** -0.5)
+    full_check(p, 0.05, f"large {dtype} d{d}")
+
+
 @pytest.mark.parametrize("merge", [1, 0])
 @pytest.mark.parametrize("nsplit", [1, 2, 5, 64])
 def test_split_counts_give_the_same_result(nsplit, merge):

@@ -16,7 +16,7 @@ if torch.cuda.is_available():
     from test_gpu_parity import full_check
 
 MFMA_HEADS = [(28, 4), (64, 8), (16, 1), (4, 4), (6, 2), (8, 1), (32, 8), (16, 2), (12, 4), (3, 1), (16, 16), (10, 2)]
-PLAIN_SHAPES = [(4, 1, 64), (6, 3, 32), (8, 8, 16), (7, 1, 40), (4, 2, 64), (8, 2, 96), (12, 4, 256), (5, 5, 128)]
+PLAIN_SHAPES = [(4, 1, 64), (6, 3, 32), (8, 8, 16), (7, 1, 40), (4, 2, 64), (8, 2, 96), (12, 4, 256), (5, 5, 128), (32, 2, 64), (34, 2, 64)]
 TAUS = [0.05, 0.02, 0.1, 0.25, 0.004, 1.0, 0.0, 0.5]
 
 
