@@ -69,7 +69,9 @@ typedef enum {
     FASTOCR_OP_TOPK_FIXATION = 1,
     FASTOCR_OP_SPARSE_DECODE_ATTN = 2,
     FASTOCR_OP_DENSE_DECODE_ATTN = 3,
-    FASTOCR_OP_FOCAL_ATTN_SCORE = 4
+    FASTOCR_OP_FOCAL_ATTN_SCORE = 4,
+    FASTOCR_OP_FOCAL_SCORE_TOPK = 5,
+    FASTOCR_OP_FOCAL_ATTN_SCORE_TOPK = 6
 } fastocr_op;
 
 /*
@@ -237,6 +239,33 @@ int fastocr_focal_attn_score(const fastocr_kv_view *kv, const fastocr_batch_view
                              float *img_mass, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * Steps 1 and 2 in one call (Sec. 3.1.2: TopK_{ceil(tau N)} applied directly to the focal layer's
+ * head-averaged attention): fastocr_focal_score followed by fastocr_topk_fixation on its scores, and
+ * the same for a whole focal layer (fastocr_focal_attn_score + fastocr_topk_fixation; Alg. 1,
+ * focal branch).  Results are those of the separate calls bit for bit (same scores, same exact
+ * select).  Arguments as in the separate calls; `scores` is required (it is also the hand-over
+ * buffer); prev_idx / sel_idx may alias.
+ * Workspace: fastocr_workspace_bytes(FASTOCR_OP_FOCAL_SCORE_TOPK | FASTOCR_OP_FOCAL_ATTN_SCORE_TOPK, ..., kmax).
+ * By default the two steps run as two launches one after the other on the stream.  With
+ * fastocr_set_tuning("select_fused", 1), when scoring runs as its single register-resident kernel
+ * and no image span exceeds 16384 tokens, the select runs INSIDE that launch: every range stores
+ * its scores at agent scope and counts itself out, and the sequence's last range to finish selects
+ * over the whole sequence -- no second launch, nobody waits.  That form is measured slower on
+ * MI355X (the select then runs on 8 waves instead of 16 and ends the launch alone), so it is not
+ * the default.
+ */
+int fastocr_focal_score_topk(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
+                             int n_q_heads, float scale, double tau, const int32_t *prev_idx,
+                             const int32_t *prev_cnt, int32_t *sel_idx, int32_t *sel_cnt, int64_t kmax,
+                             float *scores, float *lse, float *img_mass, void *ws, size_t ws_bytes,
+                             void *hip_stream);
+int fastocr_focal_attn_score_topk(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
+                                  int n_q_heads, float scale, double tau, const int32_t *prev_idx,
+                                  const int32_t *prev_cnt, int32_t *sel_idx, int32_t *sel_cnt, int64_t kmax,
+                                  void *out, float *scores, float *lse, float *img_mass, void *ws,
+                                  size_t ws_bytes, void *hip_stream);
+
+/*
  * Focal Layer Selection (Sec. 3.1.1; first block of Alg. 1).  HOST function, no GPU involved.
  *   ratio  HOST fp32 [steps][layers][batch]: the image-attention ratio r_i^(t) of Eq. 1 of layer i
  *          at warm-up step t for sequence b -- what fastocr_focal_score returns in img_mass
@@ -298,6 +327,8 @@ int fastocr_stream_probe(const void *src, void *dst, size_t bytes, void *sink, v
  *   "attn_merge"      pruned attention with several ranges per stream: 1 = merged inside the launch
  *       (default, under the same conditions as above), 0 = by a second kernel, 2 = dense attention
  *       merges inside the launch too (measured slower, kept for comparison)
+ *   "select_fused"    fastocr_focal_score_topk / fastocr_focal_attn_score_topk: 0 = the select is a launch of
+ *       its own (default), 1 = it runs inside the scoring launch when it can
  *   "timer_every"     n >= 1: see the kernel timers above
  *   "barrier_spin_us" how long a workgroup of a single-launch form waits for the others; 0 restores
  *       the default of 250000; 1 makes waiting workgroups give up at once (tests use it to exercise

@@ -21,12 +21,14 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP, ETOOLARGE = 0, -1, -2, -3, -4, -5
 STATIC_SCRATCH_BYTES = 8 << 20
 F32, BF16 = 0, 1
 OP_FOCAL_SCORE, OP_TOPK_FIXATION, OP_SPARSE_DECODE_ATTN, OP_DENSE_DECODE_ATTN, OP_FOCAL_ATTN_SCORE = 0, 1, 2, 3, 4
+OP_FOCAL_SCORE_TOPK, OP_FOCAL_ATTN_SCORE_TOPK = 5, 6
 (KERNEL_SCORE_LOGITS, KERNEL_SCORE_FINALIZE, KERNEL_TOPK, KERNEL_SPARSE_ATTN, KERNEL_DENSE_ATTN,
  KERNEL_ATTN_COMBINE, KERNEL_FOCAL_FUSED) = range(7)
 
 EXPORTS = (
     "fastocr_keep_count", "fastocr_workspace_bytes", "fastocr_focal_score", "fastocr_topk_fixation",
-    "fastocr_sparse_decode_attn", "fastocr_dense_decode_attn", "fastocr_dense_decode_attn_static", "fastocr_focal_attn_score", "fastocr_kernel_timer_enable",
+    "fastocr_sparse_decode_attn", "fastocr_dense_decode_attn", "fastocr_dense_decode_attn_static", "fastocr_focal_attn_score",
+    "fastocr_focal_score_topk", "fastocr_focal_attn_score_topk", "fastocr_kernel_timer_enable",
     "fastocr_kernel_timer_read", "fastocr_select_focal_layers", "fastocr_stream_probe", "fastocr_set_tuning", "fastocr_exchange_timeouts", "fastocr_strerror", "fastocr_version",
 )
 
@@ -85,6 +87,10 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.fastocr_dense_decode_attn_static.argtypes = [KV, BV, P, I, F, P, P, P]
     lib.fastocr_focal_attn_score.restype = I
     lib.fastocr_focal_attn_score.argtypes = [KV, BV, P, I, F, P, P, P, P, P, SZ, P]
+    lib.fastocr_focal_score_topk.restype = I
+    lib.fastocr_focal_score_topk.argtypes = [KV, BV, P, I, F, D, P, P, P, P, I64, P, P, P, P, SZ, P]
+    lib.fastocr_focal_attn_score_topk.restype = I
+    lib.fastocr_focal_attn_score_topk.argtypes = [KV, BV, P, I, F, D, P, P, P, P, I64, P, P, P, P, P, SZ, P]
     lib.fastocr_kernel_timer_enable.restype, lib.fastocr_kernel_timer_enable.argtypes = I, [I, I]
     lib.fastocr_kernel_timer_read.restype, lib.fastocr_kernel_timer_read.argtypes = I, [I, P, I]
     lib.fastocr_select_focal_layers.restype = I
@@ -314,6 +320,43 @@ def focal_attn_score(cache: KvCache, batch: SeqBatch, q: torch.Tensor, scale: fl
     _check(lib.fastocr_focal_attn_score(ctypes.byref(kv), ctypes.byref(bv), _ptr(q), q.shape[1], float(scale),
                                         _ptr(out), _ptr(scores), _ptr(lse), _ptr(img_mass), _ptr(ws), ws.numel(),
                                         _stream_handle(stream)), "fastocr_focal_attn_score")
+
+
+def focal_score_topk(cache: KvCache, batch: SeqBatch, q: torch.Tensor, scale: float, tau: float, scores: torch.Tensor,
+                     sel_idx: torch.Tensor, sel_cnt: torch.Tensor, ws: torch.Tensor,
+                     prev_idx: Optional[torch.Tensor] = None, prev_cnt: Optional[torch.Tensor] = None,
+                     lse: Optional[torch.Tensor] = None, img_mass: Optional[torch.Tensor] = None, stream=None) -> None:
+    """fastocr_focal_score_topk: scores and the selected set from one call."""
+    lib = load_library()
+    kv, bv = cache.view(), batch.view()
+    assert q.is_contiguous() and scores.is_contiguous() and scores.dtype == torch.float32
+    assert scores.shape[0] == bv.batch and (scores.shape[1] == bv.max_vis_len or bv.batch == 0)
+    assert sel_idx.dtype == torch.int32 and sel_idx.is_contiguous() and sel_cnt.dtype == torch.int32
+    if prev_idx is not None:
+        assert prev_idx.shape == sel_idx.shape and prev_idx.dtype == torch.int32 and prev_idx.is_contiguous()
+    _check(lib.fastocr_focal_score_topk(ctypes.byref(kv), ctypes.byref(bv), _ptr(q), q.shape[1], float(scale), float(tau),
+                                        _ptr(prev_idx), _ptr(prev_cnt), _ptr(sel_idx), _ptr(sel_cnt), sel_idx.shape[1],
+                                        _ptr(scores), _ptr(lse), _ptr(img_mass), _ptr(ws), ws.numel(),
+                                        _stream_handle(stream)), "fastocr_focal_score_topk")
+
+
+def focal_attn_score_topk(cache: KvCache, batch: SeqBatch, q: torch.Tensor, scale: float, tau: float, out: torch.Tensor,
+                          scores: torch.Tensor, sel_idx: torch.Tensor, sel_cnt: torch.Tensor, ws: torch.Tensor,
+                          prev_idx: Optional[torch.Tensor] = None, prev_cnt: Optional[torch.Tensor] = None,
+                          lse: Optional[torch.Tensor] = None, img_mass: Optional[torch.Tensor] = None, stream=None) -> None:
+    """fastocr_focal_attn_score_topk: a focal layer's dense output, its scores and the selected set from one call."""
+    lib = load_library()
+    kv, bv = cache.view(), batch.view()
+    assert q.is_contiguous() and out.is_contiguous() and out.shape == q.shape and out.dtype == q.dtype
+    assert scores.is_contiguous() and scores.dtype == torch.float32
+    assert scores.shape[0] == bv.batch and (scores.shape[1] == bv.max_vis_len or bv.batch == 0)
+    assert sel_idx.dtype == torch.int32 and sel_idx.is_contiguous() and sel_cnt.dtype == torch.int32
+    if prev_idx is not None:
+        assert prev_idx.shape == sel_idx.shape and prev_idx.dtype == torch.int32 and prev_idx.is_contiguous()
+    _check(lib.fastocr_focal_attn_score_topk(ctypes.byref(kv), ctypes.byref(bv), _ptr(q), q.shape[1], float(scale), float(tau),
+                                             _ptr(prev_idx), _ptr(prev_cnt), _ptr(sel_idx), _ptr(sel_cnt), sel_idx.shape[1],
+                                             _ptr(out), _ptr(scores), _ptr(lse), _ptr(img_mass), _ptr(ws), ws.numel(),
+                                             _stream_handle(stream)), "fastocr_focal_attn_score_topk")
 
 
 def select_focal_layers(ratio, rho: float, gap: int):

@@ -25,6 +25,7 @@ static std::atomic<int> g_tune_barrier_spin_us{250000};      // bounded wait of 
 static std::atomic<int> g_tune_splits[4];              // indexed by fastocr_op; 0 = automatic
 static std::atomic<int> g_tune_timer_every{1};         // per-kernel timers: which launches record events (every n-th)
 static std::atomic<int> g_exchange_distrusted{0};      // "exchange_fallback" 1
+static std::atomic<int> g_tune_select_fused{0};        // top-k inside the scoring / focal-layer launch (0 never, 1 when it fits): measured slower, off by default
 
 int tune_attn_waves() { return g_tune_attn_waves.load(std::memory_order_relaxed); }
 long long tune_spin_ticks() { return 100ll * g_tune_barrier_spin_us.load(std::memory_order_relaxed); }   // the wall clock runs at 100 MHz
@@ -290,6 +291,13 @@ size_t fastocr_workspace_bytes(int op, const fastocr_kv_view *kv, const fastocr_
         if (!bv || bv->batch < 0 || bv->max_vis_len < 0) return 0;
         return round256(topk_workspace_bytes(bv->batch, bv->max_vis_len));
     }
+    if (op == FASTOCR_OP_FOCAL_SCORE_TOPK || op == FASTOCR_OP_FOCAL_ATTN_SCORE_TOPK) {
+        // the fused launch, or the two separate calls one after the other in the same buffer
+        const size_t a = fastocr_workspace_bytes(op == FASTOCR_OP_FOCAL_SCORE_TOPK ? FASTOCR_OP_FOCAL_SCORE : FASTOCR_OP_FOCAL_ATTN_SCORE,
+                                                 kv, bv, n_q_heads, 0);
+        const size_t b = fastocr_workspace_bytes(FASTOCR_OP_TOPK_FIXATION, kv, bv, n_q_heads, kmax);
+        return a == 0 ? 0 : (a > b ? a : b);
+    }
     if (op < 0 || op > FASTOCR_OP_FOCAL_ATTN_SCORE) return 0;
     if (check_views(kv, bv, n_q_heads) != FASTOCR_OK) return 0;
     Shape s = make_shape(kv, bv, n_q_heads);
@@ -358,10 +366,28 @@ static bool use_resident(int kind, int mode, const Shape &s, ResidentPlan *rp, i
     return *slot >= 0;
 }
 
-int fastocr_focal_score(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
-                        int n_q_heads, float scale, float *scores, float *lse, float *img_mass,
-                        void *ws, size_t ws_bytes, void *hip_stream)
+static int check_topk_args(const float *scores, const fastocr_batch_view *bv, double tau, const int32_t *prev_idx,
+                           const int32_t *prev_cnt, int32_t *sel_idx, int32_t *sel_cnt, int64_t kmax)
 {
+    if (!bv || bv->batch < 0 || bv->max_vis_len < 0 || bv->max_seq_len < 0) return FASTOCR_EINVAL;
+    if (bv->max_vis_len > bv->max_seq_len) return FASTOCR_EINVAL;
+    if (bv->batch > 65535) return FASTOCR_EUNSUPPORTED;
+    if (!(tau >= 0.0 && tau <= 1.0)) return FASTOCR_EINVAL;
+    if (bv->batch > 0 && (!bv->seq_len || !bv->vis_start || !bv->vis_len)) return FASTOCR_EINVAL;
+    if (!sel_idx || !sel_cnt) return FASTOCR_EINVAL;
+    if (!scores && bv->max_vis_len > 0 && bv->batch > 0) return FASTOCR_EINVAL;
+    if ((prev_idx == nullptr) != (prev_cnt == nullptr)) return FASTOCR_EINVAL;
+    if (kmax < 1 || kmax < fastocr_keep_count(bv->max_vis_len, tau)) return FASTOCR_EINVAL;
+    return FASTOCR_OK;
+}
+
+// Scoring, optionally with the top-k inside the same launch (select != nullptr).  *fused tells the
+// caller whether the select ran inside the launch; if not, it still has to be called.
+static int focal_score_impl(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
+                            int n_q_heads, float scale, float *scores, float *lse, float *img_mass,
+                            void *ws, size_t ws_bytes, void *hip_stream, const SelectArgs *select, bool *fused)
+{
+    if (fused) *fused = false;
     int rc = check_views(kv, bv, n_q_heads);
     if (rc != FASTOCR_OK) return rc;
     rc = check_qo(kv, q, nullptr, scale);
@@ -377,26 +403,48 @@ int fastocr_focal_score(const fastocr_kv_view *kv, const fastocr_batch_view *bv,
     hipError_t e;
     int slot = -1;
     uint32_t *flag = nullptr;
-    if (use_resident(EX_SCORE, g_tune_score_resident.load(std::memory_order_relaxed), s, &rp, kResidentMinTiles, (hipStream_t)hip_stream, &slot, &flag))
-        e = launch_score_resident(s, rp, slot, flag, q, scale, scores, lse, img_mass, ws, (hipStream_t)hip_stream);
-    else
+    if (use_resident(EX_SCORE, g_tune_score_resident.load(std::memory_order_relaxed), s, &rp, kResidentMinTiles, (hipStream_t)hip_stream, &slot, &flag)) {
+        const bool fuse = select && g_tune_select_fused.load(std::memory_order_relaxed) != 0 && resident_select_fits(s);
+        e = launch_score_resident(s, rp, slot, flag, q, scale, scores, lse, img_mass, ws, (hipStream_t)hip_stream, fuse ? select : nullptr);
+        if (fused) *fused = fuse;
+    } else {
         e = launch_score(s, q, scale, scores, lse, img_mass, ws, nsplit, (hipStream_t)hip_stream);
+    }
     return e == hipSuccess ? FASTOCR_OK : FASTOCR_EHIP;
+}
+
+int fastocr_focal_score(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
+                        int n_q_heads, float scale, float *scores, float *lse, float *img_mass,
+                        void *ws, size_t ws_bytes, void *hip_stream)
+{
+    return focal_score_impl(kv, bv, q, n_q_heads, scale, scores, lse, img_mass, ws, ws_bytes, hip_stream, nullptr, nullptr);
+}
+
+int fastocr_focal_score_topk(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
+                             int n_q_heads, float scale, double tau, const int32_t *prev_idx,
+                             const int32_t *prev_cnt, int32_t *sel_idx, int32_t *sel_cnt, int64_t kmax,
+                             float *scores, float *lse, float *img_mass, void *ws, size_t ws_bytes,
+                             void *hip_stream)
+{
+    int rc = check_topk_args(scores, bv, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax);
+    if (rc != FASTOCR_OK) return rc;
+    const size_t need = fastocr_workspace_bytes(FASTOCR_OP_FOCAL_SCORE_TOPK, kv, bv, n_q_heads, kmax);
+    if (need == 0) return check_views(kv, bv, n_q_heads) != FASTOCR_OK ? check_views(kv, bv, n_q_heads) : FASTOCR_EINVAL;
+    rc = check_ws(ws, ws_bytes, need);
+    if (rc != FASTOCR_OK) return rc;
+    const SelectArgs sa{tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax};
+    bool fused = false;
+    rc = focal_score_impl(kv, bv, q, n_q_heads, scale, scores, lse, img_mass, ws, ws_bytes, hip_stream, &sa, &fused);
+    if (rc != FASTOCR_OK || fused) return rc;
+    return fastocr_topk_fixation(scores, bv, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax, ws, ws_bytes, hip_stream);
 }
 
 int fastocr_topk_fixation(const float *scores, const fastocr_batch_view *bv, double tau,
                           const int32_t *prev_idx, const int32_t *prev_cnt, int32_t *sel_idx,
                           int32_t *sel_cnt, int64_t kmax, void *ws, size_t ws_bytes, void *hip_stream)
 {
-    if (!bv || bv->batch < 0 || bv->max_vis_len < 0 || bv->max_seq_len < 0) return FASTOCR_EINVAL;
-    if (bv->max_vis_len > bv->max_seq_len) return FASTOCR_EINVAL;
-    if (bv->batch > 65535) return FASTOCR_EUNSUPPORTED;
-    if (!(tau >= 0.0 && tau <= 1.0)) return FASTOCR_EINVAL;
-    if (bv->batch > 0 && (!bv->seq_len || !bv->vis_start || !bv->vis_len)) return FASTOCR_EINVAL;
-    if (!sel_idx || !sel_cnt) return FASTOCR_EINVAL;
-    if (!scores && bv->max_vis_len > 0 && bv->batch > 0) return FASTOCR_EINVAL;
-    if ((prev_idx == nullptr) != (prev_cnt == nullptr)) return FASTOCR_EINVAL;
-    if (kmax < 1 || kmax < fastocr_keep_count(bv->max_vis_len, tau)) return FASTOCR_EINVAL;
+    const int rc0 = check_topk_args(scores, bv, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax);
+    if (rc0 != FASTOCR_OK) return rc0;
     const size_t need = fastocr_workspace_bytes(FASTOCR_OP_TOPK_FIXATION, nullptr, bv, 0, kmax);
     int rc = check_ws(ws, ws_bytes, need);
     if (rc != FASTOCR_OK) return rc;
@@ -470,10 +518,12 @@ int fastocr_dense_decode_attn_static(const fastocr_kv_view *kv, const fastocr_ba
                        out, lse, nullptr, 0, hip_stream, /*static_ws=*/true);
 }
 
-int fastocr_focal_attn_score(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
-                             int n_q_heads, float scale, void *out, float *scores, float *lse,
-                             float *img_mass, void *ws, size_t ws_bytes, void *hip_stream)
+static int focal_attn_score_impl(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
+                                 int n_q_heads, float scale, void *out, float *scores, float *lse,
+                                 float *img_mass, void *ws, size_t ws_bytes, void *hip_stream,
+                                 const SelectArgs *select, bool *fused)
 {
+    if (fused) *fused = false;
     int rc = check_views(kv, bv, n_q_heads);
     if (rc != FASTOCR_OK) return rc;
     if (!out) return FASTOCR_EINVAL;
@@ -489,12 +539,41 @@ int fastocr_focal_attn_score(const fastocr_kv_view *kv, const fastocr_batch_view
     int slot = -1;
     uint32_t *flag = nullptr;
     if (use_resident(EX_FUSED, g_tune_focal_fused.load(std::memory_order_relaxed), s, &rp, kFusedMinTiles, (hipStream_t)hip_stream, &slot, &flag)) {
-        hipError_t e = launch_focal_fused(s, rp, slot, flag, q, scale, out, scores, lse, img_mass, ws, (hipStream_t)hip_stream);
+        const bool fuse = select && g_tune_select_fused.load(std::memory_order_relaxed) != 0 && resident_select_fits(s);
+        hipError_t e = launch_focal_fused(s, rp, slot, flag, q, scale, out, scores, lse, img_mass, ws, (hipStream_t)hip_stream,
+                                          fuse ? select : nullptr);
+        if (fused) *fused = fuse;
         return e == hipSuccess ? FASTOCR_OK : FASTOCR_EHIP;
     }
     rc = fastocr_dense_decode_attn(kv, bv, q, n_q_heads, scale, out, nullptr, ws, ws_bytes, hip_stream);
     if (rc != FASTOCR_OK) return rc;
-    return fastocr_focal_score(kv, bv, q, n_q_heads, scale, scores, lse, img_mass, ws, ws_bytes, hip_stream);
+    return focal_score_impl(kv, bv, q, n_q_heads, scale, scores, lse, img_mass, ws, ws_bytes, hip_stream, select, fused);
+}
+
+int fastocr_focal_attn_score(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
+                             int n_q_heads, float scale, void *out, float *scores, float *lse,
+                             float *img_mass, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    return focal_attn_score_impl(kv, bv, q, n_q_heads, scale, out, scores, lse, img_mass, ws, ws_bytes, hip_stream, nullptr, nullptr);
+}
+
+int fastocr_focal_attn_score_topk(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
+                                  int n_q_heads, float scale, double tau, const int32_t *prev_idx,
+                                  const int32_t *prev_cnt, int32_t *sel_idx, int32_t *sel_cnt, int64_t kmax,
+                                  void *out, float *scores, float *lse, float *img_mass, void *ws,
+                                  size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_topk_args(scores, bv, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax);
+    if (rc != FASTOCR_OK) return rc;
+    const size_t need = fastocr_workspace_bytes(FASTOCR_OP_FOCAL_ATTN_SCORE_TOPK, kv, bv, n_q_heads, kmax);
+    if (need == 0) return check_views(kv, bv, n_q_heads) != FASTOCR_OK ? check_views(kv, bv, n_q_heads) : FASTOCR_EINVAL;
+    rc = check_ws(ws, ws_bytes, need);
+    if (rc != FASTOCR_OK) return rc;
+    const SelectArgs sa{tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax};
+    bool fused = false;
+    rc = focal_attn_score_impl(kv, bv, q, n_q_heads, scale, out, scores, lse, img_mass, ws, ws_bytes, hip_stream, &sa, &fused);
+    if (rc != FASTOCR_OK || fused) return rc;
+    return fastocr_topk_fixation(scores, bv, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax, ws, ws_bytes, hip_stream);
 }
 
 int fastocr_select_focal_layers(const float *ratio, int steps, int layers, int batch, double rho,
@@ -599,6 +678,7 @@ int fastocr_set_tuning(const char *key, int value)
     else if (!strcmp(key, "barrier_spin_us")) g_tune_barrier_spin_us = value ? value : 250000;
     else if (!strcmp(key, "score_resident") && value <= 2) g_tune_score_resident = value;
     else if (!strcmp(key, "focal_fused") && value <= 2) g_tune_focal_fused = value;
+    else if (!strcmp(key, "select_fused") && value <= 1) g_tune_select_fused = value;
     else if (!strcmp(key, "exchange_fallback") && value <= 1) {
         g_exchange_distrusted = value;
         if (value == 0) {

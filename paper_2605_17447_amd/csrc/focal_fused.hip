@@ -34,6 +34,7 @@ namespace fastocr {
 __device__ unsigned long long g_fus_stats[kResSlots][kResMaxWg * kResMaxHq];
 __device__ uint32_t g_fus_left[kResSlots][kResMaxBatch];
 __device__ uint32_t g_fus_timeouts;
+__device__ uint32_t g_fus_done[kResSlots][kResMaxBatch];     // fused top-k: ranges of a sequence whose scores are out
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // One logit per image tile of the wave, indexed by the (wave-uniform) tile number: the compiler
@@ -42,14 +43,16 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x32 __attribute__((ext_vector_type(32)));
 static_assert(kResTmax == 32, "one f32x32 per logit row holds kResTmax tiles");
 
-template <bool PAGED>
+template <bool PAGED, bool SELECT>
 __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
+    SelectArgs sel_args /* first: read straight from the kernel-argument segment when the select starts */,
     KvDev kv, BatchDev bv, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2,
     int batch, int nranges_uniform, int R_uniform, int sync_slot, long long spin_ticks,
     float *__restrict__ scores, float *__restrict__ lse_out, float *__restrict__ mass_part,
     float *__restrict__ att_o, float *__restrict__ att_ml, int32_t *__restrict__ seq_meta,
     uint32_t *__restrict__ gave_up_flag)
 {
+    static_assert(sizeof(unsigned char[kResWaves][2][8192]) >= (size_t)kSelLdsBytes, "the select reuses the tile buffers");
     __shared__ __align__(16) unsigned char smem[kResWaves][2][8192];      // [wave][K, V]
     __shared__ float sm_m[kResWaves][8], sm_z[kResWaves][8];
     __shared__ float sm_lse[kResMaxHq];
@@ -377,7 +380,8 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
     if (!sm_met) {
         // a range of the sequence never published: poison this range's scores
         for (int i = threadIdx.x; i < r1 - r0; i += kResThreads)
-            scores[(int64_t)b * bv.max_vis_len + r0 + i] = __builtin_nanf("");
+            store_score<SELECT>(&scores[(int64_t)b * bv.max_vis_len + r0 + i], __builtin_nanf(""));
+        if (SELECT) resident_select_tail(scores, bv, b, nranges, &g_fus_done[sync_slot][b], &smem[0][0][0]);
         leave();
         return;
     }
@@ -415,7 +419,7 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
         float a = 0.f;
         for (int g = 0; g < Hkv; ++g) a += red[g * R + i];
         a *= inv;
-        scores[(int64_t)b * bv.max_vis_len + r0 + i] = a;
+        store_score<SELECT>(&scores[(int64_t)b * bv.max_vis_len + r0 + i], a);
         local += a;
     }
     if (mass_part) {
@@ -428,6 +432,7 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
             mass_part[wg0 + rng] = t;
         }
     }
+    if (SELECT) resident_select_tail(scores, bv, b, nranges, &g_fus_done[sync_slot][b], &smem[0][0][0]);
     leave();
 }
 
@@ -457,7 +462,8 @@ size_t focal_fused_workspace_bytes(const Shape &s, const ResidentPlan &p)
 hipError_t focal_fused_timeouts(uint32_t *n) { return hipMemcpyFromSymbol(n, HIP_SYMBOL(g_fus_timeouts), sizeof(uint32_t)); }
 
 hipError_t launch_focal_fused(const Shape &s, const ResidentPlan &p, int sync_slot, uint32_t *flag, const void *q, float scale,
-                              void *out, float *scores, float *lse, float *img_mass, void *ws, hipStream_t stream)
+                              void *out, float *scores, float *lse, float *img_mass, void *ws, hipStream_t stream,
+                              const SelectArgs *select)
 {
     if (sync_slot < 0 || sync_slot >= kResSlots) return hipErrorInvalidValue;
     const int W = p.nranges * s.batch;
@@ -470,14 +476,15 @@ hipError_t launch_focal_fused(const Shape &s, const ResidentPlan &p, int sync_sl
     const long long spin_ticks = tune_spin_ticks();                  // 0.25 s unless overridden
 
     dim3 grid(W), block(kResThreads);
-    if (s.paged)
-        FASTOCR_LAUNCH(K_FOCAL_FUSED, focal_fused_kernel<true>, grid, block, 0, stream, s.kv, s.bv,
-                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens,
-                       sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, att_o, att_ml, seq_meta, flag);
-    else
-        FASTOCR_LAUNCH(K_FOCAL_FUSED, focal_fused_kernel<false>, grid, block, 0, stream, s.kv, s.bv,
-                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens,
-                       sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, att_o, att_ml, seq_meta, flag);
+    const bool fuse = select && select->sel_idx;
+    if (fuse && !resident_select_fits(s)) return hipErrorInvalidValue;
+    const SelectArgs sa = fuse ? *select : SelectArgs{0.0, nullptr, nullptr, nullptr, nullptr, 0};
+#define FASTOCR_FUS(P, S) FASTOCR_LAUNCH(K_FOCAL_FUSED, (focal_fused_kernel<P, S>), grid, block, 0, stream, sa, s.kv, s.bv, \
+                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens, \
+                       sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, att_o, att_ml, seq_meta, flag)
+    if (s.paged) { if (fuse) FASTOCR_FUS(true, true); else FASTOCR_FUS(true, false); }
+    else         { if (fuse) FASTOCR_FUS(false, true); else FASTOCR_FUS(false, false); }
+#undef FASTOCR_FUS
     if (img_mass) fused_mass_kernel<<<s.batch, 64, 0, stream>>>(mass_part, seq_meta, img_mass);
     // every sequence's partials: workgroups seq_meta[b][0] .. + seq_meta[b][1], wpk of them each
     return launch_attn_combine(s, att_o, att_ml, p.nranges * p.wpk, out, nullptr, stream, seq_meta, p.wpk);

@@ -105,16 +105,28 @@ hipError_t launch_score(const Shape &s, const void *q, float scale, float *score
 // Workspace, W = nranges * batch: image-mass partials fp32 [W], per sequence its first workgroup
 // and range count int32 [B][2] (the ranges' softmax statistics travel through static device memory).
 struct ResidentPlan { int nranges, range_tokens, wpk; };
+// The top-k fused into a register-resident launch (sel_idx == nullptr: none): the arguments of
+// fastocr_topk_fixation.
+struct SelectArgs {
+    double tau;
+    const int32_t *prev_idx, *prev_cnt;
+    int32_t *sel_idx, *sel_cnt;
+    int64_t kmax;
+};
+// whether the fused select covers the shape (image spans of up to 16384 tokens)
+bool resident_select_fits(const Shape &s);
 bool resident_plan(const Shape &s, int num_cu, ResidentPlan *plan);
 size_t resident_workspace_bytes(const Shape &s, const ResidentPlan &p);
 hipError_t launch_score_resident(const Shape &s, const ResidentPlan &p, int sync_slot, uint32_t *gave_up_flag, const void *q, float scale,
-                                 float *scores, float *lse, float *img_mass, void *ws, hipStream_t stream);
+                                 float *scores, float *lse, float *img_mass, void *ws, hipStream_t stream,
+                                 const SelectArgs *select = nullptr);
 
 // ---- focal layer in one pass: dense attention output + scores (focal_fused.hip) -----------
 // Uses the same plan as the register-resident scoring kernel.
 size_t focal_fused_workspace_bytes(const Shape &s, const ResidentPlan &p);
 hipError_t launch_focal_fused(const Shape &s, const ResidentPlan &p, int sync_slot, uint32_t *gave_up_flag, const void *q, float scale,
-                              void *out, float *scores, float *lse, float *img_mass, void *ws, hipStream_t stream);
+                              void *out, float *scores, float *lse, float *img_mass, void *ws, hipStream_t stream,
+                              const SelectArgs *select = nullptr);
 
 // ---- how often a workgroup gave up waiting for another one of its launch (each file's own count;
 // the copies synchronise with the device) ----------------------------------------------------

@@ -3,6 +3,7 @@
 // global -> LDS copy and the cross-lane moves.
 #pragma once
 #include "kernels.hpp"
+#include "topk_dev.hpp"
 
 namespace fastocr {
 
@@ -259,6 +260,58 @@ __device__ __forceinline__ void resident_retire(bool last, unsigned long long *s
             __hip_atomic_store(&stats[i], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (threadIdx.x == 0) __hip_atomic_store(left, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+}
+
+// ---- top-k of the finished scores inside the same launch --------------------------------------------
+// (Sec. 3.1.2: TopK is applied directly to the focal layer's head-averaged attention.)  Every range
+// stores its scores with agent-scope stores, waits until they have been performed, and counts
+// itself out on a per-sequence counter; the range that counts last -- every score of its sequence
+// is then visible at agent scope -- runs the exact register select of topk_dev.hpp over the whole
+// sequence (512 threads x 32 keys) and writes the set.  Nobody waits for anybody: no polling, no
+// fence.  The selecting workgroup leaves the counter at zero for the next call on the slot.
+constexpr int kSelPer = 32;
+constexpr int kSelMaxKeys = kResThreads * kSelPer;               // 16384 image tokens per sequence
+constexpr int kSelLdsBytes = 2048 + 4 * kRegCandCap + 4 * kSelMaxKeys + 256;
+
+template <bool SELECT>
+__device__ __forceinline__ void store_score(float *p, float x)
+{
+    if (SELECT) __hip_atomic_store(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *p = x;
+}
+
+// Called by every thread of a range's workgroup after its scores have been stored with
+// store_score<true>.  lds: at least kSelLdsBytes of the workgroup's LDS that nobody uses any more.
+// The select's arguments are the kernel's FIRST argument and are read from the kernel-argument
+// segment here, when they are needed: as ordinary arguments they would sit in scalar registers
+// through the whole tile loop, which has none to spare.
+__device__ __forceinline__ void resident_select_tail(const float *scores, const BatchDev &bv,
+                                                     int b, int nranges, uint32_t *done, unsigned char *lds)
+{
+    __shared__ int sm_selects;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // this thread's score stores have been performed
+    __syncthreads();                                         // ... and every other thread's of the workgroup
+    if (threadIdx.x == 0) {
+        const uint32_t before = __hip_atomic_fetch_add(done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sm_selects = before == (uint32_t)nranges - 1u;
+    }
+    __syncthreads();
+    if (!sm_selects) return;
+    const SelectArgs *sap = (const SelectArgs *)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(sap)::"memory");
+    const SelectArgs sa = *sap;
+    TopkRegShared sh;
+    sh.hist = reinterpret_cast<uint32_t (*)[256]>(lds);
+    sh.cand = reinterpret_cast<uint32_t *>(lds + 2048);
+    sh.all_keys = reinterpret_cast<uint32_t *>(lds + 2048 + 4 * kRegCandCap);
+    int *misc = reinterpret_cast<int *>(lds + 2048 + 4 * kRegCandCap + 4 * kSelMaxKeys);
+    sh.w_ac = misc;                                          // 2 * 8 wave totals, 16-byte aligned
+    sh.pick = misc + 16;
+    sh.theta_prev = reinterpret_cast<uint32_t *>(misc + 18);
+    sh.bad = misc + 19;
+    topk_reg_body<kResThreads, kSelPer, true>(scores, bv, b, sa.tau, sa.prev_idx, sa.prev_cnt, sa.sel_idx, sa.sel_cnt,
+                                              sa.kmax, sh, [](int, int) {});
+    if (threadIdx.x == 0) __hip_atomic_store(done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 }  // namespace fastocr

@@ -65,6 +65,9 @@ namespace fastocr {
 __device__ unsigned long long g_res_stats[kResSlots][kResMaxWg * kResMaxHq];
 __device__ uint32_t g_res_left[kResSlots][kResMaxBatch];
 __device__ uint32_t g_res_timeouts;          // waves that gave up waiting, since the module was loaded
+__device__ uint32_t g_res_done[kResSlots][kResMaxBatch];     // fused top-k: ranges of a sequence whose scores are out
+
+bool resident_select_fits(const Shape &s) { return s.bv.max_vis_len <= kSelMaxKeys; }
 
 bool resident_plan(const Shape &s, int num_cu, ResidentPlan *plan)
 {
@@ -98,13 +101,15 @@ size_t resident_workspace_bytes(const Shape &s, const ResidentPlan &p)
     return bytes;
 }
 
-template <bool PAGED>
+template <bool PAGED, bool SELECT>
 __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
+    SelectArgs sel_args /* first: read straight from the kernel-argument segment when the select starts */,
     KvDev kv, BatchDev bv, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2,
     int batch, int nranges_uniform, int R_uniform, int sync_slot, long long spin_ticks,
     float *__restrict__ scores, float *__restrict__ lse_out, float *__restrict__ mass_part,
     int32_t *__restrict__ mass_meta, uint32_t *__restrict__ gave_up_flag)
 {
+    static_assert(sizeof(unsigned char[kResWaves][2][8192]) >= (size_t)kSelLdsBytes, "the select reuses the tile buffers");
     __shared__ __align__(16) unsigned char smem[kResWaves][2][8192];
     __shared__ float sm_m[kResWaves][8], sm_z[kResWaves][8];
     __shared__ float sm_lse[kResMaxHq];
@@ -357,7 +362,8 @@ pre_done:
         // a range of the sequence never published (the grid was not resident as a whole): poison
         // this range's scores rather than publish numbers built on missing statistics
         for (int i = threadIdx.x; i < r1 - r0; i += kResThreads)
-            scores[(int64_t)b * bv.max_vis_len + r0 + i] = __builtin_nanf("");
+            store_score<SELECT>(&scores[(int64_t)b * bv.max_vis_len + r0 + i], __builtin_nanf(""));
+        if (SELECT) resident_select_tail(scores, bv, b, nranges, &g_res_done[sync_slot][b], &smem[0][0][0]);
         leave();
         return;
     }
@@ -388,7 +394,7 @@ fin_done:
         float a = 0.f;
         for (int g = 0; g < 2 * Hkv; ++g) a += red[g * R + i];
         a *= inv;
-        scores[(int64_t)b * bv.max_vis_len + r0 + i] = a;
+        store_score<SELECT>(&scores[(int64_t)b * bv.max_vis_len + r0 + i], a);
         local += a;
     }
     if (mass_part) {
@@ -402,6 +408,7 @@ fin_done:
             if (rng == 0) { mass_meta[2 * b] = wg0; mass_meta[2 * b + 1] = nranges; }
         }
     }
+    if (SELECT) resident_select_tail(scores, bv, b, nranges, &g_res_done[sync_slot][b], &smem[0][0][0]);
     leave();
 }
 
@@ -420,7 +427,8 @@ __global__ void resident_mass_kernel(const float *__restrict__ mass_part, const 
 hipError_t score_resident_timeouts(uint32_t *n) { return hipMemcpyFromSymbol(n, HIP_SYMBOL(g_res_timeouts), sizeof(uint32_t)); }
 
 hipError_t launch_score_resident(const Shape &s, const ResidentPlan &p, int sync_slot, uint32_t *flag, const void *q, float scale,
-                                 float *scores, float *lse, float *img_mass, void *ws, hipStream_t stream)
+                                 float *scores, float *lse, float *img_mass, void *ws, hipStream_t stream,
+                                 const SelectArgs *select)
 {
     if (sync_slot < 0 || sync_slot >= kResSlots) return hipErrorInvalidValue;
     const int W = p.nranges * s.batch;                       // workgroups = range statistics slots
@@ -433,14 +441,15 @@ hipError_t launch_score_resident(const Shape &s, const ResidentPlan &p, int sync
     const long long spin_ticks = tune_spin_ticks();                  // 0.25 s unless overridden
 
     dim3 grid(W), block(kResThreads);
-    if (s.paged)
-        FASTOCR_LAUNCH(K_SCORE_LOGITS, score_resident_kernel<true>, grid, block, 0, stream, s.kv, s.bv,
-                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens,
-                       sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, mass_meta, flag);
-    else
-        FASTOCR_LAUNCH(K_SCORE_LOGITS, score_resident_kernel<false>, grid, block, 0, stream, s.kv, s.bv,
-                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens,
-                       sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, mass_meta, flag);
+    const bool fuse = select && select->sel_idx;
+    if (fuse && !resident_select_fits(s)) return hipErrorInvalidValue;
+    const SelectArgs sa = fuse ? *select : SelectArgs{0.0, nullptr, nullptr, nullptr, nullptr, 0};
+#define FASTOCR_RES(P, S) FASTOCR_LAUNCH(K_SCORE_LOGITS, (score_resident_kernel<P, S>), grid, block, 0, stream, sa, s.kv, s.bv, \
+                       (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens, \
+                       sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, mass_meta, flag)
+    if (s.paged) { if (fuse) FASTOCR_RES(true, true); else FASTOCR_RES(true, false); }
+    else         { if (fuse) FASTOCR_RES(false, true); else FASTOCR_RES(false, false); }
+#undef FASTOCR_RES
     if (img_mass) resident_mass_kernel<<<s.batch, 64, 0, stream>>>(mass_part, mass_meta, img_mass);
     return hipGetLastError();
 }

@@ -141,7 +141,17 @@ struct TopkRegShared {
 // One workgroup of THREADS threads selects sequence b's set; thread t keeps the keys of tokens
 // PER t .. PER t + PER - 1 in registers (THREADS * PER >= max_vis_len).  publish(position, index) is
 // called by the thread that writes sel_idx[position] = index, for every entry of the result.
-template <int THREADS, int PER, typename Publish>
+// COHERENT: the scores were written earlier in the SAME launch by other workgroups (agent-scope
+// stores, completed before this workgroup was told so): they are read with agent-scope loads, which
+// never hit a line this compute unit's caches may still hold from before.
+template <bool COHERENT>
+__device__ __forceinline__ float score_at(const float *p)
+{
+    if (COHERENT) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return *p;
+}
+
+template <int THREADS, int PER, bool COHERENT = false, typename Publish>
 __device__ __forceinline__ void topk_reg_body(
     const float *__restrict__ scores, const BatchDev &bv, int b, double tau, const int32_t *prev_idx,
     const int32_t *prev_cnt, int32_t *sel_idx, int32_t *sel_cnt, int64_t kmax, const TopkRegShared &sh,
@@ -161,7 +171,14 @@ __device__ __forceinline__ void topk_reg_body(
     for (int v = 0; v < PER / 4; ++v) raw[v] = f32x4{0.f, 0.f, 0.f, 0.f};
     if (whole) {
 #pragma unroll
-        for (int v = 0; v < PER / 4; ++v) raw[v] = *reinterpret_cast<const f32x4 *>(srow + base + 4 * v);
+        for (int v = 0; v < PER / 4; ++v) {
+            if (COHERENT) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) raw[v][e] = score_at<true>(srow + base + 4 * v + e);
+            } else {
+                raw[v] = *reinterpret_cast<const f32x4 *>(srow + base + 4 * v);
+            }
+        }
     }
     const int32_t *prev = prev_idx ? prev_idx + (int64_t)b * kmax : nullptr;
     int prev0 = 0, prev1 = 0;
@@ -195,7 +212,7 @@ __device__ __forceinline__ void topk_reg_body(
             for (int e = 0; e < 4; ++e) key[4 * v + e] = real(4 * v + e) ? order_key(raw[v][e]) : 0u;
     } else {
 #pragma unroll
-        for (int j = 0; j < PER; ++j) key[j] = j < nvalid ? order_key(srow[base + j]) : 0u;
+        for (int j = 0; j < PER; ++j) key[j] = j < nvalid ? order_key(score_at<COHERENT>(srow + base + j)) : 0u;
     }
     // ---- bound from the previous set: k distinct valid tokens (strictly ascending) or ignored ----
     const bool have_prev = prev_idx && pcnt == k;
@@ -206,10 +223,10 @@ __device__ __forceinline__ void topk_reg_body(
             const int i = r == tid ? prev0 : prev[r];
             const int nx = (r + 1 < k) ? (r == tid ? prev1 : prev[r + 1]) : 0x7fffffff;
             if (i < 0 || i >= N || i >= nx) bad = 1;
-            else lo = min(lo, order_key(srow[i]));
+            else lo = min(lo, order_key(score_at<COHERENT>(srow + i)));
         }
     }
-    // ---- bound from a sample: the first key of every thread (every 16th token) ---------------------
+    // ---- bound from a sample: the first key of every thread (every PER-th token) ---------------------
     const int ns = (N + PER - 1) / PER;
     if (tid < ns) sh.cand[tid] = key[0];
     __syncthreads();

@@ -1,0 +1,143 @@
+"""Scoring (or a whole focal layer) and the top-k in one call (Sec. 3.1.2: TopK applied directly
+to the focal layer's head-averaged attention).  With "select_fused" 1 the select runs inside the
+scoring launch: the results must be those of the separate calls bit for bit -- same scores, same
+exact select -- and match the oracle, and the standalone top-k kernel must not have been launched.
+With the default (0) the one call is the two launches."""
+import numpy as np
+import pytest
+import torch
+
+import fastocr_synth as fs
+import oracle
+import paper_2605_17447_amd as fo
+from paper_2605_17447_amd import binding as fb
+from util import TinyCase
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _select_inside_the_launch():
+    fb.set_tuning("select_fused", 1)
+    yield
+    fb.set_tuning("select_fused", 0)
+
+if torch.cuda.is_available():
+    from gpu_util import DEV, GpuProblem, check_out, check_scores, problem_from_case
+
+
+def _one_call_vs_separate(p, tau, what, expect_fused=True, rounds=3):
+    kmax = max(1, fo.keep_count(p.batch.max_vis_len, tau))
+    ws = torch.empty(max(fo.workspace_bytes(op, p.cache, p.batch, p.Hq, kmax) for op in range(7)), dtype=torch.uint8, device=DEV)
+    mk = lambda: (torch.full((p.B, p.batch.max_vis_len), -7.0, dtype=torch.float32, device=DEV),
+                  torch.full((p.B, kmax), -1, dtype=torch.int32, device=DEV), torch.full((p.B,), -1, dtype=torch.int32, device=DEV))
+    oc = p.oracle_args()
+    ref_sc, _, ref_mass = oracle.focal_score(*oc)
+    ref_dense, _ = oracle.decode_attn(*oc)
+    for layer_call in (False, True):
+        # separate calls: the reference bits (cold, then warm-started in place from the cold set)
+        sc0, idx0, cnt0 = mk()
+        out0 = torch.zeros_like(p.q)
+        if layer_call:
+            fo.focal_attn_score(p.cache, p.batch, p.q, p.scale, out0, sc0, ws)
+        else:
+            fo.focal_score(p.cache, p.batch, p.q, p.scale, sc0, ws)
+        fo.topk_fixation(sc0, p.batch, tau, idx0, cnt0, ws)
+        torch.cuda.synchronize()
+        check_scores(sc0, ref_sc, p.vis_len, what + " separate scores")
+        sc_h, cnt_h, idx_h = sc0.cpu().numpy(), cnt0.cpu().numpy(), idx0.cpu().numpy()
+        for b in range(p.B):
+            assert np.array_equal(idx_h[b, : cnt_h[b]], oracle.topk(sc_h[b, : p.vis_len[b]], int(cnt_h[b])))
+        for rnd in range(rounds):
+            sc1, idx1, cnt1 = mk()
+            out1 = torch.zeros_like(p.q)
+            mass = torch.zeros((p.B,), dtype=torch.float32, device=DEV)
+            warm = rnd > 0
+            if warm:                                   # in place, from a stale set of the right size
+                idx1.copy_(idx0); cnt1.copy_(cnt0)
+                if rnd == 2:
+                    idx1[:, 0] = 0                      # a previous set that is no longer ascending is ignored
+            fb.kernel_timer_enable(fb.KERNEL_TOPK, 4)
+            if layer_call:
+                fo.focal_attn_score_topk(p.cache, p.batch, p.q, p.scale, tau, out1, sc1, idx1, cnt1, ws,
+                                         prev_idx=idx1 if warm else None, prev_cnt=cnt1 if warm else None, img_mass=mass)
+            else:
+                fo.focal_score_topk(p.cache, p.batch, p.q, p.scale, tau, sc1, idx1, cnt1, ws,
+                                    prev_idx=idx1 if warm else None, prev_cnt=cnt1 if warm else None, img_mass=mass)
+            torch.cuda.synchronize()
+            launched = len(fb.kernel_timer_read(fb.KERNEL_TOPK))
+            fb.kernel_timer_enable(fb.KERNEL_TOPK, 0)
+            assert launched == (0 if expect_fused else 1), f"{what}: stand-alone top-k launches: {launched}"
+            tag = f"{what} ({'focal layer' if layer_call else 'scoring'}, round {rnd})"
+            assert torch.equal(sc1, sc0), tag + ": scores differ from the separate call"
+            assert torch.equal(cnt1, cnt0), tag + ": counts differ"
+            for b in range(p.B):
+                k = int(cnt0[b])
+                assert torch.equal(idx1[b, :k], idx0[b, :k]), tag + f": set differs, b={b}"
+            assert np.allclose(mass.cpu().numpy(), ref_mass, atol=2e-5)
+            if layer_call:
+                assert torch.equal(out1, out0), tag + ": output differs"
+                check_out(out1, ref_dense, tag + " output")
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(28, 4), (64, 8), (8, 1), (6, 2)])
+def test_select_inside_the_scoring_launch(Hq, Hkv):
+    case = TinyCase(seed=800 + Hq, B=5, Hq=Hq, Hkv=Hkv, d=128, n_vis=[3000, 1777, 2500, 64, 0], pre=[32, 5, 0, 3, 2],
+                    post=[41, 130, 7, 0, 1], dtype="bf16")
+    _one_call_vs_separate(problem_from_case(case), 0.05, f"Hq{Hq} Hkv{Hkv}")
+    _one_call_vs_separate(problem_from_case(case), 1.0, f"Hq{Hq} Hkv{Hkv} tau 1", rounds=1)
+    _one_call_vs_separate(problem_from_case(case), 0.0, f"Hq{Hq} Hkv{Hkv} tau 0", rounds=1)
+
+
+def test_select_inside_the_launch_paged_ragged_and_constant_scores():
+    wl = fs.config(5, batch=12, steps=4, n_visual=(600, 5000), grid_w=(20, 70), text_prefix=(3, 300), page_tokens=64)
+    bt = fs.make_batch(wl, device=DEV)
+    q = fs.queries_for_step(bt, 3, [x[2] for x in fs.centres(bt)])
+    p = GpuProblem(bt.k, bt.v, q, bt.seq_len(3), bt.vis_start, bt.n_vis, wl.head_dim ** -0.5, block_table=bt.block_table)
+    _one_call_vs_separate(p, 0.1, "paged ragged")
+    # all keys equal: every score ties, the lowest indices win on both paths
+    case = TinyCase(seed=5, B=2, Hq=28, Hkv=4, d=128, n_vis=[2048, 900], pre=[4, 0], post=[3, 9], dtype="bf16")
+    case.k[:] = case.k[0, 0, 0]
+    _one_call_vs_separate(problem_from_case(case), 0.05, "constant scores")
+
+
+def test_the_separate_select_is_taken_when_it_must_be():
+    case = TinyCase(seed=31, B=2, Hq=28, Hkv=4, d=128, n_vis=[1500, 900], pre=[4, 0], post=[30, 9], dtype="bf16")
+    p = problem_from_case(case)
+    try:
+        fb.set_tuning("select_fused", 0)
+        _one_call_vs_separate(p, 0.05, "select_fused 0", expect_fused=False, rounds=2)
+        fb.set_tuning("select_fused", 1)
+        fb.set_tuning("score_resident", 0)
+        fb.set_tuning("focal_fused", 0)
+        _one_call_vs_separate(p, 0.05, "separate kernels", expect_fused=False, rounds=2)
+    finally:
+        fb.set_tuning("score_resident", 1)
+        fb.set_tuning("focal_fused", 1)
+    # fp32 cache: the plain kernels, then the stand-alone select
+    case = TinyCase(seed=32, B=2, Hq=4, Hkv=2, d=64, n_vis=[300, 200], pre=[4, 0], post=[30, 9], dtype="f32")
+    _one_call_vs_separate(problem_from_case(case), 0.05, "fp32", expect_fused=False, rounds=2)
+
+
+def test_select_inside_the_launch_at_config4_size_is_repeatable():
+    wl = fs.config(4, steps=16)
+    bt = fs.make_batch(wl, device=DEV)
+    t = 16
+    q = fs.queries_for_step(bt, t, [x[t - 1] for x in fs.centres(bt)])
+    p = GpuProblem(bt.k, bt.v, q, bt.seq_len(t), bt.vis_start, bt.n_vis, wl.head_dim ** -0.5)
+    _one_call_vs_separate(p, 0.05, "config 4", rounds=3)
+    # 50 more calls: the last range to finish differs from call to call, the result never does
+    kmax = fo.keep_count(16384, 0.05)
+    ws = torch.empty(max(fo.workspace_bytes(op, p.cache, p.batch, p.Hq, kmax) for op in range(7)), dtype=torch.uint8, device=DEV)
+    sc = torch.zeros((p.B, 16384), dtype=torch.float32, device=DEV)
+    idx = torch.zeros((p.B, kmax), dtype=torch.int32, device=DEV)
+    cnt = torch.zeros((p.B,), dtype=torch.int32, device=DEV)
+    first = None
+    for i in range(50):
+        fo.focal_score_topk(p.cache, p.batch, p.q, p.scale, 0.05, sc, idx, cnt, ws,
+                            prev_idx=idx if i else None, prev_cnt=cnt if i else None)
+        cur = (sc.clone(), idx.clone(), cnt.clone())
+        if first is None:
+            first = cur
+        else:
+            assert all(torch.equal(a, b) for a, b in zip(first, cur)), f"call {i} differs"
