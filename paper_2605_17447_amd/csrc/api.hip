@@ -238,11 +238,13 @@ static int choose_splits(int op, const Shape &s, int max_positions)
         if (fast && op == FASTOCR_OP_SPARSE_DECODE_ATTN && g_tune_attn_merge.load(std::memory_order_relaxed)) {
             // pruned attention is short: one launch whose eight-wave workgroups fill the chip once,
             // the ranges of a stream merged inside the launch.  Up to 16 tiles one workgroup has the
-            // whole list in flight at once (two tiles per wave) and a cut only adds the merge; beyond
-            // that a range per 12 tiles measured best (25 tiles, 4 or 32 streams: 15.4 / 13.2 / 11.5 /
-            // 11.7 us with 1 / 2 / 3 / 4 ranges; 40 tiles: 18.6 / 16.0 / 13.7 / 13.9 us)
+            // whole list in flight at once (two tiles per wave) and a cut only adds the merge (15 tiles,
+            // 32 streams: 10.7 / 10.8 / 10.7 / 11.5 us with 1 / 2 / 3 / 4 ranges); beyond that three
+            // ranges measured best (17 tiles, 4 streams: 10.7 / 10.7 / 10.3 / 10.6 us; 21 tiles, 32
+            // streams: 13.7 / 12.7 / 11.3 / 11.5 us; 25 tiles: 15.4 / 13.2 / 11.5 / 11.7 us; 40 tiles:
+            // 18.6 / 16.0 / 13.7 / 13.9 us), four from 48 tiles on
             int n = kNumCU / (streams > 0 ? streams : 1);
-            const int by_len = ntile <= 16 ? 1 : (ntile + 11) / 12;
+            const int by_len = ntile <= 16 ? 1 : (ntile < 48 ? 3 : 4);
             n = n < by_len ? n : by_len;
             n = n < 1 ? 1 : n;
             if (n == 1 || attn_merges_in_kernel(s, n)) return n;
