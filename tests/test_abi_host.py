@@ -165,6 +165,42 @@ def test_topk_and_sparse_validation(lib):
     assert sp(ws_bytes=64) == fb.EWORKSPACE
 
 
+def test_one_call_score_and_topk_validation_and_workspace(lib):
+    kv, bv = _kv(), _bv()
+    one = lambda tau=0.05, prev_idx=None, prev_cnt=None, sel=FAKE, cnt=FAKE, kmax=205, scores=FAKE, ws=FAKE, ws_bytes=1 << 40, \
+        k=kv, b=bv, Hq=28: lib.fastocr_focal_score_topk(ctypes.byref(k) if k else None, ctypes.byref(b), FAKE, Hq, 0.088, tau,
+                                                         prev_idx, prev_cnt, sel, cnt, kmax, scores, None, None, ws, ws_bytes, None)
+    layer = lambda out=FAKE, tau=0.05, kmax=205, ws_bytes=1 << 40, b=bv: lib.fastocr_focal_attn_score_topk(
+        ctypes.byref(kv), ctypes.byref(b), FAKE, 28, 0.088, tau, None, None, FAKE, FAKE, kmax, out, FAKE, None, None, FAKE, ws_bytes, None)
+    assert one(tau=1.5) == fb.EINVAL and one(kmax=204) == fb.EINVAL and one(prev_idx=FAKE) == fb.EINVAL
+    assert one(sel=None) == fb.EINVAL and one(scores=None) == fb.EINVAL and one(k=None) == fb.EINVAL
+    assert one(Hq=30) == fb.EINVAL
+    assert one(ws=None) == fb.EWORKSPACE and one(ws_bytes=1024) == fb.EWORKSPACE
+    assert one(b=_bv(B=0)) == fb.OK
+    assert layer(out=None) == fb.EINVAL and layer(tau=-1.0) == fb.EINVAL and layer(ws_bytes=64) == fb.EWORKSPACE
+    assert layer(b=_bv(B=0)) == fb.OK
+    w = lambda op, kmax=205: lib.fastocr_workspace_bytes(op, ctypes.byref(kv), ctypes.byref(bv), 28, kmax)
+    assert w(fb.OP_FOCAL_SCORE_TOPK) >= max(w(fb.OP_FOCAL_SCORE), w(fb.OP_TOPK_FIXATION))
+    assert w(fb.OP_FOCAL_ATTN_SCORE_TOPK) >= max(w(fb.OP_FOCAL_ATTN_SCORE), w(fb.OP_TOPK_FIXATION))
+    assert lib.fastocr_workspace_bytes(fb.OP_FOCAL_SCORE_TOPK, ctypes.byref(kv), ctypes.byref(bv), 30, 205) == 0
+    assert lib.fastocr_set_tuning(b"select_fused", 2) == fb.EINVAL
+    assert lib.fastocr_set_tuning(b"select_fused", 1) == fb.OK and lib.fastocr_set_tuning(b"select_fused", 0) == fb.OK
+
+
+def test_static_scratch_entry_point_validation(lib):
+    """The entry point that allocates nothing refuses bad arguments and shapes beyond its buffer before
+    any GPU call (FASTOCR_ETOOLARGE names the limit)."""
+    kv, bv = _kv(), _bv()
+    call = lambda k=kv, b=bv, out=FAKE, Hq=28: lib.fastocr_dense_decode_attn_static(ctypes.byref(k), ctypes.byref(b), FAKE, Hq,
+                                                                                    0.088, out, None, None)
+    assert call(out=None) == fb.EINVAL and call(Hq=30) == fb.EINVAL and call(k=_kv(dtype=7)) == fb.EUNSUPPORTED
+    assert call(b=_bv(B=0)) == fb.OK
+    big = _bv(B=4000)
+    assert lib.fastocr_workspace_bytes(fb.OP_DENSE_DECODE_ATTN, ctypes.byref(kv), ctypes.byref(big), 28, 0) > fb.STATIC_SCRATCH_BYTES
+    assert call(b=big) == fb.ETOOLARGE
+    assert "static" in fb.strerror(fb.ETOOLARGE)
+
+
 def test_exchange_timeouts_rejects_a_null_pointer(lib):
     lib.fastocr_exchange_timeouts.restype = ctypes.c_int
     lib.fastocr_exchange_timeouts.argtypes = [ctypes.c_void_p]
@@ -186,6 +222,10 @@ def test_tuning_keys(lib):
     assert lib.fastocr_set_tuning(b"timer_every", 0) == fb.EINVAL
     assert lib.fastocr_set_tuning(b"timer_every", 4) == fb.OK
     assert lib.fastocr_set_tuning(b"timer_every", 1) == fb.OK
+    assert lib.fastocr_set_tuning(b"attn_waves", 5) == fb.EINVAL and lib.fastocr_set_tuning(b"attn_waves", 0) == fb.EINVAL
+    assert lib.fastocr_set_tuning(b"attn_waves", 8) == fb.OK and lib.fastocr_set_tuning(b"attn_waves", 4) == fb.OK
+    assert lib.fastocr_set_tuning(b"exchange_fallback", 2) == fb.EINVAL
+    assert lib.fastocr_set_tuning(b"exchange_fallback", 1) == fb.OK and lib.fastocr_set_tuning(b"exchange_fallback", 0) == fb.OK
 
 
 def test_binding_views_follow_their_tensors():

@@ -120,3 +120,41 @@ def test_more_streams_than_exchange_slots_fall_back_to_the_separate_kernels():
                 r.check_against_oracle(f"round {rnd}, stream {4 * rnd + i}")
     finally:
         fb.set_tuning("splits_sparse", 0)
+
+
+def test_calls_from_several_host_threads_each_on_its_own_stream():
+    """The binding releases the interpreter lock inside the C calls, so threads really run the library's host
+    code side by side: the slot tables, tuning values and per-device words are guarded for that."""
+    import threading
+    runs = [_Run(TinyCase(seed=760 + i, B=2, Hq=28, Hkv=4, d=128, n_vis=[800 + 31 * i, 600], pre=[4, 1], post=[40 + i, 9],
+                          dtype="bf16"), 0.1) for i in range(4)]
+    fb.set_tuning("splits_sparse", 2)
+    try:
+        for r in runs:
+            r.enqueue()
+        torch.cuda.synchronize()
+        want = [r.results() for r in runs]
+        errors = []
+
+        def work(i):
+            try:
+                st = torch.cuda.Stream()
+                for _ in range(25):
+                    runs[i].enqueue(stream=st)
+                    fb.set_tuning("timer_every", 1)            # a writer among the readers
+                st.synchronize()
+            except Exception as e:                              # surfaced in the main thread
+                errors.append(e)
+
+        threads = [threading.Thread(target=work, args=(i,)) for i in range(4)]
+        for t in threads:
+            t.start()
+        for t in threads:
+            t.join()
+        torch.cuda.synchronize()
+        assert not errors, errors
+        for i, r in enumerate(runs):
+            for got, w in zip(r.results(), want[i]):
+                assert torch.equal(got, w), f"thread {i}: results changed"
+    finally:
+        fb.set_tuning("splits_sparse", 0)
