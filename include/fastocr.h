@@ -136,6 +136,9 @@ size_t fastocr_workspace_bytes(int op, const fastocr_kv_view *kv, const fastocr_
  *   scores   fp32 [batch, max_vis_len]
  *   lse      fp32 [batch, n_q_heads] natural-log sum-exp of each head's logits, or NULL
  *   img_mass fp32 [batch] sum_i scores[b,i] = the image-attention ratio of Eq. 1, or NULL
+ * Kernels: bf16 caches with head_dim 128 or 64 and at most 16 query heads per kv head run on the
+ * matrix-core kernels (all calls); every other shape (fp32 caches, other head dimensions up to 256,
+ * larger groups) runs on plain-FMA kernels that accumulate in fp64, to the same error bars.
  * Concurrency: when the shape fits (bf16, head_dim 128, 1/2/4/8 kv heads with at most 8 query heads
  * each, batch <= 256 and <= the compute-unit count) this call (and fastocr_focal_attn_score) runs as ONE kernel whose
  * workgroups -- at most one per compute unit -- wait for each other's softmax statistics, so
