@@ -27,8 +27,9 @@
  *     fastocr_sparse_decode_attn each have a form in which the workgroups of ONE launch hand each
  *     other data through static device memory (see the Concurrency notes at each call), one
  *     "exchange slot" per call in flight.  A slot belongs to a stream: the first 16 streams of a
- *     GPU that use scoring (16 for the focal layer, 4 for pruned attention) keep a slot for the
- *     life of the process, and calls in order on one stream share it safely.  A call that is being
+ *     GPU that use scoring (16 for the focal layer, 4 for pruned attention) keep a slot until
+ *     fastocr_stream_release (or the end of the process), and calls in order on one stream share
+ *     it safely.  A call that is being
  *     captured into a HIP graph gets a slot of a separate pool (48 / 48 / 12) that belongs to that
  *     capture and stream, so a replay may run next to eager calls on any stream; instantiate a
  *     captured graph once (two instances replayed at the same time would share its slots).  A
@@ -341,6 +342,15 @@ int fastocr_stream_probe(const void *src, void *dst, size_t bytes, void *sink, v
  * Returns FASTOCR_EINVAL for an unknown key or a value outside the key's range.  Values are read
  * by later calls; workspace sizes must be asked for after the split and merge keys are set. */
 int fastocr_set_tuning(const char *key, int value);
+
+/*
+ * Gives back the exchange slots a stream holds on every GPU (see "Single-launch forms" above), e.g.
+ * before the stream is destroyed, so that other streams can have them.  No call of this library
+ * may be in flight on the stream, and HIP graphs captured on it keep their own slots.  A stream
+ * that calls the library again afterwards simply gets slots anew.  Host function; always
+ * FASTOCR_OK (a stream that holds nothing is not an error).
+ */
+int fastocr_stream_release(void *hip_stream);
 
 /*
  * For the callers of the single-launch forms (see the Concurrency notes above): how many waves

@@ -29,7 +29,7 @@ EXPORTS = (
     "fastocr_keep_count", "fastocr_workspace_bytes", "fastocr_focal_score", "fastocr_topk_fixation",
     "fastocr_sparse_decode_attn", "fastocr_dense_decode_attn", "fastocr_dense_decode_attn_static", "fastocr_focal_attn_score",
     "fastocr_focal_score_topk", "fastocr_focal_attn_score_topk", "fastocr_kernel_timer_enable",
-    "fastocr_kernel_timer_read", "fastocr_select_focal_layers", "fastocr_stream_probe", "fastocr_set_tuning", "fastocr_exchange_timeouts", "fastocr_strerror", "fastocr_version",
+    "fastocr_kernel_timer_read", "fastocr_select_focal_layers", "fastocr_stream_probe", "fastocr_set_tuning", "fastocr_exchange_timeouts", "fastocr_stream_release", "fastocr_strerror", "fastocr_version",
 )
 
 
@@ -98,6 +98,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.fastocr_stream_probe.restype, lib.fastocr_stream_probe.argtypes = I, [P, P, SZ, P, P]
     lib.fastocr_set_tuning.restype, lib.fastocr_set_tuning.argtypes = I, [ctypes.c_char_p, I]
     lib.fastocr_exchange_timeouts.restype, lib.fastocr_exchange_timeouts.argtypes = I, [ctypes.POINTER(ctypes.c_uint64)]
+    lib.fastocr_stream_release.restype, lib.fastocr_stream_release.argtypes = I, [P]
     lib.fastocr_strerror.restype, lib.fastocr_strerror.argtypes = ctypes.c_char_p, [I]
     lib.fastocr_version.restype, lib.fastocr_version.argtypes = ctypes.c_char_p, []
     _lib = lib
@@ -385,6 +386,11 @@ def exchange_timeouts() -> int:
     n = ctypes.c_uint64(0)
     _check(load_library().fastocr_exchange_timeouts(ctypes.byref(n)), "fastocr_exchange_timeouts")
     return int(n.value)
+
+
+def stream_release(stream: torch.cuda.Stream) -> None:
+    """fastocr_stream_release: give back the exchange slots the stream holds (nothing of the library in flight on it)."""
+    _check(load_library().fastocr_stream_release(stream.cuda_stream or None), "fastocr_stream_release")
 
 
 def kernel_timer_enable(kernel: int, capacity: int) -> None:

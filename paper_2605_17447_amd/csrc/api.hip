@@ -80,7 +80,7 @@ int plan_cu_count()
 }
 
 // ---- exchange slots (see kernels.hpp) --------------------------------------------------------------
-struct SlotOwner { hipStream_t stream; unsigned long long capture; };
+struct SlotOwner { hipStream_t stream; unsigned long long capture; bool free; };
 struct SlotTable { std::vector<SlotOwner> eager, graph; };
 static SlotTable g_slots[EX_KINDS][kMaxDevices];
 
@@ -118,11 +118,17 @@ int exchange_slot(int kind, hipStream_t stream, uint32_t **gave_up_flag)
     SlotTable &t = g_slots[kind][dev];
     std::vector<SlotOwner> &pool = capturing ? t.graph : t.eager;
     const int cap_n = capturing ? total - n_eager : n_eager;
+    const int first = capturing ? n_eager : 0;
     for (size_t i = 0; i < pool.size(); ++i)
-        if (pool[i].stream == stream && (!capturing || pool[i].capture == cap)) return (capturing ? n_eager : 0) + (int)i;
+        if (!pool[i].free && pool[i].stream == stream && (!capturing || pool[i].capture == cap)) return first + (int)i;
+    for (size_t i = 0; i < pool.size(); ++i)
+        if (pool[i].free) {                      // released by fastocr_stream_release
+            pool[i] = SlotOwner{stream, capturing ? cap : 0ull, false};
+            return first + (int)i;
+        }
     if ((int)pool.size() >= cap_n) return -1;
-    pool.push_back(SlotOwner{stream, capturing ? cap : 0ull});
-    return (capturing ? n_eager : 0) + (int)pool.size() - 1;
+    pool.push_back(SlotOwner{stream, capturing ? cap : 0ull, false});
+    return first + (int)pool.size() - 1;
 }
 
 bool exchange_trusted()
@@ -655,6 +661,18 @@ int fastocr_stream_probe(const void *src, void *dst, size_t bytes, void *sink, v
     if (!dst && !sink) return FASTOCR_EINVAL;
     hipError_t e = launch_stream_probe(src, dst, bytes, sink, (hipStream_t)hip_stream);
     return e == hipSuccess ? FASTOCR_OK : FASTOCR_EHIP;
+}
+
+int fastocr_stream_release(void *hip_stream)
+{
+    // the slot numbers of the streams that stay must not move (their calls may be in flight), so a
+    // released entry is only marked free and handed to the next stream that asks
+    std::lock_guard<std::mutex> lock(g_mu);
+    for (int kind = 0; kind < EX_KINDS; ++kind)
+        for (int dev = 0; dev < kMaxDevices; ++dev)
+            for (SlotOwner &o : g_slots[kind][dev].eager)
+                if (!o.free && o.stream == (hipStream_t)hip_stream) o.free = true;
+    return FASTOCR_OK;
 }
 
 int fastocr_exchange_timeouts(uint64_t *count)

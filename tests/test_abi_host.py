@@ -201,6 +201,11 @@ def test_static_scratch_entry_point_validation(lib):
     assert "static" in fb.strerror(fb.ETOOLARGE)
 
 
+def test_stream_release_is_a_host_side_no_op_for_unknown_streams(lib):
+    assert lib.fastocr_stream_release(None) == fb.OK
+    assert lib.fastocr_stream_release(0x1234500) == fb.OK
+
+
 def test_exchange_timeouts_rejects_a_null_pointer(lib):
     lib.fastocr_exchange_timeouts.restype = ctypes.c_int
     lib.fastocr_exchange_timeouts.argtypes = [ctypes.c_void_p]

@@ -122,6 +122,36 @@ def test_more_streams_than_exchange_slots_fall_back_to_the_separate_kernels():
         fb.set_tuning("splits_sparse", 0)
 
 
+def test_released_streams_hand_their_slots_on():
+    """40 streams in turn, each released after use: every one runs the single-launch forms (no top-level
+    merge kernel is ever launched), where without the release the 5th stream on would fall back."""
+    run = _Run(TinyCase(seed=790, B=2, Hq=28, Hkv=4, d=128, n_vis=[900, 700], pre=[4, 1], post=[40, 9], dtype="bf16"), 0.1)
+    fb.set_tuning("splits_sparse", 2)
+    try:
+        run.enqueue()
+        torch.cuda.synchronize()
+        want = run.results()
+        streams = [torch.cuda.Stream() for _ in range(40)]
+        fb.kernel_timer_enable(fb.KERNEL_ATTN_COMBINE, 256)
+        for st in streams:
+            fb.stream_release(st)                       # whatever earlier tests left on the pool's handles
+        fb.kernel_timer_read(fb.KERNEL_ATTN_COMBINE)
+        launched_before = 0
+        for i, st in enumerate(streams):
+            run.clear()
+            run.enqueue(stream=st)
+            st.synchronize()
+            for got, w in zip(run.results(), want):
+                assert torch.equal(got, w), f"stream {i}: results changed"
+            fb.stream_release(st)
+        # the fused focal layer always ends with its merge of the waves' partials (one launch per call); pruned
+        # attention adds one only when it could not merge inside its launch
+        assert len(fb.kernel_timer_read(fb.KERNEL_ATTN_COMBINE)) == len(streams)
+    finally:
+        fb.kernel_timer_enable(fb.KERNEL_ATTN_COMBINE, 0)
+        fb.set_tuning("splits_sparse", 0)
+
+
 def test_calls_from_several_host_threads_each_on_its_own_stream():
     """The binding releases the interpreter lock inside the C calls, so threads really run the library's host
     code side by side: the slot tables, tuning values and per-device words are guarded for that."""
