@@ -107,7 +107,7 @@ int exchange_slot(int kind, hipStream_t stream, uint32_t **gave_up_flag)
         // one word of pinned host memory per device, allocated on the first eager call that reaches
         // this point (an allocation is not a capturable call) and kept until the process ends
         void *p = nullptr;
-        if (hipHostMalloc(&p, 64, hipHostMallocMapped) == hipSuccess && p) {
+        if (hipHostMalloc(&p, 64, hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess && p) {
             memset(p, 0, 64);
             g_gave_up[dev] = static_cast<uint32_t *>(p);
         } else {
