@@ -141,3 +141,36 @@ def test_select_inside_the_launch_at_config4_size_is_repeatable():
             first = cur
         else:
             assert all(torch.equal(a, b) for a, b in zip(first, cur)), f"call {i} differs"
+
+
+def test_select_inside_the_launch_replays_in_a_graph():
+    """A captured one-call focal layer (select inside the launch) keeps its exchange slot; every replay, with a new
+    query and the previous replay's set as the warm start in place, must match the eager separate calls."""
+    case = TinyCase(seed=820, B=3, Hq=28, Hkv=4, d=128, n_vis=[2100, 1700, 2500], pre=[10, 3, 0], post=[50, 30, 9], dtype="bf16")
+    p = problem_from_case(case)
+    tau = 0.05
+    kmax = fo.keep_count(p.batch.max_vis_len, tau)
+    ws = torch.empty(max(fo.workspace_bytes(op, p.cache, p.batch, p.Hq, kmax) for op in range(7)), dtype=torch.uint8, device=DEV)
+    sc = torch.zeros((p.B, p.batch.max_vis_len), dtype=torch.float32, device=DEV)
+    idx = torch.zeros((p.B, kmax), dtype=torch.int32, device=DEV)
+    cnt = torch.zeros((p.B,), dtype=torch.int32, device=DEV)
+    out = torch.zeros_like(p.q)
+    run = lambda: fo.focal_attn_score_topk(p.cache, p.batch, p.q, p.scale, tau, out, sc, idx, cnt, ws, prev_idx=idx, prev_cnt=cnt)
+    run()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run()
+    rng = np.random.default_rng(9)
+    ws2 = torch.empty_like(ws)
+    for replay in range(6):
+        p.q.copy_(torch.from_numpy(rng.standard_normal(p.q.shape).astype(np.float32)).to(DEV).to(torch.bfloat16))
+        g.replay()
+        torch.cuda.synchronize()
+        sc0, idx0, cnt0, out0 = torch.zeros_like(sc), torch.zeros_like(idx), torch.zeros_like(cnt), torch.zeros_like(out)
+        fb.set_tuning("select_fused", 0)
+        fo.focal_attn_score(p.cache, p.batch, p.q, p.scale, out0, sc0, ws2)
+        fo.topk_fixation(sc0, p.batch, tau, idx0, cnt0, ws2)
+        fb.set_tuning("select_fused", 1)
+        torch.cuda.synchronize()
+        assert torch.equal(sc, sc0) and torch.equal(out, out0) and torch.equal(cnt, cnt0) and torch.equal(idx, idx0), f"replay {replay}"
