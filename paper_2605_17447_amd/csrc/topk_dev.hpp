@@ -227,18 +227,12 @@ __device__ __forceinline__ void topk_reg_body(
         }
     }
     // ---- bound from a sample: the first key of every thread (every PER-th token) ---------------------
+    // (run before the previous set's bound is reduced: the gather of the previous set's current scores
+    // above is a dependent memory round trip, and the sample select needs nothing from memory)
     const int ns = (N + PER - 1) / PER;
     if (tid < ns) sh.cand[tid] = key[0];
     __syncthreads();
     uint32_t theta0 = 0u;
-    if (have_prev) {
-        if (bad) (*sh.bad) = 1;
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) lo = min(lo, (uint32_t)__shfl_xor((int)lo, o));
-        if (lane == 0) atomicMin(&(*sh.theta_prev), lo);
-        __syncthreads();
-        if (!(*sh.bad)) theta0 = (*sh.theta_prev);
-    }
     {
         // about 1.5 k of the N tokens should reach the bound: rank 1.5 k ns / N in the sample, plus slack
         const int r = (int)(((int64_t)3 * k * ns) / ((int64_t)2 * N)) + 24;
@@ -248,8 +242,16 @@ __device__ __forceinline__ void topk_reg_body(
             const uint32_t ths = radix_select<THREADS>(sh.cand, ns, r, sh.hist, sh.pick, &unused, 16);
             theta0 = max(theta0, ths);
         }
-        __syncthreads();
     }
+    if (have_prev) {
+        if (bad) (*sh.bad) = 1;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) lo = min(lo, (uint32_t)__shfl_xor((int)lo, o));
+        if (lane == 0) atomicMin(&(*sh.theta_prev), lo);
+        __syncthreads();
+        if (!(*sh.bad)) theta0 = max(theta0, *sh.theta_prev);
+    }
+    __syncthreads();
     // ---- candidates, compacted in index order --------------------------------------------------------
     int mine = 0;
 #pragma unroll
