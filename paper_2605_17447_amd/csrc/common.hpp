@@ -28,13 +28,19 @@ struct SeqGeom {
     int N;    // image tokens
 };
 
-__device__ __forceinline__ SeqGeom seq_geom(const BatchDev &bv, int b)
+// from the three per-sequence entries as loaded (clamped into what the batch's maxima allow)
+__device__ __forceinline__ SeqGeom seq_geom_of(const BatchDev &bv, int seq_len, int vis_start, int vis_len)
 {
     SeqGeom g;
-    g.S = min(max(bv.seq_len[b], 0), bv.max_seq_len);
-    g.v0 = min(max(bv.vis_start[b], 0), g.S);
-    g.N = min(min(max(bv.vis_len[b], 0), g.S - g.v0), bv.max_vis_len);
+    g.S = min(max(seq_len, 0), bv.max_seq_len);
+    g.v0 = min(max(vis_start, 0), g.S);
+    g.N = min(min(max(vis_len, 0), g.S - g.v0), bv.max_vis_len);
     return g;
+}
+
+__device__ __forceinline__ SeqGeom seq_geom(const BatchDev &bv, int b)
+{
+    return seq_geom_of(bv, bv.seq_len[b], bv.vis_start[b], bv.vis_len[b]);
 }
 
 // Element offset of (sequence b, token j, kv head g, component 0).

@@ -381,7 +381,7 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
         // a range of the sequence never published: poison this range's scores
         for (int i = threadIdx.x; i < r1 - r0; i += kResThreads)
             store_score<SELECT>(&scores[(int64_t)b * bv.max_vis_len + r0 + i], __builtin_nanf(""));
-        if (SELECT) resident_select_tail(scores, bv, b, nranges, &g_fus_done[sync_slot][b], &smem[0][0][0]);
+        if (SELECT) resident_select_tail(scores, b, nranges, &g_fus_done[sync_slot][b], &smem[0][0][0]);
         leave();
         return;
     }
@@ -432,7 +432,7 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
             mass_part[wg0 + rng] = t;
         }
     }
-    if (SELECT) resident_select_tail(scores, bv, b, nranges, &g_fus_done[sync_slot][b], &smem[0][0][0]);
+    if (SELECT) resident_select_tail(scores, b, nranges, &g_fus_done[sync_slot][b], &smem[0][0][0]);
     leave();
 }
 

@@ -271,7 +271,7 @@ __device__ __forceinline__ void resident_retire(bool last, unsigned long long *s
 // fence.  The selecting workgroup leaves the counter at zero for the next call on the slot.
 constexpr int kSelPer = 32;
 constexpr int kSelMaxKeys = kResThreads * kSelPer;               // 16384 image tokens per sequence
-constexpr int kSelLdsBytes = 2048 + 4 * kRegCandCap + 4 * kSelMaxKeys + 256;
+constexpr int kSelLdsBytes = 4 * kWinBins + 4 * kWinListWords + 256;
 
 template <bool SELECT>
 __device__ __forceinline__ void store_score(float *p, float x)
@@ -285,8 +285,14 @@ __device__ __forceinline__ void store_score(float *p, float x)
 // The select's arguments are the kernel's FIRST argument and are read from the kernel-argument
 // segment here, when they are needed: as ordinary arguments they would sit in scalar registers
 // through the whole tile loop, which has none to spare.
-__device__ __forceinline__ void resident_select_tail(const float *scores, const BatchDev &bv,
-                                                     int b, int nranges, uint32_t *done, unsigned char *lds)
+// (The batch description is read there too, rather than kept across the tile loop.)
+struct ResidentArgsHead {       // how both kernels' argument lists begin
+    SelectArgs sel;
+    KvDev kv;
+    BatchDev bv;
+};
+
+__device__ __forceinline__ void resident_select_tail(const float *scores, int b, int nranges, uint32_t *done, unsigned char *lds)
 {
     __shared__ int sm_selects;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // this thread's score stores have been performed
@@ -297,19 +303,17 @@ __device__ __forceinline__ void resident_select_tail(const float *scores, const 
     }
     __syncthreads();
     if (!sm_selects) return;
-    const SelectArgs *sap = (const SelectArgs *)__builtin_amdgcn_kernarg_segment_ptr();
-    asm volatile("" : "+s"(sap)::"memory");
-    const SelectArgs sa = *sap;
+    const ResidentArgsHead *ka = (const ResidentArgsHead *)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(ka)::"memory");
+    const SelectArgs sa = ka->sel;
+    const BatchDev bv = ka->bv;
     TopkRegShared sh;
-    sh.hist = reinterpret_cast<uint32_t (*)[256]>(lds);
-    sh.cand = reinterpret_cast<uint32_t *>(lds + 2048);
-    sh.all_keys = reinterpret_cast<uint32_t *>(lds + 2048 + 4 * kRegCandCap);
-    int *misc = reinterpret_cast<int *>(lds + 2048 + 4 * kRegCandCap + 4 * kSelMaxKeys);
-    sh.w_ac = misc;                                          // 2 * 8 wave totals, 16-byte aligned
-    sh.pick = misc + 16;
-    sh.theta_prev = reinterpret_cast<uint32_t *>(misc + 18);
-    sh.bad = misc + 19;
-    topk_reg_body<kResThreads, kSelPer, true>(scores, bv, b, sa.tau, sa.prev_idx, sa.prev_cnt, sa.sel_idx, sa.sel_cnt,
+    sh.hist = reinterpret_cast<uint32_t *>(lds);
+    sh.list = reinterpret_cast<uint32_t *>(lds + 4 * kWinBins);
+    int *misc = reinterpret_cast<int *>(lds + 4 * kWinBins + 4 * kWinListWords);
+    sh.w_ac = misc;                                          // 4 * 8 wave values, 16-byte aligned
+    sh.pick = misc + 32;
+    topk_reg_body<kResThreads, kSelPer, true, false>(scores, bv, b, sa.tau, sa.prev_idx, sa.prev_cnt, sa.sel_idx, sa.sel_cnt,
                                               sa.kmax, sh, [](int, int) {});
     if (threadIdx.x == 0) __hip_atomic_store(done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }

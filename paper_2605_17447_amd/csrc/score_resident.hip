@@ -363,7 +363,7 @@ pre_done:
         // this range's scores rather than publish numbers built on missing statistics
         for (int i = threadIdx.x; i < r1 - r0; i += kResThreads)
             store_score<SELECT>(&scores[(int64_t)b * bv.max_vis_len + r0 + i], __builtin_nanf(""));
-        if (SELECT) resident_select_tail(scores, bv, b, nranges, &g_res_done[sync_slot][b], &smem[0][0][0]);
+        if (SELECT) resident_select_tail(scores, b, nranges, &g_res_done[sync_slot][b], &smem[0][0][0]);
         leave();
         return;
     }
@@ -408,7 +408,7 @@ fin_done:
             if (rng == 0) { mass_meta[2 * b] = wg0; mass_meta[2 * b + 1] = nranges; }
         }
     }
-    if (SELECT) resident_select_tail(scores, bv, b, nranges, &g_res_done[sync_slot][b], &smem[0][0][0]);
+    if (SELECT) resident_select_tail(scores, b, nranges, &g_res_done[sync_slot][b], &smem[0][0][0]);
     leave();
 }
 

@@ -1,13 +1,16 @@
 // TopK_{ceil(tau N)} over one sequence's image scores (Sec. 3.1.2), exact and deterministic,
 // warm-started from the previous step's focal token set (Cross-Step Fixation Reuse, Sec. 3.2).
 //
-// The scores become order-preserving 32-bit keys.  The k-th largest key (the threshold) is found
-// by an MSB-first 8-bit radix select in LDS; everything above it, plus the lowest-index keys equal
-// to it until k, is written in ascending index order.  The select is shortened by first reducing
-// the N keys to a short candidate list bounded below by (a) the previous step's set -- the warm
-// start: its k tokens' smallest current key can only be at or below the new threshold -- and (b)
-// a sample of the scores; the writing is spread over several 1024-thread workgroups per
-// sequence; see topk_kernel.  The result never depends on either bound.
+// The scores become order-preserving 32-bit keys; the k-th largest key (the threshold) is found
+// exactly; everything above it, plus the lowest-index keys equal to it until k, is written in
+// ascending index order.  The previous step's set -- the warm start -- gives a lower bound of the
+// threshold (its k tokens' smallest current key can only be at or below it) that shortens the
+// search; the result never depends on it.
+//   Image spans up to 16384 tokens (topk_reg_kernel): one workgroup per sequence with all keys in
+//   registers; the threshold comes from histogram passes over a window of key values that starts at
+//   the bound (topk_dev.hpp).
+//   Longer spans (topk_general_kernel): keys in LDS or in the workspace, an MSB-first 8-bit radix
+//   select over a candidate list, the writing spread over several workgroups per sequence.
 
 #include "topk_dev.hpp"
 
@@ -201,23 +204,20 @@ __global__ __launch_bounds__(kTopkThreads) void topk_general_kernel(
 constexpr int kTopkPer = 16;
 constexpr int kTopkRegKeys = kTopkThreads * kTopkPer;
 
+// VEC: every row of scores starts 16-byte aligned and holds whole 16-byte pieces
+template <bool VEC>
 __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(
     const float *__restrict__ scores, BatchDev bv, double tau, const int32_t *prev_idx,
     const int32_t *prev_cnt, int32_t *sel_idx, int32_t *sel_cnt, int64_t kmax)
 {
-
-    extern __shared__ uint32_t dyn_keys[];          // all keys, only when the candidate list fails
-    __shared__ uint32_t hist[2][256];
-    __shared__ uint32_t cand[kRegCandCap];
-    __shared__ int s_pick[2];
-    __shared__ uint32_t s_theta_prev;
-    __shared__ int s_bad;
-    __shared__ __align__(16) int w_ac[2 * kTopkWaves];
+    __shared__ uint32_t hist[kWinBins];
+    __shared__ __align__(16) uint32_t list[kWinListWords];
+    __shared__ int s_pick[4];
+    __shared__ __align__(16) int w_ac[4 * kTopkWaves];
 
     TopkRegShared sh;
-    sh.hist = hist; sh.cand = cand; sh.all_keys = dyn_keys; sh.pick = s_pick;
-    sh.theta_prev = &s_theta_prev; sh.bad = &s_bad; sh.w_ac = w_ac;
-    topk_reg_body<kTopkThreads, kTopkPer>(scores, bv, blockIdx.x, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax, sh,
+    sh.hist = hist; sh.list = list; sh.pick = s_pick; sh.w_ac = w_ac;
+    topk_reg_body<kTopkThreads, kTopkPer, false, VEC>(scores, bv, blockIdx.x, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax, sh,
                                           [](int, int) {});
 }
 
@@ -258,16 +258,16 @@ hipError_t launch_topk(const float *scores, const BatchDev &bv, int batch, doubl
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kLdsKeyCap * (int)sizeof(uint32_t)) != hipSuccess)
             (void)hipGetLastError();
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(topk_reg_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kTopkRegKeys * (int)sizeof(uint32_t)) != hipSuccess)
-            (void)hipGetLastError();
         attr_set = true;
     }
     if (bv.max_vis_len <= kTopkRegKeys) {
-        // the dynamic LDS (all keys) is only touched when the candidate list fails
-        FASTOCR_LAUNCH(K_TOPK, topk_reg_kernel, dim3(batch), dim3(kTopkThreads), (size_t)bv.max_vis_len * sizeof(uint32_t),
-                       stream, scores, bv, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax);
+        const bool vec = (reinterpret_cast<uintptr_t>(scores) & 15u) == 0 && (bv.max_vis_len & 3) == 0;
+        if (vec)
+            FASTOCR_LAUNCH(K_TOPK, topk_reg_kernel<true>, dim3(batch), dim3(kTopkThreads), 0,
+                           stream, scores, bv, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax);
+        else
+            FASTOCR_LAUNCH(K_TOPK, topk_reg_kernel<false>, dim3(batch), dim3(kTopkThreads), 0,
+                           stream, scores, bv, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax);
         return hipGetLastError();
     }
     uint32_t *gkeys = reinterpret_cast<uint32_t *>(ws);

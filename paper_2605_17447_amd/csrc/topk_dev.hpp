@@ -93,14 +93,27 @@ __device__ uint32_t radix_select(const uint32_t *keys, int n, int k, uint32_t (*
     return prefix;
 }
 
-// Image spans of up to kTopkRegKeys tokens: one workgroup per sequence, thread t keeps the keys of
-// tokens 16t .. 16t+15 in registers.  The candidate list (keys at or above the bound theta0, see
-// above) and the result are both written in index order through block-wide prefix sums, so no
-// atomics or index arrays are needed, and the scores are read exactly once.
-constexpr int kRegCandCap = 8192;          // candidates this kernel selects among (keep ratios up to 1/3 at 16384 tokens)
+// ---- the register-resident select ----------------------------------------------------------------------
+// Image spans of up to THREADS * PER tokens: one workgroup per sequence, thread t keeps the keys of
+// tokens PER t .. PER t + PER - 1 in registers, so the scores are read exactly once.  The threshold
+// (the k-th largest key) is found by histogram passes straight from the registers (window_select
+// below), the result is written in index order through a block-wide prefix sum: no candidate list,
+// no atomics on memory, no index arrays.
+
+// max / min over the 64 lanes of a wave with data-parallel-primitive moves (see wave_scan_incl);
+// the result is the same in every lane
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t x)
+{
+#define FASTOCR_DPP_STEP(CTRL, ROWS) x = max(x, (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, CTRL, ROWS, 0xf, false))
+    FASTOCR_DPP_STEP(0x111, 0xf); FASTOCR_DPP_STEP(0x112, 0xf); FASTOCR_DPP_STEP(0x114, 0xf); FASTOCR_DPP_STEP(0x118, 0xf);
+    FASTOCR_DPP_STEP(0x142, 0xa); FASTOCR_DPP_STEP(0x143, 0xc);
+#undef FASTOCR_DPP_STEP
+    return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
+}
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t x) { return ~wave_max_u32(~x); }
 
 // exclusive prefix sums of (a, c) over the workgroup's THREADS threads; totals through *ta, *tc.  All threads call.
-// w_ac: 2 x THREADS/64 wave totals, 16-byte aligned.
+// w_ac: at least 2 x THREADS/64 wave totals, 16-byte aligned.
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 template <int THREADS>
 __device__ __forceinline__ void block_scan2(int a, int c, int *w_ac, int &a_excl, int &c_excl, int *ta, int *tc)
@@ -128,19 +141,171 @@ __device__ __forceinline__ void block_scan2(int a, int c, int *w_ac, int &a_excl
 }
 
 // Shared memory of topk_reg_body, provided by the calling kernel.
+constexpr int kWinBins = 512;               // bins of a histogram pass
+constexpr int kWinRank = 64;                // a bin of at most this many keys is ranked key by key
+constexpr int kWinListWords = 3 * kWinRank; // the bin's keys, then how many keys lie above / equal each of them
 struct TopkRegShared {
-    uint32_t (*hist)[256];      // [2][256]
-    uint32_t *cand;             // [kRegCandCap]
-    uint32_t *all_keys;         // [max_vis_len]: all keys, only touched when the candidate list fails
-    int *pick;                  // [2]
-    uint32_t *theta_prev;       // [1]
-    int *bad;                   // [1]
-    int *w_ac;                  // [2 * THREADS / 64], 16-byte aligned
+    uint32_t *hist;             // [kWinBins]
+    uint32_t *list;             // [kWinListWords], 16-byte aligned
+    int *pick;                  // [4]: bin, rank within it, keys copied so far
+    int *w_ac;                  // [4 * THREADS / 64], 16-byte aligned
 };
 
-// One workgroup of THREADS threads selects sequence b's set; thread t keeps the keys of tokens
-// PER t .. PER t + PER - 1 in registers (THREADS * PER >= max_vis_len).  publish(position, index) is
-// called by the thread that writes sel_idx[position] = index, for every entry of the result.
+// The k-th largest of the workgroup's keys, all of them in the threads' registers, given a window lo <= key <= key_max that holds at least the k
+// largest.  A histogram pass counts the window's keys in 512 bins of 2^shift key values; the first
+// window's bins are as fine as the spread of the keys allows (flat scores: a small fraction of an
+// octave of an fp32 score per bin; heavy tails: most keys still sit in the low bins, next to the
+// k-th).  The bin that holds the k-th largest key becomes the next window, 512 times finer, until it
+// holds at most kWinRank keys; those are copied to LDS and ranked: every pair is compared once, spread
+// over all threads, and the key with above < rank <= above + equal is the threshold.  A window of
+// single key values (shift 0) names the threshold by its bin.  One pass and the ranking is the usual
+// case.  hist and the list's counters must be zero and pick[2] = 0 on entry (the caller clears them
+// before a barrier of its own).  *ties = how many keys equal to the threshold belong to the k largest.
+template <int THREADS, int PER>
+__device__ __forceinline__ uint32_t window_select(const uint32_t (&key)[PER], uint32_t lo, uint32_t key_max,
+                                                  int k, const TopkRegShared &sh, int *ties)
+{
+    static_assert(THREADS >= kWinBins && THREADS % 256 == 0, "one thread clears one bin; whole vectors of wave totals");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t *h = sh.hist;
+    uint32_t span = key_max - lo;                    // the window: lo <= key <= lo + span
+    int shift = max(0, 23 - (int)__builtin_clz(span | 1u));                     // span >> shift < 512
+    int rank = k, nb = 0;
+    if (span == 0u) {                                // every key of the window is the same
+        *ties = k;
+        return lo;
+    }
+    // key - lo <= span in unsigned arithmetic is the whole test (a key below lo wraps around to more
+    // than any span).  Padding keys (0, past the sequence's end) are not masked out: they can only
+    // fall into the lowest bin of a window that starts at key 0, below every real key or equal to the
+    // smallest ones, and ranks are counted from the top -- neither the threshold nor the tie count
+    // sees them; the caller drops them from the output by its own mask.
+    while (true) {
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const uint32_t d = key[j] - lo;
+            if (d <= span) atomicAdd(&h[d >> shift], 1u);
+        }
+        __syncthreads();
+        if (tid < 64) {
+            // lane owns bins 511-8*lane .. 504-8*lane (descending)
+            uint32_t c[8], tot = 0u;
+#pragma unroll
+            for (int x = 0; x < 8; ++x) { c[x] = h[kWinBins - 1 - (8 * lane + x)]; tot += c[x]; }
+            const uint32_t incl = (uint32_t)wave_scan_incl((int)tot);
+            const uint32_t above = incl - tot;
+            if (above < (uint32_t)rank && incl >= (uint32_t)rank) {
+                uint32_t run = above;
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    if (run < (uint32_t)rank && run + c[x] >= (uint32_t)rank) {
+                        sh.pick[0] = kWinBins - 1 - (8 * lane + x);
+                        sh.pick[1] = rank - (int)run;
+                    }
+                    run += c[x];
+                }
+            }
+        }
+        __syncthreads();
+        const int bin = sh.pick[0];
+        rank = sh.pick[1];
+        nb = (int)h[bin];
+        lo += (uint32_t)bin << shift;
+        if (shift == 0) {                            // the window's bins were single key values
+            *ties = rank;
+            return lo;
+        }
+        span = (1u << shift) - 1u;                   // the bin is the next window
+        if (nb <= kWinRank) break;
+        shift = max(0, shift - 9);                   // ... cut into 512 bins again
+        __syncthreads();                             // everybody has read pick and the histogram
+        if (tid < kWinBins) h[tid] = 0u;
+        __syncthreads();
+    }
+    // ---- the bin's keys into LDS --------------------------------------------------------------------------
+    // At most kWinRank of the workgroup's keys are in the bin, so nearly all of a wave's PER lane masks
+    // (one per key position, in scalar registers) are empty and are skipped by a scalar branch; a wave
+    // that holds any reserves its places with one counter update.
+    if constexpr (PER <= 16) {
+        uint64_t hit[PER];
+        int mine = 0;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            hit[j] = __builtin_amdgcn_ballot_w64(key[j] - lo <= span);
+            mine += __popcll(hit[j]);
+        }
+        if (mine) {
+            int pos = 0;
+            if (lane == 0) pos = atomicAdd(&sh.pick[2], mine);
+            pos = __builtin_amdgcn_readfirstlane(pos);
+#pragma unroll
+            for (int j = 0; j < PER; ++j) {
+                if (hit[j]) {
+                    const int before = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(hit[j] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)hit[j], 0u));
+                    if (key[j] - lo <= span && pos + before < kWinRank) sh.list[pos + before] = key[j];
+                    pos += __popcll(hit[j]);
+                }
+            }
+        }
+    } else {
+        // (many keys per thread: that many lane masks would crowd the scalar registers of the kernel
+        // around this code; the places are dealt lane by lane instead)
+        uint32_t hit = 0u;                           // bit j: key j lies in the bin (shifted in from the top key down)
+#pragma unroll
+        for (int j = PER - 1; j >= 0; --j) hit = hit + hit + ((key[j] - lo <= span) ? 1u : 0u);
+        const int mine = __popc(hit);
+        const int upto = wave_scan_incl(mine);
+        const int total = __builtin_amdgcn_readlane(upto, 63);
+        if (total) {
+            int pos = 0;
+            if (lane == 0) pos = atomicAdd(&sh.pick[2], total);
+            pos = __builtin_amdgcn_readfirstlane(pos) + upto - mine;
+            if (hit) {
+#pragma unroll
+                for (int j = 0; j < PER; ++j)
+                    if (((hit >> j) & 1u) && pos < kWinRank) sh.list[pos++] = key[j];
+            }
+        }
+    }
+    __syncthreads();
+    // ---- every pair once: thread (wave w, lane i) compares key i with keys w*E .. w*E+E-1 --------------
+    {
+        constexpr int E = kWinRank / (THREADS / 64);
+        static_assert(E % 4 == 0, "whole 16-byte reads");
+        if (lane < nb && wave * E < nb) {
+            const uint32_t e = sh.list[lane];
+            int gt = 0, eq = 0;
+#pragma unroll
+            for (int v = 0; v < E / 4; ++v) {
+                const u32x4 x = reinterpret_cast<const u32x4 *>(sh.list)[wave * (E / 4) + v];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const bool there = wave * E + 4 * v + c < nb;
+                    gt += (there && x[c] > e) ? 1 : 0;
+                    eq += (there && x[c] == e) ? 1 : 0;
+                }
+            }
+            if (gt) atomicAdd(&sh.list[kWinRank + lane], (uint32_t)gt);
+            if (eq) atomicAdd(&sh.list[2 * kWinRank + lane], (uint32_t)eq);
+        }
+    }
+    __syncthreads();
+    if (tid < nb) {
+        const int gt = (int)sh.list[kWinRank + tid], eq = (int)sh.list[2 * kWinRank + tid];
+        if (gt < rank && rank <= gt + eq) { sh.pick[0] = (int)sh.list[tid]; sh.pick[1] = rank - gt; }     // equal keys write the same
+    }
+    __syncthreads();
+    *ties = sh.pick[1];
+    return (uint32_t)sh.pick[0];
+}
+
+// One workgroup of THREADS threads selects sequence b's set.  publish(position, index) is called by
+// the thread that writes sel_idx[position] = index, for every entry of the result.
+// The first window runs from a lower bound of the threshold to the largest key.  The bound is the
+// smallest key of all, or -- the warm start -- the smallest CURRENT key among the previous set's k
+// tokens when that set is k distinct valid tokens: k keys reach it, so the threshold cannot lie
+// below, and when the fixation moved little it cuts the window to the top few per cent of the keys.
+// The result never depends on the bound.
 // COHERENT: the scores were written earlier in the SAME launch by other workgroups (agent-scope
 // stores, completed before this workgroup was told so): they are read with agent-scope loads, which
 // never hit a line this compute unit's caches may still hold from before.
@@ -151,44 +316,71 @@ __device__ __forceinline__ float score_at(const float *p)
     return *p;
 }
 
-template <int THREADS, int PER, bool COHERENT = false, typename Publish>
+template <int THREADS, int PER, bool COHERENT, bool VEC, typename Publish>
 __device__ __forceinline__ void topk_reg_body(
     const float *__restrict__ scores, const BatchDev &bv, int b, double tau, const int32_t *prev_idx,
     const int32_t *prev_cnt, int32_t *sel_idx, int32_t *sel_cnt, int64_t kmax, const TopkRegShared &sh,
     Publish publish)
 {
-    const int tid = threadIdx.x, lane = tid & 63;
+    static_assert(PER <= 32 && PER % 4 == 0, "a thread's keys are tracked in 32-bit masks and loaded 16 bytes at a time");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int W = THREADS / 64;
     int32_t *out = sel_idx + (int64_t)b * kmax;
     const float *srow = scores + (int64_t)b * bv.max_vis_len;
 
-    // The thread's 16 scores and its first two entries of the previous set are requested before
-    // the sequence's geometry is known (the rows are max_vis_len and kmax entries long whatever the
-    // sequence's own counts are): one memory round trip instead of two before the keys exist.
+    // the select's LDS starts out clear (the barrier further down stands between this and its first use)
+    if (tid < kWinBins) sh.hist[tid] = 0u;
+    if (tid < 2 * kWinRank) sh.list[kWinRank + tid] = 0u;
+    if (tid == 0) sh.pick[2] = 0;
+    if (bv.max_vis_len <= 0 || kmax <= 0) {                       // no row to read from, nothing to keep
+        if (tid == 0) sel_cnt[b] = 0;
+        return;
+    }
+
+    // The thread's first two entries of the previous set and its scores are requested before the
+    // sequence's geometry is known (the rows are kmax and max_vis_len entries long whatever the
+    // sequence's own counts are): one memory round trip instead of two before the keys exist.  The
+    // previous set's entries go first: loads come back in the order they were sent, so the score
+    // that the first entry points at can be requested while the thread's own scores are still on
+    // their way.  Everything up to the keys is straight-line code with clamped addresses instead of
+    // branches: across a branch the compiler waits for every outstanding load.
+    const int32_t *pv = prev_idx ? prev_idx + (int64_t)b * kmax : reinterpret_cast<const int32_t *>(srow);
+    const int pv_last = prev_idx ? (int)min(kmax, (int64_t)0x7fffffff) - 1 : 0;
+    const int prev0 = pv[min(tid, pv_last)], prev1 = pv[min(tid + 1, pv_last)];
     const int base = tid * PER;
-    const bool whole = base + PER <= bv.max_vis_len && (reinterpret_cast<uintptr_t>(srow + base) & 15u) == 0;
-    f32x4 raw[PER / 4];
-#pragma unroll
-    for (int v = 0; v < PER / 4; ++v) raw[v] = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (whole) {
+    // VEC (rows start 16-byte aligned and hold whole 16-byte pieces; the host knows): a piece lies inside
+    // the row or past it -- then it is read from the row's start and masked out, like single scores
+    // past the row's end otherwise
+    float raw[PER];
+    if constexpr (VEC && !COHERENT) {
 #pragma unroll
         for (int v = 0; v < PER / 4; ++v) {
-            if (COHERENT) {
+            const int at = base + 4 * v + 4 <= bv.max_vis_len ? base + 4 * v : 0;
+            const f32x4 x = *reinterpret_cast<const f32x4 *>(srow + at);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) raw[v][e] = score_at<true>(srow + base + 4 * v + e);
-            } else {
-                raw[v] = *reinterpret_cast<const f32x4 *>(srow + base + 4 * v);
-            }
+            for (int e = 0; e < 4; ++e) raw[4 * v + e] = x[e];
         }
+    } else {
+#pragma unroll
+        for (int j = 0; j < PER; ++j) raw[j] = score_at<COHERENT>(srow + (base + j < bv.max_vis_len ? base + j : 0));
     }
-    const int32_t *prev = prev_idx ? prev_idx + (int64_t)b * kmax : nullptr;
-    int prev0 = 0, prev1 = 0;
-    if (prev && tid < kmax) prev0 = prev[tid];
-    if (prev && tid + 1 < kmax) prev1 = prev[tid + 1];
 
-    const SeqGeom geo = seq_geom(bv, b);
+    const int e_seq = bv.seq_len[b], e_start = bv.vis_start[b], e_vis = bv.vis_len[b];
+    const int e_prev = (prev_cnt ? prev_cnt : bv.vis_len)[b];
+    const SeqGeom geo = seq_geom_of(bv, e_seq, e_start, e_vis);
     const int N = geo.N;
     const int k = (int)min((int64_t)keep_count_dev(N, tau), kmax);
-    const int pcnt = prev_cnt ? prev_cnt[b] : -1;
+    const int pcnt = prev_cnt ? e_prev : -1;
+
+    // ---- bound from the previous set: k distinct valid tokens (strictly ascending) or none ----------
+    // entry r = tid: its current score is requested here (from a clamped address when there is no
+    // such entry), used further down
+    const bool have_prev = prev_idx && pcnt == k && k > 0 && k < N;
+    uint32_t lo_prev = have_prev ? 0xffffffffu : 0u;
+    const bool first_mine = have_prev && tid < k;
+    const bool first_ok = prev0 >= 0 && prev0 < N && prev0 < ((tid + 1 < k) ? prev1 : 0x7fffffff);
+    const float first_score = score_at<COHERENT>(srow + ((first_mine && first_ok) ? prev0 : 0));
+    if (first_mine && !first_ok) lo_prev = 0u;                    // not a set of k tokens: no bound
 
     if (k <= 0 || k >= N) {
         if (k >= N && k > 0)
@@ -196,92 +388,85 @@ __device__ __forceinline__ void topk_reg_body(
         if (tid == 0) sel_cnt[b] = k <= 0 ? 0 : N;
         return;
     }
-    if (tid == 0) { (*sh.theta_prev) = 0xffffffffu; (*sh.bad) = 0; }
 
-    // ---- the thread's 16 keys; tokens past N get key 0 and are never counted ----------------------
+    // ---- the thread's keys; tokens past N get key 0 and are never counted ---------------------------
     const int nvalid = min(max(N - base, 0), PER);
     // which of the thread's keys are real, as a bit mask in a vector register (PER lane masks kept in
     // scalar registers, as `j < nvalid` would have it, take most of the scalar file)
     const uint32_t vmask = nvalid >= 32 ? 0xffffffffu : ((1u << nvalid) - 1u);
     auto real = [&](int j) { return ((vmask >> j) & 1u) != 0u; };
     uint32_t key[PER];
-    if (whole) {
 #pragma unroll
-        for (int v = 0; v < PER / 4; ++v)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) key[4 * v + e] = real(4 * v + e) ? order_key(raw[v][e]) : 0u;
-    } else {
-#pragma unroll
-        for (int j = 0; j < PER; ++j) key[j] = j < nvalid ? order_key(score_at<COHERENT>(srow + base + j)) : 0u;
-    }
-    // ---- bound from the previous set: k distinct valid tokens (strictly ascending) or ignored ----
-    const bool have_prev = prev_idx && pcnt == k;
-    uint32_t lo = 0xffffffffu;
-    int bad = 0;
+    for (int j = 0; j < PER; ++j) key[j] = real(j) ? order_key(raw[j]) : 0u;
+    // the previous set's entries beyond the first THREADS (keep ratios above 1/PER)
     if (have_prev) {
-        for (int r = tid; r < k; r += THREADS) {
-            const int i = r == tid ? prev0 : prev[r];
-            const int nx = (r + 1 < k) ? (r == tid ? prev1 : prev[r + 1]) : 0x7fffffff;
-            if (i < 0 || i >= N || i >= nx) bad = 1;
-            else lo = min(lo, order_key(score_at<COHERENT>(srow + i)));
+        for (int r = tid + THREADS; r < k; r += THREADS) {
+            const int i = pv[r];
+            const int nx = (r + 1 < k) ? pv[r + 1] : 0x7fffffff;
+            if (i < 0 || i >= N || i >= nx) lo_prev = 0u;
+            else lo_prev = min(lo_prev, order_key(score_at<COHERENT>(srow + i)));
         }
+        if (first_mine && first_ok) lo_prev = min(lo_prev, order_key(first_score));
     }
-    // ---- bound from a sample: the first key of every thread (every PER-th token) ---------------------
-    // (run before the previous set's bound is reduced: the gather of the previous set's current scores
-    // above is a dependent memory round trip, and the sample select needs nothing from memory)
-    const int ns = (N + PER - 1) / PER;
-    if (tid < ns) sh.cand[tid] = key[0];
-    __syncthreads();
-    uint32_t theta0 = 0u;
-    {
-        // about 1.5 k of the N tokens should reach the bound: rank 1.5 k ns / N in the sample, plus slack
-        const int r = (int)(((int64_t)3 * k * ns) / ((int64_t)2 * N)) + 24;
-        if (r < ns) {
-            int unused;
-            // the upper 16 bits are enough for a bound (fp32: sign, exponent, 7 mantissa bits)
-            const uint32_t ths = radix_select<THREADS>(sh.cand, ns, r, sh.hist, sh.pick, &unused, 16);
-            theta0 = max(theta0, ths);
-        }
-    }
-    if (have_prev) {
-        if (bad) (*sh.bad) = 1;
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) lo = min(lo, (uint32_t)__shfl_xor((int)lo, o));
-        if (lane == 0) atomicMin(&(*sh.theta_prev), lo);
-        __syncthreads();
-        if (!(*sh.bad)) theta0 = max(theta0, *sh.theta_prev);
-    }
-    __syncthreads();
-    // ---- candidates, compacted in index order --------------------------------------------------------
-    int mine = 0;
-#pragma unroll
-    for (int j = 0; j < PER; ++j) mine += (real(j) && key[j] >= theta0) ? 1 : 0;
-    int pos, unused_excl, nc, unused_tot;
-    block_scan2<THREADS>(mine, 0, sh.w_ac, pos, unused_excl, &nc, &unused_tot);
-    const bool from_cand = nc >= k && nc <= kRegCandCap;
-    uint32_t theta;
-    int ties;
-    if (from_cand) {
-#pragma unroll
-        for (int j = 0; j < PER; ++j)
-            if (real(j) && key[j] >= theta0) sh.cand[pos++] = key[j];
-        __syncthreads();
-        theta = radix_select<THREADS>(sh.cand, nc, k, sh.hist, sh.pick, &ties);
-    } else {
-#pragma unroll
-        for (int j = 0; j < PER; ++j)
-            if (real(j)) sh.all_keys[base + j] = key[j];
-        __syncthreads();
-        theta = radix_select<THREADS>(sh.all_keys, N, k, sh.hist, sh.pick, &ties);
-    }
-    // ---- the result in ascending index order; ties go to the lowest indices ------------------------
-    // bit j of the masks: key j of this thread lies above / on the threshold
-    uint32_t m_gt = 0u, m_eq = 0u;
+    // ---- the largest and the smallest key and the previous set's bound: one exchange through LDS --------
+    uint32_t kmx = 0u, kmn = 0xffffffffu;
 #pragma unroll
     for (int j = 0; j < PER; ++j) {
-        m_gt |= (real(j) && key[j] > theta) ? (1u << j) : 0u;
-        m_eq |= (real(j) && key[j] == theta) ? (1u << j) : 0u;
+        kmx = max(kmx, key[j]);                                   // (padding keys are 0)
+        kmn = min(kmn, key[j]);
     }
+    if (nvalid < PER) {                                           // the thread at the sequence's end and those past it
+        kmn = 0xffffffffu;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) kmn = min(kmn, real(j) ? key[j] : 0xffffffffu);
+    }
+    // A third bound costs nothing more: every thread that holds a real key holds one at or above the
+    // smallest of the threads' own maxima, so when k does not exceed the number of such threads, k keys
+    // reach that value (scores without structure: about a third of the keys, which spares the
+    // histogram pass the other two thirds of its LDS atomics).
+    uint32_t lo_own = (nvalid > 0 && k <= (N + PER - 1) / PER) ? kmx : (nvalid > 0 ? 0u : 0xffffffffu);
+    kmx = wave_max_u32(kmx);
+    kmn = wave_min_u32(kmn);
+    lo_prev = wave_min_u32(lo_prev);
+    lo_own = wave_min_u32(lo_own);
+    if (lane == 0) {
+        sh.w_ac[wave] = (int)kmx;
+        sh.w_ac[W + wave] = (int)~kmn;
+        sh.w_ac[2 * W + wave] = (int)~lo_prev;
+        sh.w_ac[3 * W + wave] = (int)~lo_own;
+    }
+    __syncthreads();
+    uint32_t nmn = 0u, nlo = 0u, now = 0u;                        // complements: everything is a maximum
+#pragma unroll
+    for (int v = 0; v < W / 4; ++v) {
+        const i32x4 *wv = reinterpret_cast<const i32x4 *>(sh.w_ac);
+        const i32x4 x = wv[v], y = wv[W / 4 + v], z = wv[2 * (W / 4) + v], u = wv[3 * (W / 4) + v];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            kmx = max(kmx, (uint32_t)x[e]);
+            nmn = max(nmn, (uint32_t)y[e]);
+            nlo = max(nlo, (uint32_t)z[e]);
+            now = max(now, (uint32_t)u[e]);
+        }
+    }
+    // (a sequence whose threads past its end vote 0xffffffff alone cannot happen: N >= 1 here)
+    const uint32_t lo = max(max(~nmn, ~nlo), ~now);               // (w_ac is next written two barriers further on)
+
+    // ---- the threshold ---------------------------------------------------------------------------------
+    int ties;
+    const uint32_t theta = window_select<THREADS, PER>(key, lo, kmx, k, sh, &ties);
+
+    // ---- the result in ascending index order; ties go to the lowest indices ------------------------
+    // bit j of the masks: key j of this thread lies above / on the threshold
+    // (shifted in from the top key down: a compare and an add-with-carry per key and mask; a padding key,
+    // 0, is never above a threshold and is taken off the ties by the validity mask)
+    uint32_t m_gt = 0u, m_eq = 0u;
+#pragma unroll
+    for (int j = PER - 1; j >= 0; --j) {
+        m_gt = m_gt + m_gt + ((key[j] > theta) ? 1u : 0u);
+        m_eq = m_eq + m_eq + ((key[j] == theta) ? 1u : 0u);
+    }
+    m_eq &= vmask;
     int gt_excl, eq_excl, gt_tot, eq_tot;
     block_scan2<THREADS>(__popc(m_gt), __popc(m_eq), sh.w_ac, gt_excl, eq_excl, &gt_tot, &eq_tot);
     // of this thread's keys on the threshold, the first (ties - eq_excl) are still wanted

@@ -61,10 +61,16 @@ def make_scores(rng, B, W, kind):
         s[0, 7 % W] = -np.inf
     elif kind == "const":
         s = np.full((B, W), 0.125)
+    elif kind == "cluster":         # a dense cluster a few thousand ulps wide under a few far outliers: the
+        # select has to narrow its window several times, down to single key values (with repeats)
+        s = (1.0 + rng.integers(0, 3000, size=(B, W)) * 2.0 ** -23).astype(np.float32)
+        s[:, ::1000] = 100.0
+        s[1 % B] = (1.0 + rng.integers(0, 200000, size=W) * 2.0 ** -23).astype(np.float32)     # wider: ends in a ranked bin
+        s[1 % B, ::777] = 1.0e6
     return s.astype(np.float32)
 
 
-@pytest.mark.parametrize("kind", ["softmax", "ties", "signed", "const"])
+@pytest.mark.parametrize("kind", ["softmax", "ties", "signed", "const", "cluster"])
 @pytest.mark.parametrize("W", [1, 5, 64, 1000, 4096, 16384, 20000])
 def test_cold_topk_is_bit_exact(kind, W):
     rng = np.random.default_rng(W * 3 + len(kind))
@@ -133,3 +139,50 @@ def test_rows_beyond_the_count_are_left_alone_and_pitch_may_exceed_k():
     idx, cnt = run_topk(s, [500, 100], 0.1, kmax=77)
     assert_same(idx, cnt, expect(s, [500, 100], 0.1))
     assert np.all(idx[0, 50:] == -5) and np.all(idx[1, 10:] == -5)
+
+
+def test_warm_start_with_more_kept_tokens_than_threads_and_few_kept_tokens():
+    """Keep ratios above 1/16 (the previous set is longer than the workgroup, and the bound from the
+    threads' own maxima does not apply) and a very small one."""
+    rng = np.random.default_rng(4)
+    B, W = 3, 16384
+    vis_len = [16384, 10000, 16001]
+    for kind in ("softmax", "cluster"):
+        s = make_scores(rng, B, W, kind)
+        for tau in (0.25, 0.004):
+            want = expect(s, vis_len, tau)
+            kmax = fo.keep_count(W, tau)
+            s_prev = (s * (1 + 0.02 * rng.normal(size=s.shape))).astype(np.float32)
+            prev = np.zeros((B, kmax), np.int32)
+            for b, r in enumerate(expect(s_prev, vis_len, tau)):
+                prev[b, : len(r)] = r
+            cnts = np.array([len(w) for w in want], np.int32)
+            idx, cnt = run_topk(s, vis_len, tau, prev=(prev, cnts), kmax=kmax)
+            assert_same(idx, cnt, want, f"{kind} tau={tau} warm")
+            idx, cnt = run_topk(s, vis_len, tau, kmax=kmax)
+            assert_same(idx, cnt, want, f"{kind} tau={tau} cold")
+
+
+def test_score_rows_that_do_not_start_on_16_bytes():
+    """A view into a larger buffer: rows start 4 bytes past a 16-byte boundary (the kernel then
+    reads score by score), with and without a previous set."""
+    rng = np.random.default_rng(5)
+    B, W, tau = 2, 4096, 0.05
+    s = make_scores(rng, B, W, "softmax")
+    vis_len = [4096, 3000]
+    want = expect(s, vis_len, tau)
+    big = torch.zeros(B * W + 1, dtype=torch.float32, device=DEV)
+    sc = big[1:].view(B, W)
+    sc.copy_(torch.from_numpy(s))
+    assert sc.data_ptr() % 16 == 4
+    batch = fo.SeqBatch.from_lists([n + 3 for n in vis_len], [1] * B, vis_len, DEV)
+    batch.max_vis_len = W
+    batch.max_seq_len = W + 3
+    kmax = fo.keep_count(W, tau)
+    ws = torch.empty(256, dtype=torch.uint8, device=DEV)
+    idx = torch.full((B, kmax), -5, dtype=torch.int32, device=DEV)
+    cnt = torch.full((B,), -5, dtype=torch.int32, device=DEV)
+    fo.topk_fixation(sc, batch, tau, idx, cnt, ws)
+    assert_same(idx.cpu().numpy(), cnt.cpu().numpy(), want, "unaligned cold")
+    fo.topk_fixation(sc, batch, tau, idx, cnt, ws, idx, cnt)
+    assert_same(idx.cpu().numpy(), cnt.cpu().numpy(), want, "unaligned warm, in place")
