@@ -50,6 +50,10 @@ def parse_args():
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch the plain copy / read probe kernels of known size (1 GiB) three times "
                          "each, so that a profiler's byte counters can be scaled against them")
+    ap.add_argument("--one-query", action="store_true",
+                    help="every step uses the first step's queries (for hardware-counter passes, where each of the "
+                         "generator's several hundred small launches costs a large fraction of a second; the bytes "
+                         "a launch moves do not depend on the queries' values)")
     ap.add_argument("--step", choices=["three_step", "focal_layer"], default="three_step",
                     help="what one timed step is: the metric's three-step path (default), or a focal layer as "
                          "the controller runs it (dense output + scores from one pass over K and V, then top-k); "
@@ -193,8 +197,11 @@ def main():
     progress("caches generated")
     cs = fs.centres(bt, t_first + total)
     B, Hq, Hkv, d = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim
+    n_q = 1 if args.one_query else total
     qs = torch.stack([fs.queries_for_step(bts[i % L], t_first + i, [c[t_first + i - 1] for c in cs])
-                      for i in range(total)])
+                      for i in range(n_q)])
+    if args.one_query:
+        qs = qs.expand(total, *qs.shape[1:])
     progress("queries generated")
     seq_lens = torch.tensor([bt.seq_len(t_first + i) for i in range(total)], dtype=torch.int32, device=dev)
     vis_start = torch.tensor(bt.vis_start, dtype=torch.int32, device=dev)
@@ -321,7 +328,8 @@ def main():
                                "prefix, decode steps %d..%d, tau %g, warm-started top-k, steps rotate "
                                "over %d distinct caches"
                                % (wl.config_id, wl.name, B, Hq, Hkv, d, max_vis, bt.prefix[0], t_first + n_warm,
-                                  t_first + total - 1, tau, L)},
+                                  t_first + total - 1, tau, L)
+                               + (", every step with the first step's queries" if args.one_query else "")},
         "roofline": roofline,
         "sequence_layer_steps_per_s": round(value * B, 1),
     }
