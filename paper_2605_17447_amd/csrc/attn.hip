@@ -244,8 +244,7 @@ __global__ __launch_bounds__(64 * kWaves, 8 / kWaves) void attn_mfma_kernel(
         float mx = s[0];
 #pragma unroll
         for (int e = 1; e < 8; ++e) mx = fmaxf(mx, s[e]);
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        mx = rows_max(mx);
         const float m_new = fmaxf(m, mx);          // finite: every tile holds a valid position
         const float alpha = fast_exp2(m - m_new);
         float p[8], ps = 0.f;
@@ -341,8 +340,7 @@ __global__ __launch_bounds__(64 * kWaves, 8 / kWaves) void attn_mfma_kernel(
 tiles_done:
 
     // ---- cross-wave merge through LDS -----------------------------------------------------
-    zl += __shfl_xor(zl, 16);
-    zl += __shfl_xor(zl, 32);
+    zl = rows_sum(zl);
     float *buf = reinterpret_cast<float *>(smem[wave]);        // [16 heads][D dims]
 #pragma unroll
     for (int t = 0; t < NACC; ++t)

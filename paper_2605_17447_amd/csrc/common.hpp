@@ -125,6 +125,36 @@ __device__ __forceinline__ int wave_scan_incl(int x)
     return x;
 }
 
+// A lane's value together with that of the lane 16 (32) away, for commutative reductions: gfx950 swaps
+// rows of 16 lanes (halves of 32) between two registers in one VALU instruction, where a general
+// lane permute is a trip through the LDS crossbar.  Of the two results one is the lane's own value and
+// the other its partner's (which is which depends on the lane's row, and does not matter to op).
+template <typename Op>
+__device__ __forceinline__ float with_lane_xor16(float x, Op op)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    return op(__builtin_bit_cast(float, (uint32_t)r[0]), __builtin_bit_cast(float, (uint32_t)r[1]));
+}
+template <typename Op>
+__device__ __forceinline__ float with_lane_xor32(float x, Op op)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return op(__builtin_bit_cast(float, (uint32_t)r[0]), __builtin_bit_cast(float, (uint32_t)r[1]));
+}
+// max / sum over the lanes that differ in bits 4 and 5 of the lane number (the four rows of a wave)
+__device__ __forceinline__ float rows_max(float x)
+{
+    auto mx = [](float a, float b) { return fmaxf(a, b); };
+    return with_lane_xor32(with_lane_xor16(x, mx), mx);
+}
+__device__ __forceinline__ float rows_sum(float x)
+{
+    auto add = [](float a, float b) { return a + b; };
+    return with_lane_xor32(with_lane_xor16(x, add), add);
+}
+
 // exp2 with exp2(-inf) = 0 and no NaN for (-inf) - (-inf) handled by the callers
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 

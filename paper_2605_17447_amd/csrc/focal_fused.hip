@@ -263,8 +263,7 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
         }
         float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
         mx = fmaxf(mx, dpp_move<kDppRor8>(mx));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        mx = rows_max(mx);
         const float m_new = fmaxf(m, mx);
         if (__builtin_amdgcn_ballot_w64(m_new != m) != 0ull) {
             const float alpha = fast_exp2(m - m_new);
@@ -324,8 +323,7 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
 
     // ---- attention partial of this wave: O^T columns n and n + 8 are the same head's halves -----
     z += dpp_move<kDppRor8>(z);
-    z += __shfl_xor(z, 16);
-    z += __shfl_xor(z, 32);
+    z = rows_sum(z);
 #pragma unroll
     for (int t = 0; t < 8; ++t)
 #pragma unroll

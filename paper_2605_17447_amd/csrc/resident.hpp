@@ -42,6 +42,7 @@ __device__ __forceinline__ float dpp_move(float x)
 constexpr int kDppXor1 = 0xB1;          // quad_perm [1,0,3,2]
 constexpr int kDppXor2 = 0x4E;          // quad_perm [2,3,0,1]
 constexpr int kDppHalfMirror = 0x141;   // lane i <-> 7 - i within each 8 lanes
+constexpr int kDppRowMirror = 0x140;    // lane i <-> 15 - i within each 16 lanes
 constexpr int kDppRor8 = 0x128;         // lane i <- lane i ^ 8
 
 // ---- which (sequence, image-token range) a workgroup of a register-resident kernel works on ------

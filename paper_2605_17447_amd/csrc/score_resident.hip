@@ -311,11 +311,22 @@ img_done:
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the trailing refills must not land later
 
     // ---- range statistics: lanes -> waves -> workgroup -> workspace ------------------------------
+    // over the 16 lanes of a row (the tile's tokens li) with DPP moves -- pairs, quads, the mirrored half,
+    // the mirrored row: each step leaves both partners with the same bits -- then over the two rows that
+    // hold the same heads (lanes 32 apart) with a half swap
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-#pragma unroll
-        for (int o = 1; o < 16; o <<= 1) softmax_merge(m[r], z[r], __shfl_xor(m[r], o), __shfl_xor(z[r], o));
-        softmax_merge(m[r], z[r], __shfl_xor(m[r], 32), __shfl_xor(z[r], 32));
+        softmax_merge(m[r], z[r], dpp_move<kDppXor1>(m[r]), dpp_move<kDppXor1>(z[r]));
+        softmax_merge(m[r], z[r], dpp_move<kDppXor2>(m[r]), dpp_move<kDppXor2>(z[r]));
+        softmax_merge(m[r], z[r], dpp_move<kDppHalfMirror>(m[r]), dpp_move<kDppHalfMirror>(z[r]));
+        softmax_merge(m[r], z[r], dpp_move<kDppRowMirror>(m[r]), dpp_move<kDppRowMirror>(z[r]));
+        const uint32_t mu = __builtin_bit_cast(uint32_t, m[r]), zu = __builtin_bit_cast(uint32_t, z[r]);
+        const auto ms = __builtin_amdgcn_permlane32_swap(mu, mu, false, false);
+        const auto zs = __builtin_amdgcn_permlane32_swap(zu, zu, false, false);
+        // (element 0 and 1 hold the two halves' values, the same pair in both halves)
+        m[r] = __builtin_bit_cast(float, (uint32_t)ms[0]);
+        z[r] = __builtin_bit_cast(float, (uint32_t)zs[0]);
+        softmax_merge(m[r], z[r], __builtin_bit_cast(float, (uint32_t)ms[1]), __builtin_bit_cast(float, (uint32_t)zs[1]));
     }
     if (li == 0 && lg < 2) {
 #pragma unroll
