@@ -354,7 +354,7 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
     // every head's log-sum-exp from the ranges' statistics: wave w merges ranges w, w+8, ..
     {
         float M, Z;
-        const bool ok = resident_gather(stats, rng, nranges, Hq, G, Hkv, wpk, sm_m, sm_z, spin_ticks, M, Z);
+        const bool ok = resident_gather<4>(stats, rng, nranges, Hq, G, Hkv, wpk, sm_m, sm_z, spin_ticks, M, Z);
         if (!ok && lane_p == 0) {
             sm_met = 0;
             __hip_atomic_fetch_add(&g_fus_timeouts, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -27,6 +27,8 @@
 
 namespace fastocr {
 
+constexpr int kResGatherGroup = 8;      // ranges whose statistics a wave asks for at a time
+
 #define RES_DECLARE(J) f32x4 park_##J;
 // image tile J of the wave: multiply, keep the logits, refill the tile's LDS slot
 #define RES_STREAM_STEP(J)                                                                          \
@@ -337,6 +339,9 @@ img_done:
     unsigned long long *stats = g_res_stats[sync_slot] + (int64_t)wg0 * Hq;
     resident_publish(stats + (int64_t)rng * Hq, sm_m, sm_z, Hq, G, Hkv, wpk);
     if (threadIdx.x == 0) sm_met = 1;
+    // the other ranges' statistics are asked for right away: for the range that finishes last they are
+    // all there, and the round trip passes behind the exponentials below
+    const StatRows<kResGatherGroup> early = resident_gather_request<kResGatherGroup>(stats, rng, nranges, Hq);
     // while the words travel: the parked logits become probabilities relative to the wave's own
     // maxima (m[r] is wave-wide after the merge above); the sequence-wide factor follows below
     if (nimg > 0) {
@@ -348,7 +353,7 @@ pre_done:
     // ---- every head's log-sum-exp from the ranges' statistics: wave w merges ranges w, w+8, .. ------
     {
         float M, Z;
-        const bool ok = resident_gather(stats, rng, nranges, Hq, G, Hkv, wpk, sm_m, sm_z, spin_ticks, M, Z);
+        const bool ok = resident_gather<kResGatherGroup>(stats, rng, nranges, Hq, G, Hkv, wpk, sm_m, sm_z, spin_ticks, M, Z, &early);
         if (!ok && lane == 0) {
             sm_met = 0;
             __hip_atomic_fetch_add(&g_res_timeouts, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
