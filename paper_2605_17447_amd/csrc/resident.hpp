@@ -262,6 +262,88 @@ __device__ __forceinline__ bool resident_gather(const unsigned long long *stats,
     return true;
 }
 
+// The same for a wave that needs the sequence-wide statistics of ITS OWN group of heads only (kv head
+// kvh: heads kvh*G .. kvh*G+G-1), which is all a wave needs to finish its own logits: no exchange
+// between the workgroup's waves, no barrier.  Lane 8s + x looks after head x of the group in the
+// ranges s, s + 8, s + 16, ..; the eight partial results per head are then combined with lane moves,
+// and every lane with the same x ends up with the same (max, sum-exp).  GROUP words per lane are in
+// flight at a time; resident_heads_request sends the first group without waiting.
+template <int GROUP>
+__device__ __forceinline__ StatRows<GROUP> resident_heads_request(const unsigned long long *stats, int rng, int nranges, int Hq,
+                                                                  int G, int kvh, int i0 = 0)
+{
+    const int lane = threadIdx.x & 63, x = lane & 7, s = lane >> 3;
+    StatRows<GROUP> rows;
+#pragma unroll
+    for (int j = 0; j < GROUP; ++j) {
+        const int rr = s + 8 * (i0 + j);
+        rows.mz[j] = 1ull;                                       // nothing to read: counts as there
+        if (rr < nranges && rr != rng && x < G)
+            rows.mz[j] = __hip_atomic_load(stats + (int64_t)rr * Hq + kvh * G + x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    return rows;
+}
+
+template <int GROUP>
+__device__ __forceinline__ bool resident_heads_gather(const unsigned long long *stats, int rng, int nranges, int Hq, int G,
+                                                      int Hkv, int wpk, int kvh, const float (*sm_m)[8], const float (*sm_z)[8],
+                                                      long long spin_ticks, float &M, float &Z, const StatRows<GROUP> *first = nullptr)
+{
+    const int lane = threadIdx.x & 63, x = lane & 7, s = lane >> 3;
+    M = kMinusHuge;
+    Z = 0.f;
+    const long long t_start = wall_clock64();
+    const int rounds = (nranges + 7) / 8;
+    for (int i0 = 0; i0 < rounds; i0 += GROUP) {
+        StatRows<GROUP> rows = (first != nullptr && i0 == 0) ? *first : resident_heads_request<GROUP>(stats, rng, nranges, Hq, G, kvh, i0);
+        while (true) {
+            bool missing = false;
+#pragma unroll
+            for (int j = 0; j < GROUP; ++j) missing = missing || rows.mz[j] == 0ull;
+            if (__builtin_amdgcn_ballot_w64(missing) == 0ull) break;
+            __builtin_amdgcn_s_sleep(1);
+            if (wall_clock64() - t_start > spin_ticks) return false;
+#pragma unroll
+            for (int j = 0; j < GROUP; ++j) {
+                const int rr = s + 8 * (i0 + j);
+                if (rows.mz[j] == 0ull)                          // (zero only where this lane has something to read)
+                    rows.mz[j] = __hip_atomic_load(stats + (int64_t)rr * Hq + kvh * G + x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < GROUP; ++j) {
+            const int rr = s + 8 * (i0 + j);
+            if (rr >= nranges || x >= G) continue;
+            if (rr == rng) {
+                float Mo, Zo;
+                resident_own_stats(sm_m, sm_z, kvh * G + x, G, Hkv, wpk, Mo, Zo);
+                softmax_merge(M, Z, Mo, Zo);
+            } else {
+                softmax_merge(M, Z, __uint_as_float((uint32_t)rows.mz[j]), __uint_as_float((uint32_t)(rows.mz[j] >> 32)));
+            }
+        }
+    }
+    // the eight lanes of a head (8 apart): the other half of the row, the next row, the other half of the wave
+    softmax_merge(M, Z, dpp_move<kDppRor8>(M), dpp_move<kDppRor8>(Z));
+    {
+        const uint32_t mu = __builtin_bit_cast(uint32_t, M), zu = __builtin_bit_cast(uint32_t, Z);
+        const auto ms = __builtin_amdgcn_permlane16_swap(mu, mu, false, false);
+        const auto zs = __builtin_amdgcn_permlane16_swap(zu, zu, false, false);
+        M = __builtin_bit_cast(float, (uint32_t)ms[0]);
+        Z = __builtin_bit_cast(float, (uint32_t)zs[0]);
+        softmax_merge(M, Z, __builtin_bit_cast(float, (uint32_t)ms[1]), __builtin_bit_cast(float, (uint32_t)zs[1]));
+    }
+    {
+        const uint32_t mu = __builtin_bit_cast(uint32_t, M), zu = __builtin_bit_cast(uint32_t, Z);
+        const auto ms = __builtin_amdgcn_permlane32_swap(mu, mu, false, false);
+        const auto zs = __builtin_amdgcn_permlane32_swap(zu, zu, false, false);
+        M = __builtin_bit_cast(float, (uint32_t)ms[0]);
+        Z = __builtin_bit_cast(float, (uint32_t)zs[0]);
+        softmax_merge(M, Z, __builtin_bit_cast(float, (uint32_t)ms[1]), __builtin_bit_cast(float, (uint32_t)zs[1]));
+    }
+    return true;
+}
+
 // Called by every thread when the workgroup is done reading (after a __syncthreads): `last` says
 // whether this range was the sequence's last to finish reading; it then clears the sequence's words
 // and the count.

@@ -12,14 +12,17 @@
 //     per lane, two 8 KB slots per wave, no staging registers); the XOR swizzle that makes the
 //     MFMA operand reads conflict-free is applied by permuting which 16-byte chunk of a row each
 //     lane fetches;
-//   - C[head][token] = Q * K^T with v_mfma_f32_16x16x32_bf16 leaves 4 heads x 1 token per lane; those
-//     4 logits stay in 4 VGPRs named for the tile -- the image-tile loop is fully unrolled for
-//     that (up to 32 tiles = 128 VGPRs per lane); text tokens only feed the softmax statistics;
-//   - the ranges of one sequence exchange their per-head (max, sum-exp) through static device
+//   - C[head][token] = Q * K^T with v_mfma_f32_16x16x32_bf16 leaves 4 heads x 1 token per lane; each
+//     logit becomes its softmax weight 2^(logit - ref) at once, relative to a reference that the lane
+//     fixed with its first live logit (as accurate as relative to the true maximum for any exponent
+//     in range), and the 4 weights stay in 4 VGPRs named for the tile -- the image-tile loop is fully
+//     unrolled for that (up to 32 tiles = 128 VGPRs per lane); text tokens only feed the sums;
+//   - the ranges of one sequence exchange their per-head (reference, sum) through static device
 //     memory: each range publishes one self-validating 64-bit word per head (agent-scope atomic
-//     store; zero = not there yet) and polls for the others' (bounded spin, no counter, no fence);
-//   - every wave then turns its parked logits into probabilities, the heads of a token are
-//     summed through LDS and the finished scores are written -- the only HBM writes.
+//     store; zero = not there yet) and every wave polls for the other ranges' words of its own heads
+//     (bounded spin, no counter, no fence), asking for them the moment its stream ends;
+//   - every wave then scales its parked weights to the sequence's normalisers, the heads of a token
+//     are summed through LDS and the finished scores are written -- the only HBM writes.
 // Shapes that do not fit (group size > 8, Hkv not dividing 8, more sequences than compute
 // units, more than 32 tiles per wave, pages shorter than a tile) take the two-kernel path.
 #include "kernels.hpp"
@@ -29,22 +32,21 @@ namespace fastocr {
 
 constexpr int kResGatherGroup = 8;      // ranges whose statistics a wave asks for at a time
 
-#define RES_DECLARE(J) f32x4 park_##J;
-// image tile J of the wave: multiply, keep the logits, refill the tile's LDS slot
+#define RES_DECLARE(J) f32x4 park_##J = f32x4{0.f, 0.f, 0.f, 0.f};
+// image tile J of the wave: multiply, keep the weights, refill the tile's LDS slot
 #define RES_STREAM_STEP(J)                                                                          \
     {                                                                                               \
         wait_and_read(ntext + (J), kb);                                                             \
         issue_img((J) + 2, ntext + (J));                                                            \
-        park_##J = logits_of(kb, img_first(J) + tok_in_tile < r1);                                  \
+        park_##J = weights_of(kb, img_first(J) + tok_in_tile < r1);                                  \
         if ((J) + 1 >= nimg) goto img_done;                                                         \
     }
-// tile J while the statistics travel: logits -> probabilities relative to the wave's own maximum
-#define RES_PREEXP_STEP(J)                                                                          \
+// tile J when a lane moves its reference (see weights_of): the weights kept so far follow
+#define RES_RESCALE_STEP(J)                                                                         \
     {                                                                                               \
-        _Pragma("unroll") for (int r = 0; r < 4; ++r) park_##J[r] = fast_exp2(park_##J[r] - m[r]);  \
-        if ((J) + 1 >= nimg) goto pre_done;                                                         \
+        _Pragma("unroll") for (int r = 0; r < 4; ++r) park_##J[r] *= alpha[r];                      \
     }
-// tile J after the exchange: rescaled to the sequence's normalisers, this lane's 4 heads summed;
+// tile J after the exchange: from the lane's reference to the sequence's normalisers, this lane's 4 heads summed;
 // the partner lane's 4 heads of the same token go to a row of their own (a cross-lane move per
 // tile would cost more than the second row does in the final sum)
 #define RES_FINISH_STEP(J)                                                                          \
@@ -114,8 +116,6 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
     static_assert(sizeof(unsigned char[kResWaves][2][8192]) >= (size_t)kSelLdsBytes, "the select reuses the tile buffers");
     __shared__ __align__(16) unsigned char smem[kResWaves][2][8192];
     __shared__ float sm_m[kResWaves][8], sm_z[kResWaves][8];
-    __shared__ float sm_lse[kResMaxHq];
-    __shared__ float sm_pm[kResWaves][64], sm_pz[kResWaves][64];
     __shared__ float sm_red[kResWaves];
     __shared__ int sm_met, sm_last;
 
@@ -238,9 +238,16 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
 
     const int hbase = 4 * (lg & 1);
     const int tok_in_tile = li + 16 * (lg >> 1);
-    float m[4], z[4];
+    // Softmax weights are kept relative to a reference per lane and head that is fixed by the lane's
+    // first live logit: 2^(logit - ref) is as accurate for any exponent in range as it is relative to
+    // the true maximum, so neither a running maximum nor a second pass of exponentials is needed, and
+    // what is parked in the registers is the weight itself.  A logit more than 2^64 above the reference
+    // (not seen on real logits, but no input may break the result) moves the reference there and
+    // rescales what the lane holds.
+    float ref[4], z[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) { m[r] = kMinusHuge; z[r] = 0.f; }
+    for (int r = 0; r < 4; ++r) { ref[r] = kMinusHuge; z[r] = 0.f; }
+    RES_EACH_TILE(RES_DECLARE)
 
     // LDS byte addresses of this lane's four B-operand chunks (rows li and 16 + li of slot 0)
     uint32_t rd_addr[4];
@@ -270,8 +277,9 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
             : "v"(rd_addr[0] + so), "v"(rd_addr[1] + so), "v"(rd_addr[2] + so), "v"(rd_addr[3] + so)
             : "memory");
     };
-    // logits (log2 domain) of this lane's token for its 4 heads; dead positions come out -inf
-    auto logits_of = [&](u32x4(&kb)[8], bool live) -> f32x4 {
+    // weights 2^(logit - ref) of this lane's token for its 4 heads (logits in the log2 domain); dead
+    // positions come out 0
+    auto weights_of = [&](u32x4(&kb)[8], bool live) -> f32x4 {
         f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
@@ -281,12 +289,28 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
         for (int kk = 0; kk < 4; ++kk)
             s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qhi[kk]),
                                                         __builtin_bit_cast(bf16x8, kb[4 + kk]), s, 0, 0, 0);
+        bool moved = false;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             s[r] = live ? s[r] * scale_log2 : -INFINITY;
-            const float mn = fmaxf(m[r], s[r]);
-            z[r] = z[r] * fast_exp2(m[r] - mn) + fast_exp2(s[r] - mn);
-            m[r] = mn;
+            if (ref[r] == kMinusHuge) ref[r] = fmaxf(s[r], kMinusHuge);          // the first live logit
+            moved = moved || s[r] - ref[r] > 64.f;
+        }
+        if (__builtin_amdgcn_ballot_w64(moved) != 0ull) {
+            float alpha[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const bool mv = s[r] - ref[r] > 64.f;
+                alpha[r] = mv ? fast_exp2(ref[r] - s[r]) : 1.f;
+                ref[r] = mv ? s[r] : ref[r];
+                z[r] *= alpha[r];
+            }
+            RES_EACH_TILE(RES_RESCALE_STEP)
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            s[r] = fast_exp2(s[r] - ref[r]);
+            z[r] += s[r];
         }
         return s;
     };
@@ -294,7 +318,6 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
     // ---- stream: text tiles (statistics only), then image tiles (logits parked in registers) -----
     // The wave's tiles are numbered 0 .. ntext + nimg - 1 in that order; tile n uses slot n & 1 and
     // two tiles are always in flight.
-    RES_EACH_TILE(RES_DECLARE)
     u32x4 kb[8];
     if (ntext + nimg > 0) {
         // the first two tiles
@@ -303,7 +326,7 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
         for (int x = 0; x < ntext; ++x) {
             wait_and_read(x, kb);
             if (x + 2 < ntext || nimg == 0) issue_text(x + 2, x); else issue_img(x + 2 - ntext, x);
-            (void)logits_of(kb, text_first(x) + tok_in_tile < Tn);
+            (void)weights_of(kb, text_first(x) + tok_in_tile < Tn);
         }
     }
     if (nimg > 0) {
@@ -312,57 +335,58 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
 img_done:
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the trailing refills must not land later
 
+    // The other ranges' statistics of this wave's heads are asked for at once: with the chip's memory
+    // queues full of other workgroups' streams a load takes microseconds to come back, and for the
+    // ranges that finish late everybody else's words are there already -- the answer then arrives
+    // while this range reduces and publishes its own.
+    unsigned long long *stats = g_res_stats[sync_slot] + (int64_t)wg0 * Hq;
+    const StatRows<kResGatherGroup> early = resident_heads_request<kResGatherGroup>(stats, rng, nranges, Hq, G, kvh);
+
     // ---- range statistics: lanes -> waves -> workgroup -> workspace ------------------------------
     // over the 16 lanes of a row (the tile's tokens li) with DPP moves -- pairs, quads, the mirrored half,
-    // the mirrored row: each step leaves both partners with the same bits -- then over the two rows that
-    // hold the same heads (lanes 32 apart) with a half swap
+    // the mirrored row -- then over the two rows that hold the same heads (lanes 32 apart) with a half
+    // swap: first the largest reference, then the sums brought to it
+    float m[4];           // the wave's common reference per head
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        softmax_merge(m[r], z[r], dpp_move<kDppXor1>(m[r]), dpp_move<kDppXor1>(z[r]));
-        softmax_merge(m[r], z[r], dpp_move<kDppXor2>(m[r]), dpp_move<kDppXor2>(z[r]));
-        softmax_merge(m[r], z[r], dpp_move<kDppHalfMirror>(m[r]), dpp_move<kDppHalfMirror>(z[r]));
-        softmax_merge(m[r], z[r], dpp_move<kDppRowMirror>(m[r]), dpp_move<kDppRowMirror>(z[r]));
-        const uint32_t mu = __builtin_bit_cast(uint32_t, m[r]), zu = __builtin_bit_cast(uint32_t, z[r]);
-        const auto ms = __builtin_amdgcn_permlane32_swap(mu, mu, false, false);
-        const auto zs = __builtin_amdgcn_permlane32_swap(zu, zu, false, false);
-        // (element 0 and 1 hold the two halves' values, the same pair in both halves)
-        m[r] = __builtin_bit_cast(float, (uint32_t)ms[0]);
-        z[r] = __builtin_bit_cast(float, (uint32_t)zs[0]);
-        softmax_merge(m[r], z[r], __builtin_bit_cast(float, (uint32_t)ms[1]), __builtin_bit_cast(float, (uint32_t)zs[1]));
+        float M = ref[r];
+        M = fmaxf(M, dpp_move<kDppXor1>(M));
+        M = fmaxf(M, dpp_move<kDppXor2>(M));
+        M = fmaxf(M, dpp_move<kDppHalfMirror>(M));
+        M = fmaxf(M, dpp_move<kDppRowMirror>(M));
+        M = with_lane_xor32(M, [](float a, float b) { return fmaxf(a, b); });
+        float Z = z[r] * fast_exp2(ref[r] - M);
+        Z += dpp_move<kDppXor1>(Z);
+        Z += dpp_move<kDppXor2>(Z);
+        Z += dpp_move<kDppHalfMirror>(Z);
+        Z += dpp_move<kDppRowMirror>(Z);
+        Z = with_lane_xor32(Z, [](float a, float b) { return a + b; });
+        m[r] = M;
+        z[r] = Z;
     }
     if (li == 0 && lg < 2) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) { sm_m[wave][hbase + r] = m[r]; sm_z[wave][hbase + r] = z[r]; }
     }
+    if (threadIdx.x == 0) sm_met = 1;
     __syncthreads();
     // publish this range's statistics (resident.hpp: every word is its own "ready" flag)
-    unsigned long long *stats = g_res_stats[sync_slot] + (int64_t)wg0 * Hq;
     resident_publish(stats + (int64_t)rng * Hq, sm_m, sm_z, Hq, G, Hkv, wpk);
-    if (threadIdx.x == 0) sm_met = 1;
-    // the other ranges' statistics are asked for right away: for the range that finishes last they are
-    // all there, and the round trip passes behind the exponentials below
-    const StatRows<kResGatherGroup> early = resident_gather_request<kResGatherGroup>(stats, rng, nranges, Hq);
-    // while the words travel: the parked logits become probabilities relative to the wave's own
-    // maxima (m[r] is wave-wide after the merge above); the sequence-wide factor follows below
-    if (nimg > 0) {
-        RES_EACH_TILE(RES_PREEXP_STEP)
-    }
-pre_done:
-    __syncthreads();
 
-    // ---- every head's log-sum-exp from the ranges' statistics: wave w merges ranges w, w+8, .. ------
+    // ---- the log-sum-exp of this wave's heads over the whole sequence (lane 8s + x: head x of the group) ----
+    float l2;
     {
         float M, Z;
-        const bool ok = resident_gather<kResGatherGroup>(stats, rng, nranges, Hq, G, Hkv, wpk, sm_m, sm_z, spin_ticks, M, Z, &early);
+        const bool ok = resident_heads_gather<kResGatherGroup>(stats, rng, nranges, Hq, G, Hkv, wpk, kvh, sm_m, sm_z, spin_ticks,
+                                                               M, Z, &early);
         if (!ok && lane == 0) {
             sm_met = 0;
             __hip_atomic_fetch_add(&g_res_timeouts, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (gave_up_flag) __hip_atomic_store(gave_up_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
-        sm_pm[wave][lane] = M;
-        sm_pz[wave][lane] = Z;
+        l2 = Z > 0.f ? M + log2f(Z) : -INFINITY;
     }
-    __syncthreads();
+    __syncthreads();      // whether every wave has met its ranges; the tile buffers are free for the head sums
     // This range is done reading: count it out.  The last one of the sequence (it has seen every
     // other one finish reading) clears the sequence's words and the count when the kernel ends.
     uint32_t *left = &g_res_left[sync_slot][b];
@@ -383,21 +407,16 @@ pre_done:
         leave();
         return;
     }
-    if ((int)threadIdx.x < Hq) {
-        const int h = threadIdx.x;
-        float M = kMinusHuge, Z = 0.f;
-#pragma unroll
-        for (int w = 0; w < kResWaves; ++w) softmax_merge(M, Z, sm_pm[w][h], sm_pz[w][h]);
-        const float l2 = Z > 0.f ? M + log2f(Z) : -INFINITY;
-        sm_lse[h] = l2;
-        if (lse_out && rng == 0) lse_out[(int64_t)b * Hq + h] = l2 * kLn2;
-    }
-    __syncthreads();
+    if (lse_out && rng == 0 && sub == 0 && lane < G) lse_out[(int64_t)b * Hq + kvh * G + lane] = l2 * kLn2;
 
     // ---- probabilities of the parked logits, summed over the heads of each token ---------------
-    float cf[4];          // from "relative to the wave's maximum" to "relative to the head's normaliser"
+    float cf[4];          // from "relative to the lane's reference" to "relative to the head's normaliser"
 #pragma unroll
-    for (int r = 0; r < 4; ++r) cf[r] = (hbase + r < G) ? fast_exp2(m[r] - sm_lse[kvh * G + hbase + r]) : 0.f;
+    for (int r = 0; r < 4; ++r) {
+        const float la = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, l2), r));
+        const float lb = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, l2), 4 + r));
+        cf[r] = (hbase + r < G) ? fast_exp2(ref[r] - (hbase ? lb : la)) : 0.f;
+    }
     float *red = reinterpret_cast<float *>(&smem[0][0][0]);          // [2 Hkv][R], at most 64 KB
     if (nimg > 0) {
         RES_EACH_TILE(RES_FINISH_STEP)
