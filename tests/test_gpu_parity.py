@@ -721,3 +721,30 @@ def test_kernel_timer_records_every_nth_launch():
     finally:
         fb.set_tuning("timer_every", 1)
         fb.kernel_timer_enable(kid, 0)
+
+
+def test_logits_far_above_a_lane_s_first_one_move_its_reference():
+    """The register-resident kernels keep softmax weights relative to each lane's first live logit.
+    Here the text tokens and most image tokens sit near logit -80 and scattered image tokens near
+    +12: 133 octaves apart, more than an fp32 exponent holds, so the result is only right if the
+    kernel moves a lane's reference (it does beyond 64 octaves) and rescales what the lane holds.
+    A second sequence runs the other way round, and one head sees zeros."""
+    torch.manual_seed(11)
+    B, Hq, Hkv, d, N, P, T = 2, 8, 2, 128, 3000, 70, 9
+    S = P + N + T
+    scale = float(np.float32(d ** -0.5))
+    q = torch.ones((B, Hq, d), dtype=torch.float32)
+    q[:, 3] = 0.0                                        # a head whose logits are all zero
+    q[:, 5] *= 0.5
+    lvl = torch.full((B, S), -80.0)
+    lvl[0, P + 37: P + N: 53] = 12.0                     # rare high logits, first met deep into the stream
+    lvl[0, P + 2000:P + 2040] = 10.0
+    lvl[1] = 11.0
+    lvl[1, P + 100: P + N: 7] = -80.0
+    lvl[1, :P] = -78.0
+    k = (lvl / (scale * d))[:, None, :, None].expand(B, Hkv, S, d).clone()
+    k = k + 0.002 * torch.randn(B, Hkv, S, d)
+    v = torch.randn(B, Hkv, S, d)
+    p = GpuProblem(k.to(torch.bfloat16).to(DEV), v.to(torch.bfloat16).to(DEV), q.to(torch.bfloat16).to(DEV),
+                   [S, S - 4], [P, P], [N, N - 4], scale)
+    full_check(p, 0.05, "moving reference", exact_topk=True)
