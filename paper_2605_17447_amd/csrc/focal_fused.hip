@@ -55,8 +55,6 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
     static_assert(sizeof(unsigned char[kResWaves][2][8192]) >= (size_t)kSelLdsBytes, "the select reuses the tile buffers");
     __shared__ __align__(16) unsigned char smem[kResWaves][2][8192];      // [wave][K, V]
     __shared__ float sm_m[kResWaves][8], sm_z[kResWaves][8];
-    __shared__ float sm_lse[kResMaxHq];
-    __shared__ float sm_pm[kResWaves][64], sm_pz[kResWaves][64];
     __shared__ float sm_red[kResWaves];
     __shared__ int sm_met, sm_last;
 
@@ -344,26 +342,28 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
             sm_z[wave][li_p] = z;
         }
     }
+    if (threadIdx.x == 0) sm_met = 1;
     __syncthreads();
 
     // ---- range statistics: published as self-validating words, gathered by polling (resident.hpp) ----
+    // (Asking for the other ranges' words before the partial is written, as the scoring kernel does at the
+    // end of its stream, gains 0.4 us at the largest shapes and loses 2 us at the small ones, where the
+    // ranges end together, the first answer comes back incomplete and a second round trip follows.)
     unsigned long long *stats = g_fus_stats[sync_slot] + (int64_t)wg0 * Hq;
     resident_publish(stats + (int64_t)rng * Hq, sm_m, sm_z, Hq, G, Hkv, wpk);
-    if (threadIdx.x == 0) sm_met = 1;
-    __syncthreads();
-    // every head's log-sum-exp from the ranges' statistics: wave w merges ranges w, w+8, ..
+    // the log-sum-exp of this wave's heads over the whole sequence (lane 8s + x: head x of the group)
+    float lh;
     {
         float M, Z;
-        const bool ok = resident_gather<4>(stats, rng, nranges, Hq, G, Hkv, wpk, sm_m, sm_z, spin_ticks, M, Z);
+        const bool ok = resident_heads_gather<4>(stats, rng, nranges, Hq, G, Hkv, wpk, kvh, sm_m, sm_z, spin_ticks, M, Z);
         if (!ok && lane_p == 0) {
             sm_met = 0;
             __hip_atomic_fetch_add(&g_fus_timeouts, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (gave_up_flag) __hip_atomic_store(gave_up_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
-        sm_pm[wave][lane_p] = M;
-        sm_pz[wave][lane_p] = Z;
+        lh = (hcol_p < G && Z > 0.f) ? M + log2f(Z) : (hcol_p < G ? -INFINITY : INFINITY);
     }
-    __syncthreads();
+    __syncthreads();      // whether every wave has met its ranges
     // This range is done reading: count it out.  The last one of the sequence clears the
     // sequence's words and the count when the kernel ends.
     uint32_t *left = &g_fus_left[sync_slot][b];
@@ -383,19 +383,9 @@ __global__ __launch_bounds__(kResThreads) void focal_fused_kernel(
         leave();
         return;
     }
-    if ((int)threadIdx.x < Hq) {
-        const int h = threadIdx.x;
-        float M = kMinusHuge, Z = 0.f;
-#pragma unroll
-        for (int w = 0; w < kResWaves; ++w) softmax_merge(M, Z, sm_pm[w][h], sm_pz[w][h]);
-        const float l2 = Z > 0.f ? M + log2f(Z) : -INFINITY;
-        sm_lse[h] = l2;
-        if (lse_out && rng == 0) lse_out[(int64_t)b * Hq + h] = l2 * kLn2;
-    }
-    __syncthreads();
+    if (lse_out && rng == 0 && sub == 0 && lane_p < G) lse_out[(int64_t)b * Hq + kvh * G + lane_p] = lh * kLn2;
 
     // ---- probabilities of the parked logits, summed over the heads of each token ---------------
-    const float lh = hcol_p < G ? sm_lse[kvh * G + hcol_p] : INFINITY;
     float *red = reinterpret_cast<float *>(&smem[0][0][0]);          // [Hkv][R], at most 32 KB
     for (int J = 0; J < nimg; ++J) {
         // this lane_p's 4 tokens of tile J, one head each on 8 neighbouring lanes
