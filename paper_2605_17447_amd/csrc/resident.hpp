@@ -187,87 +187,21 @@ __device__ __forceinline__ void resident_publish(unsigned long long *row, const 
     }
 }
 
-// Called by every wave: wave w merges ranges w, w+8, .. of the sequence; lane = head.  The rows of GROUP
-// ranges are requested together and polled until every word is there (one memory round trip per
-// attempt; a row that is complete is not asked for again by the next group).  Only rows that are
-// still missing are polled, by the one wave of each workgroup that looks after them: a few hundred
-// bytes per attempt, served by the memory-side cache, next to nothing against the ranges still
-// streaming.  resident_gather_request sends the first attempt for the first group without waiting, so
-// that its round trip can pass behind other work; resident_gather takes its answer as the first
-// attempt.  The workgroup's own statistics never leave the chip.  Returns false when a word did not
-// appear within spin_ticks of the 100 MHz wall clock.
+// Gathering the statistics: a wave needs the sequence-wide (reference, sum) of ITS OWN group of heads
+// only (kv head kvh: heads kvh*G .. kvh*G+G-1), which is all it takes to finish its own weights: no
+// exchange between the workgroup's waves, no barrier.  Lane 8s + x looks after head x of the group
+// in the ranges s, s + 8, s + 16, ..; the eight partial results per head are then combined with lane
+// moves, and every lane with the same x ends up with the same pair.  GROUP words per lane are
+// requested together and polled until every one is there (one memory round trip per attempt; only
+// what is still missing is asked for again: a few hundred bytes per attempt, served by the
+// memory-side cache, next to nothing against the ranges still streaming).  resident_heads_request
+// sends the first attempt for the first group without waiting, so that its round trip can pass
+// behind other work; resident_heads_gather takes its answer as the first attempt.  The workgroup's
+// own statistics never leave the chip.  Returns false when a word did not appear within spin_ticks
+// of the 100 MHz wall clock.
 template <int GROUP>
 struct StatRows { unsigned long long mz[GROUP]; };
 
-template <int GROUP>
-__device__ __forceinline__ StatRows<GROUP> resident_gather_request(const unsigned long long *stats, int rng, int nranges, int Hq,
-                                                                   int x0 = 0)
-{
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int nmine = nranges > wave ? (nranges - wave + kResWaves - 1) / kResWaves : 0;
-    StatRows<GROUP> rows;
-#pragma unroll
-    for (int j = 0; j < GROUP; ++j) {
-        const int rr = wave + kResWaves * (x0 + j);
-        rows.mz[j] = 1ull;                                       // not this wave's to read: counts as there
-        if (x0 + j < nmine && rr != rng && lane < Hq)
-            rows.mz[j] = __hip_atomic_load(stats + (int64_t)rr * Hq + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    return rows;
-}
-
-template <int GROUP>
-__device__ __forceinline__ bool resident_gather(const unsigned long long *stats, int rng, int nranges, int Hq, int G,
-                                                int Hkv, int wpk, const float (*sm_m)[8], const float (*sm_z)[8],
-                                                long long spin_ticks, float &M, float &Z, const StatRows<GROUP> *first = nullptr)
-{
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    M = kMinusHuge;
-    Z = 0.f;
-    const long long t_start = wall_clock64();
-    // ranges of this wave: wave + 8 x, x = 0 .. nmine-1 (nmine <= 32 as nranges <= 256)
-    const int nmine = nranges > wave ? (nranges - wave + kResWaves - 1) / kResWaves : 0;
-    for (int x0 = 0; x0 < nmine; x0 += GROUP) {
-        StatRows<GROUP> rows = (first != nullptr && x0 == 0) ? *first : resident_gather_request<GROUP>(stats, rng, nranges, Hq, x0);
-        while (true) {
-            bool missing = false;
-#pragma unroll
-            for (int j = 0; j < GROUP; ++j) missing = missing || rows.mz[j] == 0ull;
-            if (__builtin_amdgcn_ballot_w64(missing) == 0ull) break;
-            __builtin_amdgcn_s_sleep(1);
-            if (wall_clock64() - t_start > spin_ticks) return false;
-            // ask again for what is missing only
-#pragma unroll
-            for (int j = 0; j < GROUP; ++j) {
-                const int rr = wave + kResWaves * (x0 + j);
-                if (__builtin_amdgcn_ballot_w64(rows.mz[j] == 0ull) != 0ull && lane < Hq)
-                    rows.mz[j] = __hip_atomic_load(stats + (int64_t)rr * Hq + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < GROUP; ++j) {
-            const int rr = wave + kResWaves * (x0 + j);
-            if (x0 + j >= nmine || lane >= Hq) continue;
-            if (rr == rng) {
-                float Mo, Zo;
-                resident_own_stats(sm_m, sm_z, lane, G, Hkv, wpk, Mo, Zo);
-                softmax_merge(M, Z, Mo, Zo);
-            } else {
-                softmax_merge(M, Z, __uint_as_float((uint32_t)rows.mz[j]), __uint_as_float((uint32_t)(rows.mz[j] >> 32)));
-            }
-        }
-    }
-    return true;
-}
-
-// The same for a wave that needs the sequence-wide statistics of ITS OWN group of heads only (kv head
-// kvh: heads kvh*G .. kvh*G+G-1), which is all a wave needs to finish its own logits: no exchange
-// between the workgroup's waves, no barrier.  Lane 8s + x looks after head x of the group in the
-// ranges s, s + 8, s + 16, ..; the eight partial results per head are then combined with lane moves,
-// and every lane with the same x ends up with the same (max, sum-exp).  GROUP words per lane are in
-// flight at a time; resident_heads_request sends the first group without waiting.
 template <int GROUP>
 __device__ __forceinline__ StatRows<GROUP> resident_heads_request(const unsigned long long *stats, int rng, int nranges, int Hq,
                                                                   int G, int kvh, int i0 = 0)
