@@ -50,10 +50,13 @@ def parse_args():
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch the plain copy / read probe kernels of known size (1 GiB) three times "
                          "each, so that a profiler's byte counters can be scaled against them")
-    ap.add_argument("--one-query", action="store_true",
-                    help="every step uses the first step's queries (for hardware-counter passes, where each of the "
-                         "generator's several hundred small launches costs a large fraction of a second; the bytes "
-                         "a launch moves do not depend on the queries' values)")
+    ap.add_argument("--counter-pass", action="store_true",
+                    help="inputs for hardware-counter passes: the caches are filled by one random-normal launch each "
+                         "(the same distribution as the seeded generator's, which takes thousands of small launches: "
+                         "under the counter collection on this pool such runs have stalled before reaching the "
+                         "library's kernels) and every step uses one set of queries drawn on the host; shapes, "
+                         "dtypes and launch configurations are unchanged, and the bytes a launch moves do not "
+                         "depend on the values")
     ap.add_argument("--step", choices=["three_step", "focal_layer"], default="three_step",
                     help="what one timed step is: the metric's three-step path (default), or a focal layer as "
                          "the controller runs it (dense output + scores from one pass over K and V, then top-k); "
@@ -192,16 +195,20 @@ def main():
 
     # ---- inputs (resident before timing) ---------------------------------------------------
     L = max(1, args.layers)
-    bts = [fs.make_batch(wl, device=dev, layer=l) for l in range(L)]
+    bts = [fs.make_batch(wl, device=dev, layer=l, plain_fill=args.counter_pass) for l in range(L)]
     bt = bts[0]
     progress("caches generated")
     cs = fs.centres(bt, t_first + total)
+    progress("fixation centres generated")
     B, Hq, Hkv, d = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim
-    n_q = 1 if args.one_query else total
-    qs = torch.stack([fs.queries_for_step(bts[i % L], t_first + i, [c[t_first + i - 1] for c in cs])
-                      for i in range(n_q)])
-    if args.one_query:
-        qs = qs.expand(total, *qs.shape[1:])
+    if args.counter_pass:
+        # drawn on the host and copied: no generator launch runs under the counter collection
+        gen = torch.Generator().manual_seed(fs.BASE_SEED)
+        q1 = torch.randn((B, Hq, d), generator=gen, dtype=torch.float32).to(wl.torch_dtype).to(dev)
+        qs = q1.unsqueeze(0).expand(total, B, Hq, d)
+    else:
+        qs = torch.stack([fs.queries_for_step(bts[i % L], t_first + i, [c[t_first + i - 1] for c in cs])
+                          for i in range(total)])
     progress("queries generated")
     seq_lens = torch.tensor([bt.seq_len(t_first + i) for i in range(total)], dtype=torch.int32, device=dev)
     vis_start = torch.tensor(bt.vis_start, dtype=torch.int32, device=dev)
@@ -329,7 +336,8 @@ def main():
                                "over %d distinct caches"
                                % (wl.config_id, wl.name, B, Hq, Hkv, d, max_vis, bt.prefix[0], t_first + n_warm,
                                   t_first + total - 1, tau, L)
-                               + (", every step with the first step's queries" if args.one_query else "")},
+                               + (", caches filled by plain random-normal launches and one set of host-drawn queries for every step "
+                                  "(counter pass)" if args.counter_pass else "")},
         "roofline": roofline,
         "sequence_layer_steps_per_s": round(value * B, 1),
     }

@@ -134,8 +134,13 @@ def _row_ids(layer: int, n_kv_heads: int, tokens: torch.Tensor) -> torch.Tensor:
 
 
 def make_batch(wl: Workload, seed: int = BASE_SEED, device="cpu", layer: int = 0,
-               chunk_tokens: int = 8192) -> Batch:
-    """Generate one layer's K and V (N(0,1), rounded to the storage dtype)."""
+               chunk_tokens: int = 8192, plain_fill: bool = False) -> Batch:
+    """Generate one layer's K and V (N(0,1), rounded to the storage dtype).
+
+    plain_fill: the same geometry, page tables and distribution, but the values come from one
+    random-normal launch per tensor (torch's generator) instead of the counter-based generator's
+    many small ones; they are NOT reproducible across devices and never go to the oracle.
+    """
     device = torch.device(device)
     seed = seed + 1000003 * wl.config_id
     n_vis, gw, gh, prefix = _geometry(wl, seed)
@@ -161,6 +166,11 @@ def make_batch(wl: Workload, seed: int = BASE_SEED, device="cpu", layer: int = 0
     else:
         bt.k = torch.zeros((wl.batch, H, cap, d), dtype=dt, device=device)
         bt.v = torch.zeros((wl.batch, H, cap, d), dtype=dt, device=device)
+    if plain_fill:
+        g = torch.Generator(device=device).manual_seed(seed + 7919 * layer)
+        bt.k = torch.randn(bt.k.shape, generator=g, device=device, dtype=torch.float32).to(dt)
+        bt.v = torch.randn(bt.v.shape, generator=g, device=device, dtype=torch.float32).to(dt)
+        return bt
     for b in range(wl.batch):
         for t0 in range(0, caps[b], chunk_tokens):
             toks = torch.arange(t0, min(t0 + chunk_tokens, caps[b]), device=device, dtype=torch.int64)
