@@ -314,7 +314,7 @@ def main():
         path_bytes = sum((n + t_) * 2 * R + 8 * n + 8 * k_ + 2 * Hq * d * e for n, t_, k_ in zip(bt.n_vis, tn, keep))
     path_gbs = path_bytes / (ms_per_step * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "focal_fused_kernel (focal layer: K and V stream, dense output and scores)" if focal_mode
-                else "score_resident_kernel (focal scoring: K stream, logits kept in registers)",
+                else "score_resident_kernel (focal scoring: K stream, softmax weights kept in registers)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_source,
                 "path_frac": round(path_gbs / HBM_PEAK_GBS, 4), "path_achieved": round(path_gbs, 1),

@@ -1,9 +1,9 @@
-// Focal-layer scoring with the logits kept on chip (Eq. 1; text under Eq. 2).
+// Focal-layer scoring with the softmax weights kept on chip (Eq. 1; text under Eq. 2).
 //
 // The head average is taken after each head's softmax, so a score needs every head's
 // normaliser over the whole cache.  The two-kernel path parks all fp32 logits in HBM; mixing
 // those writes into the K stream costs far more than their bytes on this chip.  This kernel
-// keeps them in registers instead:
+// keeps what it needs of them in registers instead:
 //   - one 512-thread workgroup per (image-token range, sequence), at most one per compute unit,
 //     so the whole grid is resident at once; a ragged batch's sequences get ranges in proportion
 //     to their lengths (resident_alloc in resident.hpp);
@@ -315,7 +315,7 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
         return s;
     };
 
-    // ---- stream: text tiles (statistics only), then image tiles (logits parked in registers) -----
+    // ---- stream: text tiles (statistics only), then image tiles (weights parked in registers) ----
     // The wave's tiles are numbered 0 .. ntext + nimg - 1 in that order; tile n uses slot n & 1 and
     // two tiles are always in flight.
     u32x4 kb[8];
@@ -409,7 +409,7 @@ img_done:
     }
     if (lse_out && rng == 0 && sub == 0 && lane < G) lse_out[(int64_t)b * Hq + kvh * G + lane] = l2 * kLn2;
 
-    // ---- probabilities of the parked logits, summed over the heads of each token ---------------
+    // ---- the parked weights brought to the normalisers, summed over the heads of each token ------
     float cf[4];          // from "relative to the lane's reference" to "relative to the head's normaliser"
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
