@@ -204,8 +204,11 @@ __global__ __launch_bounds__(kTopkThreads) void topk_general_kernel(
 constexpr int kTopkPer = 16;
 constexpr int kTopkRegKeys = kTopkThreads * kTopkPer;
 
-// VEC: every row of scores starts 16-byte aligned and holds whole 16-byte pieces
-template <bool VEC>
+// VEC: every row of scores starts 16-byte aligned and holds whole 16-byte pieces.  PER: keys per
+// thread, the fewest that hold the longest image span (every per-key instruction is executed by all
+// sixteen waves whether their keys are real or padding: at 4096 tokens, 16 keys per thread would be
+// four times the work).
+template <bool VEC, int PER>
 __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(
     const float *__restrict__ scores, BatchDev bv, double tau, const int32_t *prev_idx,
     const int32_t *prev_cnt, int32_t *sel_idx, int32_t *sel_cnt, int64_t kmax)
@@ -217,7 +220,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(
 
     TopkRegShared sh;
     sh.hist = hist; sh.list = list; sh.pick = s_pick; sh.w_ac = w_ac;
-    topk_reg_body<kTopkThreads, kTopkPer, false, VEC>(scores, bv, blockIdx.x, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax, sh,
+    topk_reg_body<kTopkThreads, PER, false, VEC>(scores, bv, blockIdx.x, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax, sh,
                                           [](int, int) {});
 }
 
@@ -262,12 +265,12 @@ hipError_t launch_topk(const float *scores, const BatchDev &bv, int batch, doubl
     }
     if (bv.max_vis_len <= kTopkRegKeys) {
         const bool vec = (reinterpret_cast<uintptr_t>(scores) & 15u) == 0 && (bv.max_vis_len & 3) == 0;
-        if (vec)
-            FASTOCR_LAUNCH(K_TOPK, topk_reg_kernel<true>, dim3(batch), dim3(kTopkThreads), 0,
-                           stream, scores, bv, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax);
-        else
-            FASTOCR_LAUNCH(K_TOPK, topk_reg_kernel<false>, dim3(batch), dim3(kTopkThreads), 0,
-                           stream, scores, bv, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax);
+#define FASTOCR_TOPK_REG(V, P) FASTOCR_LAUNCH(K_TOPK, (topk_reg_kernel<V, P>), dim3(batch), dim3(kTopkThreads), 0, stream, scores, \
+                                              bv, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax)
+        if (bv.max_vis_len <= kTopkThreads * 4) { if (vec) FASTOCR_TOPK_REG(true, 4); else FASTOCR_TOPK_REG(false, 4); }
+        else if (bv.max_vis_len <= kTopkThreads * 8) { if (vec) FASTOCR_TOPK_REG(true, 8); else FASTOCR_TOPK_REG(false, 8); }
+        else { if (vec) FASTOCR_TOPK_REG(true, kTopkPer); else FASTOCR_TOPK_REG(false, kTopkPer); }
+#undef FASTOCR_TOPK_REG
         return hipGetLastError();
     }
     uint32_t *gkeys = reinterpret_cast<uint32_t *>(ws);

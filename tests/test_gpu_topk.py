@@ -71,7 +71,7 @@ def make_scores(rng, B, W, kind):
 
 
 @pytest.mark.parametrize("kind", ["softmax", "ties", "signed", "const", "cluster"])
-@pytest.mark.parametrize("W", [1, 5, 64, 1000, 4096, 16384, 20000])
+@pytest.mark.parametrize("W", [1, 5, 64, 1000, 4096, 6000, 8192, 16384, 20000])
 def test_cold_topk_is_bit_exact(kind, W):
     rng = np.random.default_rng(W * 3 + len(kind))
     B = 3
