@@ -116,3 +116,18 @@ def test_planted_fixation_is_found_by_the_oracle_statistically():
     wl = fs.config(2, steps=1)
     rec2 = [_recall(wl, fs.BASE_SEED + 5 * s)[0] for s in range(3)]
     assert np.mean(rec2) > 0.7
+
+
+def test_plain_fill_keeps_geometry_tables_and_distribution():
+    """The fill used under hardware counters: one random-normal launch per tensor instead of the seeded
+    generator's many; everything but the values is the seeded batch's."""
+    wl = fs.config(5, batch=3, n_visual=(300, 700), steps=8)
+    a = fs.make_batch(wl, device="cpu", plain_fill=True)
+    b = fs.make_batch(wl, device="cpu")
+    assert (a.n_vis, a.prefix, a.vis_start, a.grid_w, a.grid_h, a.cap) == (b.n_vis, b.prefix, b.vis_start, b.grid_w, b.grid_h, b.cap)
+    assert torch.equal(a.block_table, b.block_table)
+    assert a.k.shape == b.k.shape and a.v.shape == b.v.shape and a.k.dtype == b.k.dtype
+    for x in (a.k, a.v):
+        x = x.float()
+        assert abs(float(x.mean())) < 0.01 and abs(float(x.std()) - 1.0) < 0.02
+    assert not torch.equal(a.k, a.v)
