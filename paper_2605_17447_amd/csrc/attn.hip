@@ -54,6 +54,18 @@ __device__ unsigned long long g_merge_words[kMergeSlots][kMergeWords];
 __device__ unsigned long long g_merge_ticket[kMergeSlots][kMergeMaxStreams];
 __device__ uint32_t g_merge_timeouts;                        // sticky count of merges that gave up
 
+// Where dim `dim` of head `head` sits in a wave's [16 heads][D] join buffer.  A head's row is a
+// multiple of 64 LDS banks long, so with the plain order the 64 lanes of a store -- 16 heads x 4 lane
+// groups whose dims differ by 32 -- would meet in two banks (a 32-way conflict on each of the 32
+// stores per wave).  With the dim XORed by the head number and its bit 6 folded into bit 4 the 64
+// lanes of a store fall into 64 different banks, and so do the 64 consecutive dims a wave reads.
+template <int D>
+__device__ __forceinline__ int join_slot(int head, int dim)
+{
+    if constexpr (D == 128) return dim ^ (head & 15) ^ ((dim & 64) >> 2);
+    else return dim;
+}
+
 __device__ __forceinline__ unsigned long long tagged(float x, uint32_t tag)
 {
     return (unsigned long long)__float_as_uint(x) | ((unsigned long long)tag << 32);
@@ -341,7 +353,7 @@ tiles_done:
 
     // ---- cross-wave merge through LDS -----------------------------------------------------
     zl = rows_sum(zl);
-    float *buf = reinterpret_cast<float *>(smem[wave]);        // [16 heads][D dims]
+    float *buf = reinterpret_cast<float *>(smem[wave]);        // [16 heads][D dims], dims permuted per head (join_slot)
 #pragma unroll
     for (int t = 0; t < NACC; ++t)
 #pragma unroll
@@ -349,7 +361,7 @@ tiles_done:
             // the operand row 4lg + r of block t: dim 8 row + t (D = 128), dim 8 (row & 7) + 2 t + (row >> 3) (D = 64)
             const int row = 4 * lg + r;
             const int dim = D == 128 ? 8 * row + t : 8 * (row & 7) + 2 * t + (row >> 3);
-            buf[li * D + dim] = acc[t][r];
+            buf[li * D + join_slot<D>(li, dim)] = acc[t][r];
         }
     if (lg == 0) { sm_m[wave][li] = m; sm_z[wave][li] = zl; }
     __syncthreads();
@@ -368,7 +380,7 @@ tiles_done:
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) {
                 const float f = fast_exp2(sm_m[w][hh] - M);
-                o += f * reinterpret_cast<const float *>(smem[w])[hh * D + c];
+                o += f * reinterpret_cast<const float *>(smem[w])[hh * D + join_slot<D>(hh, c)];
                 Z += f * sm_z[w][hh];
             }
         }
