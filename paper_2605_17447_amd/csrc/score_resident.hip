@@ -182,14 +182,24 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
     const unsigned char *kbytes = reinterpret_cast<const unsigned char *>(kv.k);
 
     // rows first_tok .. first_tok + rv - 1 of the sequence, contiguous token indices
+    // paged caches: a tile's two block-table entries are fetched while the tile before it is
+    // issued, so the latency of those scalar loads is not in front of the tile's row loads
+    int ahead_tok = -1, ahead_pg = 0, ahead_a = 0, ahead_b = 0;
+    auto pages_ahead = [&](int first_tok) {
+        const int32_t *bt = kv.block_table + (int64_t)b * kv.max_pages;
+        ahead_tok = first_tok;
+        ahead_pg = (int)((uint32_t)first_tok / (uint32_t)kv.page_tokens);
+        ahead_a = bt[min(ahead_pg, kv.max_pages - 1)];
+        ahead_b = bt[min(ahead_pg + 1, kv.max_pages - 1)];
+    };
     auto issue_run = [&](int first_tok, int rv, int seq_no) {
         unsigned char *dst = smem[wave][seq_no & 1];
         const uint32_t limit = (uint32_t)(rv - 1) * stride_b;
         if (PAGED) {
             const int pt = kv.page_tokens;
-            const int pg0 = first_tok / pt, in0 = first_tok - pg0 * pt;
-            const int32_t *bt = kv.block_table + (int64_t)b * kv.max_pages;
-            const int64_t pa = bt[min(pg0, kv.max_pages - 1)], pb = bt[min(pg0 + 1, kv.max_pages - 1)];
+            if (ahead_tok != first_tok) pages_ahead(first_tok);
+            const int pg0 = ahead_pg, in0 = first_tok - pg0 * pt;
+            const int64_t pa = ahead_a, pb = ahead_b;
             // row r of the tile lives at base_a + r*stride while in0 + r < pt, else at base_b + r*stride
             const unsigned char *base_a = kbytes + 2 * (pa * kv.stride_page + (int64_t)kvh * kv.stride_head + (int64_t)in0 * kv.stride_token);
             const unsigned char *base_b = kbytes + 2 * (pb * kv.stride_page + (int64_t)kvh * kv.stride_head + (int64_t)(in0 - pt) * kv.stride_token);
@@ -222,6 +232,7 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
         }
         const int jf = img_first(x);
         issue_run(v0 + jf, min(kResTile, r1 - jf), seq_no);
+        if (PAGED && x + 1 < nimg) pages_ahead(v0 + img_first(x + 1));
     };
     // text tile x of the wave: text positions map to tokens with a gap at the image span, so the
     // rows are addressed one by one
