@@ -251,16 +251,19 @@ def main():
 
     progress("inputs resident")
     # ---- timed region ------------------------------------------------------------------------
+    # The kernel timer is set up before the warm-up steps (its events are created there), so that the GPU
+    # does not sit idle between the warm-up and the timed steps for longer than the synchronize takes.
+    every = max(1, args.time_every)
+    fb.set_tuning("timer_every", every)
+    fb.kernel_timer_enable(timed_kernel, (total + every - 1) // every + 1)
     for i in range(n_warm):
         step_fn(i)
     torch.cuda.synchronize()
-    every = max(1, args.time_every)
-    fb.set_tuning("timer_every", every)
-    fb.kernel_timer_enable(timed_kernel, (n_steps + every - 1) // every)
-    torch.cuda.synchronize()
+    fb.kernel_timer_read(timed_kernel)          # drops the warm-up steps' samples
     t0 = time.perf_counter()
     for i in range(n_warm, total):
         step_fn(i)
+    issued = time.perf_counter() - t0           # host time to issue every launch (the GPU must be the slower side)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     progress("timed region done")
@@ -340,6 +343,7 @@ def main():
                                   "(counter pass)" if args.counter_pass else "")},
         "roofline": roofline,
         "sequence_layer_steps_per_s": round(value * B, 1),
+        "host_issue_ms_per_step": round(issued * 1e3 / n_steps, 5),
     }
 
     # ---- extras: comparator and per-kernel breakdown (outside the timed region) ---------------
