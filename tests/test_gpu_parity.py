@@ -101,8 +101,9 @@ def test_generic_bf16_shapes(Hq, Hkv, d):
 
 # ------------------------------------------------------------------ bf16 MFMA path
 
-@pytest.mark.parametrize("Hq,Hkv", [(28, 4), (64, 8), (16, 1), (4, 4), (6, 2)])
+@pytest.mark.parametrize("Hq,Hkv", [(28, 4), (64, 8), (16, 1), (4, 4), (6, 2), (16, 2), (12, 2)])
 def test_mfma_bf16_ragged_batch(Hq, Hkv):
+    # (16, 2) and (12, 2): the head shapes of 3B- and 1.7B-class decoders like the two models of Sec. 4.1
     case = TinyCase(seed=100 + Hq, B=3, Hq=Hq, Hkv=Hkv, d=128, n_vis=[1000, 777, 1500], pre=[32, 5, 0],
                     post=[41, 130, 7], dtype="bf16")
     full_check(problem_from_case(case), 0.05, f"mfma Hq{Hq} Hkv{Hkv}")
