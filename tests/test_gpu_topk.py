@@ -82,6 +82,22 @@ def test_cold_topk_is_bit_exact(kind, W):
         assert_same(idx, cnt, expect(s, vis_len, tau), f"{kind} W={W} tau={tau}")
 
 
+@pytest.mark.parametrize("W", [300, 4096, 16384, 20000])
+def test_nan_scores_order_above_every_number(W):
+    """A score the scoring launch could not finish is a (positive, quiet) NaN; the select takes those
+    first, like the largest numbers.  The oracle's sort has no place for a NaN, so it gets the same
+    rows with +inf in their place (no other infinity is present)."""
+    rng = np.random.default_rng(W)
+    s = make_scores(rng, 3, W, "softmax")
+    vis_len = [W, W // 2 + 1, W - 3]
+    for b in range(3):
+        s[b, rng.choice(vis_len[b], 3, replace=False)] = np.nan
+    stand_in = np.where(np.isnan(s), np.float32(np.inf), s)
+    for tau in (0.02, 0.5):
+        idx, cnt = run_topk(s, vis_len, tau)
+        assert_same(idx, cnt, expect(stand_in, vis_len, tau), f"NaN W={W} tau={tau}")
+
+
 def test_scores_beyond_the_lds_key_capacity_use_the_workspace():
     rng = np.random.default_rng(1)
     s = make_scores(rng, 2, 40000, "softmax")
