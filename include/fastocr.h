@@ -140,8 +140,8 @@ size_t fastocr_workspace_bytes(int op, const fastocr_kv_view *kv, const fastocr_
  * Kernels: bf16 caches with head_dim 128 or 64 and at most 16 query heads per kv head run on the
  * matrix-core kernels (all calls); every other shape (fp32 caches, other head dimensions up to 256,
  * larger groups) runs on plain-FMA kernels that accumulate in fp64, to the same error bars.
- * Concurrency: when the shape fits (bf16, head_dim 128, 1/2/4/8 kv heads with at most 8 query heads
- * each, batch <= 256 and <= the compute-unit count) this call (and fastocr_focal_attn_score) runs as ONE kernel whose
+ * Concurrency: when the shape fits (bf16, head_dim 128 or 64, 1/2/4/8 kv heads with at most 8 query heads
+ * each, batch <= 256 and <= the compute-unit count) this call (and, at head_dim 128, fastocr_focal_attn_score) runs as ONE kernel whose
  * workgroups -- at most one per compute unit -- wait for each other's softmax statistics, so
  * all of them must be on the chip together.  Launched alone on the GPU (any number of calls in
  * order on one stream, HIP graphs included) that always holds.  If other kernels occupy compute

@@ -315,7 +315,7 @@ size_t fastocr_workspace_bytes(int op, const fastocr_kv_view *kv, const fastocr_
         const size_t dense = fastocr_workspace_bytes(FASTOCR_OP_DENSE_DECODE_ATTN, kv, bv, n_q_heads, 0);
         need = need > dense ? need : dense;
         ResidentPlan rp;
-        if (resident_plan(s, plan_cu_count(), &rp)) {
+        if (s.kv.head_dim == 128 && resident_plan(s, plan_cu_count(), &rp)) {
             const size_t fused = round256(focal_fused_workspace_bytes(s, rp) + 256);
             need = need > fused ? need : fused;
         }
@@ -368,6 +368,7 @@ static bool use_resident(int kind, int mode, const Shape &s, ResidentPlan *rp, i
 {
     const int cus = plan_cu_count();
     if (mode == 0 || !resident_plan(s, cus, rp)) return false;
+    if (kind == EX_FUSED && s.kv.head_dim != 128) return false;      // the one-pass focal kernel: head_dim 128 only
     if (rp->nranges * s.batch > cus) return false;
     if (mode != 2 && (rp->range_tokens / (32 * rp->wpk) < min_tiles || !exchange_trusted())) return false;
     *slot = exchange_slot(kind, stream, flag);

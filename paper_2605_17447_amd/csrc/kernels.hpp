@@ -37,7 +37,8 @@ struct Shape {
     bool vec16;     // every cache row starts 16-byte aligned and head_dim covers whole 16-byte pieces
     bool fast;      // the MFMA kernels cover this shape: bf16, head_dim 128 or 64, group size <= 16,
                     // 16-byte aligned rows (decided once from the views by the C-ABI layer); the
-                    // single-launch forms (register-resident kernels, in-launch merge) need head_dim 128
+                    // one-pass focal kernel and the in-launch merge need head_dim 128, register-resident
+                    // scoring takes both
 };
 
 inline bool mfma_path(const Shape &s) { return s.fast; }

@@ -8,10 +8,10 @@
 //     so the whole grid is resident at once; a ragged batch's sequences get ranges in proportion
 //     to their lengths (resident_alloc in resident.hpp);
 //   - wave w streams KV head w % Hkv (8/Hkv waves share a head and interleave its tiles), a
-//     32-token tile (8 KB) at a time.  Tiles travel HBM -> LDS directly (global_load_lds, 16 bytes
-//     per lane, two 8 KB slots per wave, no staging registers); the XOR swizzle that makes the
-//     MFMA operand reads conflict-free is applied by permuting which 16-byte chunk of a row each
-//     lane fetches;
+//     32-token tile (8 KB at head_dim 128, 4 KB at 64) at a time.  Tiles travel HBM -> LDS directly
+//     (global_load_lds, 16 bytes per lane, two slots per wave, no staging registers); the XOR swizzle
+//     that makes the MFMA operand reads conflict-free is applied by permuting which 16-byte chunk of a
+//     row each lane fetches;
 //   - C[head][token] = Q * K^T with v_mfma_f32_16x16x32_bf16 leaves 4 heads x 1 token per lane; each
 //     logit becomes its softmax weight 2^(logit - ref) at once, relative to a reference that the lane
 //     fixed with its first live logit (as accurate as relative to the true maximum for any exponent
@@ -23,6 +23,7 @@
 //     (bounded spin, no counter, no fence), asking for them the moment its stream ends;
 //   - every wave then scales its parked weights to the sequence's normalisers, the heads of a token
 //     are summed through LDS and the finished scores are written -- the only HBM writes.
+// head_dim 128 or 64 (a template parameter: rows of 256 or 128 bytes, 4 or 2 k-steps per logit).
 // Shapes that do not fit (group size > 8, Hkv not dividing 8, more sequences than compute
 // units, more than 32 tiles per wave, pages shorter than a tile) take the two-kernel path.
 #include "kernels.hpp"
@@ -76,7 +77,7 @@ bool resident_select_fits(const Shape &s) { return s.bv.max_vis_len <= kSelMaxKe
 bool resident_plan(const Shape &s, int num_cu, ResidentPlan *plan)
 {
     const int Hkv = s.kv.n_kv_heads;
-    if (!s.fast || s.kv.head_dim != 128 || Hkv < 1 || s.n_q_heads % Hkv != 0) return false;
+    if (!s.fast || (s.kv.head_dim != 128 && s.kv.head_dim != 64) || Hkv < 1 || s.n_q_heads % Hkv != 0) return false;
     const int G = s.n_q_heads / Hkv;
     if (G > 8 || s.n_q_heads > kResMaxHq) return false;
     if (Hkv != 1 && Hkv != 2 && Hkv != 4 && Hkv != 8) return false;
@@ -105,7 +106,7 @@ size_t resident_workspace_bytes(const Shape &s, const ResidentPlan &p)
     return bytes;
 }
 
-template <bool PAGED, bool SELECT>
+template <int D, bool PAGED, bool SELECT>
 __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
     SelectArgs sel_args /* first: read straight from the kernel-argument segment when the select starts */,
     KvDev kv, BatchDev bv, const uint16_t *__restrict__ q, int Hq, int G, float scale_log2,
@@ -121,9 +122,16 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
 
     // wave-uniform quantities are kept in scalar registers: tile bookkeeping, addresses and loop
     // exits then cost no vector instructions
+    static_assert(D == 128 || D == 64, "head_dim 128 or 64");
+    constexpr int KS = D / 32;             // k-steps of a logit
+    constexpr int NL = D / 16;             // 1 KB load instructions per 32-token tile
+    constexpr int RPL = 32 / NL;           // rows one load instruction brings
+    constexpr int CPR = D / 8;             // 16-byte chunks of a row
+    constexpr int ROWB = 2 * D;            // bytes of a row
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
-    const int li = lane & 15, lg = lane >> 4;
+    const int li = lane & 15, lg = lane >> 4;                      // the lane in the matrix products
+    const int lrow = lane / CPR, lslot = lane % CPR;               // the lane in a load: row of the load's group, chunk slot in LDS
     const int Hkv = kv.n_kv_heads;
     const int wpk = kResWaves / Hkv;
     const int kvh = wave % Hkv, sub = wave / Hkv;
@@ -145,16 +153,16 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
     const int ntext = ntt > slot ? (ntt - slot + nslots - 1) / nslots : 0;
 
     // Q as the A operand (rows 0..7 for the tile's first 16 tokens, rows 8..15 for the second 16)
-    u32x4 qlo[4], qhi[4];
+    u32x4 qlo[KS], qhi[KS];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
+    for (int kk = 0; kk < KS; ++kk) {
         qlo[kk] = u32x4{0u, 0u, 0u, 0u};
         qhi[kk] = u32x4{0u, 0u, 0u, 0u};
         const int hl = li, hh = li - 8;
         if (hl < G && hl < 8)
-            qlo[kk] = *reinterpret_cast<const u32x4 *>(q + ((int64_t)b * Hq + (int64_t)kvh * G + hl) * 128 + 8 * (4 * kk + lg));
+            qlo[kk] = *reinterpret_cast<const u32x4 *>(q + ((int64_t)b * Hq + (int64_t)kvh * G + hl) * D + 8 * (4 * kk + lg));
         if (hh >= 0 && hh < G)
-            qhi[kk] = *reinterpret_cast<const u32x4 *>(q + ((int64_t)b * Hq + (int64_t)kvh * G + hh) * 128 + 8 * (4 * kk + lg));
+            qhi[kk] = *reinterpret_cast<const u32x4 *>(q + ((int64_t)b * Hq + (int64_t)kvh * G + hh) * D + 8 * (4 * kk + lg));
     }
     const uint16_t *kbase = reinterpret_cast<const uint16_t *>(kv.k);
 
@@ -169,16 +177,22 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
     };
     auto text_first = [&](int x) { return (slot + x * nslots) * kResTile; };       // text-relative
 
-    // A tile goes into LDS slot (sequence number & 1) of the wave: load e brings rows 4e .. 4e+3,
-    // lane (lg, li) the 16-byte chunk li ^ (row & 15) of row 4e + lg, which lands at
-    // slot + 1024 e + 16 lane.  Rows past the end of a ragged tile are clamped to its last row.
-    // Addresses are a wave-uniform 64-bit base (scalar registers) plus a 32-bit byte offset per lane.
+    // A tile goes into LDS slot (sequence number & 1) of the wave, rows of 2 D bytes one after the
+    // other: load e brings rows RPL e .. RPL e + RPL - 1 (4 rows of 256 bytes, or 8 of 128), lane
+    // (lrow, lslot) one 16-byte chunk of row r = RPL e + lrow, which lands at slot + 1024 e + 16 lane,
+    // i.e. in chunk slot lslot of its row.  The chunk it fetches is lslot ^ f(r), so that slot x of a row
+    // holds chunk x ^ f(r): f(r) = r & 15 (D 128) or (r >> 1) & 7 (D 64, two rows to 64 banks) makes the
+    // MFMA operand reads conflict-free.  f(RPL e + lrow) = fl ^ 4 (e & NV-1) with fl = lrow or lrow >> 1.
+    // Rows past the end of a ragged tile are clamped to its last row.  Addresses are a wave-uniform
+    // 64-bit base (scalar registers) plus a 32-bit byte offset per lane.
+    constexpr int NV = D == 128 ? 4 : 2;                 // distinct chunk permutations over the loads of a tile
     const int64_t seq_base = row_offset<false>(kv, b, 0, kvh);
     const uint32_t stride_b = (uint32_t)kv.stride_token * 2u;            // bytes; 32 rows fit 32 bits (host-checked)
-    const uint32_t rowoff_lg = (uint32_t)lg * stride_b;
-    uint32_t chunk_b[4];                                 // byte offset of this lane's chunk, by e & 3
+    const uint32_t rowoff_lg = (uint32_t)lrow * stride_b;
+    const int fl = D == 128 ? lrow : (lrow >> 1);
+    uint32_t chunk_b[NV];                                // byte offset of this lane's chunk, by e & (NV - 1)
 #pragma unroll
-    for (int k = 0; k < 4; ++k) chunk_b[k] = 16u * (uint32_t)((li ^ lg) ^ (4 * k));
+    for (int k = 0; k < NV; ++k) chunk_b[k] = 16u * (uint32_t)((lslot ^ fl) ^ (4 * k));
     const unsigned char *kbytes = reinterpret_cast<const unsigned char *>(kv.k);
 
     // rows first_tok .. first_tok + rv - 1 of the sequence, contiguous token indices
@@ -205,29 +219,29 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
             const unsigned char *base_b = kbytes + 2 * (pb * kv.stride_page + (int64_t)kvh * kv.stride_head + (int64_t)(in0 - pt) * kv.stride_token);
             const uint32_t split = (uint32_t)(pt - in0) * stride_b;      // first byte offset of the second page
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const uint32_t ro = min(rowoff_lg + (uint32_t)(4 * e) * stride_b, limit);
+            for (int e = 0; e < NL; ++e) {
+                const uint32_t ro = min(rowoff_lg + (uint32_t)(RPL * e) * stride_b, limit);
                 const unsigned char *base = ro >= split ? base_b : base_a;
-                lds_dma16(reinterpret_cast<const uint16_t *>(base + (ro + chunk_b[e & 3])), dst + 1024 * e);
+                lds_dma16(reinterpret_cast<const uint16_t *>(base + (ro + chunk_b[e & (NV - 1)])), dst + 1024 * e);
             }
         } else {
             const unsigned char *base = kbytes + 2 * (seq_base + (int64_t)first_tok * kv.stride_token);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const uint32_t ro = min(rowoff_lg + (uint32_t)(4 * e) * stride_b, limit);
-                lds_dma16(reinterpret_cast<const uint16_t *>(base + (ro + chunk_b[e & 3])), dst + 1024 * e);
+            for (int e = 0; e < NL; ++e) {
+                const uint32_t ro = min(rowoff_lg + (uint32_t)(RPL * e) * stride_b, limit);
+                lds_dma16(reinterpret_cast<const uint16_t *>(base + (ro + chunk_b[e & (NV - 1)])), dst + 1024 * e);
             }
         }
     };
     // image tile x of the wave.  Past the last one the issue stays unconditional (the reader's
-    // "at most 8 loads outstanding" wait counts on it) but fetches 256 bytes of the query, which
-    // are in cache, instead of cache rows that nobody will use.
-    const uint16_t *qrow = q + ((int64_t)b * Hq + (int64_t)kvh * G) * 128;
+    // "at most NL loads outstanding" wait counts on it) but fetches a row of the query, which
+    // is in cache, instead of cache rows that nobody will use.
+    const uint16_t *qrow = q + ((int64_t)b * Hq + (int64_t)kvh * G) * D;
     auto issue_img = [&](int x, int seq_no) {
         if (x >= nimg) {
             unsigned char *dst = smem[wave][seq_no & 1];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) lds_dma16(qrow + chunk_b[e & 3] / 2, dst + 1024 * e);
+            for (int e = 0; e < NL; ++e) lds_dma16(qrow + chunk_b[e & (NV - 1)] / 2, dst + 1024 * e);
             return;
         }
         const int jf = img_first(x);
@@ -240,10 +254,10 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
         const int tf = text_first(min(x, ntext - 1));
         unsigned char *dst = smem[wave][seq_no & 1];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int tc = min(tf + 4 * e + lg, Tn - 1);
+        for (int e = 0; e < NL; ++e) {
+            const int tc = min(tf + RPL * e + lrow, Tn - 1);
             const int tok = tc < v0 ? tc : tc + N;
-            lds_dma16(kbase + row_offset<PAGED>(kv, b, tok, kvh) + chunk_b[e & 3] / 2, dst + 1024 * e);
+            lds_dma16(kbase + row_offset<PAGED>(kv, b, tok, kvh) + chunk_b[e & (NV - 1)] / 2, dst + 1024 * e);
         }
     };
 
@@ -260,19 +274,32 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
     for (int r = 0; r < 4; ++r) { ref[r] = kMinusHuge; z[r] = 0.f; }
     RES_EACH_TILE(RES_DECLARE)
 
-    // LDS byte addresses of this lane's four B-operand chunks (rows li and 16 + li of slot 0)
-    uint32_t rd_addr[4];
+    // LDS byte addresses of this lane's B-operand chunks, one per k-step (row li of slot 0; row 16 + li
+    // has the same f and lies 16 rows further on)
+    uint32_t rd_addr[KS];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
-        rd_addr[kk] = lds_address(&smem[wave][0][0]) + li * 256 + ((((4 * kk + lg) ^ li) & 15) << 4);
+    for (int kk = 0; kk < KS; ++kk)
+        rd_addr[kk] = lds_address(&smem[wave][0][0]) + li * ROWB + ((((4 * kk + lg) ^ (D == 128 ? li : (li >> 1))) & (CPR - 1)) << 4);
 
-    // Tile number seq_no of the wave has landed once at most the 8 loads of the next tile are
+    // Tile number seq_no of the wave has landed once at most the NL loads of the next tile are
     // outstanding; read it in the MFMA B layout.  The reads are written in assembly together with
     // their waits: the compiler does not order LDS reads after loads that land in LDS by
     // themselves (left to itself it waits for ALL outstanding loads, the prefetch included), and
     // it must not move the products above the wait either.
-    auto wait_and_read = [&](int seq_no, u32x4(&kb)[8]) {
+    auto wait_and_read = [&](int seq_no, u32x4(&kb)[2 * KS]) {
         const uint32_t so = (seq_no & 1) * 8192;
+        if constexpr (D == 64) {
+            asm volatile(
+                "s_waitcnt vmcnt(4)\n\t"
+                "ds_read_b128 %0, %4\n\t"
+                "ds_read_b128 %1, %5\n\t"
+                "ds_read_b128 %2, %4 offset:2048\n\t"
+                "ds_read_b128 %3, %5 offset:2048\n\t"
+                "s_waitcnt lgkmcnt(0)"
+                : "=&v"(kb[0]), "=&v"(kb[1]), "=&v"(kb[2]), "=&v"(kb[3])
+                : "v"(rd_addr[0] + so), "v"(rd_addr[1] + so)
+                : "memory");
+        } else
         asm volatile(
             "s_waitcnt vmcnt(8)\n\t"
             "ds_read_b128 %0, %8\n\t"
@@ -290,16 +317,16 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
     };
     // weights 2^(logit - ref) of this lane's token for its 4 heads (logits in the log2 domain); dead
     // positions come out 0
-    auto weights_of = [&](u32x4(&kb)[8], bool live) -> f32x4 {
+    auto weights_of = [&](u32x4(&kb)[2 * KS], bool live) -> f32x4 {
         f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
+        for (int kk = 0; kk < KS; ++kk)
             s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qlo[kk]),
                                                         __builtin_bit_cast(bf16x8, kb[kk]), s, 0, 0, 0);
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
+        for (int kk = 0; kk < KS; ++kk)
             s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qhi[kk]),
-                                                        __builtin_bit_cast(bf16x8, kb[4 + kk]), s, 0, 0, 0);
+                                                        __builtin_bit_cast(bf16x8, kb[KS + kk]), s, 0, 0, 0);
         bool moved = false;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -329,7 +356,7 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
     // ---- stream: text tiles (statistics only), then image tiles (weights parked in registers) ----
     // The wave's tiles are numbered 0 .. ntext + nimg - 1 in that order; tile n uses slot n & 1 and
     // two tiles are always in flight.
-    u32x4 kb[8];
+    u32x4 kb[2 * KS];
     if (ntext + nimg > 0) {
         // the first two tiles
         if (ntext > 0) issue_text(0, 0); else issue_img(0, 0);
@@ -490,11 +517,14 @@ hipError_t launch_score_resident(const Shape &s, const ResidentPlan &p, int sync
     const bool fuse = select && select->sel_idx;
     if (fuse && !resident_select_fits(s)) return hipErrorInvalidValue;
     const SelectArgs sa = fuse ? *select : SelectArgs{0.0, nullptr, nullptr, nullptr, nullptr, 0};
-#define FASTOCR_RES(P, S) FASTOCR_LAUNCH(K_SCORE_LOGITS, (score_resident_kernel<P, S>), grid, block, 0, stream, sa, s.kv, s.bv, \
+#define FASTOCR_RES(D, P, S) FASTOCR_LAUNCH(K_SCORE_LOGITS, (score_resident_kernel<D, P, S>), grid, block, 0, stream, sa, s.kv, s.bv, \
                        (const uint16_t *)q, s.n_q_heads, G, scale_log2, s.batch, p.nranges, p.range_tokens, \
                        sync_slot, spin_ticks, scores, lse, img_mass ? mass_part : nullptr, mass_meta, flag)
-    if (s.paged) { if (fuse) FASTOCR_RES(true, true); else FASTOCR_RES(true, false); }
-    else         { if (fuse) FASTOCR_RES(false, true); else FASTOCR_RES(false, false); }
+#define FASTOCR_RES_D(D) \
+    if (s.paged) { if (fuse) FASTOCR_RES(D, true, true); else FASTOCR_RES(D, true, false); } \
+    else         { if (fuse) FASTOCR_RES(D, false, true); else FASTOCR_RES(D, false, false); }
+    if (s.kv.head_dim == 64) { FASTOCR_RES_D(64) } else { FASTOCR_RES_D(128) }
+#undef FASTOCR_RES_D
 #undef FASTOCR_RES
     if (img_mass) resident_mass_kernel<<<s.batch, 64, 0, stream>>>(mass_part, mass_meta, img_mass);
     return hipGetLastError();

@@ -480,6 +480,41 @@ def test_scoring_paths_paged(resident):
         fb.set_tuning("score_resident", 1)
 
 
+@pytest.mark.parametrize("resident", [2, 0])
+@pytest.mark.parametrize("Hq,Hkv", [(32, 8), (16, 2), (7, 1), (12, 4)])
+def test_scoring_paths_head_dim_64(resident, Hq, Hkv):
+    """head_dim 64 through the register-resident kernel (128-byte rows: eight rows per load, two k-steps
+    per product) and through the two kernels; which of them ran is read off the finalize kernel's
+    launch count.  Contiguous ragged batch in both layouts, then a paged one."""
+    fb.set_tuning("score_resident", resident)
+    fb.kernel_timer_enable(fb.KERNEL_SCORE_FINALIZE, 8)
+    try:
+        case = TinyCase(seed=264 + Hq, B=40, Hq=Hq, Hkv=Hkv, d=64, n_vis=[1500 + 37 * i for i in range(40)],
+                        pre=[i % 7 * 5 for i in range(40)], post=[(i * 13) % 90 for i in range(40)], dtype="bf16")
+        for layout in ("bhsd", "bshd"):
+            p = problem_from_case(case, layout=layout)
+            ref_sc, ref_lse, ref_mass = oracle.focal_score(*p.oracle_args())
+            sc, lse, mass = p.scores(want_lse=True, want_mass=True)
+            check_scores(sc, ref_sc, p.vis_len, f"d64 {layout} resident={resident} scores")
+            assert np.allclose(lse.cpu().numpy(), ref_lse, rtol=2e-5, atol=2e-5)
+            assert np.allclose(mass.cpu().numpy(), ref_mass, atol=2e-5)
+            assert len(fb.kernel_timer_read(fb.KERNEL_SCORE_FINALIZE)) == (0 if resident else 1)
+        wl = fs.config(5, batch=24, steps=4, n_visual=(600, 3000), grid_w=(20, 60), text_prefix=(3, 300), page_tokens=64,
+                       head_dim=64, n_q_heads=Hq, n_kv_heads=Hkv)
+        bt = fs.make_batch(wl, device=DEV)
+        q = fs.queries_for_step(bt, 3, [x[2] for x in fs.centres(bt)])
+        p = GpuProblem(bt.k, bt.v, q, bt.seq_len(3), bt.vis_start, bt.n_vis, wl.head_dim ** -0.5,
+                       block_table=bt.block_table)
+        ref_sc, ref_lse, _ = oracle.focal_score(*p.oracle_args())
+        sc, lse, _ = p.scores(want_lse=True)
+        check_scores(sc, ref_sc, p.vis_len, f"d64 paged resident={resident}")
+        assert np.allclose(lse.cpu().numpy(), ref_lse, rtol=2e-5, atol=2e-5)
+        assert len(fb.kernel_timer_read(fb.KERNEL_SCORE_FINALIZE)) == (0 if resident else 1)
+    finally:
+        fb.kernel_timer_enable(fb.KERNEL_SCORE_FINALIZE, 0)
+        fb.set_tuning("score_resident", 1)
+
+
 # ------------------------------------------------------------------ the focal layer in one pass
 
 @pytest.mark.parametrize("fused", [2, 0])
