@@ -184,7 +184,7 @@ int fastocr_topk_fixation(const float *scores, const fastocr_batch_view *bv, dou
  * An entry outside the span is clamped into it.  An empty J_b gives a zero row.
  *   out  [batch, n_q_heads, head_dim], kv->dtype (bf16 rounded to nearest even), 16-byte aligned;
  *        q as in fastocr_focal_score
- * Concurrency: when a (sequence, kv head) stream is cut into 2 .. 4 ranges (bf16, head_dim 128, at
+ * Concurrency: when a (sequence, kv head) stream is cut into 2 .. 4 ranges (bf16, head_dim 128 or 64, at
  * most 8 query heads per kv head, at most 128 streams) and the call's stream owns an exchange slot,
  * the stream's last workgroup waits for the partial results of the others, which were dispatched
  * before it and wait for nobody.  That wait is microseconds; if it exceeds 0.25 s the affected

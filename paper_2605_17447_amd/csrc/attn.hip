@@ -47,7 +47,7 @@ constexpr int kMergeMaxSplits = 4;
 constexpr unsigned long long kTicketUnit = 12;                  // divisible by every range count 2 .. kMergeMaxSplits
 constexpr int kMergeMaxStreams = 128;
 constexpr int kMergeMaxG = 8;
-constexpr int kMergeStatsAt = kMergeMaxG * 128;                 // a partial: o[G][128], then m[G], then Z[G]
+constexpr int kMergeStatsAt = kMergeMaxG * 128;                 // a partial: o[G][D] (D <= 128), then at a fixed place m[G], then Z[G]
 constexpr int kMergePitch = kMergeMaxG * 130;                   // words per published partial, whatever G is
 constexpr size_t kMergeWords = (size_t)kMergeMaxStreams * (kMergeMaxSplits - 1) * kMergePitch;   // per slot: 3.2 MB
 __device__ unsigned long long g_merge_words[kMergeSlots][kMergeWords];
@@ -104,7 +104,6 @@ __global__ __launch_bounds__(64 * kWaves, 8 / kWaves) void attn_mfma_kernel(
     __shared__ uint32_t sm_tag;
 
     static_assert(D == 128 || D == 64, "head_dim 128 or 64");
-    static_assert(D == 128 || MODE != kMerge, "the in-launch merge's word layout is for head_dim 128");
     constexpr int KS = D / 32;            // k-steps of the logits
     constexpr int NACC = D / 16;          // 16-dim blocks of the output
     constexpr int NL = D / 16;            // 1 KB load instructions per 32-token K (or V) tile
@@ -657,7 +656,7 @@ size_t attn_workspace_bytes(const Shape &s, int nsplit)
 
 bool attn_merges_in_kernel(const Shape &s, int nsplit)
 {
-    if (!mfma_path(s) || s.kv.head_dim != 128 || nsplit < 2 || nsplit > kMergeMaxSplits) return false;
+    if (!mfma_path(s) || nsplit < 2 || nsplit > kMergeMaxSplits) return false;
     const size_t streams = (size_t)s.batch * s.kv.n_kv_heads;
     const size_t G = s.n_q_heads / s.kv.n_kv_heads;
     return streams <= (size_t)kMergeMaxStreams && G <= (size_t)kMergeMaxG;
@@ -680,6 +679,7 @@ static void launch_mfma(int kid, const Shape &s, const void *q, float scale_log2
         (uint16_t *)out, lse, slot, spin_ticks, flag)
     if (s.kv.head_dim == 64) {
         if (nsplit == 1) FASTOCR_ATTN(64, 8, kDirect);
+        else if (merge) FASTOCR_ATTN(64, 8, kMerge);
         else if (tune_attn_waves() == 8) FASTOCR_ATTN(64, 8, kPartial);
         else FASTOCR_ATTN(64, 4, kPartial);
     }

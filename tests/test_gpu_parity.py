@@ -175,14 +175,15 @@ def test_split_counts_give_the_same_result(nsplit, merge):
         fb.set_tuning("attn_merge", 1)
 
 
+@pytest.mark.parametrize("d", [128, 64])
 @pytest.mark.parametrize("Hq,Hkv", [(28, 4), (64, 8), (8, 1)])
 @pytest.mark.parametrize("nsplit", [2, 3, 4])
-def test_pruned_attention_merged_inside_the_launch(Hq, Hkv, nsplit):
+def test_pruned_attention_merged_inside_the_launch(Hq, Hkv, nsplit, d):
     """Ranges of a stream hand their partials to the stream's last range through tagged words in
     static device memory.  Twelve calls in a row (three times round the slots) with a fresh query
     each: a stale word of an earlier call taken for a fresh one would show as a wrong output.
     Sequences shorter than the number of waves leave some ranges without a token."""
-    case = TinyCase(seed=40 + Hq + nsplit, B=4, Hq=Hq, Hkv=Hkv, d=128, n_vis=[1500, 900, 64, 0], pre=[40, 3, 0, 2],
+    case = TinyCase(seed=40 + Hq + nsplit, B=4, Hq=Hq, Hkv=Hkv, d=d, n_vis=[1500, 900, 64, 0], pre=[40, 3, 0, 2],
                     post=[77, 130, 5, 1], dtype="bf16")
     p = problem_from_case(case)
     oc = list(p.oracle_args())
@@ -229,10 +230,10 @@ def test_merged_pruned_attention_with_alternating_shapes():
     exchange slots: a word's place must not depend on the call's shape, or a word left by one shape
     could carry the tag another shape is waiting for."""
     shapes = [dict(B=4, Hq=28, Hkv=4, nsplit=2), dict(B=2, Hq=64, Hkv=8, nsplit=3), dict(B=3, Hq=8, Hkv=2, nsplit=4),
-              dict(B=5, Hq=12, Hkv=4, nsplit=2)]
+              dict(B=5, Hq=12, Hkv=4, nsplit=2), dict(B=3, Hq=32, Hkv=4, nsplit=3, d=64)]
     probs = []
     for i, sh in enumerate(shapes):
-        case = TinyCase(seed=900 + i, B=sh["B"], Hq=sh["Hq"], Hkv=sh["Hkv"], d=128, n_vis=[900 + 100 * j for j in range(sh["B"])],
+        case = TinyCase(seed=900 + i, B=sh["B"], Hq=sh["Hq"], Hkv=sh["Hkv"], d=sh.get("d", 128), n_vis=[900 + 100 * j for j in range(sh["B"])],
                         pre=[7 * j for j in range(sh["B"])], post=[40 + j for j in range(sh["B"])], dtype="bf16")
         p = problem_from_case(case)
         oc = p.oracle_args()
@@ -242,7 +243,7 @@ def test_merged_pruned_attention_with_alternating_shapes():
         probs.append((p, torch.from_numpy(ref_idx).to(DEV).contiguous(), torch.from_numpy(ref_cnt).to(DEV), ref, sh["nsplit"]))
     try:
         for rnd in range(9):
-            for i in ((0, 1, 2, 3), (3, 1, 0, 2), (2, 0, 3, 1))[rnd % 3]:
+            for i in ((0, 4, 1, 2, 3), (3, 1, 4, 0, 2), (2, 0, 3, 4, 1))[rnd % 3]:
                 p, sel, selc, ref, nsplit = probs[i]
                 fb.set_tuning("splits_sparse", nsplit)
                 check_out(p.sparse(sel, selc), ref, f"round {rnd}, shape {i}")
