@@ -25,6 +25,7 @@ static std::atomic<int> g_tune_barrier_spin_us{250000};      // bounded wait of 
 static std::atomic<int> g_tune_splits[4];              // indexed by fastocr_op; 0 = automatic
 static std::atomic<int> g_tune_timer_every{1};         // per-kernel timers: which launches record events (every n-th)
 static std::atomic<int> g_exchange_distrusted{0};      // "exchange_fallback" 1
+static std::atomic<int> g_tune_graph_replay{0};        // 1: the caller replays its calls from a HIP graph, where a launch follows the one before within half a microsecond
 static std::atomic<int> g_tune_select_fused{0};        // top-k inside the scoring / focal-layer launch (0 never, 1 when it fits): measured slower, off by default
 
 int tune_attn_waves() { return g_tune_attn_waves.load(std::memory_order_relaxed); }
@@ -224,8 +225,25 @@ static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 // Number of position ranges per (sequence, kv head): enough workgroups to fill the chip a few
 // times over, never less than one tile per wave.  A pure function of the host-side shape so
 // that the workspace query and the launch agree.
-static int choose_splits(int op, const Shape &s, int max_positions)
+// Pruned attention as partials over four-wave workgroups of about one tile per wave, at most two
+// workgroups per compute unit: the finest cut choose_splits ever makes of a short list (and, being
+// monotone in the list's length, what the workspace is sized for).
+static int finest_splits(const Shape &s, int max_positions)
 {
+    const int streams = s.batch * s.kv.n_kv_heads;
+    const int ntile = (max_positions + 31) / 32;
+    const int by_work = (ntile + 3) / 4;
+    const int most = streams > 0 ? 2 * plan_cu_count() / streams : 1;
+    const int n = by_work < most ? by_work : most;
+    return n < 1 ? 1 : n;
+}
+
+// replay: 0 / 1 = as if "graph_replay" were that, -1 = the tuning's value.  *partials (if given) is set
+// when the choice only holds as partials in the workspace followed by the merge kernel.
+static int choose_splits(int op, const Shape &s, int max_positions, bool *partials = nullptr, int replay = -1)
+{
+    if (partials) *partials = false;
+    if (replay < 0) replay = g_tune_graph_replay.load(std::memory_order_relaxed);
     const bool fast = s.fast;
     const int kNumCU = plan_cu_count();
     const int forced = g_tune_splits[op].load(std::memory_order_relaxed);
@@ -253,7 +271,22 @@ static int choose_splits(int op, const Shape &s, int max_positions)
             const int by_len = ntile <= 16 ? 1 : (ntile < 48 ? 3 : 4);
             n = n < by_len ? n : by_len;
             n = n < 1 ? 1 : n;
-            if (n == 1 || attn_merges_in_kernel(s, n)) return n;
+            if (n == 1 || attn_merges_in_kernel(s, n)) {
+                // A compute unit gathers rows at a few tens of GB/s, so a short list of few streams is
+                // done sooner the more compute units share it -- but every range a stream is cut into
+                // makes the in-launch merge wait longer for words to cross the chip (3 - 4 us against a
+                // plain store of the partial).  Replayed from a graph, where the merge kernel starts
+                // 0.4 us after the launch before it (eager: 2 - 3 us), partials over four-wave workgroups
+                // of one tile per wave plus that kernel win whenever the single launch would leave half
+                // of the chip idle (28- and 36-layer stacks, batch 4 - 12, 8 - 32 streams of 15 - 47
+                // tiles: 356 -> 331, 495 -> 443, 364 -> 323, 548 -> 452, 403 -> 327 us per decode step;
+                // eager the same choice costs 2 us per call).
+                if (replay == 1 && streams > 0 && 2 * streams * n <= kNumCU && finest_splits(s, max_positions) > n) {
+                    if (partials) *partials = true;
+                    return finest_splits(s, max_positions);
+                }
+                return n;
+            }
         }
         nsplit = (target_wg + streams - 1) / (streams > 0 ? streams : 1);
         // pruned attention is short: when eight waves get at most eight tiles each, or at least half
@@ -321,8 +354,14 @@ size_t fastocr_workspace_bytes(int op, const fastocr_kv_view *kv, const fastocr_
         }
         return need;
     }
-    // fewer positions never need more ranges, so a bound taken with a larger kmax (or none) also covers
-    const int nsplit = choose_splits(op, s, op == FASTOCR_OP_SPARSE_DECODE_ATTN ? sparse_positions(bv, kmax) : bv->max_seq_len);
+    // fewer positions never need more ranges, so a bound taken with a larger kmax (or none) also covers;
+    // pruned attention: sized for the finest cut as well, whether or not "graph_replay" asks for it
+    const int positions = op == FASTOCR_OP_SPARSE_DECODE_ATTN ? sparse_positions(bv, kmax) : bv->max_seq_len;
+    int nsplit = choose_splits(op, s, positions, nullptr, 0);
+    if (op == FASTOCR_OP_SPARSE_DECODE_ATTN && s.fast && g_tune_splits[op].load(std::memory_order_relaxed) <= 0) {
+        const int finest = finest_splits(s, positions);
+        nsplit = nsplit > finest ? nsplit : finest;
+    }
     if (op == FASTOCR_OP_FOCAL_SCORE) {
         // sized for either scoring path, so that the choice can be made at launch
         size_t need = score_workspace_bytes(s, nsplit);
@@ -488,7 +527,8 @@ static int attn_common(int op, const fastocr_kv_view *kv, const fastocr_batch_vi
     if (rc != FASTOCR_OK) return rc;
     if (bv->batch == 0) return FASTOCR_OK;
     Shape s = make_shape(kv, bv, n_q_heads);
-    const int nsplit = choose_splits(op, s, op == FASTOCR_OP_SPARSE_DECODE_ATTN ? sparse_positions(bv, kmax) : bv->max_seq_len);
+    bool partials = false;
+    const int nsplit = choose_splits(op, s, op == FASTOCR_OP_SPARSE_DECODE_ATTN ? sparse_positions(bv, kmax) : bv->max_seq_len, &partials);
     // the ranges of a stream merged inside the launch: when asked for, the shape fits, the stream has
     // an exchange slot and no such wait has ever been given up in this process (the range count
     // does not depend on the last two, so the workspace the caller sized always covers the
@@ -498,7 +538,7 @@ static int attn_common(int op, const fastocr_kv_view *kv, const fastocr_batch_vi
     uint32_t *flag = nullptr;
     // (never for the static-workspace entry point: the first in-launch merge on a device allocates
     // the pinned "gave up" word)
-    if (!static_ws && ((op == FASTOCR_OP_SPARSE_DECODE_ATTN && mode != 0) || mode == 2) && attn_merges_in_kernel(s, nsplit) && exchange_trusted())
+    if (!static_ws && !partials && ((op == FASTOCR_OP_SPARSE_DECODE_ATTN && mode != 0) || mode == 2) && attn_merges_in_kernel(s, nsplit) && exchange_trusted())
         merge_slot = exchange_slot(EX_MERGE, (hipStream_t)hip_stream, &flag);
     hipError_t e = launch_attn(s, q, scale, sel_idx, sel_cnt, kmax, out, lse, ws, nsplit, merge_slot, flag, (hipStream_t)hip_stream);
     return e == hipSuccess ? FASTOCR_OK : FASTOCR_EHIP;
@@ -694,6 +734,7 @@ int fastocr_set_tuning(const char *key, int value)
     else if (!strcmp(key, "splits_sparse")) g_tune_splits[FASTOCR_OP_SPARSE_DECODE_ATTN] = value;
     else if (!strcmp(key, "splits_dense")) g_tune_splits[FASTOCR_OP_DENSE_DECODE_ATTN] = value;
     else if (!strcmp(key, "attn_waves") && (value == 4 || value == 8)) g_tune_attn_waves = value;
+    else if (!strcmp(key, "graph_replay") && (value == 0 || value == 1)) g_tune_graph_replay = value;
     else if (!strcmp(key, "timer_every") && value >= 1) g_tune_timer_every = value;
     else if (!strcmp(key, "attn_merge") && value <= 2) g_tune_attn_merge = value;
     else if (!strcmp(key, "barrier_spin_us")) g_tune_barrier_spin_us = value ? value : 250000;

@@ -212,6 +212,23 @@ def test_exchange_timeouts_rejects_a_null_pointer(lib):
     assert lib.fastocr_exchange_timeouts(None) == -1          # FASTOCR_EINVAL, before any GPU call
 
 
+def test_pruned_attention_workspace_grows_with_the_kept_count_and_ignores_graph_replay(lib):
+    """A workspace sized with a larger kmax (or none) must cover every call with a smaller one, whichever
+    way the list is cut: the size is monotone in kmax and the same with "graph_replay" 0 and 1."""
+    for B, Hkv, Hq, S, N in [(1, 4, 28, 4700, 4096), (4, 2, 16, 10300, 8100), (12, 2, 12, 4700, 3969), (8, 4, 28, 4400, 4096),
+                             (20, 2, 16, 9000, 8100), (16, 8, 64, 17200, 16384), (40, 1, 8, 3000, 2500)]:
+        kv, bv = _kv(Hkv=Hkv, S=S), _bv(B=B, S=S, N=N)
+        sizes = []
+        for kmax in [1, 13, 64, 205, 410, 820, 2048, N, 0]:          # 0 = unknown: the whole sequence
+            w0 = lib.fastocr_workspace_bytes(fb.OP_SPARSE_DECODE_ATTN, ctypes.byref(kv), ctypes.byref(bv), Hq, kmax)
+            assert lib.fastocr_set_tuning(b"graph_replay", 1) == fb.OK
+            w1 = lib.fastocr_workspace_bytes(fb.OP_SPARSE_DECODE_ATTN, ctypes.byref(kv), ctypes.byref(bv), Hq, kmax)
+            assert lib.fastocr_set_tuning(b"graph_replay", 0) == fb.OK
+            assert w0 == w1 and w0 > 0 and w0 % 256 == 0
+            sizes.append(w0)
+        assert sizes == sorted(sizes), (B, Hkv, sizes)
+
+
 def test_tuning_keys(lib):
     assert lib.fastocr_set_tuning(b"splits_dense", 3) == fb.OK
     kv, bv = _kv(), _bv()
@@ -229,6 +246,8 @@ def test_tuning_keys(lib):
     assert lib.fastocr_set_tuning(b"timer_every", 1) == fb.OK
     assert lib.fastocr_set_tuning(b"attn_waves", 5) == fb.EINVAL and lib.fastocr_set_tuning(b"attn_waves", 0) == fb.EINVAL
     assert lib.fastocr_set_tuning(b"attn_waves", 8) == fb.OK and lib.fastocr_set_tuning(b"attn_waves", 4) == fb.OK
+    assert lib.fastocr_set_tuning(b"graph_replay", 2) == fb.EINVAL
+    assert lib.fastocr_set_tuning(b"graph_replay", 1) == fb.OK and lib.fastocr_set_tuning(b"graph_replay", 0) == fb.OK
     assert lib.fastocr_set_tuning(b"exchange_fallback", 2) == fb.EINVAL
     assert lib.fastocr_set_tuning(b"exchange_fallback", 1) == fb.OK and lib.fastocr_set_tuning(b"exchange_fallback", 0) == fb.OK
 

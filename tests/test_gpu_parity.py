@@ -225,6 +225,35 @@ def test_pruned_attention_merged_inside_the_launch_paged(nsplit):
         fb.set_tuning("splits_sparse", 0)
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,d,n0", [(4, 16, 2, 128, 8100), (8, 28, 4, 128, 4096), (12, 12, 2, 128, 3969), (3, 32, 4, 64, 5000),
+                                           (1, 28, 4, 128, 4096)])
+def test_pruned_attention_cut_fine_for_graph_replay(B, Hq, Hkv, d, n0):
+    """With "graph_replay" 1 a short list of few streams is cut into about one tile per wave and merged by
+    the second kernel (its launch is counted), with 0 it stays one launch; both match the oracle, and the
+    workspace asked for once, for the whole sequence, serves both."""
+    case = TinyCase(seed=1300 + B, B=B, Hq=Hq, Hkv=Hkv, d=d, n_vis=[n0 - 211 * j for j in range(B)],
+                    pre=[64 + 3 * j for j in range(B)], post=[500 + 17 * j for j in range(B)], dtype="bf16")
+    p = problem_from_case(case)
+    oc = p.oracle_args()
+    ref_sc, _, _ = oracle.focal_score(*oc)
+    ref_idx, ref_cnt = oracle.topk_fixation(ref_sc, p.vis_len, 0.05)
+    ref, _ = oracle.decode_attn(*oc, ref_idx, ref_cnt)
+    sel, selc = torch.from_numpy(ref_idx).to(DEV).contiguous(), torch.from_numpy(ref_cnt).to(DEV)
+    ws = p.ws(fb.OP_SPARSE_DECODE_ATTN, 0)
+    out = torch.zeros_like(p.q)
+    fb.kernel_timer_enable(fb.KERNEL_ATTN_COMBINE, 8)
+    try:
+        for replay, merges in ((1, 1), (0, 0), (1, 1)):
+            fb.set_tuning("graph_replay", replay)
+            out.zero_()
+            fo.sparse_decode_attn(p.cache, p.batch, p.q, p.scale, sel, selc, out, ws)
+            check_out(out, ref, f"graph_replay {replay}")
+            assert len(fb.kernel_timer_read(fb.KERNEL_ATTN_COMBINE)) == merges
+    finally:
+        fb.set_tuning("graph_replay", 0)
+        fb.kernel_timer_enable(fb.KERNEL_ATTN_COMBINE, 0)
+
+
 def test_merged_pruned_attention_with_alternating_shapes():
     """Calls of different shapes (heads per group, ranges per stream, streams) take turns on the same
     exchange slots: a word's place must not depend on the call's shape, or a word left by one shape
