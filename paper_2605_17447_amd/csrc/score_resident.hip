@@ -32,6 +32,7 @@
 namespace fastocr {
 
 constexpr int kResGatherGroup = 8;      // ranges whose statistics a wave asks for at a time
+constexpr float kRefSlack = 16.f;       // how far (log2 units) a logit may rise above its lane's reference before the reference moves
 
 #define RES_DECLARE(J) f32x4 park_##J = f32x4{0.f, 0.f, 0.f, 0.f};
 // image tile J of the wave: multiply, keep the weights, refill the tile's LDS slot
@@ -264,11 +265,14 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
     const int hbase = 4 * (lg & 1);
     const int tok_in_tile = li + 16 * (lg >> 1);
     // Softmax weights are kept relative to a reference per lane and head that is fixed by the lane's
-    // first live logit: 2^(logit - ref) is as accurate for any exponent in range as it is relative to
-    // the true maximum, so neither a running maximum nor a second pass of exponentials is needed, and
-    // what is parked in the registers is the weight itself.  A logit more than 2^64 above the reference
-    // (not seen on real logits, but no input may break the result) moves the reference there and
-    // rescales what the lane holds.
+    // first live logit, so neither a running maximum nor a second pass of exponentials is needed, and
+    // what is parked in the registers is the weight itself.  The exponent logit - ref is rounded to
+    // fp32, half an ulp of its own size: relative to the true maximum the weights that matter have
+    // exponents near 0, relative to a far reference they do not, and the weight's relative error is
+    // that rounding times ln 2.  So a logit more than kRefSlack above the reference moves the reference
+    // there and rescales what the lane holds: exponents stay below 16 (error <= 3.3e-7 of the weight,
+    // what the two-kernel path reaches; with a slack of 64 a score of 0.3 was off by 1.3e-6), and a
+    // lane moves once per 11 nats its logits rise above its first one -- rarely.
     float ref[4], z[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) { ref[r] = kMinusHuge; z[r] = 0.f; }
@@ -332,13 +336,13 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
         for (int r = 0; r < 4; ++r) {
             s[r] = live ? s[r] * scale_log2 : -INFINITY;
             if (ref[r] == kMinusHuge) ref[r] = fmaxf(s[r], kMinusHuge);          // the first live logit
-            moved = moved || s[r] - ref[r] > 64.f;
+            moved = moved || s[r] - ref[r] > kRefSlack;
         }
         if (__builtin_amdgcn_ballot_w64(moved) != 0ull) {
             float alpha[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const bool mv = s[r] - ref[r] > 64.f;
+                const bool mv = s[r] - ref[r] > kRefSlack;
                 alpha[r] = mv ? fast_exp2(ref[r] - s[r]) : 1.f;
                 ref[r] = mv ? s[r] : ref[r];
                 z[r] *= alpha[r];
