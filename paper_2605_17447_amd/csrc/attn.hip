@@ -583,6 +583,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(
 // dim lane): it walks every SL-th partial with 16-byte loads, four of them in flight, and the
 // split lanes are then added through LDS in a fixed order -- the serial walk of the kernel above
 // is bound by memory latency once a head has more than a handful of partials.
+constexpr int kCombineFew = 32;        // up to this many partials per head the wide merge takes its one-round-trip form
 template <typename T>
 __global__ __launch_bounds__(256) void attn_combine_wide_kernel(
     const float *__restrict__ part_o, const float *__restrict__ part_ml, int nsplit, int d,
@@ -613,23 +614,51 @@ __global__ __launch_bounds__(256) void attn_combine_wide_kernel(
     const int SL = 256 / DL;
     const int dl = t & (DL - 1), sl = t / DL;
 
-    float mloc = -INFINITY;
-    for (int s = t; s < nsplit; s += 256) mloc = fmaxf(mloc, ml[s * ml_step]);
-    mloc = wave_max(mloc);
-    if ((t & 63) == 0) sm_max[t >> 6] = mloc;
-    __syncthreads();
-    const float M = fmaxf(fmaxf(sm_max[0], sm_max[1]), fmaxf(sm_max[2], sm_max[3]));
-
-    float Z = 0.f;
+    float Z = 0.f, M;
     f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (M > -INFINITY && dl < nd4) {
-        const float *po = pbase + 4 * dl;
+    if (nsplit <= kCombineFew && nsplit <= 4 * SL) {
+        // A handful of partials (a short list cut fine): one memory round trip instead of two.  The
+        // thread's (at most four) accumulators are requested first, from clamped addresses; then every
+        // thread reads all the maxima itself -- the same addresses across the workgroup, requests that
+        // travel together with the others -- instead of waiting for a reduction through LDS.
+        f32x4 a[4];
+        float mm[4], zz[4];
+        const int dc = dl < nd4 ? dl : nd4 - 1;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int sk = sl + k * SL < nsplit ? sl + k * SL : 0;
+            a[k] = *reinterpret_cast<const f32x4 *>(pbase + 4 * dc + sk * o_step);
+            mm[k] = ml[sk * ml_step];
+            zz[k] = ml[sk * ml_step + 1];
+        }
+        M = -INFINITY;
+        for (int x = 0; x < nsplit; ++x) M = fmaxf(M, ml[x * ml_step]);
+        if (M > -INFINITY && dl < nd4) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if (sl + k * SL < nsplit) {
+                    const float f = fast_exp2(mm[k] - M);
+                    Z += f * zz[k];
+                    o += a[k] * f;
+                }
+            }
+        }
+    } else {
+        float mloc = -INFINITY;
+        for (int s = t; s < nsplit; s += 256) mloc = fmaxf(mloc, ml[s * ml_step]);
+        mloc = wave_max(mloc);
+        if ((t & 63) == 0) sm_max[t >> 6] = mloc;
+        __syncthreads();
+        M = fmaxf(fmaxf(sm_max[0], sm_max[1]), fmaxf(sm_max[2], sm_max[3]));
+        if (M > -INFINITY && dl < nd4) {
+            const float *po = pbase + 4 * dl;
 #pragma unroll 4
-        for (int s = sl; s < nsplit; s += SL) {
-            const float f = fast_exp2(ml[s * ml_step] - M);
-            Z += f * ml[s * ml_step + 1];
-            const f32x4 a = *reinterpret_cast<const f32x4 *>(po + s * o_step);
-            o += a * f;
+            for (int s = sl; s < nsplit; s += SL) {
+                const float f = fast_exp2(ml[s * ml_step] - M);
+                Z += f * ml[s * ml_step + 1];
+                const f32x4 a = *reinterpret_cast<const f32x4 *>(po + s * o_step);
+                o += a * f;
+            }
         }
     }
     if (dl < nd4) *reinterpret_cast<f32x4 *>(&sm_o[sl * d + 4 * dl]) = o;
