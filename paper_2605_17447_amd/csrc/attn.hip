@@ -773,8 +773,9 @@ hipError_t launch_attn_combine(const Shape &s, const float *part_o, const float 
     const int d = s.kv.head_dim;
     dim3 grid(s.n_q_heads, s.batch), block(256);
     if (seq_meta && d % 4 != 0) return hipErrorInvalidValue;
-    if (d % 4 == 0 && (nsplit > 2 || seq_meta)) {
-        // several partials per head: spread them over the workgroup's threads
+    if (d % 4 == 0 && (nsplit >= 2 || seq_meta)) {
+        // several partials per head: spread them over the workgroup's threads (two partials as well: its
+        // form for few partials needs one memory round trip where the plain walk below needs two)
         if (s.dtype == DT_BF16)
             FASTOCR_LAUNCH(K_ATTN_COMBINE, attn_combine_wide_kernel<uint16_t>, grid, block, 0, stream, part_o, part_ml, nsplit, d, (uint16_t *)out, lse, seq_meta, wpk);
         else
