@@ -332,8 +332,8 @@ int fastocr_stream_probe(const void *src, void *dst, size_t bytes, void *sink, v
  *       (default, under the same conditions as above), 0 = by a second kernel, 2 = dense attention
  *       merges inside the launch too (measured slower, kept for comparison)
  *   "graph_replay"    1 = the caller replays its calls from a HIP graph, where a launch starts well under a
- *       microsecond after the one before: pruned attention over short lists of few streams (where one
- *       launch would leave half of the chip idle) is then cut into about one tile per wave and merged by
+ *       microsecond after the one before: pruned attention over short lists of few streams (as long as
+ *       every workgroup of the cut finds a compute unit) is then cut into one tile per wave and merged by
  *       a second kernel; 0 (default) = calls are launched one by one, such lists stay one launch.  The
  *       workspace size covers both, results agree to rounding.
  *   "select_fused"    fastocr_focal_score_topk / fastocr_focal_attn_score_topk: 0 = the select is a launch of

@@ -225,15 +225,17 @@ static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 // Number of position ranges per (sequence, kv head): enough workgroups to fill the chip a few
 // times over, never less than one tile per wave.  A pure function of the host-side shape so
 // that the workspace query and the launch agree.
-// Pruned attention as partials over four-wave workgroups of about one tile per wave, at most two
-// workgroups per compute unit: the finest cut choose_splits ever makes of a short list (and, being
-// monotone in the list's length, what the workspace is sized for).
-static int finest_splits(const Shape &s, int max_positions)
+// Pruned attention as partials over four-wave workgroups of one tile per wave: the finest cut
+// choose_splits ever makes of a short list.  *fits: such a cut leaves at most one workgroup per compute
+// unit (only then is it taken).  The value is capped at that and so monotone in the list's length:
+// it is what the workspace is sized for, whatever length the calls then have.
+static int finest_splits(const Shape &s, int max_positions, bool *fits = nullptr)
 {
     const int streams = s.batch * s.kv.n_kv_heads;
     const int ntile = (max_positions + 31) / 32;
     const int by_work = (ntile + 3) / 4;
-    const int most = streams > 0 ? 2 * plan_cu_count() / streams : 1;
+    const int most = streams > 0 ? plan_cu_count() / streams : 1;
+    if (fits) *fits = by_work <= most;
     const int n = by_work < most ? by_work : most;
     return n < 1 ? 1 : n;
 }
@@ -277,13 +279,16 @@ static int choose_splits(int op, const Shape &s, int max_positions, bool *partia
                 // makes the in-launch merge wait longer for words to cross the chip (3 - 4 us against a
                 // plain store of the partial).  Replayed from a graph, where the merge kernel starts
                 // 0.4 us after the launch before it (eager: 2 - 3 us), partials over four-wave workgroups
-                // of one tile per wave plus that kernel win whenever the single launch would leave half
-                // of the chip idle (28- and 36-layer stacks, batch 4 - 12, 8 - 32 streams of 15 - 47
-                // tiles: 356 -> 331, 495 -> 443, 364 -> 323, 548 -> 452, 403 -> 327 us per decode step;
-                // eager the same choice costs 2 us per call).
-                if (replay == 1 && streams > 0 && 2 * streams * n <= kNumCU && finest_splits(s, max_positions) > n) {
+                // of one tile per wave plus that kernel win as long as those workgroups find a compute
+                // unit each (28- and 36-layer stacks, batch 4 - 16, 8 - 64 streams of 15 - 47 tiles:
+                // 356 -> 331, 391 -> 376, 495 -> 443, 364 -> 323, 548 -> 452, 403 -> 327 us per decode
+                // step; with 96 and 128 streams of 15 tiles, where they would not: 418 -> 464 and
+                // 449 -> 506 us, so those keep the single launch; eager the fine cut costs 2 us per call).
+                bool fits = false;
+                const int fine = finest_splits(s, max_positions, &fits);
+                if (replay == 1 && fits && fine > n) {
                     if (partials) *partials = true;
-                    return finest_splits(s, max_positions);
+                    return fine;
                 }
                 return n;
             }
