@@ -189,7 +189,7 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
     constexpr int NV = D == 128 ? 4 : 2;                 // distinct chunk permutations over the loads of a tile
     const int64_t seq_base = row_offset<false>(kv, b, 0, kvh);
     const uint32_t stride_b = (uint32_t)kv.stride_token * 2u;            // bytes; 32 rows fit 32 bits (host-checked)
-    const uint32_t rowoff_lg = (uint32_t)lrow * stride_b;
+    const uint32_t rowoff_row = (uint32_t)lrow * stride_b;
     const int fl = D == 128 ? lrow : (lrow >> 1);
     uint32_t chunk_b[NV];                                // byte offset of this lane's chunk, by e & (NV - 1)
 #pragma unroll
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
             const uint32_t split = (uint32_t)(pt - in0) * stride_b;      // first byte offset of the second page
 #pragma unroll
             for (int e = 0; e < NL; ++e) {
-                const uint32_t ro = min(rowoff_lg + (uint32_t)(RPL * e) * stride_b, limit);
+                const uint32_t ro = min(rowoff_row + (uint32_t)(RPL * e) * stride_b, limit);
                 const unsigned char *base = ro >= split ? base_b : base_a;
                 lds_dma16(reinterpret_cast<const uint16_t *>(base + (ro + chunk_b[e & (NV - 1)])), dst + 1024 * e);
             }
@@ -229,7 +229,7 @@ __global__ __launch_bounds__(kResThreads) void score_resident_kernel(
             const unsigned char *base = kbytes + 2 * (seq_base + (int64_t)first_tok * kv.stride_token);
 #pragma unroll
             for (int e = 0; e < NL; ++e) {
-                const uint32_t ro = min(rowoff_lg + (uint32_t)(RPL * e) * stride_b, limit);
+                const uint32_t ro = min(rowoff_row + (uint32_t)(RPL * e) * stride_b, limit);
                 lds_dma16(reinterpret_cast<const uint16_t *>(base + (ro + chunk_b[e & (NV - 1)])), dst + 1024 * e);
             }
         }
