@@ -257,6 +257,9 @@ int fastocr_focal_attn_score(const fastocr_kv_view *kv, const fastocr_batch_view
  * over the whole sequence -- no second launch, nobody waits.  That form is measured slower on
  * MI355X (the select then runs on 8 waves instead of 16 and ends the launch alone), so it is not
  * the default.
+ * fastocr_focal_attn_score_topk by default: when the layer runs as its one-pass kernel and no image span
+ * exceeds 16384 tokens, the merge of the dense output's partials is done by extra workgroups of the
+ * select's launch (both depend on the one-pass kernel only): two launches instead of three, same bits.
  */
 int fastocr_focal_score_topk(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
                              int n_q_heads, float scale, double tau, const int32_t *prev_idx,

@@ -72,7 +72,7 @@ class FixationController:
         if need is None:
             bound = _b.SeqBatch(batch.seq_len, batch.vis_start, batch.vis_len, self._bound_seq, self._bound_vis)
             need = 0
-            for op in (_b.OP_FOCAL_ATTN_SCORE, _b.OP_TOPK_FIXATION, _b.OP_SPARSE_DECODE_ATTN, _b.OP_DENSE_DECODE_ATTN):
+            for op in (_b.OP_FOCAL_ATTN_SCORE, _b.OP_FOCAL_ATTN_SCORE_TOPK, _b.OP_TOPK_FIXATION, _b.OP_SPARSE_DECODE_ATTN, _b.OP_DENSE_DECODE_ATTN):
                 need = max(need, self.ops.workspace_bytes(op, cache, bound, self.n_q_heads, self.kmax))
             self._need[id(cache)] = need
         if self._ws is None or self._ws_bytes < need:
@@ -107,12 +107,12 @@ class FixationController:
                 continue
             selects = (l in self.focal) or (l == 0 and self.kept_from is None)
             if selects:
-                # the layer's own output over the full cache and the scores its successors are pruned by
-                ops.focal_attn_score(cache, batch, q, self.scale, out, self.scores, ws, stream=stream)
+                # the layer's own output over the full cache, the scores its successors are pruned by and
+                # their top-k, from one call (its last launch merges the output's partials and selects)
                 warm = self.kept_from is not None
-                ops.topk_fixation(self.scores, batch, self.tau, self.kept_idx, self.kept_cnt, ws,
-                                  prev_idx=self.kept_idx if warm else None,
-                                  prev_cnt=self.kept_cnt if warm else None, stream=stream)
+                ops.focal_attn_score_topk(cache, batch, q, self.scale, self.tau, out, self.scores, self.kept_idx,
+                                          self.kept_cnt, ws, prev_idx=self.kept_idx if warm else None,
+                                          prev_cnt=self.kept_cnt if warm else None, stream=stream)
                 self.kept_from = l
                 if on_select is not None:
                     on_select(l, self.scores, self.kept_idx, self.kept_cnt)

@@ -572,12 +572,15 @@ int fastocr_dense_decode_attn_static(const fastocr_kv_view *kv, const fastocr_ba
                        out, lse, nullptr, 0, hip_stream, /*static_ws=*/true);
 }
 
+// defer (with *deferred): when the one-pass kernel runs and the top-k that follows can take the merge
+// of the output's partials into its own launch, that merge is not launched here but described in *defer.
 static int focal_attn_score_impl(const fastocr_kv_view *kv, const fastocr_batch_view *bv, const void *q,
                                  int n_q_heads, float scale, void *out, float *scores, float *lse,
                                  float *img_mass, void *ws, size_t ws_bytes, void *hip_stream,
-                                 const SelectArgs *select, bool *fused)
+                                 const SelectArgs *select, bool *fused, CombineArgs *defer = nullptr, bool *deferred = nullptr)
 {
     if (fused) *fused = false;
+    if (deferred) *deferred = false;
     int rc = check_views(kv, bv, n_q_heads);
     if (rc != FASTOCR_OK) return rc;
     if (!out) return FASTOCR_EINVAL;
@@ -594,9 +597,11 @@ static int focal_attn_score_impl(const fastocr_kv_view *kv, const fastocr_batch_
     uint32_t *flag = nullptr;
     if (use_resident(EX_FUSED, g_tune_focal_fused.load(std::memory_order_relaxed), s, &rp, kFusedMinTiles, (hipStream_t)hip_stream, &slot, &flag)) {
         const bool fuse = select && g_tune_select_fused.load(std::memory_order_relaxed) != 0 && resident_select_fits(s);
+        const bool hand_on = defer && deferred && !fuse && topk_takes_combine(bv->max_vis_len, kv->head_dim);
         hipError_t e = launch_focal_fused(s, rp, slot, flag, q, scale, out, scores, lse, img_mass, ws, (hipStream_t)hip_stream,
-                                          fuse ? select : nullptr);
+                                          fuse ? select : nullptr, hand_on ? defer : nullptr);
         if (fused) *fused = fuse;
+        if (hand_on) *deferred = true;
         return e == hipSuccess ? FASTOCR_OK : FASTOCR_EHIP;
     }
     rc = fastocr_dense_decode_attn(kv, bv, q, n_q_heads, scale, out, nullptr, ws, ws_bytes, hip_stream);
@@ -624,9 +629,19 @@ int fastocr_focal_attn_score_topk(const fastocr_kv_view *kv, const fastocr_batch
     rc = check_ws(ws, ws_bytes, need);
     if (rc != FASTOCR_OK) return rc;
     const SelectArgs sa{tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax};
-    bool fused = false;
-    rc = focal_attn_score_impl(kv, bv, q, n_q_heads, scale, out, scores, lse, img_mass, ws, ws_bytes, hip_stream, &sa, &fused);
+    bool fused = false, deferred = false;
+    CombineArgs merge;
+    rc = focal_attn_score_impl(kv, bv, q, n_q_heads, scale, out, scores, lse, img_mass, ws, ws_bytes, hip_stream, &sa, &fused,
+                               &merge, &deferred);
     if (rc != FASTOCR_OK || fused) return rc;
+    if (deferred) {
+        // the merge of the output's partials and the top-k both wait for the one-pass kernel only: one launch
+        // (the select keeps its keys in registers at these sizes and uses no workspace, the partials stay where they are)
+        BatchDev bd{bv->seq_len, bv->vis_start, bv->vis_len, bv->max_seq_len, bv->max_vis_len};
+        hipError_t e = launch_topk(scores, bd, bv->batch, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax, ws,
+                                   (hipStream_t)hip_stream, &merge);
+        return e == hipSuccess ? FASTOCR_OK : FASTOCR_EHIP;
+    }
     return fastocr_topk_fixation(scores, bv, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax, ws, ws_bytes, hip_stream);
 }
 

@@ -20,6 +20,7 @@
 // K is loaded the same coalesced way and re-laid to the A layout through a wave-private,
 // XOR-swizzled LDS tile.
 #include "kernels.hpp"
+#include "combine.hpp"
 
 namespace fastocr {
 
@@ -579,11 +580,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(
     if (lse && c == 0) lse[bh] = Z > 0.f ? (M + log2f(Z)) * kLn2 : -INFINITY;
 }
 
-// The same merge for many partials per head (head_dim a multiple of 4).  A thread is (split lane,
-// dim lane): it walks every SL-th partial with 16-byte loads, four of them in flight, and the
-// split lanes are then added through LDS in a fixed order -- the serial walk of the kernel above
-// is bound by memory latency once a head has more than a handful of partials.
-constexpr int kCombineFew = 32;        // up to this many partials per head the wide merge takes its one-round-trip form
+// The same merge with the partials spread over the workgroup's threads (combine.hpp).
 template <typename T>
 __global__ __launch_bounds__(256) void attn_combine_wide_kernel(
     const float *__restrict__ part_o, const float *__restrict__ part_ml, int nsplit, int d,
@@ -591,85 +588,9 @@ __global__ __launch_bounds__(256) void attn_combine_wide_kernel(
 {
     __shared__ float sm_max[4];
     __shared__ float sm_z[256];
-    __shared__ __align__(16) float sm_o[1024];         // [split lane][d]: SL * d <= 1024 as DL >= d/4
-    const int64_t bh = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;    // b*Hq + h
-    const int t = threadIdx.x;
-    // partial s of this head: statistics at ml[s * ml_step], accumulator at po[s * o_step]
-    const float *ml = part_ml + bh * nsplit * 2;
-    const float *pbase = part_o + bh * nsplit * d;
-    int64_t ml_step = 2, o_step = d;
-    if (seq_meta) {
-        const int Hq = gridDim.x, h = blockIdx.x, b = blockIdx.y;
-        const int64_t first = (int64_t)seq_meta[2 * b] * wpk;
-        nsplit = seq_meta[2 * b + 1] * wpk;
-        ml = part_ml + (first * Hq + h) * 2;
-        pbase = part_o + (first * Hq + h) * d;
-        ml_step = 2 * (int64_t)Hq;
-        o_step = (int64_t)Hq * d;
-    }
-    // dim lanes: the power of two covering d/4 (1 .. 64); split lanes: the rest of the 256 threads
-    const int nd4 = d / 4;
-    int DL = 1;
-    while (DL < nd4) DL <<= 1;
-    const int SL = 256 / DL;
-    const int dl = t & (DL - 1), sl = t / DL;
-
-    float Z = 0.f, M;
-    f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (nsplit <= kCombineFew && nsplit <= 4 * SL) {
-        // A handful of partials (a short list cut fine): one memory round trip instead of two.  The
-        // thread's (at most four) accumulators are requested first, from clamped addresses; then every
-        // thread reads all the maxima itself -- the same addresses across the workgroup, requests that
-        // travel together with the others -- instead of waiting for a reduction through LDS.
-        f32x4 a[4];
-        float mm[4], zz[4];
-        const int dc = dl < nd4 ? dl : nd4 - 1;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int sk = sl + k * SL < nsplit ? sl + k * SL : 0;
-            a[k] = *reinterpret_cast<const f32x4 *>(pbase + 4 * dc + sk * o_step);
-            mm[k] = ml[sk * ml_step];
-            zz[k] = ml[sk * ml_step + 1];
-        }
-        M = -INFINITY;
-        for (int x = 0; x < nsplit; ++x) M = fmaxf(M, ml[x * ml_step]);
-        if (M > -INFINITY && dl < nd4) {
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                if (sl + k * SL < nsplit) {
-                    const float f = fast_exp2(mm[k] - M);
-                    Z += f * zz[k];
-                    o += a[k] * f;
-                }
-            }
-        }
-    } else {
-        float mloc = -INFINITY;
-        for (int s = t; s < nsplit; s += 256) mloc = fmaxf(mloc, ml[s * ml_step]);
-        mloc = wave_max(mloc);
-        if ((t & 63) == 0) sm_max[t >> 6] = mloc;
-        __syncthreads();
-        M = fmaxf(fmaxf(sm_max[0], sm_max[1]), fmaxf(sm_max[2], sm_max[3]));
-        if (M > -INFINITY && dl < nd4) {
-            const float *po = pbase + 4 * dl;
-#pragma unroll 4
-            for (int s = sl; s < nsplit; s += SL) {
-                const float f = fast_exp2(ml[s * ml_step] - M);
-                Z += f * ml[s * ml_step + 1];
-                const f32x4 a = *reinterpret_cast<const f32x4 *>(po + s * o_step);
-                o += a * f;
-            }
-        }
-    }
-    if (dl < nd4) *reinterpret_cast<f32x4 *>(&sm_o[sl * d + 4 * dl]) = o;
-    if (dl == 0) sm_z[sl] = Z;
-    __syncthreads();
-    if (t < d) {
-        float acc = 0.f, zt = 0.f;
-        for (int x = 0; x < SL; ++x) { acc += sm_o[x * d + t]; zt += sm_z[x]; }
-        store_elem<T>(out + bh * d + t, zt > 0.f ? acc / zt : 0.f);
-        if (lse && t == 0) lse[bh] = zt > 0.f ? (M + log2f(zt)) * kLn2 : -INFINITY;
-    }
+    __shared__ __align__(16) float sm_o[1024];
+    combine_wide_body<T>(part_o, part_ml, nsplit, d, out, lse, seq_meta, wpk, blockIdx.x, blockIdx.y, gridDim.x,
+                         CombineShared{sm_max, sm_z, sm_o});
 }
 
 // -----------------------------------------------------------------------------------------

@@ -451,7 +451,7 @@ hipError_t focal_fused_timeouts(uint32_t *n) { return hipMemcpyFromSymbol(n, HIP
 
 hipError_t launch_focal_fused(const Shape &s, const ResidentPlan &p, int sync_slot, uint32_t *flag, const void *q, float scale,
                               void *out, float *scores, float *lse, float *img_mass, void *ws, hipStream_t stream,
-                              const SelectArgs *select)
+                              const SelectArgs *select, CombineArgs *defer)
 {
     if (sync_slot < 0 || sync_slot >= kResSlots) return hipErrorInvalidValue;
     const int W = p.nranges * s.batch;
@@ -475,6 +475,10 @@ hipError_t launch_focal_fused(const Shape &s, const ResidentPlan &p, int sync_sl
 #undef FASTOCR_FUS
     if (img_mass) fused_mass_kernel<<<s.batch, 64, 0, stream>>>(mass_part, seq_meta, img_mass);
     // every sequence's partials: workgroups seq_meta[b][0] .. + seq_meta[b][1], wpk of them each
+    if (defer) {
+        *defer = CombineArgs{att_o, att_ml, p.nranges * p.wpk, s.kv.head_dim, s.n_q_heads, p.wpk, seq_meta, (uint16_t *)out};
+        return hipGetLastError();
+    }
     return launch_attn_combine(s, att_o, att_ml, p.nranges * p.wpk, out, nullptr, stream, seq_meta, p.wpk);
 }
 

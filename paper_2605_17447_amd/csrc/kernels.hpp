@@ -125,9 +125,19 @@ hipError_t launch_score_resident(const Shape &s, const ResidentPlan &p, int sync
 // ---- focal layer in one pass: dense attention output + scores (focal_fused.hip) -----------
 // Uses the same plan as the register-resident scoring kernel.
 size_t focal_fused_workspace_bytes(const Shape &s, const ResidentPlan &p);
+// A merge of attention partials handed on to the launch that follows (see launch_topk).
+struct CombineArgs {
+    const float *part_o, *part_ml;
+    int nsplit, d, n_q_heads, wpk;
+    const int32_t *seq_meta;
+    uint16_t *out;              // bf16 [B, Hq, d]
+};
+// defer != nullptr: the merge of the output's partials is not launched; *defer describes it and the
+// caller passes it to launch_topk, whose launch then does both (the top-k and that merge depend on
+// this kernel only, not on each other).
 hipError_t launch_focal_fused(const Shape &s, const ResidentPlan &p, int sync_slot, uint32_t *gave_up_flag, const void *q, float scale,
                               void *out, float *scores, float *lse, float *img_mass, void *ws, hipStream_t stream,
-                              const SelectArgs *select = nullptr);
+                              const SelectArgs *select = nullptr, CombineArgs *defer = nullptr);
 
 // ---- how often a workgroup gave up waiting for another one of its launch (each file's own count;
 // the copies synchronise with the device) ----------------------------------------------------
@@ -137,9 +147,13 @@ hipError_t attn_merge_timeouts(uint32_t *n);
 
 // ---- top-k (topk.hip) -------------------------------------------------------------------
 size_t topk_workspace_bytes(int batch, int max_vis_len);
+// combine != nullptr (only when topk_takes_combine says so): the launch gets one more workgroup per
+// (sequence, query head), which merges that head's attention partials.
 hipError_t launch_topk(const float *scores, const BatchDev &bv, int batch, double tau,
                        const int32_t *prev_idx, const int32_t *prev_cnt, int32_t *sel_idx,
-                       int32_t *sel_cnt, int64_t kmax, void *ws, hipStream_t stream);
+                       int32_t *sel_cnt, int64_t kmax, void *ws, hipStream_t stream,
+                       const CombineArgs *combine = nullptr);
+bool topk_takes_combine(int max_vis_len, int head_dim);
 
 // ---- streaming probe (probe.hip) ----------------------------------------------------------
 hipError_t launch_stream_probe(const void *src, void *dst, size_t bytes, void *sink, hipStream_t stream);

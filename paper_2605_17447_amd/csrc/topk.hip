@@ -13,6 +13,7 @@
 //   select over a candidate list, the writing spread over several workgroups per sequence.
 
 #include "topk_dev.hpp"
+#include "combine.hpp"
 
 namespace fastocr {
 
@@ -224,6 +225,37 @@ __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(
                                           [](int, int) {});
 }
 
+// The same, with batch * Hq more workgroups behind the selecting ones: each merges the attention
+// partials of one (sequence, query head) of the focal layer whose scores are being selected from.
+// The two kinds of workgroup share nothing but the launch.
+template <bool VEC, int PER>
+__global__ __launch_bounds__(kTopkThreads) void focal_tail_kernel(
+    const float *__restrict__ scores, BatchDev bv, double tau, const int32_t *prev_idx,
+    const int32_t *prev_cnt, int32_t *sel_idx, int32_t *sel_cnt, int64_t kmax, int batch, CombineArgs c)
+{
+    __shared__ uint32_t hist[kWinBins];
+    __shared__ __align__(16) uint32_t list[kWinListWords];
+    __shared__ int s_pick[4];
+    __shared__ __align__(16) int w_ac[4 * kTopkWaves];
+    __shared__ float sm_max[4];
+    __shared__ float sm_z[256];
+    __shared__ __align__(16) float sm_o[1024];
+
+    if ((int)blockIdx.x < batch) {
+        TopkRegShared sh;
+        sh.hist = hist; sh.list = list; sh.pick = s_pick; sh.w_ac = w_ac;
+        topk_reg_body<kTopkThreads, PER, false, VEC>(scores, bv, blockIdx.x, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax, sh,
+                                              [](int, int) {});
+    } else {
+        const int x = (int)blockIdx.x - batch;
+        const int b = x / c.n_q_heads, h = x - b * c.n_q_heads;
+        combine_wide_body<uint16_t>(c.part_o, c.part_ml, c.nsplit, c.d, c.out, nullptr, c.seq_meta, c.wpk, h, b, c.n_q_heads,
+                                    CombineShared{sm_max, sm_z, sm_o});
+    }
+}
+
+bool topk_takes_combine(int max_vis_len, int head_dim) { return max_vis_len > 0 && max_vis_len <= kTopkRegKeys && head_dim % 4 == 0 && head_dim <= 256; }
+
 // Workgroups per sequence: one per 1024 image tokens, as long as the grid still fits the chip in
 // one round (each workgroup occupies a compute unit with its keys in LDS).
 static int topk_parts(int batch, int max_vis_len)
@@ -244,8 +276,9 @@ size_t topk_workspace_bytes(int batch, int max_vis_len)
 
 hipError_t launch_topk(const float *scores, const BatchDev &bv, int batch, double tau,
                        const int32_t *prev_idx, const int32_t *prev_cnt, int32_t *sel_idx,
-                       int32_t *sel_cnt, int64_t kmax, void *ws, hipStream_t stream)
+                       int32_t *sel_cnt, int64_t kmax, void *ws, hipStream_t stream, const CombineArgs *combine)
 {
+    if (combine && !topk_takes_combine(bv.max_vis_len, combine->d)) return hipErrorInvalidValue;
     const int lds_keys = bv.max_vis_len <= kLdsKeyCap ? bv.max_vis_len : 0;
     const size_t dyn = (size_t)lds_keys * sizeof(uint32_t);
     // once per device: the opt-in belongs to the device's copy of the code
@@ -267,6 +300,16 @@ hipError_t launch_topk(const float *scores, const BatchDev &bv, int batch, doubl
         const bool vec = (reinterpret_cast<uintptr_t>(scores) & 15u) == 0 && (bv.max_vis_len & 3) == 0;
 #define FASTOCR_TOPK_REG(V, P) FASTOCR_LAUNCH(K_TOPK, (topk_reg_kernel<V, P>), dim3(batch), dim3(kTopkThreads), 0, stream, scores, \
                                               bv, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax)
+        if (combine) {
+            const dim3 grid(batch + batch * combine->n_q_heads);
+#define FASTOCR_TAIL(V, P) FASTOCR_LAUNCH(K_TOPK, (focal_tail_kernel<V, P>), grid, dim3(kTopkThreads), 0, stream, scores, \
+                                          bv, tau, prev_idx, prev_cnt, sel_idx, sel_cnt, kmax, batch, *combine)
+            if (bv.max_vis_len <= kTopkThreads * 4) { if (vec) FASTOCR_TAIL(true, 4); else FASTOCR_TAIL(false, 4); }
+            else if (bv.max_vis_len <= kTopkThreads * 8) { if (vec) FASTOCR_TAIL(true, 8); else FASTOCR_TAIL(false, 8); }
+            else { if (vec) FASTOCR_TAIL(true, kTopkPer); else FASTOCR_TAIL(false, kTopkPer); }
+#undef FASTOCR_TAIL
+            return hipGetLastError();
+        }
         if (bv.max_vis_len <= kTopkThreads * 4) { if (vec) FASTOCR_TOPK_REG(true, 4); else FASTOCR_TOPK_REG(false, 4); }
         else if (bv.max_vis_len <= kTopkThreads * 8) { if (vec) FASTOCR_TOPK_REG(true, 8); else FASTOCR_TOPK_REG(false, 8); }
         else { if (vec) FASTOCR_TOPK_REG(true, kTopkPer); else FASTOCR_TOPK_REG(false, kTopkPer); }

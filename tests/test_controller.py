@@ -32,6 +32,12 @@ class Recorder:
     def topk_fixation(self, scores, batch, tau, sel_idx, sel_cnt, ws, prev_idx=None, prev_cnt=None, **kw):
         self.calls.append(("topk", prev_idx is not None))
 
+    def focal_attn_score_topk(self, cache, batch, q, scale, tau, out, scores, sel_idx, sel_cnt, ws, prev_idx=None,
+                              prev_cnt=None, **kw):
+        # a selecting layer is one call: its own full attention, its scores and their top-k
+        self.calls.append(("dense+score", cache))
+        self.calls.append(("topk", prev_idx is not None))
+
     def sparse_decode_attn(self, cache, batch, q, scale, sel_idx, sel_cnt, out, ws, **kw):
         self.calls.append(("sparse", cache))
 

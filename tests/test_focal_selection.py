@@ -110,6 +110,11 @@ class _Recorder:
     def topk_fixation(self, *a, **k):
         self.calls.append("topk")
 
+    def focal_attn_score_topk(self, *a, img_mass=None, **k):
+        # a selecting layer is one call: full attention, scores and their top-k
+        self.calls.append(("dense+score", img_mass is not None))
+        self.calls.append("topk")
+
     def sparse_decode_attn(self, *a, **k):
         self.calls.append("sparse")
 

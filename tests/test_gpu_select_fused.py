@@ -174,3 +174,55 @@ def test_select_inside_the_launch_replays_in_a_graph():
         fb.set_tuning("select_fused", 1)
         torch.cuda.synchronize()
         assert torch.equal(sc, sc0) and torch.equal(out, out0) and torch.equal(cnt, cnt0) and torch.equal(idx, idx0), f"replay {replay}"
+
+
+@pytest.mark.parametrize("Hq,Hkv,d_unused", [(28, 4, 0), (64, 8, 0), (16, 2, 0), (8, 1, 0)])
+def test_focal_layer_one_call_merges_its_output_in_the_select_s_launch(Hq, Hkv, d_unused):
+    """With the select a launch of its own (the default), the one-call focal layer hands the merge of its
+    output's partials to that launch: no merge kernel is launched, and scores, set and output are the
+    separate calls' bit for bit.  Image spans beyond what the register select holds keep the merge kernel."""
+    fb.set_tuning("select_fused", 0)
+    try:
+        case = TinyCase(seed=870 + Hq, B=4, Hq=Hq, Hkv=Hkv, d=128, n_vis=[3000, 1777, 64, 0], pre=[32, 5, 3, 2],
+                        post=[41, 130, 0, 1], dtype="bf16")
+        p = problem_from_case(case)
+        tau = 0.05
+        kmax = max(1, fo.keep_count(p.batch.max_vis_len, tau))
+        ws = torch.empty(max(fo.workspace_bytes(op, p.cache, p.batch, p.Hq, kmax) for op in range(7)), dtype=torch.uint8, device=DEV)
+        sc = torch.zeros((p.B, p.batch.max_vis_len), dtype=torch.float32, device=DEV)
+        idx = torch.zeros((p.B, kmax), dtype=torch.int32, device=DEV)
+        cnt = torch.zeros((p.B,), dtype=torch.int32, device=DEV)
+        out = torch.zeros_like(p.q)
+        fb.kernel_timer_enable(fb.KERNEL_ATTN_COMBINE, 8)
+        fo.focal_attn_score_topk(p.cache, p.batch, p.q, p.scale, tau, out, sc, idx, cnt, ws)
+        torch.cuda.synchronize()
+        assert len(fb.kernel_timer_read(fb.KERNEL_ATTN_COMBINE)) == 0
+        fo.focal_attn_score(p.cache, p.batch, p.q, p.scale, out, sc, ws)
+        torch.cuda.synchronize()
+        assert len(fb.kernel_timer_read(fb.KERNEL_ATTN_COMBINE)) == 1
+        _one_call_vs_separate(p, tau, f"merge in the select's launch Hq{Hq} Hkv{Hkv}", expect_fused=False)
+    finally:
+        fb.kernel_timer_enable(fb.KERNEL_ATTN_COMBINE, 0)
+        fb.set_tuning("select_fused", 1)
+
+
+def test_focal_layer_one_call_with_a_long_image_span_keeps_the_merge_kernel():
+    fb.set_tuning("select_fused", 0)
+    try:
+        case = TinyCase(seed=871, B=2, Hq=8, Hkv=2, d=128, n_vis=[17000, 9000], pre=[12, 0], post=[30, 9], dtype="bf16")
+        p = problem_from_case(case)
+        tau = 0.05
+        kmax = max(1, fo.keep_count(p.batch.max_vis_len, tau))
+        ws = torch.empty(max(fo.workspace_bytes(op, p.cache, p.batch, p.Hq, kmax) for op in range(7)), dtype=torch.uint8, device=DEV)
+        sc = torch.zeros((p.B, p.batch.max_vis_len), dtype=torch.float32, device=DEV)
+        idx = torch.zeros((p.B, kmax), dtype=torch.int32, device=DEV)
+        cnt = torch.zeros((p.B,), dtype=torch.int32, device=DEV)
+        out = torch.zeros_like(p.q)
+        fb.kernel_timer_enable(fb.KERNEL_ATTN_COMBINE, 8)
+        fo.focal_attn_score_topk(p.cache, p.batch, p.q, p.scale, tau, out, sc, idx, cnt, ws)
+        torch.cuda.synchronize()
+        assert len(fb.kernel_timer_read(fb.KERNEL_ATTN_COMBINE)) == 1
+        _one_call_vs_separate(p, tau, "long image span", expect_fused=False, rounds=2)
+    finally:
+        fb.kernel_timer_enable(fb.KERNEL_ATTN_COMBINE, 0)
+        fb.set_tuning("select_fused", 1)
