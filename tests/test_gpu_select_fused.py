@@ -176,7 +176,7 @@ def test_select_inside_the_launch_replays_in_a_graph():
         assert torch.equal(sc, sc0) and torch.equal(out, out0) and torch.equal(cnt, cnt0) and torch.equal(idx, idx0), f"replay {replay}"
 
 
-@pytest.mark.parametrize("Hq,Hkv,d_unused", [(28, 4, 0), (64, 8, 0), (16, 2, 0), (8, 1, 0)])
+@pytest.mark.parametrize("Hq,Hkv,d_unused", [(28, 4, 0), (64, 8, 0), (16, 2, 0), (8, 1, 0), (6, 2, 0), (7, 1, 0)])
 def test_focal_layer_one_call_merges_its_output_in_the_select_s_launch(Hq, Hkv, d_unused):
     """With the select a launch of its own (the default), the one-call focal layer hands the merge of its
     output's partials to that launch: no merge kernel is launched, and scores, set and output are the
