@@ -143,13 +143,13 @@ def stack_extras(fs, fo, torch, np, dev, tau, cfg, n_time=30, **over):
         return (time.perf_counter() - t0) * 1e6 / n
 
     eager_us = timed(lambda: (ctl.step(3, batch, qs, outs), seq_len.add_(1)), 5)
-    fo.binding.set_tuning("graph_replay", 1)           # the captured step is told that it will be replayed
+    ctl.graph_replay = True                            # the captured step is told that it will be replayed
     try:
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
             ctl.step(3, batch, qs, outs)
     finally:
-        fo.binding.set_tuning("graph_replay", 0)
+        ctl.graph_replay = False
     timed(lambda: (g.replay(), seq_len.add_(1)), 3)
     graph_us = timed(lambda: (g.replay(), seq_len.add_(1)), n_time)
     seq_len.copy_(torch.tensor(bt.seq_len(t_start + 2), dtype=torch.int32))

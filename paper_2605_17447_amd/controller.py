@@ -62,6 +62,9 @@ class FixationController:
         # (a size never shrinks as sequences grow), not at every step
         self._bound_seq, self._bound_vis = int(max_seq_len), int(max_vis_len)
         self._need = {}
+        # set while a step is being captured into a HIP graph: the library is then told that its launches
+        # will follow each other closely (fastocr_set_tuning("graph_replay", 1)) for the calls of that step
+        self.graph_replay = False
 
     def _workspace(self, cache, batch):
         if batch.max_seq_len > self._bound_seq or batch.max_vis_len > self._bound_vis:
@@ -86,6 +89,15 @@ class FixationController:
         Returns the schedule it ran as (layer, mode, kept-set source) triples.
         ``on_select(layer, scores, kept_idx, kept_cnt)`` is called right after a selecting layer
         has been enqueued (the tensors are the controller's own buffers, valid in stream order)."""
+        if not self.graph_replay:
+            return self._step(t, batch, queries, outs, stream, on_select)
+        self.ops.set_tuning("graph_replay", 1)
+        try:
+            return self._step(t, batch, queries, outs, stream, on_select)
+        finally:
+            self.ops.set_tuning("graph_replay", 0)
+
+    def _step(self, t, batch, queries, outs, stream, on_select):
         ops, trace = self.ops, []
         post_warmup = t > self.warmup
         if post_warmup and self.focal is None:

@@ -113,3 +113,20 @@ def test_focal_gap_and_range_are_validated():
         mk((28,), 1)
     with pytest.raises(ValueError):
         plan_step(5, 4, (), 2, True)
+
+
+def test_graph_replay_switch_brackets_the_step_s_calls():
+    class Tuned(Recorder):
+        def set_tuning(self, key, value):
+            self.calls.append(("tune", key, value))
+    rec = Tuned()
+    ctl = FixationController([0, 1, 2], 4, 0.125, [1], 0.05, 0, 300, 256, 1, "cpu", ops=rec)
+    q = [torch.zeros(1)] * 3
+    ctl.step(1, _BATCH, q, q)
+    assert not [c for c in rec.calls if c[0] == "tune"]
+    rec.calls.clear()
+    ctl.graph_replay = True
+    ctl.step(2, _BATCH, q, q)
+    assert rec.calls[0] == ("tune", "graph_replay", 1) and rec.calls[-1] == ("tune", "graph_replay", 0)
+    assert len([c for c in rec.calls if c[0] == "tune"]) == 2
+

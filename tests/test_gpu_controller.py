@@ -141,7 +141,14 @@ def test_a_captured_decode_step_replays_like_the_eager_one(form):
         fb.set_tuning("focal_fused", 1)
 
 
-def _captured_step_replays():
+def test_a_captured_decode_step_with_the_graph_replay_hint():
+    """The same with the controllers told that their steps are replayed from a graph (pruned attention over
+    these short lists is then partials plus the merge kernel): eager and captured steps still agree bit for
+    bit, because the hint, not the capture, decides the launch shapes."""
+    _captured_step_replays(hint=True)
+
+
+def _captured_step_replays(hint=False):
     L, focal, tau, steps = 5, (1, 3), 0.1, 10
     wl = fs.config(3, batch=2, n_layers=L, focal_layers=focal, steps=steps, warmup=0, n_visual=(1024, 1024),
                    grid_w=(32, 32), text_prefix=(30, 30))
@@ -154,6 +161,7 @@ def _captured_step_replays():
     max_seq, max_vis = max(bt.seq_len(steps)), max(bt.n_vis)
     mk = lambda: fo.FixationController(caches, Hq, scale, focal, tau, 0, max_seq, max_vis, B, DEV, focal_gap=1)
     eager, graphed = mk(), mk()
+    eager.graph_replay = graphed.graph_replay = hint
     queries = lambda t: [fs.queries_for_step(bts[l], t, [c[t - 1] for c in cs]) for l in range(L)]
     vis_start = torch.tensor(bt.vis_start, dtype=torch.int32, device=DEV)
     vis_len = torch.tensor(bt.n_vis, dtype=torch.int32, device=DEV)
